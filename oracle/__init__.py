@@ -1,0 +1,27 @@
+"""CPU oracle for the PPO / BC / symmetry / RND hot path (fp64, numpy).
+
+TEST INFRASTRUCTURE ONLY.  This package is a plain, slow, obviously-correct
+statement of what the GPU library computes.  It is imported by the tests, by
+the smoke check and by the benchmark's CPU-baseline leg, and by nothing else:
+the product path never calls it and shares no code, tables or helpers with it.
+
+Everything is computed in float64 from the caller's (float32) inputs.  Library
+primitives used as steps: numpy matmul, numpy stable argsort.  There is no
+blocking, fusion or reordering beyond what each cited definition states.
+
+Pin status (what independent fact each function is checked against lives in
+tests/test_oracle_*.py):
+  rng.mix64 / permutation / act_noise ... pinned (big-int reimplementation,
+                                          bijection, moments)
+  gae.gae ............................... pinned (closed forms, O(T^2) brute force)
+  gae.normalize_advantages .............. pinned (mean 0, unbiased std 1)
+  gaussian.* ............................ pinned (scipy normal pdf, entropy closed form,
+                                          Monte-Carlo KL)
+  mlp.forward / backward ................ pinned (affine special case, finite differences)
+  ppo.minibatch_loss_and_grads .......... pinned (ratio==1 case, clip cases,
+                                          finite differences of the scalar loss)
+  adam.clip_scale / adam.adam_step ...... pinned (hand-stepped scalar table)
+  symmetry.* ............................ pinned (involution, equivariant net, identity map)
+  bc.* .................................. pinned (zero loss, normal-equation gradient)
+  rnd.* ................................. pinned (two-pass mean/var, zero error)
+"""
