@@ -1,0 +1,260 @@
+/*
+ * rslx — single-GPU (gfx950) library for the data-parallel hot path of a GPU-only PPO
+ * training loop: batched actor-critic inference (act), the GAE / returns reverse scan,
+ * the multi-epoch minibatch PPO update, the DAgger-style behaviour-cloning update,
+ * symmetry augmentation and the RND curiosity reward.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Plain C ABI.  Every function returns an int32 status (RSLX_OK = 0); on failure nothing
+ *    has been launched unless stated, and rslx_last_error() gives a thread-local message.
+ *  - "device" pointers are HIP device memory owned by the caller.  The library never
+ *    allocates, frees or keeps them.  Scratch memory comes from the caller's workspace
+ *    (`ws`, `ws_bytes`), sized by the matching *_workspace_bytes() query; a workspace that is
+ *    too small gives RSLX_ERR_WORKSPACE.  Device pointers must be 16-byte aligned.
+ *  - "host" pointers are ordinary host memory, read (or written) before the call returns.
+ *  - All matrices are dense row-major fp32 unless said otherwise.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream).
+ *    No entry point synchronises with the host; outputs are valid once the stream reaches
+ *    the end of the enqueued work.  Calls that share a workspace must be stream-ordered.
+ *  - Flat parameter layout of a network (struct rslx_mlp): for each linear layer l in order,
+ *    W_l as [dims[l], dims[l+1]] row-major (y = x W + b), then b_l [dims[l+1]]; an actor's
+ *    buffer ends with log_std[dims[n_layers]].  grads / adam_m / adam_v mirror this layout.
+ *    Hidden layers use ELU with parameter elu_alpha; the last layer is linear.
+ */
+#ifndef RSLX_H
+#define RSLX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RSLX_OK 0
+#define RSLX_ERR_INVALID_ARG 1
+#define RSLX_ERR_SHAPE 2
+#define RSLX_ERR_WORKSPACE 3
+#define RSLX_ERR_HIP 4
+#define RSLX_ERR_UNSUPPORTED 5
+
+#define RSLX_MAX_LAYERS 8
+#define RSLX_MAX_ACTIONS 64
+
+/* Columns of the per-minibatch statistics rows written by the update calls. */
+#define RSLX_NSTATS 8
+#define RSLX_STAT_SURROGATE 0
+#define RSLX_STAT_VALUE_LOSS 1
+#define RSLX_STAT_ENTROPY 2
+#define RSLX_STAT_KL 3
+#define RSLX_STAT_GRAD_NORM 4 /* before clipping */
+#define RSLX_STAT_CLIP_FRAC 5
+#define RSLX_STAT_MIRROR_LOSS 6
+#define RSLX_STAT_RND_LOSS 7
+/* rslx_bc_update uses column 0 for the MSE loss and column 4 for the gradient norm. */
+
+/* rslx_act flags */
+#define RSLX_ACT_DETERMINISTIC 1u /* actions := mu (no noise) */
+#define RSLX_ACT_VALUES_ONLY 2u   /* only the critic runs; only `values` is written */
+
+/* A multi-layer perceptron over caller-owned device buffers (paper Sec. 3, "Network"). */
+typedef struct rslx_mlp {
+  int32_t n_layers;                  /* number of linear layers, 1..RSLX_MAX_LAYERS */
+  int32_t dims[RSLX_MAX_LAYERS + 1]; /* dims[0] = input width, dims[n_layers] = output width */
+  float elu_alpha;                   /* ELU parameter of the hidden layers (workloads use 1) */
+  int32_t has_log_std;               /* 1: params end with log_std[dims[n_layers]] (actor) */
+  float* params;                     /* device, flat layout above */
+  float* grads;                      /* device, same layout; NULL for frozen networks */
+  float* adam_m;                     /* device, same layout; NULL for frozen networks */
+  float* adam_v;                     /* device, same layout; NULL for frozen networks */
+} rslx_mlp;
+
+/* Rollout storage [T, N, .] flattened to B = T*N rows, flat row b = t*N + n (paper Sec. 3:
+ * the Runner stores what act() and the environment return; all device, read-only). */
+typedef struct rslx_rollout {
+  int32_t T, N;            /* steps per rollout, parallel environments */
+  int32_t Da, Dc, A;       /* actor obs width, critic obs width, action width */
+  const float* obs_actor;  /* [B, Da] */
+  const float* obs_critic; /* [B, Dc] (may alias obs_actor) */
+  const float* actions;    /* [B, A] */
+  const float* logp;       /* [B]  log-density of actions under the collecting policy */
+  const float* values;     /* [B]  critic values at collection */
+  const float* mu;         /* [B, A] collecting policy mean (KL statistic) */
+  const float* sigma;      /* [B, A] collecting policy std  (KL statistic) */
+  const float* advantages; /* [B]  (normalised) advantages from rslx_gae */
+  const float* returns;    /* [B]  returns from rslx_gae */
+} rslx_rollout;
+
+/* Hyper-parameters of the PPO update (paper Sec. 2.1; Schulman et al. 2017). */
+typedef struct rslx_ppo_cfg {
+  float clip;          /* epsilon of the ratio clip and of the value clip */
+  float value_coef;    /* c_v */
+  float entropy_coef;  /* c_e */
+  float max_grad_norm; /* global L2 clip; <= 0 or inf disables */
+  float lr, beta1, beta2, adam_eps;
+  int32_t epochs;      /* E */
+  int32_t minibatches; /* M; B % M must be 0 */
+  int32_t use_clipped_value_loss;
+  uint64_t seed;        /* permutation stream */
+  uint64_t call_index;  /* permutation stream: which update call */
+  int32_t epoch_offset; /* permutation of epoch e uses e + epoch_offset (resume mid-update) */
+} rslx_ppo_cfg;
+
+/* Mirror maps (paper Sec. 2.2): mirror(x)[j] = sign[j] * x[perm[j]].  Each map is given twice:
+ * a host copy (validated: must be a signed permutation with mirror o mirror = id) and a device
+ * copy used by the kernels.  Both copies must hold the same values. */
+typedef struct rslx_sym {
+  const int32_t* perm_obs_a_host; const float* sign_obs_a_host; /* [Da] */
+  const int32_t* perm_obs_c_host; const float* sign_obs_c_host; /* [Dc] */
+  const int32_t* perm_act_host;   const float* sign_act_host;   /* [A]  */
+  const int32_t* perm_obs_a; const float* sign_obs_a;           /* device copies */
+  const int32_t* perm_obs_c; const float* sign_obs_c;
+  const int32_t* perm_act;   const float* sign_act;
+  float mirror_loss_coef; /* c_sym; 0 keeps the augmentation and drops the loss term */
+} rslx_sym;
+
+/* RND predictor training inside the PPO update (paper Sec. 2.2). */
+typedef struct rslx_rnd_train {
+  const rslx_mlp* target;    /* frozen */
+  rslx_mlp* predictor;       /* trained: params, grads, adam_m, adam_v required */
+  const int32_t* subset_idx; /* device [n_subset] columns of obs_actor fed to both nets, or NULL = all */
+  int32_t n_subset;          /* must equal target->dims[0]; Da when subset_idx is NULL */
+  float lr;                  /* predictor's own Adam learning rate (betas/eps as in the PPO cfg) */
+  int64_t* adam_step;        /* host, in-out: predictor's own step counter */
+} rslx_rnd_train;
+
+/* Hyper-parameters of the behaviour-cloning update (paper Sec. 2.1, DAgger-style BC). */
+typedef struct rslx_bc_cfg {
+  float lr, beta1, beta2, adam_eps;
+  float max_grad_norm; /* <= 0 disables clipping */
+  int32_t epochs, minibatches;
+  uint64_t seed, call_index;
+  int32_t epoch_offset;
+} rslx_bc_cfg;
+
+/* ---- housekeeping ------------------------------------------------------------------- */
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t rslx_version(void);
+/* Message of the last failure on the calling thread ("" if none).  Never NULL. */
+const char* rslx_last_error(void);
+/* RSLX_OK if the current HIP device is a gfx950 part, RSLX_ERR_UNSUPPORTED / RSLX_ERR_HIP otherwise. */
+int32_t rslx_device_check(void);
+
+/* ---- permutation of one epoch (update step U0) --------------------------------------- */
+
+/* Shuffled minibatch order (paper Sec. 2.1: multi-epoch minibatch updates; the generator is this
+ * library's own):  mix64 = SplitMix64 output function,
+ *   key_i = mix64(mix64(mix64(mix64(seed) ^ call_index) ^ epoch) ^ i),  i in [0, B)
+ *   perm  = indices sorted ascending by (key_i, i).
+ * perm_out: device int32 [B].  Result is bit-exact and independent of scheduling. */
+size_t rslx_permutation_workspace_bytes(int32_t B);
+int32_t rslx_permutation(uint64_t seed, uint64_t call_index, int32_t epoch, int32_t B,
+                         int32_t* perm_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- act(): one rollout step (paper Sec. 2.1 / Sec. 3: Runner -> Algorithm.act) ------ */
+
+/* mu = actor(obs_actor), V = critic(obs_critic); sigma = exp(log_std);
+ * a = mu + sigma * eps;  logp = -1/2 sum ((a-mu)/sigma)^2 - sum log sigma - A/2 log(2 pi).
+ * eps: device [N, A] standard-normal noise, or NULL to draw it from the counter generator
+ *   h = mix64(mix64(mix64(seed ^ 0xAC7) ^ step) ^ (n*A + j)); u1 = ((h>>40)+1) 2^-24;
+ *   u2 = ((h>>8) & 0xFFFFFF) 2^-24; eps = sqrt(-2 ln u1) cos(2 pi u2).
+ * Outputs (device): actions [N,A], logp [N], values [N], mu [N,A], sigma [N,A]; typically
+ * pointers into slot t of the rollout storage.  With RSLX_ACT_VALUES_ONLY only `values` is
+ * written and actor / actor outputs may be NULL. */
+size_t rslx_act_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* critic, int32_t N);
+int32_t rslx_act(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor,
+                 const float* obs_critic, int32_t N, uint64_t seed, uint64_t step,
+                 const float* eps_or_null, float* actions, float* logp, float* values, float* mu,
+                 float* sigma, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- GAE / returns (paper Sec. 2.1; time-limit handling Sec. 3) ---------------------- */
+
+/* With V_T = last_values and A_T = 0, for t = T-1..0:
+ *   delta = r_t + gamma (1-d_t) V_{t+1} - V_t;  A_t = delta + gamma lam (1-d_t) A_{t+1};
+ *   R_t = A_t + V_t.   If timeouts != NULL, r_t is first replaced by r_t + gamma V_t timeout_t.
+ * If normalize_adv != 0, advantages are then replaced by (A - mean) / (std + 1e-8) with the
+ * mean and the unbiased (n-1) std taken over all T*N entries; returns use the raw A.
+ * rewards, values [T,N]; last_values [N]; dones, timeouts uint8 [T,N]; outputs [T,N]. All device. */
+size_t rslx_gae_workspace_bytes(int32_t T, int32_t N);
+int32_t rslx_gae(const float* rewards, const float* values, const float* last_values,
+                 const uint8_t* dones, const uint8_t* timeouts_or_null, int32_t T, int32_t N,
+                 float gamma, float lam, int32_t normalize_adv, float* advantages, float* returns,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/* ---- fused gradient-clip + Adam over one flat buffer (update steps U5/U6) ------------- */
+
+/* s = min(1, max_grad_norm / (||g||_2 + 1e-6)) (1 when max_grad_norm <= 0), then Adam
+ * (Kingma & Ba 2015) with g*s:  m,v moments in place, bias correction with step t = *adam_step+1,
+ * theta -= lr * m_hat / (sqrt(v_hat) + eps).  *adam_step (host) is incremented.
+ * params, grads, m, v: device [n].  grad_norm_out: device float[1] or NULL. */
+size_t rslx_adam_workspace_bytes(int64_t n);
+int32_t rslx_adam_step(float* params, const float* grads, float* m, float* v, int64_t n, float lr,
+                       float beta1, float beta2, float eps, float max_grad_norm, int64_t* adam_step,
+                       float* grad_norm_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- PPO update (paper Sec. 2.1, 2.2, 3) ---------------------------------------------- */
+
+/* E epochs x M minibatches over the B = T*N rollout rows.  For every minibatch (rows
+ * perm_e[m*mb : (m+1)*mb], mb = B/M): forward of actor and critic, Gaussian log-density and
+ * entropy, ratio = exp(logp_new - logp_old),
+ *   L_pi = mean max(-A ratio, -A clamp(ratio, 1-clip, 1+clip))
+ *   L_V  = mean max((V-R)^2, (V_old + clamp(V-V_old, -clip, clip) - R)^2)   (or mean (R-V)^2)
+ *   L    = L_pi + c_v L_V - c_e mean(entropy) [+ c_sym L_mirror]
+ * backward, one global gradient norm over actor (with log_std) and critic, clip, Adam.
+ * With `sym`: every minibatch is followed by its mirrored copy (2*mb rows; obs and actions
+ * mirrored, advantages / returns / old values / old log-densities copied), means run over
+ * 2*mb rows, and L_mirror = mean over mb rows and A dims of
+ * (mu(mirror(o)) - stopgrad(mirror_a(mu(o))))^2.
+ * With `rnd`: the predictor is trained on the same rows with its own Adam on
+ * mean((pred(x) - target(x))^2), outside the PPO gradient norm.
+ * In-out: actor/critic params, adam_m, adam_v (device), *adam_step (host, shared by both nets).
+ * Out: grads hold the last minibatch's unclipped gradient; stats: device [E*M, RSLX_NSTATS]. */
+size_t rslx_ppo_update_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* critic,
+                                       const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
+                                       const rslx_sym* sym_or_null, const rslx_rnd_train* rnd_or_null);
+int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* ro,
+                        const rslx_ppo_cfg* cfg, const rslx_sym* sym_or_null,
+                        const rslx_rnd_train* rnd_or_null, int64_t* adam_step, float* stats,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* ---- behaviour cloning update (paper Sec. 2.1) ---------------------------------------- */
+
+/* targets = teacher(obs_teacher) (once; or the caller's precomputed `targets_or_null` [B, A]);
+ * per minibatch L = mean over rows and action dims of (student(obs_student) - target)^2,
+ * backward, optional clip, Adam.  obs_student [B, Ds], obs_teacher [B, Dt] device.
+ * stats: device [E*M, RSLX_NSTATS] (column 0 loss, column 4 gradient norm, others 0). */
+size_t rslx_bc_update_workspace_bytes(const rslx_mlp* student, const rslx_mlp* teacher, int32_t B,
+                                      const rslx_bc_cfg* cfg);
+int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student,
+                       const float* obs_teacher, const float* targets_or_null, int32_t B,
+                       const rslx_bc_cfg* cfg, int64_t* adam_step, float* stats, void* ws,
+                       size_t ws_bytes, void* stream);
+
+/* ---- symmetry augmentation (paper Sec. 2.2) -------------------------------------------- */
+
+/* obs_out[0:B] = obs_in, obs_out[B:2B][:, j] = sign_obs_a[j] * obs_in[:, perm_obs_a[j]]; the same
+ * for actions with perm_act / sign_act.  Uses the *_obs_a and *_act maps of `sym` (host copies
+ * validated, device copies read by the kernel).  obs_in [B, D], act_in [B, A] (either may be
+ * NULL to skip it), outputs [2B, D], [2B, A]; all device.  RSLX_ERR_INVALID_ARG if a map is not
+ * an involutive signed permutation. */
+int32_t rslx_sym_augment(const rslx_sym* sym, const float* obs_in, const float* act_in, int32_t B,
+                         int32_t D, int32_t A, float* obs_out, float* act_out, void* stream);
+
+/* ---- RND intrinsic reward (paper Sec. 2.2) --------------------------------------------- */
+
+/* x = obs[:, subset]; r_raw_n = sum_k (predictor(x_n) - target(x_n))_k^2.  If update_stats,
+ * running = {mean, var, count} (device float[3], population variance) is merged with the N new
+ * values (Chan et al. pairwise update) before use.  r_int = r_raw / sqrt(var + 1e-8) is written
+ * to r_int_out [N]; if rewards_inout != NULL, rewards_inout[n] += weight * r_int[n]. */
+size_t rslx_rnd_workspace_bytes(const rslx_mlp* target, int32_t N);
+int32_t rslx_rnd(const rslx_mlp* target, const rslx_mlp* predictor, const float* obs, int32_t N,
+                 int32_t D, const int32_t* subset_idx_or_null, int32_t n_subset, float* running,
+                 float weight, int32_t update_stats, float* r_int_out, float* rewards_inout_or_null,
+                 void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSLX_H */

@@ -1,0 +1,811 @@
+// Host side of librslx: argument validation, workspace carving and launch sequencing for the C ABI
+// declared in include/rslx.h.  No entry point synchronises with the host or allocates device memory.
+#include <climits>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/rslx.h"
+#include "kernels.h"
+
+namespace {
+
+using namespace rslx;
+
+thread_local std::string g_last_error;
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+#define RSLX_HIP(expr)                                                                    \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) return fail(RSLX_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+#define RSLX_TRY(expr)             \
+  do {                             \
+    int32_t rc_ = (expr);          \
+    if (rc_ != RSLX_OK) return rc_; \
+  } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint64_t mix64_host(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+// ---- workspace carving: the same code sizes the workspace (base == nullptr) and hands out pointers ----
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T>
+  T* take(size_t count) {
+    off = (off + 255) / 256 * 256;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+// ---- network helpers ---------------------------------------------------------------------------------
+int64_t layer_offset(const rslx_mlp& n, int l) {
+  int64_t o = 0;
+  for (int i = 0; i < l; ++i) o += (int64_t)n.dims[i] * n.dims[i + 1] + n.dims[i + 1];
+  return o;
+}
+int64_t weight_count(const rslx_mlp& n) { return layer_offset(n, n.n_layers); }
+int64_t param_count(const rslx_mlp& n) { return weight_count(n) + (n.has_log_std ? n.dims[n.n_layers] : 0); }
+
+int32_t check_mlp(const rslx_mlp* n, const char* name, bool trainable) {
+  if (!n) return fail(RSLX_ERR_INVALID_ARG, "%s: null network", name);
+  if (n->n_layers < 1 || n->n_layers > RSLX_MAX_LAYERS) return fail(RSLX_ERR_SHAPE, "%s: n_layers %d out of range", name, n->n_layers);
+  for (int i = 0; i <= n->n_layers; ++i)
+    if (n->dims[i] < 1 || n->dims[i] > (1 << 20)) return fail(RSLX_ERR_SHAPE, "%s: dims[%d] = %d", name, i, n->dims[i]);
+  if (!n->params || !aligned16(n->params)) return fail(RSLX_ERR_INVALID_ARG, "%s: params null or not 16-byte aligned", name);
+  if (trainable) {
+    if (!n->grads || !n->adam_m || !n->adam_v) return fail(RSLX_ERR_INVALID_ARG, "%s: grads / adam_m / adam_v required", name);
+    if (!aligned16(n->grads) || !aligned16(n->adam_m) || !aligned16(n->adam_v))
+      return fail(RSLX_ERR_INVALID_ARG, "%s: optimiser buffers not 16-byte aligned", name);
+  }
+  return RSLX_OK;
+}
+
+// View of a network's input matrix (see GemmProblem in kernels.h).
+struct XView {
+  const float* base = nullptr;
+  int ld = 0;
+  const int32_t* row_idx = nullptr;
+  const int32_t* col_map = nullptr;
+  const float* col_sign = nullptr;
+  int idx_mod = INT_MAX;
+  int map_from = INT_MAX;
+};
+
+// Per-network activation storage for `rows` rows: out[l] = output of layer l, dz[l] = gradient w.r.t. the
+// pre-activation of hidden layer l.  The caller may point out[last] at its own buffer.
+struct NetBufs {
+  float* out[RSLX_MAX_LAYERS] = {};
+  float* dz[RSLX_MAX_LAYERS] = {};
+};
+
+void carve_net(Carver& c, const rslx_mlp& n, int64_t rows, bool backward, NetBufs& b) {
+  for (int l = 0; l < n.n_layers; ++l) b.out[l] = c.take<float>((size_t)rows * n.dims[l + 1]);
+  if (backward)
+    for (int l = 0; l + 1 < n.n_layers; ++l) b.dz[l] = c.take<float>((size_t)rows * n.dims[l + 1]);
+}
+
+GemmProblem blank_problem() {
+  GemmProblem p;
+  memset(&p, 0, sizeof p);
+  p.idx_mod = INT_MAX;
+  p.map_from = INT_MAX;
+  p.bias_off = -1;
+  p.n_split = 1;
+  return p;
+}
+
+void set_x(GemmProblem& p, const XView& x) {
+  p.A = x.base; p.lda = x.ld; p.row_idx = x.row_idx; p.col_map = x.col_map; p.col_sign = x.col_sign;
+  p.idx_mod = x.idx_mod; p.map_from = x.map_from;
+}
+
+struct NetJob {
+  const rslx_mlp* net;
+  XView x;
+  int32_t rows;
+  NetBufs* bufs;
+};
+
+// Forward of up to two networks of equal depth, one grouped launch per layer.
+int32_t forward_nets(const NetJob* jobs, int count, hipStream_t stream) {
+  if (count == 2 && jobs[0].net->n_layers != jobs[1].net->n_layers) {
+    RSLX_TRY(forward_nets(jobs, 1, stream));
+    return forward_nets(jobs + 1, 1, stream);
+  }
+  const int L = jobs[0].net->n_layers;
+  for (int l = 0; l < L; ++l) {
+    GemmBatch b;
+    b.count = count;
+    for (int i = 0; i < count; ++i) {
+      const rslx_mlp& n = *jobs[i].net;
+      GemmProblem p = blank_problem();
+      if (l == 0) {
+        set_x(p, jobs[i].x);
+      } else {
+        p.A = jobs[i].bufs->out[l - 1];
+        p.lda = n.dims[l];
+      }
+      const float* W = n.params + layer_offset(n, l);
+      p.B = W; p.ldb = n.dims[l + 1];
+      p.aux = W + (int64_t)n.dims[l] * n.dims[l + 1];
+      p.C = jobs[i].bufs->out[l]; p.ldc = n.dims[l + 1];
+      p.M = jobs[i].rows; p.N = n.dims[l + 1]; p.K = n.dims[l];
+      p.elu = (l + 1 < L) ? 1 : 0;
+      p.alpha = n.elu_alpha;
+      p.a_vec = (p.K % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
+      p.b_vec = (p.N % 4 == 0 && aligned16(p.B)) ? 1 : 0;
+      b.p[i] = p;
+    }
+    RSLX_HIP(launch_gemm(GEMM_FWD, b, stream));
+  }
+  return RSLX_OK;
+}
+
+struct BwdJob {
+  const rslx_mlp* net;
+  XView x;
+  int32_t rows;
+  NetBufs* bufs;
+  const float* d_out;    // [rows, dims[L]]
+  float* partials;       // n_split buffers of split_stride floats, flat gradient layout
+  int64_t split_stride;
+};
+
+int choose_split(int32_t rows) {
+  int s = rows / 1536;
+  if (s < 1) s = 1;
+  if (s > 16) s = 16;
+  return s;
+}
+int chunk_for(int32_t rows, int n_split) {
+  int c = (rows + n_split - 1) / n_split;
+  return (c + 15) / 16 * 16;
+}
+
+// Backward of up to two networks of equal depth: per layer one grouped weight-gradient launch (split over
+// rows, partial sums) and one grouped input-gradient launch.
+int32_t backward_nets(const BwdJob* jobs, int count, int n_split, hipStream_t stream) {
+  if (count == 2 && jobs[0].net->n_layers != jobs[1].net->n_layers) {
+    RSLX_TRY(backward_nets(jobs, 1, n_split, stream));
+    return backward_nets(jobs + 1, 1, n_split, stream);
+  }
+  const int L = jobs[0].net->n_layers;
+  for (int l = L - 1; l >= 0; --l) {
+    GemmBatch bw, bx;
+    bw.count = bx.count = count;
+    for (int i = 0; i < count; ++i) {
+      const rslx_mlp& n = *jobs[i].net;
+      const float* dz = (l == L - 1) ? jobs[i].d_out : jobs[i].bufs->dz[l];
+      GemmProblem p = blank_problem();
+      if (l == 0) {
+        set_x(p, jobs[i].x);
+      } else {
+        p.A = jobs[i].bufs->out[l - 1];
+        p.lda = n.dims[l];
+      }
+      p.B = dz; p.ldb = n.dims[l + 1];
+      p.C = jobs[i].partials + layer_offset(n, l); p.ldc = n.dims[l + 1];
+      p.M = n.dims[l]; p.N = n.dims[l + 1]; p.K = jobs[i].rows;
+      p.n_split = n_split;
+      p.k_chunk = chunk_for(jobs[i].rows, n_split);
+      p.split_stride = jobs[i].split_stride;
+      p.bias_off = n.dims[l] * n.dims[l + 1];
+      p.a_vec = (p.M % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
+      p.b_vec = (p.N % 4 == 0 && aligned16(p.B)) ? 1 : 0;
+      bw.p[i] = p;
+      if (l > 0) {
+        GemmProblem q = blank_problem();
+        q.A = dz; q.lda = n.dims[l + 1];
+        q.B = n.params + layer_offset(n, l); q.ldb = n.dims[l + 1];
+        q.C = jobs[i].bufs->dz[l - 1]; q.ldc = n.dims[l];
+        q.aux = jobs[i].bufs->out[l - 1];
+        q.M = jobs[i].rows; q.N = n.dims[l]; q.K = n.dims[l + 1];
+        q.alpha = n.elu_alpha;
+        q.a_vec = (q.K % 4 == 0 && aligned16(q.A)) ? 1 : 0;
+        q.b_vec = (q.K % 4 == 0 && aligned16(q.B)) ? 1 : 0;
+        bx.p[i] = q;
+      }
+    }
+    RSLX_HIP(launch_gemm(GEMM_DW, bw, stream));
+    if (l > 0) RSLX_HIP(launch_gemm(GEMM_DX, bx, stream));
+  }
+  return RSLX_OK;
+}
+
+bool involution_ok(const int32_t* perm, const float* sign, int n) {
+  if (!perm || !sign) return false;
+  for (int j = 0; j < n; ++j) {
+    if (perm[j] < 0 || perm[j] >= n) return false;
+    if (sign[j] != 1.0f && sign[j] != -1.0f) return false;
+  }
+  for (int j = 0; j < n; ++j) {
+    if (perm[perm[j]] != j) return false;
+    if (sign[j] * sign[perm[j]] != 1.0f) return false;
+  }
+  return true;
+}
+
+float bias_correction(float beta, int64_t t) { return (float)(1.0 - std::pow((double)beta, (double)t)); }
+
+int64_t round4(int64_t n) { return (n + 3) / 4 * 4; }
+
+}  // namespace
+
+// ======================================================================================================
+extern "C" {
+
+int32_t rslx_version(void) { return 100; }
+
+const char* rslx_last_error(void) { return g_last_error.c_str(); }
+
+int32_t rslx_device_check(void) {
+  int dev = 0;
+  RSLX_HIP(hipGetDevice(&dev));
+  hipDeviceProp_t prop;
+  RSLX_HIP(hipGetDeviceProperties(&prop, dev));
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return fail(RSLX_ERR_UNSUPPORTED, "device %d is %s, this library is built for gfx950", dev, prop.gcnArchName);
+  return RSLX_OK;
+}
+
+// ---- permutation ---------------------------------------------------------------------------------------
+size_t rslx_permutation_workspace_bytes(int32_t B) { return B > 0 ? perm_workspace_bytes(B) + 256 : 256; }
+
+int32_t rslx_permutation(uint64_t seed, uint64_t call_index, int32_t epoch, int32_t B, int32_t* perm_out, void* ws,
+                         size_t ws_bytes, void* stream) {
+  if (B < 0 || epoch < 0) return fail(RSLX_ERR_SHAPE, "rslx_permutation: B = %d, epoch = %d", B, epoch);
+  if (B == 0) return RSLX_OK;
+  if (!perm_out || !ws) return fail(RSLX_ERR_INVALID_ARG, "rslx_permutation: null pointer");
+  if (ws_bytes < rslx_permutation_workspace_bytes(B)) return fail(RSLX_ERR_WORKSPACE, "rslx_permutation: workspace too small");
+  Carver c(ws);
+  void* w = c.take<char>(perm_workspace_bytes(B));
+  const uint64_t base = mix64_host(mix64_host(mix64_host(seed) ^ call_index) ^ (uint64_t)epoch);
+  RSLX_HIP(launch_permutation(base, B, perm_out, w, (hipStream_t)stream));
+  return RSLX_OK;
+}
+
+// ---- act ---------------------------------------------------------------------------------------------------
+static size_t act_carve(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, int32_t N, NetBufs* ba, NetBufs* bc) {
+  NetBufs ta, tc;
+  if (actor) carve_net(c, *actor, N, false, ta);
+  if (critic) carve_net(c, *critic, N, false, tc);
+  if (ba) *ba = ta;
+  if (bc) *bc = tc;
+  return c.off + 256;
+}
+
+size_t rslx_act_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* critic, int32_t N) {
+  if (N <= 0) return 256;
+  Carver c(nullptr);
+  return act_carve(c, actor, critic, N, nullptr, nullptr);
+}
+
+int32_t rslx_act(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
+                 int32_t N, uint64_t seed, uint64_t step, const float* eps_or_null, float* actions, float* logp,
+                 float* values, float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+  const bool values_only = (flags & RSLX_ACT_VALUES_ONLY) != 0;
+  if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_act: N = %d", N);
+  RSLX_TRY(check_mlp(critic, "rslx_act critic", false));
+  if (critic->dims[critic->n_layers] != 1) return fail(RSLX_ERR_SHAPE, "rslx_act: critic output width must be 1");
+  if (!values_only) {
+    RSLX_TRY(check_mlp(actor, "rslx_act actor", false));
+    if (!actor->has_log_std) return fail(RSLX_ERR_INVALID_ARG, "rslx_act: actor needs log_std");
+    if (actor->dims[actor->n_layers] > RSLX_MAX_ACTIONS) return fail(RSLX_ERR_SHAPE, "rslx_act: action width > %d", RSLX_MAX_ACTIONS);
+    if (!obs_actor || !actions || !logp || !mu || !sigma) return fail(RSLX_ERR_INVALID_ARG, "rslx_act: null actor input / output");
+  }
+  if (!obs_critic || !values) return fail(RSLX_ERR_INVALID_ARG, "rslx_act: null critic input / output");
+  if (N == 0) return RSLX_OK;
+  const rslx_mlp* a = values_only ? nullptr : actor;
+  if (!ws || ws_bytes < rslx_act_workspace_bytes(a, critic, N)) return fail(RSLX_ERR_WORKSPACE, "rslx_act: workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  NetBufs ba, bc;
+  act_carve(c, a, critic, N, &ba, &bc);
+  bc.out[critic->n_layers - 1] = values;              // [N, 1] lands directly in the caller's buffer
+  NetJob jobs[2];
+  int nj = 0;
+  if (a) {
+    ba.out[a->n_layers - 1] = mu;
+    XView xa; xa.base = obs_actor; xa.ld = a->dims[0];
+    jobs[nj++] = NetJob{a, xa, N, &ba};
+  }
+  XView xc; xc.base = obs_critic; xc.ld = critic->dims[0];
+  jobs[nj++] = NetJob{critic, xc, N, &bc};
+  RSLX_TRY(forward_nets(jobs, nj, s));
+  if (a) {
+    const int A = a->dims[a->n_layers];
+    const uint64_t base = mix64_host(mix64_host(seed ^ 0xAC7ull) ^ step);
+    RSLX_HIP(launch_act_head(mu, a->params + weight_count(*a), eps_or_null, base, N, A,
+                             (flags & RSLX_ACT_DETERMINISTIC) ? 1 : 0, actions, logp, mu, sigma, s));
+  }
+  return RSLX_OK;
+}
+
+// ---- GAE -----------------------------------------------------------------------------------------------------
+size_t rslx_gae_workspace_bytes(int32_t T, int32_t N) {
+  (void)T;
+  if (N <= 0) return 256;
+  return (size_t)gae_num_blocks(N) * 16 + 16 + 512;
+}
+
+int32_t rslx_gae(const float* rewards, const float* values, const float* last_values, const uint8_t* dones,
+                 const uint8_t* timeouts_or_null, int32_t T, int32_t N, float gamma, float lam, int32_t normalize_adv,
+                 float* advantages, float* returns, void* ws, size_t ws_bytes, void* stream) {
+  if (T < 0 || N < 0) return fail(RSLX_ERR_SHAPE, "rslx_gae: T = %d, N = %d", T, N);
+  if (T == 0 || N == 0) return RSLX_OK;
+  if (!rewards || !values || !last_values || !dones || !advantages || !returns)
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_gae: null pointer");
+  if (!aligned16(advantages)) return fail(RSLX_ERR_INVALID_ARG, "rslx_gae: advantages not 16-byte aligned");
+  if ((int64_t)T * N > (int64_t)INT_MAX * 4) return fail(RSLX_ERR_SHAPE, "rslx_gae: T*N too large");
+  double* partials = nullptr;
+  if (normalize_adv) {
+    if (!ws || ws_bytes < rslx_gae_workspace_bytes(T, N)) return fail(RSLX_ERR_WORKSPACE, "rslx_gae: workspace too small");
+    Carver c(ws);
+    partials = c.take<double>((size_t)gae_num_blocks(N) * 2 + 2);
+  }
+  RSLX_HIP(launch_gae(rewards, values, last_values, dones, timeouts_or_null, T, N, gamma, lam, normalize_adv ? 1 : 0,
+                      advantages, returns, partials, (hipStream_t)stream));
+  return RSLX_OK;
+}
+
+// ---- Adam ----------------------------------------------------------------------------------------------------
+size_t rslx_adam_workspace_bytes(int64_t n) { return n > 0 ? (size_t)reduce_num_blocks(n) * 8 + 512 : 256; }
+
+int32_t rslx_adam_step(float* params, const float* grads, float* m, float* v, int64_t n, float lr, float beta1,
+                       float beta2, float eps, float max_grad_norm, int64_t* adam_step, float* grad_norm_out, void* ws,
+                       size_t ws_bytes, void* stream) {
+  if (n < 0) return fail(RSLX_ERR_SHAPE, "rslx_adam_step: n = %lld", (long long)n);
+  if (!adam_step) return fail(RSLX_ERR_INVALID_ARG, "rslx_adam_step: null adam_step");
+  if (n == 0) { ++*adam_step; return RSLX_OK; }
+  if (!params || !grads || !m || !v) return fail(RSLX_ERR_INVALID_ARG, "rslx_adam_step: null pointer");
+  if (!aligned16(params) || !aligned16(grads) || !aligned16(m) || !aligned16(v))
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_adam_step: buffers not 16-byte aligned");
+  if (!ws || ws_bytes < rslx_adam_workspace_bytes(n)) return fail(RSLX_ERR_WORKSPACE, "rslx_adam_step: workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  const int nb = reduce_num_blocks(n);
+  double* sumsq = c.take<double>(nb);
+  RSLX_HIP(launch_sumsq(grads, n, sumsq, s));
+  const int64_t t = *adam_step + 1;
+  AdamArgs a;
+  memset(&a, 0, sizeof a);
+  a.seg[0] = AdamSegment{params, grads, m, v, n};
+  a.n_seg = 1;
+  a.sumsq_blocks = sumsq; a.n_sumsq = nb;
+  a.max_grad_norm = max_grad_norm;
+  a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps;
+  a.bc1 = bias_correction(beta1, t); a.bc2 = bias_correction(beta2, t);
+  a.grad_norm_out = grad_norm_out;
+  RSLX_HIP(launch_adam(a, s));
+  *adam_step = t;
+  return RSLX_OK;
+}
+
+// ---- PPO update ------------------------------------------------------------------------------------------------
+namespace {
+
+struct TrainBufs {        // per trained network
+  NetBufs act;
+  float* d_out = nullptr;
+  float* partials = nullptr;
+  int64_t stride = 0;
+  double* sumsq = nullptr;
+  int n_sumsq = 0;
+};
+
+struct PpoPlan {
+  int32_t B, mb, rows, n_split;
+  int32_t* perms = nullptr;          // [E, B]
+  void* perm_ws = nullptr;
+  TrainBufs actor, critic, pred;
+  NetBufs targ;
+  double* sumsq_all = nullptr;       // actor blocks, critic blocks, log_std slot
+  double* loss_partials = nullptr;
+  double* mse_partials = nullptr;
+  size_t bytes = 0;
+};
+
+void carve_train(Carver& c, const rslx_mlp& n, int64_t rows, int n_split, TrainBufs& t) {
+  carve_net(c, n, rows, true, t.act);
+  t.d_out = c.take<float>((size_t)rows * n.dims[n.n_layers]);
+  t.stride = round4(param_count(n));
+  t.partials = c.take<float>((size_t)t.stride * n_split);
+  t.n_sumsq = reduce_num_blocks(weight_count(n));
+}
+
+void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
+              const rslx_sym* sym, const rslx_rnd_train* rnd, PpoPlan& p) {
+  p.B = ro->T * ro->N;
+  p.mb = p.B / cfg->minibatches;
+  p.rows = sym ? 2 * p.mb : p.mb;
+  p.n_split = choose_split(p.rows);
+  p.perms = c.take<int32_t>((size_t)cfg->epochs * p.B);
+  p.perm_ws = c.take<char>(perm_workspace_bytes(p.B));
+  carve_train(c, *actor, p.rows, p.n_split, p.actor);
+  carve_train(c, *critic, p.rows, p.n_split, p.critic);
+  p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 1);
+  p.actor.sumsq = p.sumsq_all;
+  p.critic.sumsq = p.sumsq_all + p.actor.n_sumsq;
+  p.loss_partials = c.take<double>((size_t)ppo_loss_num_blocks(p.mb) * (PPO_NPART_FIXED + ro->A));
+  if (rnd) {
+    carve_train(c, *rnd->predictor, p.mb, choose_split(p.mb), p.pred);
+    p.pred.sumsq = c.take<double>(p.pred.n_sumsq);
+    carve_net(c, *rnd->target, p.mb, false, p.targ);
+    const int K = rnd->target->dims[rnd->target->n_layers];
+    p.mse_partials = c.take<double>(mse_num_blocks((int64_t)p.mb * K));
+  }
+  p.bytes = c.off + 256;
+}
+
+int32_t ppo_validate(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
+                     const rslx_sym* sym, const rslx_rnd_train* rnd, bool need_buffers) {
+  if (!ro || !cfg) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null rollout or cfg");
+  RSLX_TRY(check_mlp(actor, "rslx_ppo_update actor", need_buffers));
+  RSLX_TRY(check_mlp(critic, "rslx_ppo_update critic", need_buffers));
+  if (!actor->has_log_std) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: actor needs log_std");
+  if (ro->T < 1 || ro->N < 1 || (int64_t)ro->T * ro->N > (1 << 30)) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: T = %d, N = %d", ro->T, ro->N);
+  if (ro->Da != actor->dims[0] || ro->Dc != critic->dims[0] || ro->A != actor->dims[actor->n_layers] ||
+      critic->dims[critic->n_layers] != 1)
+    return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: rollout widths do not match the networks");
+  if (ro->A > 32) return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update: action width %d > 32", ro->A);
+  if (cfg->epochs < 0 || cfg->minibatches < 1) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: epochs / minibatches");
+  if ((ro->T * ro->N) % cfg->minibatches != 0)
+    return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: T*N = %d is not a multiple of minibatches = %d", ro->T * ro->N, cfg->minibatches);
+  if (need_buffers) {
+    if (!ro->obs_actor || !ro->obs_critic || !ro->actions || !ro->logp || !ro->values || !ro->mu || !ro->sigma ||
+        !ro->advantages || !ro->returns)
+      return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null rollout buffer");
+  }
+  if (sym) {
+    if (!involution_ok(sym->perm_obs_a_host, sym->sign_obs_a_host, ro->Da) ||
+        !involution_ok(sym->perm_obs_c_host, sym->sign_obs_c_host, ro->Dc) ||
+        !involution_ok(sym->perm_act_host, sym->sign_act_host, ro->A))
+      return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: mirror map is not an involutive signed permutation");
+    if (need_buffers && (!sym->perm_obs_a || !sym->sign_obs_a || !sym->perm_obs_c || !sym->sign_obs_c || !sym->perm_act || !sym->sign_act))
+      return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null device mirror map");
+  }
+  if (rnd) {
+    RSLX_TRY(check_mlp(rnd->target, "rslx_ppo_update rnd target", false));
+    RSLX_TRY(check_mlp(rnd->predictor, "rslx_ppo_update rnd predictor", need_buffers));
+    if (rnd->target->n_layers != rnd->predictor->n_layers) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: rnd nets differ in depth");
+    for (int i = 0; i <= rnd->target->n_layers; ++i)
+      if (rnd->target->dims[i] != rnd->predictor->dims[i]) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: rnd nets differ in shape");
+    if (rnd->n_subset != rnd->target->dims[0] || (!rnd->subset_idx && rnd->n_subset != ro->Da))
+      return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: rnd subset width");
+    if (need_buffers && !rnd->adam_step) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: rnd adam_step null");
+  }
+  return RSLX_OK;
+}
+
+// reduce split partials of one network into grads (weights and biases only) + squared-norm blocks
+int32_t reduce_net(const rslx_mlp& n, const TrainBufs& t, int n_split, hipStream_t s) {
+  RSLX_HIP(launch_reduce_partials(t.partials, n_split, t.stride, weight_count(n), n.grads, t.sumsq, s));
+  return RSLX_OK;
+}
+
+}  // namespace
+
+size_t rslx_ppo_update_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_rollout* ro,
+                                       const rslx_ppo_cfg* cfg, const rslx_sym* sym, const rslx_rnd_train* rnd) {
+  if (ppo_validate(actor, critic, ro, cfg, sym, rnd, false) != RSLX_OK) return 0;
+  Carver c(nullptr);
+  PpoPlan p;
+  ppo_plan(c, actor, critic, ro, cfg, sym, rnd, p);
+  return p.bytes;
+}
+
+int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
+                        const rslx_sym* sym, const rslx_rnd_train* rnd, int64_t* adam_step, float* stats, void* ws,
+                        size_t ws_bytes, void* stream) {
+  RSLX_TRY(ppo_validate(actor, critic, ro, cfg, sym, rnd, true));
+  if (!adam_step || !stats) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null adam_step or stats");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  PpoPlan p;
+  ppo_plan(c, actor, critic, ro, cfg, sym, rnd, p);
+  if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_ppo_update: workspace %zu < %zu bytes", ws_bytes, p.bytes);
+  const int A = ro->A, L_a = actor->n_layers, L_c = critic->n_layers;
+
+  for (int e = 0; e < cfg->epochs; ++e) {
+    const uint64_t base = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
+    RSLX_HIP(launch_permutation(base, p.B, p.perms + (size_t)e * p.B, p.perm_ws, s));
+  }
+
+  for (int e = 0; e < cfg->epochs; ++e) {
+    for (int m = 0; m < cfg->minibatches; ++m) {
+      const int32_t* idx = p.perms + (size_t)e * p.B + (size_t)m * p.mb;
+      float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
+
+      XView xa, xc;
+      xa.base = ro->obs_actor; xa.ld = ro->Da; xa.row_idx = idx;
+      xc.base = ro->obs_critic; xc.ld = ro->Dc; xc.row_idx = idx;
+      if (sym) {
+        xa.idx_mod = xc.idx_mod = p.mb;
+        xa.map_from = xc.map_from = p.mb;
+        xa.col_map = sym->perm_obs_a; xa.col_sign = sym->sign_obs_a;
+        xc.col_map = sym->perm_obs_c; xc.col_sign = sym->sign_obs_c;
+      }
+      NetJob fj[2] = {NetJob{actor, xa, p.rows, &p.actor.act}, NetJob{critic, xc, p.rows, &p.critic.act}};
+      RSLX_TRY(forward_nets(fj, 2, s));
+
+      PpoLossArgs la;
+      memset(&la, 0, sizeof la);
+      la.mu = p.actor.act.out[L_a - 1];
+      la.v = p.critic.act.out[L_c - 1];
+      la.log_std = actor->params + weight_count(*actor);
+      la.idx = idx;
+      la.actions = ro->actions; la.logp_old = ro->logp; la.adv = ro->advantages; la.returns = ro->returns;
+      la.v_old = ro->values; la.mu_old = ro->mu; la.sigma_old = ro->sigma;
+      la.perm_act = sym ? sym->perm_act : nullptr;
+      la.sign_act = sym ? sym->sign_act : nullptr;
+      la.mb = p.mb; la.rows = p.rows; la.A = A;
+      la.clip = cfg->clip; la.value_coef = cfg->value_coef; la.entropy_coef = cfg->entropy_coef;
+      la.mirror_coef = sym ? sym->mirror_loss_coef : 0.f;
+      la.clipped_value = cfg->use_clipped_value_loss;
+      la.d_mu = p.actor.d_out; la.d_v = p.critic.d_out;
+      la.partials = p.loss_partials;
+      RSLX_HIP(launch_ppo_loss(la, s));
+      RSLX_HIP(launch_ppo_loss_finish(p.loss_partials, ppo_loss_num_blocks(p.mb), p.rows, p.mb, A, la.log_std,
+                                      cfg->entropy_coef, actor->grads + weight_count(*actor), stats_row,
+                                      p.sumsq_all + p.actor.n_sumsq + p.critic.n_sumsq, s));
+
+      BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.partials, p.actor.stride},
+                      BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.partials, p.critic.stride}};
+      RSLX_TRY(backward_nets(bj, 2, p.n_split, s));
+      RSLX_TRY(reduce_net(*actor, p.actor, p.n_split, s));
+      RSLX_TRY(reduce_net(*critic, p.critic, p.n_split, s));
+
+      const int64_t t = *adam_step + 1;
+      AdamArgs aa;
+      memset(&aa, 0, sizeof aa);
+      aa.seg[0] = AdamSegment{actor->params, actor->grads, actor->adam_m, actor->adam_v, param_count(*actor)};
+      aa.seg[1] = AdamSegment{critic->params, critic->grads, critic->adam_m, critic->adam_v, param_count(*critic)};
+      aa.n_seg = 2;
+      aa.sumsq_blocks = p.sumsq_all; aa.n_sumsq = p.actor.n_sumsq + p.critic.n_sumsq + 1;
+      aa.max_grad_norm = cfg->max_grad_norm;
+      aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;
+      aa.bc1 = bias_correction(cfg->beta1, t); aa.bc2 = bias_correction(cfg->beta2, t);
+      aa.grad_norm_out = stats_row + RSLX_STAT_GRAD_NORM;
+      RSLX_HIP(launch_adam(aa, s));
+      *adam_step = t;
+
+      if (rnd) {
+        const rslx_mlp& pr = *rnd->predictor;
+        const int K = pr.dims[pr.n_layers];
+        XView xr;
+        xr.base = ro->obs_actor; xr.ld = ro->Da; xr.row_idx = idx;
+        if (rnd->subset_idx) { xr.col_map = rnd->subset_idx; xr.map_from = 0; }
+        NetJob rj[2] = {NetJob{&pr, xr, p.mb, &p.pred.act}, NetJob{rnd->target, xr, p.mb, &p.targ}};
+        RSLX_TRY(forward_nets(rj, 2, s));
+        const int nbm = mse_num_blocks((int64_t)p.mb * K);
+        RSLX_HIP(launch_mse(p.pred.act.out[pr.n_layers - 1], p.targ.out[pr.n_layers - 1], nullptr, p.mb, K,
+                            p.pred.d_out, p.mse_partials, s));
+        RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)p.mb * K, stats_row + RSLX_STAT_RND_LOSS, s));
+        const int ns = choose_split(p.mb);
+        BwdJob rb{&pr, xr, p.mb, &p.pred.act, p.pred.d_out, p.pred.partials, p.pred.stride};
+        RSLX_TRY(backward_nets(&rb, 1, ns, s));
+        RSLX_TRY(reduce_net(pr, p.pred, ns, s));
+        const int64_t tr = *rnd->adam_step + 1;
+        AdamArgs ar;
+        memset(&ar, 0, sizeof ar);
+        ar.seg[0] = AdamSegment{pr.params, pr.grads, pr.adam_m, pr.adam_v, param_count(pr)};
+        ar.n_seg = 1;
+        ar.sumsq_blocks = p.pred.sumsq; ar.n_sumsq = 0;
+        ar.max_grad_norm = 0.f;
+        ar.lr = rnd->lr; ar.beta1 = cfg->beta1; ar.beta2 = cfg->beta2; ar.eps = cfg->adam_eps;
+        ar.bc1 = bias_correction(cfg->beta1, tr); ar.bc2 = bias_correction(cfg->beta2, tr);
+        RSLX_HIP(launch_adam(ar, s));
+        *rnd->adam_step = tr;
+      }
+    }
+  }
+  return RSLX_OK;
+}
+
+// ---- behaviour cloning ---------------------------------------------------------------------------------------------
+namespace {
+struct BcPlan {
+  int32_t mb, n_split;
+  int32_t* perms = nullptr;
+  void* perm_ws = nullptr;
+  TrainBufs student;
+  NetBufs teacher;
+  float* targets = nullptr;
+  double* mse_partials = nullptr;
+  size_t bytes = 0;
+};
+
+void bc_plan(Carver& c, const rslx_mlp* student, const rslx_mlp* teacher, int32_t B, const rslx_bc_cfg* cfg, BcPlan& p) {
+  p.mb = B / cfg->minibatches;
+  p.n_split = choose_split(p.mb);
+  p.perms = c.take<int32_t>((size_t)cfg->epochs * B);
+  p.perm_ws = c.take<char>(perm_workspace_bytes(B));
+  carve_train(c, *student, p.mb, p.n_split, p.student);
+  p.student.sumsq = c.take<double>(p.student.n_sumsq);
+  const int A = student->dims[student->n_layers];
+  if (teacher) {
+    carve_net(c, *teacher, p.mb, false, p.teacher);
+    p.targets = c.take<float>((size_t)B * A);
+  }
+  p.mse_partials = c.take<double>(mse_num_blocks((int64_t)p.mb * A));
+  p.bytes = c.off + 256;
+}
+
+int32_t bc_validate(const rslx_mlp* student, const rslx_mlp* teacher, int32_t B, const rslx_bc_cfg* cfg, bool need_buffers) {
+  if (!cfg) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: null cfg");
+  RSLX_TRY(check_mlp(student, "rslx_bc_update student", need_buffers));
+  if (teacher) {
+    RSLX_TRY(check_mlp(teacher, "rslx_bc_update teacher", false));
+    if (teacher->dims[teacher->n_layers] != student->dims[student->n_layers])
+      return fail(RSLX_ERR_SHAPE, "rslx_bc_update: teacher and student action widths differ");
+  }
+  if (B < 1 || cfg->minibatches < 1 || cfg->epochs < 0 || B % cfg->minibatches != 0)
+    return fail(RSLX_ERR_SHAPE, "rslx_bc_update: B = %d is not a positive multiple of minibatches = %d", B, cfg->minibatches);
+  return RSLX_OK;
+}
+}  // namespace
+
+size_t rslx_bc_update_workspace_bytes(const rslx_mlp* student, const rslx_mlp* teacher, int32_t B, const rslx_bc_cfg* cfg) {
+  if (bc_validate(student, teacher, B, cfg, false) != RSLX_OK) return 0;
+  Carver c(nullptr);
+  BcPlan p;
+  bc_plan(c, student, teacher, B, cfg, p);
+  return p.bytes;
+}
+
+int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student, const float* obs_teacher,
+                       const float* targets_or_null, int32_t B, const rslx_bc_cfg* cfg, int64_t* adam_step, float* stats,
+                       void* ws, size_t ws_bytes, void* stream) {
+  const rslx_mlp* tch = targets_or_null ? nullptr : teacher;
+  if (!targets_or_null && !teacher) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: need a teacher or precomputed targets");
+  RSLX_TRY(bc_validate(student, tch, B, cfg, true));
+  if (!obs_student || !adam_step || !stats) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: null pointer");
+  if (tch && !obs_teacher) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: null teacher observations");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  BcPlan p;
+  bc_plan(c, student, tch, B, cfg, p);
+  if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_bc_update: workspace %zu < %zu bytes", ws_bytes, p.bytes);
+  const int A = student->dims[student->n_layers];
+  const int Ls = student->n_layers;
+
+  const float* targets = targets_or_null;
+  if (tch) {                           // teacher means for every row, one minibatch-sized slab at a time
+    for (int k = 0; k < cfg->minibatches; ++k) {
+      NetBufs tb = p.teacher;
+      tb.out[tch->n_layers - 1] = p.targets + (size_t)k * p.mb * A;
+      XView xt; xt.base = obs_teacher + (size_t)k * p.mb * tch->dims[0]; xt.ld = tch->dims[0];
+      NetJob j{tch, xt, p.mb, &tb};
+      RSLX_TRY(forward_nets(&j, 1, s));
+    }
+    targets = p.targets;
+  }
+  for (int e = 0; e < cfg->epochs; ++e) {
+    const uint64_t base = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
+    RSLX_HIP(launch_permutation(base, B, p.perms + (size_t)e * B, p.perm_ws, s));
+  }
+  const int nbm = mse_num_blocks((int64_t)p.mb * A);
+  for (int e = 0; e < cfg->epochs; ++e) {
+    for (int m = 0; m < cfg->minibatches; ++m) {
+      const int32_t* idx = p.perms + (size_t)e * B + (size_t)m * p.mb;
+      float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
+      RSLX_HIP(launch_fill(stats_row, RSLX_NSTATS, 0.f, s));
+      XView xs; xs.base = obs_student; xs.ld = student->dims[0]; xs.row_idx = idx;
+      NetJob fj{student, xs, p.mb, &p.student.act};
+      RSLX_TRY(forward_nets(&fj, 1, s));
+      RSLX_HIP(launch_mse(p.student.act.out[Ls - 1], targets, idx, p.mb, A, p.student.d_out, p.mse_partials, s));
+      RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)p.mb * A, stats_row, s));
+      BwdJob bj{student, xs, p.mb, &p.student.act, p.student.d_out, p.student.partials, p.student.stride};
+      RSLX_TRY(backward_nets(&bj, 1, p.n_split, s));
+      RSLX_TRY(reduce_net(*student, p.student, p.n_split, s));
+      const int64_t t = *adam_step + 1;
+      AdamArgs aa;
+      memset(&aa, 0, sizeof aa);
+      aa.seg[0] = AdamSegment{student->params, student->grads, student->adam_m, student->adam_v, weight_count(*student)};
+      aa.n_seg = 1;
+      aa.sumsq_blocks = p.student.sumsq; aa.n_sumsq = p.student.n_sumsq;
+      aa.max_grad_norm = cfg->max_grad_norm;
+      aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;
+      aa.bc1 = bias_correction(cfg->beta1, t); aa.bc2 = bias_correction(cfg->beta2, t);
+      aa.grad_norm_out = stats_row + RSLX_STAT_GRAD_NORM;
+      RSLX_HIP(launch_adam(aa, s));
+      *adam_step = t;
+    }
+  }
+  return RSLX_OK;
+}
+
+// ---- symmetry augmentation ---------------------------------------------------------------------------------------------
+int32_t rslx_sym_augment(const rslx_sym* sym, const float* obs_in, const float* act_in, int32_t B, int32_t D, int32_t A,
+                         float* obs_out, float* act_out, void* stream) {
+  if (!sym) return fail(RSLX_ERR_INVALID_ARG, "rslx_sym_augment: null sym");
+  if (B < 0 || D < 0 || A < 0) return fail(RSLX_ERR_SHAPE, "rslx_sym_augment: negative size");
+  hipStream_t s = (hipStream_t)stream;
+  if (obs_in) {
+    if (!involution_ok(sym->perm_obs_a_host, sym->sign_obs_a_host, D))
+      return fail(RSLX_ERR_INVALID_ARG, "rslx_sym_augment: observation map is not an involutive signed permutation");
+    if (!obs_out || !sym->perm_obs_a || !sym->sign_obs_a) return fail(RSLX_ERR_INVALID_ARG, "rslx_sym_augment: null pointer");
+  }
+  if (act_in) {
+    if (!involution_ok(sym->perm_act_host, sym->sign_act_host, A))
+      return fail(RSLX_ERR_INVALID_ARG, "rslx_sym_augment: action map is not an involutive signed permutation");
+    if (!act_out || !sym->perm_act || !sym->sign_act) return fail(RSLX_ERR_INVALID_ARG, "rslx_sym_augment: null pointer");
+  }
+  if (obs_in) RSLX_HIP(launch_sym_augment(obs_in, B, D, sym->perm_obs_a, sym->sign_obs_a, obs_out, s));
+  if (act_in) RSLX_HIP(launch_sym_augment(act_in, B, A, sym->perm_act, sym->sign_act, act_out, s));
+  return RSLX_OK;
+}
+
+// ---- RND reward -----------------------------------------------------------------------------------------------------
+static size_t rnd_carve(Carver& c, const rslx_mlp* net, int32_t N, NetBufs* bp, NetBufs* bt, double** partials) {
+  NetBufs p, t;
+  carve_net(c, *net, N, false, p);
+  carve_net(c, *net, N, false, t);
+  double* pp = c.take<double>((size_t)rnd_num_blocks(N) * 2 + 2);
+  if (bp) *bp = p;
+  if (bt) *bt = t;
+  if (partials) *partials = pp;
+  return c.off + 256;
+}
+
+size_t rslx_rnd_workspace_bytes(const rslx_mlp* target, int32_t N) {
+  if (!target || N <= 0 || target->n_layers < 1 || target->n_layers > RSLX_MAX_LAYERS) return 256;
+  Carver c(nullptr);
+  return rnd_carve(c, target, N, nullptr, nullptr, nullptr);
+}
+
+int32_t rslx_rnd(const rslx_mlp* target, const rslx_mlp* predictor, const float* obs, int32_t N, int32_t D,
+                 const int32_t* subset_idx_or_null, int32_t n_subset, float* running, float weight, int32_t update_stats,
+                 float* r_int_out, float* rewards_inout_or_null, void* ws, size_t ws_bytes, void* stream) {
+  RSLX_TRY(check_mlp(target, "rslx_rnd target", false));
+  RSLX_TRY(check_mlp(predictor, "rslx_rnd predictor", false));
+  if (target->n_layers != predictor->n_layers) return fail(RSLX_ERR_SHAPE, "rslx_rnd: networks differ in depth");
+  for (int i = 0; i <= target->n_layers; ++i)
+    if (target->dims[i] != predictor->dims[i]) return fail(RSLX_ERR_SHAPE, "rslx_rnd: networks differ in shape");
+  if (N < 0 || D < 1) return fail(RSLX_ERR_SHAPE, "rslx_rnd: N = %d, D = %d", N, D);
+  if (n_subset != target->dims[0] || (!subset_idx_or_null && n_subset != D)) return fail(RSLX_ERR_SHAPE, "rslx_rnd: subset width");
+  if (!obs || !running || !r_int_out) return fail(RSLX_ERR_INVALID_ARG, "rslx_rnd: null pointer");
+  if (N == 0) return RSLX_OK;
+  if (!ws || ws_bytes < rslx_rnd_workspace_bytes(target, N)) return fail(RSLX_ERR_WORKSPACE, "rslx_rnd: workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  NetBufs bp, bt;
+  double* partials = nullptr;
+  rnd_carve(c, target, N, &bp, &bt, &partials);
+  XView x;
+  x.base = obs; x.ld = D;
+  if (subset_idx_or_null) { x.col_map = subset_idx_or_null; x.map_from = 0; }
+  NetJob jobs[2] = {NetJob{predictor, x, N, &bp}, NetJob{target, x, N, &bt}};
+  RSLX_TRY(forward_nets(jobs, 2, s));
+  const int L = target->n_layers;
+  RSLX_HIP(launch_rnd_reward(bp.out[L - 1], bt.out[L - 1], N, target->dims[L], running, weight, update_stats ? 1 : 0,
+                             r_int_out, rewards_inout_or_null, partials, s));
+  return RSLX_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,734 @@
+// Streaming, reduction and bookkeeping kernels of librslx for gfx950: GAE reverse scan, advantage
+// normalisation, minibatch permutation (hash keys + bucket sort), split-K gradient reduction with the
+// squared-norm, fused clip + Adam, Gaussian policy head, PPO loss head, MSE head, mirror augmentation,
+// RND reward normalisation.  Wavefronts are 64 lanes wide throughout.
+#include "kernels.h"
+
+namespace rslx {
+
+constexpr int WAVE = 64;
+
+// ---- reductions -----------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
+  return v;
+}
+
+// Sum over the workgroup; result valid in thread 0.  `smem` holds one double per wavefront.
+__device__ __forceinline__ double block_sum(double v, double* smem) {
+  const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+  const int nw = (blockDim.x + WAVE - 1) / WAVE;
+  v = wave_sum(v);
+  __syncthreads();
+  if (lane == 0) smem[w] = v;
+  __syncthreads();
+  double t = 0.0;
+  if (threadIdx.x == 0)
+    for (int i = 0; i < nw; ++i) t += smem[i];
+  return t;
+}
+
+__global__ void fill_kernel(float* p, long n, float value) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
+hipError_t launch_fill(float* p, int64_t n, float value, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, (long)n, value);
+  return hipGetLastError();
+}
+
+// ---- GAE ----------------------------------------------------------------------------------------------
+// One lane per environment column: loads are coalesced across n, the T-step recurrence runs in registers.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void gae_scan_kernel(const float* __restrict__ rewards, const float* __restrict__ values,
+                                                         const float* __restrict__ last_values,
+                                                         const uint8_t* __restrict__ dones,
+                                                         const uint8_t* __restrict__ timeouts, int T, int N, float gamma,
+                                                         float lam, float* __restrict__ adv, float* __restrict__ ret,
+                                                         double* __restrict__ partials) {
+  __shared__ double smem[BLOCK / WAVE];
+  const int n = blockIdx.x * BLOCK + threadIdx.x;
+  double s = 0.0, q = 0.0;
+  if (n < N) {
+    float a_next = 0.f;
+    float v_next = last_values[n];
+    const float gl = gamma * lam;
+#pragma unroll 8
+    for (int t = T - 1; t >= 0; --t) {
+      const long o = (long)t * N + n;
+      float r = rewards[o];
+      const float v = values[o];
+      const float nd = dones[o] ? 0.f : 1.f;
+      if (timeouts != nullptr && timeouts[o]) r += gamma * v;
+      const float delta = r + gamma * nd * v_next - v;
+      a_next = delta + gl * nd * a_next;
+      adv[o] = a_next;
+      ret[o] = a_next + v;
+      s += (double)a_next;
+      q += (double)a_next * (double)a_next;
+      v_next = v;
+    }
+  }
+  if (partials != nullptr) {
+    double ts = block_sum(s, smem);
+    double tq = block_sum(q, smem);
+    if (threadIdx.x == 0) {
+      partials[2 * blockIdx.x] = ts;
+      partials[2 * blockIdx.x + 1] = tq;
+    }
+  }
+}
+
+// Single workgroup: total sum / sum of squares -> mean and 1 / (std + 1e-8), unbiased std.
+__global__ __launch_bounds__(256) void adv_stats_kernel(const double* __restrict__ partials, int nblocks, long count,
+                                                        float* __restrict__ mean_inv) {
+  __shared__ double smem[4];
+  double s = 0.0, q = 0.0;
+  for (int i = threadIdx.x; i < nblocks; i += 256) {
+    s += partials[2 * i];
+    q += partials[2 * i + 1];
+  }
+  double ts = block_sum(s, smem);
+  double tq = block_sum(q, smem);
+  if (threadIdx.x == 0) {
+    double mean = ts / (double)count;
+    double var = count > 1 ? (tq - ts * mean) / (double)(count - 1) : 0.0;
+    if (var < 0.0) var = 0.0;
+    mean_inv[0] = (float)mean;
+    mean_inv[1] = (float)(1.0 / (sqrt(var) + 1e-8));
+  }
+}
+
+__global__ __launch_bounds__(256) void adv_normalize_kernel(float* __restrict__ adv, long count,
+                                                            const float* __restrict__ mean_inv) {
+  const float mean = mean_inv[0], inv = mean_inv[1];
+  long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i + 3 < count) {
+    float4 v = *reinterpret_cast<float4*>(adv + i);
+    v.x = (v.x - mean) * inv; v.y = (v.y - mean) * inv; v.z = (v.z - mean) * inv; v.w = (v.w - mean) * inv;
+    *reinterpret_cast<float4*>(adv + i) = v;
+  } else {
+    for (; i < count; ++i) adv[i] = (adv[i] - mean) * inv;
+  }
+}
+
+static int gae_block(int32_t N) { return N >= 65536 ? 256 : 64; }
+int gae_num_blocks(int32_t N) { int b = gae_block(N); return (N + b - 1) / b; }
+
+hipError_t launch_gae(const float* rewards, const float* values, const float* last_values, const uint8_t* dones,
+                      const uint8_t* timeouts, int32_t T, int32_t N, float gamma, float lam, int32_t normalize,
+                      float* adv, float* ret, double* partials, hipStream_t stream) {
+  const int nb = gae_num_blocks(N);
+  double* part = normalize ? partials : nullptr;
+  if (gae_block(N) == 256)
+    hipLaunchKernelGGL((gae_scan_kernel<256>), dim3(nb), dim3(256), 0, stream, rewards, values, last_values, dones,
+                       timeouts, T, N, gamma, lam, adv, ret, part);
+  else
+    hipLaunchKernelGGL((gae_scan_kernel<64>), dim3(nb), dim3(64), 0, stream, rewards, values, last_values, dones,
+                       timeouts, T, N, gamma, lam, adv, ret, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !normalize) return e;
+  const long count = (long)T * N;
+  float* mean_inv = reinterpret_cast<float*>(partials + 2 * (size_t)nb);
+  hipLaunchKernelGGL(adv_stats_kernel, dim3(1), dim3(256), 0, stream, partials, nb, count, mean_inv);
+  const unsigned blocks = (unsigned)((count + 1023) / 1024);
+  hipLaunchKernelGGL(adv_normalize_kernel, dim3(blocks), dim3(256), 0, stream, adv, count, mean_inv);
+  return hipGetLastError();
+}
+
+// ---- permutation ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+// Keys are uniform 64-bit hashes, so their top bits spread the B items evenly over nb buckets
+// (about 32 per bucket).  Bucket membership is order independent; the order inside a bucket is then
+// fixed by ranking on (key, index), which makes the result independent of atomic scheduling.
+struct PermPlan {
+  int32_t nb;      // buckets (power of two)
+  int32_t shift;   // key >> shift = bucket
+};
+static PermPlan perm_plan(int32_t B) {
+  PermPlan p;
+  int lg = 0;
+  while ((1 << (lg + 1)) * 32 <= B && lg < 24) ++lg;
+  p.nb = 1 << lg;
+  p.shift = 64 - lg;
+  return p;
+}
+__device__ __forceinline__ int bucket_of(uint64_t key, int shift) { return shift >= 64 ? 0 : (int)(key >> shift); }
+
+__global__ void perm_zero_kernel(int* counts, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) counts[i] = 0;
+}
+__global__ void perm_hist_kernel(uint64_t base, int B, int shift, int* counts) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B) atomicAdd(&counts[bucket_of(mix64(base ^ (uint64_t)i), shift)], 1);
+}
+// Exclusive scan of counts[0..nb) by one workgroup; offsets has nb + 1 entries; cursors are reset.
+__global__ __launch_bounds__(1024) void perm_scan_kernel(const int* counts, int nb, int* offsets, int* cursor) {
+  __shared__ int wsum[16];
+  __shared__ int carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int base = 0; base < nb; base += 1024) {
+    int i = base + threadIdx.x;
+    int c = i < nb ? counts[i] : 0;
+    int x = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int y = __shfl_up(x, o, 64);
+      if (lane >= o) x += y;
+    }
+    if (lane == 63) wsum[w] = x;
+    __syncthreads();
+    int before = 0;
+    for (int k = 0; k < w; ++k) before += wsum[k];
+    int excl = carry + before + x - c;
+    if (i < nb) {
+      offsets[i] = excl;
+      cursor[i] = 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 1023) carry = excl + c;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) offsets[nb] = carry;
+}
+__global__ void perm_scatter_kernel(uint64_t base, int B, int shift, const int* offsets, int* cursor, uint64_t* keys,
+                                    int* idx) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B) return;
+  uint64_t k = mix64(base ^ (uint64_t)i);
+  int b = bucket_of(k, shift);
+  int pos = offsets[b] + atomicAdd(&cursor[b], 1);
+  keys[pos] = k;
+  idx[pos] = i;
+}
+__global__ void perm_rank_kernel(int B, int shift, const int* offsets, const uint64_t* keys, const int* idx, int* perm) {
+  int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= B) return;
+  const uint64_t k = keys[e];
+  const int i = idx[e];
+  const int b = bucket_of(k, shift);
+  const int s = offsets[b], t = offsets[b + 1];
+  int rank = 0;
+  for (int o = s; o < t; ++o) {
+    uint64_t ko = keys[o];
+    rank += (ko < k || (ko == k && idx[o] < i)) ? 1 : 0;
+  }
+  perm[s + rank] = i;
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t perm_workspace_bytes(int32_t B) {
+  PermPlan p = perm_plan(B);
+  return align_up((size_t)(p.nb + 1) * 4, 256) * 3 + align_up((size_t)B * 8, 256) + align_up((size_t)B * 4, 256);
+}
+
+hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, void* ws, hipStream_t stream) {
+  if (B <= 0) return hipSuccess;
+  PermPlan p = perm_plan(B);
+  char* w = static_cast<char*>(ws);
+  const size_t seg = align_up((size_t)(p.nb + 1) * 4, 256);
+  int* counts = reinterpret_cast<int*>(w);
+  int* offsets = reinterpret_cast<int*>(w + seg);
+  int* cursor = reinterpret_cast<int*>(w + 2 * seg);
+  uint64_t* keys = reinterpret_cast<uint64_t*>(w + 3 * seg);
+  int* idx = reinterpret_cast<int*>(w + 3 * seg + align_up((size_t)B * 8, 256));
+  const unsigned gb = (unsigned)((B + 255) / 256);
+  hipLaunchKernelGGL(perm_zero_kernel, dim3((p.nb + 256) / 256), dim3(256), 0, stream, counts, p.nb + 1);
+  hipLaunchKernelGGL(perm_hist_kernel, dim3(gb), dim3(256), 0, stream, base_key, B, p.shift, counts);
+  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, p.nb, offsets, cursor);
+  hipLaunchKernelGGL(perm_scatter_kernel, dim3(gb), dim3(256), 0, stream, base_key, B, p.shift, offsets, cursor, keys, idx);
+  hipLaunchKernelGGL(perm_rank_kernel, dim3(gb), dim3(256), 0, stream, B, p.shift, offsets, keys, idx, perm_out);
+  return hipGetLastError();
+}
+
+// ---- split-K reduction + squared norm ---------------------------------------------------------------
+constexpr int RED_PER_BLOCK = 1024;  // floats per workgroup
+int reduce_num_blocks(int64_t n) { return (int)((n + RED_PER_BLOCK - 1) / RED_PER_BLOCK); }
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partials, int n_split,
+                                                              long split_stride, long n, float* __restrict__ grads,
+                                                              double* __restrict__ sumsq_blocks) {
+  __shared__ double smem[4];
+  const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  double q = 0.0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const long i = i0 + c;
+    if (i < n) {
+      float s = 0.f;
+      for (int k = 0; k < n_split; ++k) s += partials[(long)k * split_stride + i];
+      grads[i] = s;
+      q += (double)s * (double)s;
+    }
+  }
+  double t = block_sum(q, smem);
+  if (threadIdx.x == 0) sumsq_blocks[blockIdx.x] = t;
+}
+
+hipError_t launch_reduce_partials(const float* partials, int32_t n_split, int64_t split_stride, int64_t n, float* grads,
+                                  double* sumsq_blocks, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(reduce_num_blocks(n)), dim3(256), 0, stream, partials, n_split,
+                     (long)split_stride, (long)n, grads, sumsq_blocks);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void sumsq_kernel(const float* __restrict__ g, long n, double* __restrict__ out) {
+  __shared__ double smem[4];
+  const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  double q = 0.0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    if (i0 + c < n) q += (double)g[i0 + c] * (double)g[i0 + c];
+  double t = block_sum(q, smem);
+  if (threadIdx.x == 0) out[blockIdx.x] = t;
+}
+
+hipError_t launch_sumsq(const float* g, int64_t n, double* sumsq_blocks, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sumsq_kernel, dim3(reduce_num_blocks(n)), dim3(256), 0, stream, g, (long)n, sumsq_blocks);
+  return hipGetLastError();
+}
+
+// ---- fused clip + Adam ------------------------------------------------------------------------------
+// Every workgroup re-reduces the (short) list of per-block squared norms in the same order, so the clip
+// scale is identical everywhere and no extra launch or atomic is needed.
+__global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
+  __shared__ double smem[4];
+  __shared__ float s_scale;
+  double q = 0.0;
+  for (int i = threadIdx.x; i < a.n_sumsq; i += 256) q += a.sumsq_blocks[i];
+  double tot = block_sum(q, smem);
+  if (threadIdx.x == 0) {
+    float norm = (float)sqrt(tot);
+    float s = 1.0f;
+    if (a.max_grad_norm > 0.f && a.max_grad_norm < 3.0e38f) s = fminf(1.0f, a.max_grad_norm / (norm + 1e-6f));
+    s_scale = s;
+    if (a.grad_norm_out != nullptr && blockIdx.x == 0 && blockIdx.y == 0) *a.grad_norm_out = norm;
+  }
+  __syncthreads();
+  const float scale = s_scale;
+  const AdamSegment& sg = a.seg[blockIdx.y];
+  const float ob1 = 1.0f - a.beta1, ob2 = 1.0f - a.beta2;
+  const float inv_bc1 = 1.0f / a.bc1, inv_bc2 = 1.0f / a.bc2;
+  const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i0 >= sg.n) return;
+  if (i0 + 3 < sg.n) {
+    float4 p = *reinterpret_cast<float4*>(sg.params + i0);
+    float4 g = *reinterpret_cast<const float4*>(sg.grads + i0);
+    float4 m = *reinterpret_cast<float4*>(sg.m + i0);
+    float4 v = *reinterpret_cast<float4*>(sg.v + i0);
+    float* pp = &p.x; float* gp = &g.x; float* mp = &m.x; float* vp = &v.x;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float gg = gp[c] * scale;
+      mp[c] = a.beta1 * mp[c] + ob1 * gg;
+      vp[c] = a.beta2 * vp[c] + ob2 * gg * gg;
+      pp[c] -= a.lr * (mp[c] * inv_bc1) / (sqrtf(vp[c] * inv_bc2) + a.eps);
+    }
+    *reinterpret_cast<float4*>(sg.params + i0) = p;
+    *reinterpret_cast<float4*>(sg.m + i0) = m;
+    *reinterpret_cast<float4*>(sg.v + i0) = v;
+  } else {
+    for (long i = i0; i < sg.n; ++i) {
+      const float gg = sg.grads[i] * scale;
+      const float m = a.beta1 * sg.m[i] + ob1 * gg;
+      const float v = a.beta2 * sg.v[i] + ob2 * gg * gg;
+      sg.m[i] = m;
+      sg.v[i] = v;
+      sg.params[i] -= a.lr * (m * inv_bc1) / (sqrtf(v * inv_bc2) + a.eps);
+    }
+  }
+}
+
+hipError_t launch_adam(const AdamArgs& a, hipStream_t stream) {
+  int64_t nmax = 0;
+  for (int i = 0; i < a.n_seg; ++i) nmax = a.seg[i].n > nmax ? a.seg[i].n : nmax;
+  if (nmax <= 0) return hipSuccess;
+  dim3 grid((unsigned)((nmax + 1023) / 1024), a.n_seg);
+  hipLaunchKernelGGL(adam_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ---- Gaussian head of act() -------------------------------------------------------------------------
+constexpr float LOG_2PI = 1.8378770664093453f;
+
+__global__ __launch_bounds__(256) void act_head_kernel(const float* __restrict__ mu_in, const float* __restrict__ log_std,
+                                                       const float* __restrict__ eps_in, uint64_t noise_base, int N,
+                                                       int A, int deterministic, float* __restrict__ actions,
+                                                       float* __restrict__ logp, float* __restrict__ mu_out,
+                                                       float* __restrict__ sigma_out) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float acc = 0.f, sum_ls = 0.f;
+  for (int jj = 0; jj < A; ++jj) {
+    const long o = (long)n * A + jj;
+    const float ls = log_std[jj];
+    const float sg = expf(ls);
+    const float mu = mu_in[o];
+    float e;
+    if (deterministic) {
+      e = 0.f;
+    } else if (eps_in != nullptr) {
+      e = eps_in[o];
+    } else {
+      const uint64_t h = mix64(noise_base ^ (uint64_t)o);
+      const float u1 = (float)((uint32_t)(h >> 40) + 1u) * 5.9604644775390625e-08f;   // 2^-24
+      const float u2 = (float)((uint32_t)(h >> 8) & 0xFFFFFFu) * 5.9604644775390625e-08f;
+      e = sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2);
+    }
+    const float act = mu + sg * e;
+    const float z = (act - mu) / sg;
+    acc += z * z;
+    sum_ls += ls;
+    actions[o] = act;
+    mu_out[o] = mu;
+    sigma_out[o] = sg;
+  }
+  logp[n] = -0.5f * acc - sum_ls - 0.5f * (float)A * LOG_2PI;
+}
+
+hipError_t launch_act_head(const float* mu_in, const float* log_std, const float* eps, uint64_t noise_base, int32_t N,
+                           int32_t A, int32_t deterministic, float* actions, float* logp, float* mu_out,
+                           float* sigma_out, hipStream_t stream) {
+  hipLaunchKernelGGL(act_head_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, mu_in, log_std, eps, noise_base, N, A,
+                     deterministic, actions, logp, mu_out, sigma_out);
+  return hipGetLastError();
+}
+
+__global__ void copy_kernel(const float* __restrict__ src, int n, float* __restrict__ dst) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+hipError_t launch_copy_column(const float* src, int32_t n, float* dst, hipStream_t stream) {
+  hipLaunchKernelGGL(copy_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, src, n, dst);
+  return hipGetLastError();
+}
+
+// ---- PPO loss head -------------------------------------------------------------------------------------
+// One lane per minibatch row i (and, with symmetry, its mirrored twin at row i + mb).
+constexpr int AMAX = 32;
+int ppo_loss_num_blocks(int32_t mb) { return (mb + 255) / 256; }
+
+struct RowTerms { float surr, vloss, clipped; };
+
+__device__ __forceinline__ RowTerms ppo_row(const PpoLossArgs& a, float logp_new, float logp_old, float adv, float v,
+                                            float v_old, float ret, float inv_rows, float* d_logp, float* d_v) {
+  RowTerms t;
+  const float ratio = expf(logp_new - logp_old);
+  const float rc = fminf(fmaxf(ratio, 1.0f - a.clip), 1.0f + a.clip);
+  const float s1 = -adv * ratio, s2 = -adv * rc;
+  t.surr = fmaxf(s1, s2);
+  *d_logp = (s1 >= s2 ? -adv : 0.f) * inv_rows * ratio;
+  t.clipped = fabsf(ratio - 1.0f) > a.clip ? 1.f : 0.f;
+  if (a.clipped_value) {
+    const float vc = v_old + fminf(fmaxf(v - v_old, -a.clip), a.clip);
+    const float e1 = (v - ret) * (v - ret), e2 = (vc - ret) * (vc - ret);
+    t.vloss = fmaxf(e1, e2);
+    *d_v = (e1 >= e2 ? 2.0f * (v - ret) : 0.f) * inv_rows * a.value_coef;
+  } else {
+    t.vloss = (ret - v) * (ret - v);
+    *d_v = 2.0f * (v - ret) * inv_rows * a.value_coef;
+  }
+  return t;
+}
+
+__global__ __launch_bounds__(256) void ppo_loss_kernel(const PpoLossArgs a) {
+  __shared__ double smem[4];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int A = a.A;
+  const bool sym = a.rows > a.mb;
+  const float inv_rows = 1.0f / (float)a.rows;
+  float surr = 0.f, vloss = 0.f, kl = 0.f, clipped = 0.f, mirror = 0.f;
+  float dls[AMAX];
+#pragma unroll
+  for (int jj = 0; jj < AMAX; ++jj) dls[jj] = 0.f;
+
+  if (i < a.mb) {
+    const long b = a.idx[i];
+    const float adv = a.adv[b], ret = a.returns[b], v_old = a.v_old[b], logp_old = a.logp_old[b];
+    float mu[AMAX], act[AMAX], sg[AMAX];
+    float zz = 0.f, sum_ls = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < AMAX; ++jj) {
+      if (jj < A) {
+        const float ls = a.log_std[jj];
+        sg[jj] = expf(ls);
+        mu[jj] = a.mu[(long)i * A + jj];
+        act[jj] = a.actions[b * A + jj];
+        const float z = (act[jj] - mu[jj]) / sg[jj];
+        zz += z * z;
+        sum_ls += ls;
+        const float so = a.sigma_old[b * A + jj], mo = a.mu_old[b * A + jj];
+        kl += logf(sg[jj] / so) + (so * so + (mo - mu[jj]) * (mo - mu[jj])) / (2.0f * sg[jj] * sg[jj]) - 0.5f;
+      }
+    }
+    const float logp_new = -0.5f * zz - sum_ls - 0.5f * (float)A * LOG_2PI;
+    float d_logp, d_v;
+    RowTerms t = ppo_row(a, logp_new, logp_old, adv, a.v[i], v_old, ret, inv_rows, &d_logp, &d_v);
+    surr += t.surr; vloss += t.vloss; clipped += t.clipped;
+    a.d_v[i] = d_v;
+#pragma unroll
+    for (int jj = 0; jj < AMAX; ++jj) {
+      if (jj < A) {
+        const float z = (act[jj] - mu[jj]) / sg[jj];
+        a.d_mu[(long)i * A + jj] = d_logp * z / sg[jj];
+        dls[jj] += d_logp * (z * z - 1.0f);
+      }
+    }
+    if (sym) {
+      const long im = (long)i + a.mb;
+      float zz2 = 0.f;
+      float mum[AMAX], zm[AMAX];
+#pragma unroll
+      for (int jj = 0; jj < AMAX; ++jj) {
+        if (jj < A) {
+          mum[jj] = a.mu[im * A + jj];
+          const float am = a.sign_act[jj] * a.actions[b * A + a.perm_act[jj]];
+          zm[jj] = (am - mum[jj]) / sg[jj];
+          zz2 += zm[jj] * zm[jj];
+        }
+      }
+      const float logp_m = -0.5f * zz2 - sum_ls - 0.5f * (float)A * LOG_2PI;
+      float d_logp_m, d_v_m;
+      RowTerms tm = ppo_row(a, logp_m, logp_old, adv, a.v[im], v_old, ret, inv_rows, &d_logp_m, &d_v_m);
+      surr += tm.surr; vloss += tm.vloss; clipped += tm.clipped;
+      a.d_v[im] = d_v_m;
+      const float msc = a.mirror_coef * 2.0f / ((float)a.mb * (float)A);
+#pragma unroll
+      for (int jj = 0; jj < AMAX; ++jj) {
+        if (jj < A) {
+          const float target = a.sign_act[jj] * a.mu[(long)i * A + a.perm_act[jj]];
+          const float diff = mum[jj] - target;
+          mirror += diff * diff;
+          a.d_mu[im * A + jj] = d_logp_m * zm[jj] / sg[jj] + msc * diff;
+          dls[jj] += d_logp_m * (zm[jj] * zm[jj] - 1.0f);
+        }
+      }
+    }
+  }
+  double* out = a.partials + (long)blockIdx.x * (PPO_NPART_FIXED + A);
+  double r;
+  r = block_sum((double)surr, smem);    if (threadIdx.x == 0) out[0] = r;
+  r = block_sum((double)vloss, smem);   if (threadIdx.x == 0) out[1] = r;
+  r = block_sum((double)kl, smem);      if (threadIdx.x == 0) out[2] = r;
+  r = block_sum((double)clipped, smem); if (threadIdx.x == 0) out[3] = r;
+  r = block_sum((double)mirror, smem);  if (threadIdx.x == 0) out[4] = r;
+#pragma unroll
+  for (int jj = 0; jj < AMAX; ++jj) {
+    if (jj < A) {
+      r = block_sum((double)dls[jj], smem);
+      if (threadIdx.x == 0) out[PPO_NPART_FIXED + jj] = r;
+    }
+  }
+}
+
+hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(ppo_loss_kernel, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// One wavefront: lane c sums component c over the blocks in block order.
+__global__ __launch_bounds__(64) void ppo_loss_finish_kernel(const double* __restrict__ partials, int blocks, int rows,
+                                                             int mb, int A, const float* __restrict__ log_std,
+                                                             float entropy_coef, float* __restrict__ d_log_std,
+                                                             float* __restrict__ stats_row,
+                                                             double* __restrict__ sumsq_slot) {
+  const int c = threadIdx.x;
+  const int ncomp = PPO_NPART_FIXED + A;
+  double s = 0.0;
+  if (c < ncomp)
+    for (int b = 0; b < blocks; ++b) s += partials[(long)b * ncomp + c];
+  double g2 = 0.0;
+  if (c >= PPO_NPART_FIXED && c < ncomp) {
+    const float g = (float)s - entropy_coef;
+    d_log_std[c - PPO_NPART_FIXED] = g;
+    g2 = (double)g * (double)g;
+  }
+  g2 = wave_sum(g2);
+  double ent = 0.0;
+  if (c < A) ent = 0.5 + 0.5 * (double)LOG_2PI + (double)log_std[c];
+  ent = wave_sum(ent);
+  if (c == 0) {
+    *sumsq_slot = g2;
+    stats_row[0] = (float)(s / rows);
+    stats_row[2] = (float)ent;
+  }
+  if (c == 1) stats_row[1] = (float)(s / rows);
+  if (c == 2) stats_row[3] = (float)(s / mb);
+  if (c == 3) stats_row[5] = (float)(s / rows);
+  if (c == 4) stats_row[6] = rows > mb ? (float)(s / ((double)mb * A)) : 0.f;
+  if (c == 5) stats_row[7] = 0.f;
+}
+
+hipError_t launch_ppo_loss_finish(const double* partials, int32_t blocks, int32_t rows, int32_t mb, int32_t A,
+                                  const float* log_std, float entropy_coef, float* d_log_std, float* stats_row,
+                                  double* sumsq_slot, hipStream_t stream) {
+  hipLaunchKernelGGL(ppo_loss_finish_kernel, dim3(1), dim3(64), 0, stream, partials, blocks, rows, mb, A, log_std,
+                     entropy_coef, d_log_std, stats_row, sumsq_slot);
+  return hipGetLastError();
+}
+
+// ---- MSE head -----------------------------------------------------------------------------------------
+int mse_num_blocks(int64_t n) { return (int)((n + 1023) / 1024); }
+
+__global__ __launch_bounds__(256) void mse_kernel(const float* __restrict__ y, const float* __restrict__ target,
+                                                  const int32_t* __restrict__ target_idx, int rows, int width,
+                                                  float* __restrict__ d_y, double* __restrict__ partials) {
+  __shared__ double smem[4];
+  const long n = (long)rows * width;
+  const float sc = 2.0f / (float)n;
+  const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  double q = 0.0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const long i = i0 + c;
+    if (i < n) {
+      const long r = i / width;
+      const long col = i - r * width;
+      const long tr = target_idx ? (long)target_idx[r] : r;
+      const float d = y[i] - target[tr * width + col];
+      d_y[i] = sc * d;
+      q += (double)d * (double)d;
+    }
+  }
+  double t = block_sum(q, smem);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
+hipError_t launch_mse(const float* y, const float* target, const int32_t* target_idx, int32_t rows, int32_t width,
+                      float* d_y, double* partials, hipStream_t stream) {
+  const int64_t n = (int64_t)rows * width;
+  hipLaunchKernelGGL(mse_kernel, dim3(mse_num_blocks(n)), dim3(256), 0, stream, y, target, target_idx, rows, width, d_y,
+                     partials);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void mse_finish_kernel(const double* __restrict__ partials, int blocks, long count,
+                                                         float* __restrict__ stat_out) {
+  __shared__ double smem[4];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < blocks; i += 256) s += partials[i];
+  double t = block_sum(s, smem);
+  if (threadIdx.x == 0) *stat_out = (float)(t / (double)count);
+}
+
+hipError_t launch_mse_finish(const double* partials, int32_t blocks, int64_t count, float* stat_out, hipStream_t stream) {
+  hipLaunchKernelGGL(mse_finish_kernel, dim3(1), dim3(256), 0, stream, partials, blocks, (long)count, stat_out);
+  return hipGetLastError();
+}
+
+// ---- symmetry augmentation ----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sym_augment_kernel(const float* __restrict__ in, long B, int D,
+                                                          const int32_t* __restrict__ perm, const float* __restrict__ sign,
+                                                          float* __restrict__ out) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  const long n = B * D;
+  if (i >= n) return;
+  const long r = i / D;
+  const int jj = (int)(i - r * D);
+  out[i] = in[i];
+  out[n + i] = sign[jj] * in[r * D + perm[jj]];
+}
+
+hipError_t launch_sym_augment(const float* in, int32_t B, int32_t D, const int32_t* perm, const float* sign, float* out,
+                              hipStream_t stream) {
+  const long n = (long)B * D;
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sym_augment_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, in, (long)B, D, perm,
+                     sign, out);
+  return hipGetLastError();
+}
+
+// ---- RND reward ---------------------------------------------------------------------------------------
+int rnd_num_blocks(int32_t N) { return (N + 255) / 256; }
+
+__global__ __launch_bounds__(256) void rnd_raw_kernel(const float* __restrict__ yp, const float* __restrict__ yt, int N,
+                                                      int K, float* __restrict__ raw, double* __restrict__ partials) {
+  __shared__ double smem[4];
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  double s = 0.0, q = 0.0;
+  if (n < N) {
+    float acc = 0.f;
+    for (int k = 0; k < K; ++k) {
+      const float d = yp[(long)n * K + k] - yt[(long)n * K + k];
+      acc += d * d;
+    }
+    raw[n] = acc;
+    s = (double)acc;
+    q = s * s;
+  }
+  double ts = block_sum(s, smem);
+  double tq = block_sum(q, smem);
+  if (threadIdx.x == 0) {
+    partials[2 * blockIdx.x] = ts;
+    partials[2 * blockIdx.x + 1] = tq;
+  }
+}
+
+// Single workgroup: batch moments, pairwise merge into running = {mean, var, count}, 1/sqrt(var + 1e-8).
+__global__ __launch_bounds__(256) void rnd_stats_kernel(const double* __restrict__ partials, int blocks, int N,
+                                                        float* __restrict__ running, int update,
+                                                        float* __restrict__ inv_out) {
+  __shared__ double smem[4];
+  double s = 0.0, q = 0.0;
+  for (int i = threadIdx.x; i < blocks; i += 256) {
+    s += partials[2 * i];
+    q += partials[2 * i + 1];
+  }
+  double ts = block_sum(s, smem);
+  double tq = block_sum(q, smem);
+  if (threadIdx.x == 0) {
+    double mean = running[0], var = running[1], count = running[2];
+    if (update) {
+      const double nb = (double)N;
+      const double mb = ts / nb;
+      double vb = tq / nb - mb * mb;
+      if (vb < 0.0) vb = 0.0;
+      const double tot = count + nb;
+      const double delta = mb - mean;
+      const double m2 = var * count + vb * nb + delta * delta * count * nb / tot;
+      mean = mean + delta * nb / tot;
+      var = m2 / tot;
+      count = tot;
+      running[0] = (float)mean;
+      running[1] = (float)var;
+      running[2] = (float)count;
+    }
+    *inv_out = (float)(1.0 / sqrt(var + 1e-8));
+  }
+}
+
+__global__ __launch_bounds__(256) void rnd_apply_kernel(float* __restrict__ r_int, int N, const float* __restrict__ inv,
+                                                        float weight, float* __restrict__ rewards) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  const float r = r_int[n] * inv[0];
+  r_int[n] = r;
+  if (rewards != nullptr) rewards[n] += weight * r;
+}
+
+hipError_t launch_rnd_reward(const float* yp, const float* yt, int32_t N, int32_t K, float* running, float weight,
+                             int32_t update_stats, float* r_int, float* rewards, double* partials, hipStream_t stream) {
+  const int nb = rnd_num_blocks(N);
+  float* inv = reinterpret_cast<float*>(partials + 2 * (size_t)nb);
+  hipLaunchKernelGGL(rnd_raw_kernel, dim3(nb), dim3(256), 0, stream, yp, yt, N, K, r_int, partials);
+  hipLaunchKernelGGL(rnd_stats_kernel, dim3(1), dim3(256), 0, stream, partials, nb, N, running, update_stats, inv);
+  hipLaunchKernelGGL(rnd_apply_kernel, dim3(nb), dim3(256), 0, stream, r_int, N, inv, weight, rewards);
+  return hipGetLastError();
+}
+
+}  // namespace rslx

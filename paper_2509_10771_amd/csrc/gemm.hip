@@ -1,0 +1,298 @@
+// fp32 matrix-core contraction for gfx950 (v_mfma_f32_32x32x2_f32), used by every dense layer of the
+// actor, critic, student, teacher and RND networks: forward, input gradient and weight gradient.
+//
+// Tiling: one workgroup = 4 wavefronts (256 lanes) computes a BM x BN block of C.  Operand tiles of
+// BK = 16 contraction steps are staged through LDS in contraction-major order (As[k][m], Bs[k][n]),
+// so that the 32 lanes of an MFMA operand row read 32 consecutive words (bank-conflict free), and are
+// double-buffered: global loads of tile k+1 are in flight while tile k feeds the matrix cores.
+//
+// MFMA 32x32x2 fp32 register layout (wave64, lane l, g = l / 32, j = l % 32):
+//   A operand: A[row = j][k = g]      B operand: B[k = g][col = j]
+//   D/C, 16 accumulators r = 0..15:   D[row = 8 * (r / 4) + 4 * g + r % 4][col = j]
+#include "kernels.h"
+
+namespace rslx {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;    // contraction steps per LDS tile
+constexpr int PAD = 4;    // LDS row padding (floats); keeps rows 16-byte aligned
+constexpr int NT = 256;   // lanes per workgroup
+
+__device__ __forceinline__ int wrap_row(const GemmProblem& P, int r) { return r >= P.idx_mod ? r - P.idx_mod : r; }
+
+__device__ __forceinline__ int src_row(const GemmProblem& P, int r) {
+  int rr = wrap_row(P, r);
+  return P.row_idx ? P.row_idx[rr] : rr;
+}
+
+// One element of the gathered / column-mapped view X(r, c).
+__device__ __forceinline__ float x_elem(const GemmProblem& P, int r, int c) {
+  long base = (long)src_row(P, r) * P.lda;
+  if (P.col_map != nullptr && r >= P.map_from) {
+    float s = P.col_sign ? P.col_sign[c] : 1.0f;
+    return s * P.A[base + P.col_map[c]];
+  }
+  return P.A[base + c];
+}
+
+// ---- tile fetch: operand stored with the contraction index contiguous (rows = M or N index) -------
+// Produces R*BK/NT values per lane; element (row, k) lands at lds[k][row].
+template <int R, bool IS_X>
+__device__ __forceinline__ void fetch_kcontig(const GemmProblem& P, const float* __restrict__ base, int ld, bool vec,
+                                              int row0, int row_end, int k0, int k_end, float (&reg)[R * BK / NT]) {
+  const int tid = threadIdx.x;
+  if (vec) {
+#pragma unroll
+    for (int p = 0; p < R / 64; ++p) {
+      int row = row0 + p * 64 + tid / 4;
+      int kk = k0 + 4 * (tid % 4);
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < row_end && kk < k_end) {
+        long sr = IS_X ? (long)src_row(P, row) : (long)row;
+        v = *reinterpret_cast<const float4*>(base + sr * ld + kk);
+      }
+      reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < R / 16; ++p) {
+      int row = row0 + p * 16 + tid / 16;
+      int kk = k0 + tid % 16;
+      float v = 0.f;
+      if (row < row_end && kk < k_end) v = IS_X ? x_elem(P, row, kk) : base[(long)row * ld + kk];
+      reg[p] = v;
+    }
+  }
+}
+
+template <int R, int S>
+__device__ __forceinline__ void stash_kcontig(bool vec, float (*lds)[S], const float (&reg)[R * BK / NT]) {
+  const int tid = threadIdx.x;
+  if (vec) {
+#pragma unroll
+    for (int p = 0; p < R / 64; ++p) {
+      int row = p * 64 + tid / 4;
+      int kq = 4 * (tid % 4);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) lds[kq + c][row] = reg[4 * p + c];
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < R / 16; ++p) lds[tid % 16][p * 16 + tid / 16] = reg[p];
+  }
+}
+
+// ---- tile fetch: operand stored with the M / N index contiguous (rows = contraction index) --------
+template <int Cw, bool IS_X>
+__device__ __forceinline__ void fetch_direct(const GemmProblem& P, const float* __restrict__ base, int ld, bool vec,
+                                             int col0, int col_end, int k0, int k_end, float (&reg)[Cw * BK / NT]) {
+  const int tid = threadIdx.x;
+  if (vec) {
+    constexpr int V = Cw / 4;        // float4 per tile row
+    constexpr int RP = NT / V;       // tile rows per pass
+#pragma unroll
+    for (int p = 0; p < BK / RP; ++p) {
+      int kk = k0 + p * RP + tid / V;
+      int col = col0 + 4 * (tid % V);
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (kk < k_end && col < col_end) {
+        long sr = IS_X ? (long)src_row(P, kk) : (long)kk;
+        v = *reinterpret_cast<const float4*>(base + sr * ld + col);
+      }
+      reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
+    }
+  } else {
+    constexpr int RP = NT / Cw;
+#pragma unroll
+    for (int p = 0; p < BK / RP; ++p) {
+      int kk = k0 + p * RP + tid / Cw;
+      int col = col0 + tid % Cw;
+      float v = 0.f;
+      if (kk < k_end && col < col_end) v = IS_X ? x_elem(P, kk, col) : base[(long)kk * ld + col];
+      reg[p] = v;
+    }
+  }
+}
+
+template <int Cw, int S>
+__device__ __forceinline__ void stash_direct(bool vec, float (*lds)[S], const float (&reg)[Cw * BK / NT]) {
+  const int tid = threadIdx.x;
+  if (vec) {
+    constexpr int V = Cw / 4;
+    constexpr int RP = NT / V;
+#pragma unroll
+    for (int p = 0; p < BK / RP; ++p) {
+      float4 v = make_float4(reg[4 * p], reg[4 * p + 1], reg[4 * p + 2], reg[4 * p + 3]);
+      *reinterpret_cast<float4*>(&lds[p * RP + tid / V][4 * (tid % V)]) = v;
+    }
+  } else {
+    constexpr int RP = NT / Cw;
+#pragma unroll
+    for (int p = 0; p < BK / RP; ++p) lds[p * RP + tid / Cw][tid % Cw] = reg[p];
+  }
+}
+
+template <int MODE, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
+  static_assert(WM * WN == 4, "four wavefronts per workgroup");
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 block");
+  constexpr int SA = BM + PAD, SB = BN + PAD;
+  __shared__ __align__(16) float As[2][BK][SA];
+  __shared__ __align__(16) float Bs[2][BK][SB];
+
+  const GemmProblem& P = batch.p[blockIdx.z];
+  const int tiles_n = (P.N + BN - 1) / BN;
+  const int tiles_m = (P.M + BM - 1) / BM;
+  const int tile = blockIdx.x;
+  if (tile >= tiles_m * tiles_n) return;
+  const int split = blockIdx.y;
+  if (MODE == GEMM_DW && split >= P.n_split) return;
+  const int tn = tile % tiles_n, tm = tile / tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int k_begin = (MODE == GEMM_DW) ? split * P.k_chunk : 0;
+  const int k_end = (MODE == GEMM_DW) ? min(P.K, k_begin + P.k_chunk) : P.K;
+  const int nk = (k_end - k_begin + BK - 1) / BK;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, j = lane & 31;
+  const int wm = wave / WN, wn = wave % WN;
+  const int a_off = wm * (TM * 32) + j, b_off = wn * (TN * 32) + j;
+  // 16-byte fetches need at least 64 rows / columns per tile to give every lane a slot
+  const bool avec = P.a_vec != 0 && BM >= 64, bvec = P.b_vec != 0 && BN >= 64;
+
+  float ra[BM * BK / NT], rb[BN * BK / NT];
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  float bsum = 0.f;   // DW: column sum of dZ for the bias gradient
+
+  auto fetch = [&](int k0) {
+    if (MODE == GEMM_DW) {
+      fetch_direct<BM, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
+      fetch_direct<BN, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
+    } else if (MODE == GEMM_FWD) {
+      fetch_kcontig<BM, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
+      fetch_direct<BN, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
+    } else {
+      fetch_kcontig<BM, false>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
+      fetch_kcontig<BN, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
+    }
+  };
+  auto stash = [&](int buf) {
+    if (MODE == GEMM_DW) {
+      stash_direct<BM, SA>(avec, As[buf], ra);
+      stash_direct<BN, SB>(bvec, Bs[buf], rb);
+    } else if (MODE == GEMM_FWD) {
+      stash_kcontig<BM, SA>(avec, As[buf], ra);
+      stash_direct<BN, SB>(bvec, Bs[buf], rb);
+    } else {
+      stash_kcontig<BM, SA>(avec, As[buf], ra);
+      stash_kcontig<BN, SB>(bvec, Bs[buf], rb);
+    }
+  };
+
+  if (nk > 0) {
+    fetch(k_begin);
+    stash(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) fetch(k_begin + (kt + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      float a[TM], b[TN];
+#pragma unroll
+      for (int t = 0; t < TM; ++t) a[t] = As[buf][kk + g][a_off + t * 32];
+#pragma unroll
+      for (int t = 0; t < TN; ++t) b[t] = Bs[buf][kk + g][b_off + t * 32];
+#pragma unroll
+      for (int x = 0; x < TM; ++x)
+#pragma unroll
+        for (int y = 0; y < TN; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
+    }
+    if (MODE == GEMM_DW && tm == 0 && tid < BN) {
+#pragma unroll
+      for (int kk = 0; kk < BK; ++kk) bsum += Bs[buf][kk][tid];
+    }
+    if (kt + 1 < nk) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue -------------------------------------------------------------------------------
+  float* Cb = P.C;
+  if (MODE == GEMM_DW) Cb += (long)split * P.split_stride;
+#pragma unroll
+  for (int x = 0; x < TM; ++x) {
+#pragma unroll
+    for (int y = 0; y < TN; ++y) {
+      const int col = n0 + wn * (TN * 32) + y * 32 + j;
+      if (col >= P.N) continue;
+      float bias = 0.f;
+      if (MODE == GEMM_FWD && P.aux) bias = P.aux[col];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * (TM * 32) + x * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+        if (row >= P.M) continue;
+        float v = acc[x][y][r];
+        const long o = (long)row * P.ldc + col;
+        if (MODE == GEMM_FWD) {
+          v += bias;
+          if (P.elu) v = v > 0.f ? v : P.alpha * expm1f(v);
+        } else if (MODE == GEMM_DX) {
+          if (P.aux) {
+            float h = P.aux[o];
+            v *= (h > 0.f) ? 1.0f : (h + P.alpha);
+          }
+        }
+        Cb[o] = v;
+      }
+    }
+  }
+  if (MODE == GEMM_DW && tm == 0 && P.bias_off >= 0 && tid < BN && n0 + tid < P.N) Cb[P.bias_off + n0 + tid] = bsum;
+}
+
+template <int MODE, int BM, int BN, int WM, int WN>
+static hipError_t launch_cfg(const GemmBatch& batch, hipStream_t stream) {
+  int tiles = 0, splits = 1;
+  for (int i = 0; i < batch.count; ++i) {
+    const GemmProblem& P = batch.p[i];
+    int t = ((P.M + BM - 1) / BM) * ((P.N + BN - 1) / BN);
+    tiles = t > tiles ? t : tiles;
+    if (MODE == GEMM_DW) splits = P.n_split > splits ? P.n_split : splits;
+  }
+  if (tiles == 0) return hipSuccess;
+  dim3 grid(tiles, splits, batch.count);
+  hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN>), grid, dim3(NT), 0, stream, batch);
+  return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t launch_mode(const GemmBatch& batch, hipStream_t stream) {
+  int maxM = 0, maxN = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    maxM = batch.p[i].M > maxM ? batch.p[i].M : maxM;
+    maxN = batch.p[i].N > maxN ? batch.p[i].N : maxN;
+  }
+  if (maxN <= 32) return launch_cfg<MODE, 128, 32, 4, 1>(batch, stream);
+  if (maxM <= 64) return launch_cfg<MODE, 64, 128, 1, 4>(batch, stream);
+  if (maxN <= 64) return launch_cfg<MODE, 128, 64, 2, 2>(batch, stream);
+  return launch_cfg<MODE, 128, 128, 2, 2>(batch, stream);
+}
+
+hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream) {
+  switch (mode) {
+    case GEMM_FWD: return launch_mode<GEMM_FWD>(batch, stream);
+    case GEMM_DX: return launch_mode<GEMM_DX>(batch, stream);
+    default: return launch_mode<GEMM_DW>(batch, stream);
+  }
+}
+
+}  // namespace rslx

@@ -1,0 +1,133 @@
+// Internal interface between the host-side entry points and the HIP kernels of librslx.
+// Not part of the public ABI (that is include/rslx.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rslx {
+
+// ---------------------------------------------------------------------------------------------
+// Dense fp32 contraction on the matrix cores, three operand arrangements of one kernel:
+//   GEMM_FWD  C[r, n]   = act( sum_k X(r, k) W[k, n] + bias[n] )          (layer forward)
+//   GEMM_DX   C[r, kin] = ( sum_n dZ[r, n] W[kin, n] ) * ELU'(H[r, kin])   (input gradient)
+//   GEMM_DW   C_s[kin, n] = sum_{r in split s} X(r, kin) dZ[r, n]          (weight gradient, split
+//             over rows; the block row holding kin = 0 also emits the column sums of dZ = db)
+// X(r, c) is a view of a row-major matrix with an optional row gather and column map:
+//   src_row = row_idx ? row_idx[r mod idx_mod] : r mod idx_mod
+//   X(r, c) = (r >= map_from && col_map) ? col_sign[c] * A[src_row, col_map[c]] : A[src_row, c]
+// which covers minibatch gathering, mirrored copies and feature subsets without materialising them.
+// ---------------------------------------------------------------------------------------------
+enum GemmMode : int { GEMM_FWD = 0, GEMM_DX = 1, GEMM_DW = 2 };
+
+struct GemmProblem {
+  const float* A;           // FWD/DW: X storage; DX: dZ
+  const float* B;           // FWD/DX: W [K_in, N_out] row-major; DW: dZ
+  float* C;                 // FWD/DX: output; DW: base of split partial 0
+  const float* aux;         // FWD: bias[N] or null; DX: H at C's coordinates (ldc) or null
+  const int32_t* row_idx;   // optional row gather for X (device)
+  const int32_t* col_map;   // optional column map for X (device)
+  const float* col_sign;    // optional column sign for X (device, with col_map)
+  int32_t idx_mod;          // rows r >= idx_mod wrap to r - idx_mod (INT32_MAX = no wrap)
+  int32_t map_from;         // rows >= map_from use col_map / col_sign
+  int32_t M, N, K;          // GEMM extents (K is the contraction length)
+  int32_t lda, ldb, ldc;
+  int32_t elu;              // FWD: 1 = ELU epilogue, 0 = linear
+  float alpha;              // ELU parameter
+  int32_t k_chunk;          // DW: contraction rows per split
+  int32_t n_split;          // DW: number of splits (grid.y)
+  int64_t split_stride;     // DW: floats between consecutive partial buffers
+  int32_t bias_off;         // DW: offset of the db partial inside a partial buffer, -1 = none
+  int32_t a_vec, b_vec;     // 1 = operand may be fetched with 16-byte loads
+};
+
+struct GemmBatch {
+  GemmProblem p[2];
+  int32_t count;
+};
+
+hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------
+// Streaming / reduction kernels (elementwise.hip)
+// ---------------------------------------------------------------------------------------------
+int gae_num_blocks(int32_t N);
+hipError_t launch_gae(const float* rewards, const float* values, const float* last_values,
+                      const uint8_t* dones, const uint8_t* timeouts, int32_t T, int32_t N, float gamma,
+                      float lam, int32_t normalize, float* adv, float* ret, double* partials,
+                      hipStream_t stream);
+
+// Permutation by sorting 64-bit hash keys (bucket scatter + in-bucket ranking).
+size_t perm_workspace_bytes(int32_t B);
+hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, void* ws, hipStream_t stream);
+
+// Sum the split partials of a flat gradient buffer, write grads, emit per-block sums of squares.
+int reduce_num_blocks(int64_t n);
+hipError_t launch_reduce_partials(const float* partials, int32_t n_split, int64_t split_stride, int64_t n,
+                                  float* grads, double* sumsq_blocks, hipStream_t stream);
+// Per-block sums of squares of an existing gradient buffer.
+hipError_t launch_sumsq(const float* g, int64_t n, double* sumsq_blocks, hipStream_t stream);
+
+struct AdamSegment {
+  float* params; const float* grads; float* m; float* v;
+  int64_t n;
+};
+struct AdamArgs {
+  AdamSegment seg[2];
+  int32_t n_seg;
+  const double* sumsq_blocks;  // per-block sums of squares covering every clipped tensor
+  int32_t n_sumsq;
+  float max_grad_norm;         // <= 0: no clipping
+  float lr, beta1, beta2, eps;
+  float bc1, bc2;              // 1 - beta1^t, 1 - beta2^t
+  float* grad_norm_out;        // optional device scalar (stats column)
+};
+hipError_t launch_adam(const AdamArgs& a, hipStream_t stream);
+
+// Gaussian head of act(): noise, action, log-density.
+hipError_t launch_act_head(const float* mu_in, const float* log_std, const float* eps, uint64_t noise_base,
+                           int32_t N, int32_t A, int32_t deterministic, float* actions, float* logp, float* mu_out,
+                           float* sigma_out, hipStream_t stream);
+hipError_t launch_copy_column(const float* src, int32_t n, float* dst, hipStream_t stream);
+
+// PPO loss head: per-row loss terms, d loss / d mu and d loss / d V, block partial sums.
+struct PpoLossArgs {
+  const float* mu;        // [rows, A] new means (rows = mb or 2*mb)
+  const float* v;         // [rows]
+  const float* log_std;   // [A]
+  const int32_t* idx;     // [mb] rollout rows of this minibatch
+  const float* actions; const float* logp_old; const float* adv; const float* returns; const float* v_old;
+  const float* mu_old; const float* sigma_old;
+  const int32_t* perm_act; const float* sign_act;  // mirror map of actions (null without symmetry)
+  int32_t mb, rows, A;
+  float clip, value_coef, entropy_coef, mirror_coef;
+  int32_t clipped_value;
+  float* d_mu;            // [rows, A]
+  float* d_v;             // [rows]
+  double* partials;       // [blocks, PPO_NPART]
+};
+constexpr int PPO_NPART_FIXED = 5;  // surrogate, value, kl, clip count, mirror ; then A entries of dlog_std
+int ppo_loss_num_blocks(int32_t mb);
+hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream);
+// Reduce the loss partials: writes the stats row, the log_std gradient and its squared norm.
+hipError_t launch_ppo_loss_finish(const double* partials, int32_t blocks, int32_t rows, int32_t mb, int32_t A,
+                                  const float* log_std, float entropy_coef, float* d_log_std, float* stats_row,
+                                  double* sumsq_slot, hipStream_t stream);
+
+// Mean-squared-error head: d = 2 (y - target) / (rows * width), block partial sums of squared error.
+int mse_num_blocks(int64_t n);
+hipError_t launch_mse(const float* y, const float* target, const int32_t* target_idx, int32_t rows, int32_t width,
+                      float* d_y, double* partials, hipStream_t stream);
+hipError_t launch_mse_finish(const double* partials, int32_t blocks, int64_t count, float* stat_out, hipStream_t stream);
+
+hipError_t launch_sym_augment(const float* in, int32_t B, int32_t D, const int32_t* perm, const float* sign,
+                              float* out, hipStream_t stream);
+
+// RND reward: row sums of squared differences, batch moments, running-stat merge, normalisation.
+int rnd_num_blocks(int32_t N);
+hipError_t launch_rnd_reward(const float* yp, const float* yt, int32_t N, int32_t K, float* running, float weight,
+                             int32_t update_stats, float* r_int, float* rewards, double* partials, hipStream_t stream);
+
+hipError_t launch_fill(float* p, int64_t n, float value, hipStream_t stream);
+
+}  // namespace rslx
