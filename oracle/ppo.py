@@ -92,13 +92,15 @@ def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg
     ratio_c = np.clip(ratio, 1.0 - cfg.clip, 1.0 + cfg.clip)
     s1, s2 = -adv * ratio, -adv * ratio_c
     surrogate = np.mean(np.maximum(s1, s2))
-    d_ratio = np.where(s1 >= s2, -adv, 0.0) / n        # clipped branch is flat in ratio
+    in_range = (ratio >= 1.0 - cfg.clip) & (ratio <= 1.0 + cfg.clip)
+    d_ratio = np.where(in_range | (s1 >= s2), -adv, 0.0) / n        # clipped branch is flat in ratio outside the range
 
     if cfg.use_clipped_value_loss:
         v_clip = v_old + np.clip(V - v_old, -cfg.clip, cfg.clip)
         e1, e2 = (V - ret) ** 2, (v_clip - ret) ** 2
         value_loss = np.mean(np.maximum(e1, e2))
-        dV = np.where(e1 >= e2, 2.0 * (V - ret), 0.0) / n
+        # the clipped branch is flat in V only where the clamp is active; inside the clip range V_clip == V
+        dV = np.where((np.abs(V - v_old) <= cfg.clip) | (e1 >= e2), 2.0 * (V - ret), 0.0) / n
     else:
         value_loss = np.mean((ret - V) ** 2)
         dV = 2.0 * (V - ret) / n
@@ -136,14 +138,15 @@ def rnd_predictor_loss_and_grad(pred_flat, targ_flat, dims, x, alpha=1.0):
     return float(np.mean(diff ** 2)), mlp.pack(grads)
 
 
-def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=None):
+def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=None, record=False):
     """E epochs x M minibatches over the flattened [T*N] rollout.
 
     actor/critic: flat parameter vectors.  opt: dict with m_a, v_a, m_c, v_c (flat
     Adam moments) and step (shared counter).  rollout: dict of arrays with B = T*N
     leading rows (flat index b = t*N + n).  rnd: optional dict with
     pred, targ (flat), dims, subset (column indices or None), m, v, step, lr.
-    Returns dict(actor, critic, opt, stats[E*M, 8], g_actor, g_critic, rnd, perms).
+    Returns dict(actor, critic, opt, stats[E*M, 8], g_actor, g_critic, rnd, perms); with record=True also
+    `trace`: per optimiser step the state before it, its gradients and the state after it.
     """
     actor = np.asarray(actor, np.float64).copy(); critic = np.asarray(critic, np.float64).copy()
     opt = {k: (np.asarray(v, np.float64).copy() if k != "step" else int(v)) for k, v in opt.items()}
@@ -156,7 +159,7 @@ def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=N
     if rnd is not None:
         rnd = dict(rnd); rnd["pred"] = np.asarray(rnd["pred"], np.float64).copy()
         rnd["m"] = np.asarray(rnd["m"], np.float64).copy(); rnd["v"] = np.asarray(rnd["v"], np.float64).copy()
-    stats, perms = [], []
+    stats, perms, trace = [], [], []
     g_a = g_c = None
     for e in range(cfg.epochs):
         perm = rng.permutation(cfg.seed, cfg.call_index, e + cfg.epoch_offset, B)
@@ -164,6 +167,8 @@ def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=N
         for m in range(cfg.minibatches):
             I = perm[m * mb:(m + 1) * mb]
             batch = {k: v[I] for k, v in flat.items()}
+            before = dict(actor=actor.copy(), critic=critic.copy(), opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()},
+                          rnd=None if rnd is None else {k: (np.copy(v) if k in ("pred", "m", "v") else v) for k, v in rnd.items()}) if record else None
             terms, g_a, g_c = minibatch_loss_and_grads(actor, critic, dims_a, dims_c, batch, cfg, sym)
             norm = adam.global_norm([g_a, g_c])
             s = adam.clip_scale(norm, cfg.max_grad_norm)
@@ -179,7 +184,10 @@ def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=N
                 rnd["pred"], rnd["m"], rnd["v"], rnd["step"] = adam.adam_step(
                     rnd["pred"], g_p, rnd["m"], rnd["v"], rnd["step"], rnd.get("lr", cfg.lr), cfg.beta1, cfg.beta2, cfg.adam_eps)
                 rnd["g"] = g_p
+            if record:
+                trace.append(dict(rows=I, before=before, g_actor=g_a, g_critic=g_c, actor=actor.copy(), critic=critic.copy(),
+                                  g_pred=None if rnd is None else rnd["g"], pred=None if rnd is None else rnd["pred"].copy()))
             stats.append([terms["surrogate"], terms["value_loss"], terms["entropy"], terms["kl"], norm,
                           terms["clip_frac"], terms["mirror_loss"], rnd_loss])
     return dict(actor=actor, critic=critic, opt=opt, stats=np.array(stats), g_actor=g_a, g_critic=g_c,
-                rnd=rnd, perms=np.array(perms))
+                rnd=rnd, perms=np.array(perms), trace=trace)

@@ -432,13 +432,15 @@ __device__ __forceinline__ RowTerms ppo_row(const PpoLossArgs& a, float logp_new
   const float rc = fminf(fmaxf(ratio, 1.0f - a.clip), 1.0f + a.clip);
   const float s1 = -adv * ratio, s2 = -adv * rc;
   t.surr = fmaxf(s1, s2);
-  *d_logp = (s1 >= s2 ? -adv : 0.f) * inv_rows * ratio;
+  const bool ratio_in = ratio >= 1.0f - a.clip && ratio <= 1.0f + a.clip;
+  *d_logp = ((ratio_in || s1 >= s2) ? -adv : 0.f) * inv_rows * ratio;
   t.clipped = fabsf(ratio - 1.0f) > a.clip ? 1.f : 0.f;
   if (a.clipped_value) {
     const float vc = v_old + fminf(fmaxf(v - v_old, -a.clip), a.clip);
     const float e1 = (v - ret) * (v - ret), e2 = (vc - ret) * (vc - ret);
     t.vloss = fmaxf(e1, e2);
-    *d_v = (e1 >= e2 ? 2.0f * (v - ret) : 0.f) * inv_rows * a.value_coef;
+    const bool v_in = fabsf(v - v_old) <= a.clip;   // inside the clip range the clipped branch equals the plain one
+    *d_v = ((v_in || e1 >= e2) ? 2.0f * (v - ret) : 0.f) * inv_rows * a.value_coef;
   } else {
     t.vloss = (ret - v) * (ret - v);
     *d_v = 2.0f * (v - ret) * inv_rows * a.value_coef;

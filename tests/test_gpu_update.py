@@ -1,15 +1,26 @@
-"""GPU parity of the PPO and BC updates against the fp64 oracle: loss terms, gradients, post-update parameters."""
+"""GPU parity of the PPO and BC updates against the fp64 oracle.
+
+Two kinds of comparison:
+  * step-forced: every optimiser step of the oracle's trajectory is replayed on the GPU from the oracle's own
+    state before that step (parameters, Adam moments, step count) on exactly that minibatch's rows; loss terms,
+    gradients and post-step parameters must agree to relative 1e-4.
+  * free-running: one whole multi-step call; the first step and the final parameters must agree to 1e-4, later
+    loss terms to a looser bound, because Adam's early steps (update ~ lr * sign(g)) turn rounding-level
+    differences of near-zero gradient entries into full-size steps that no fp32 implementation can track.
+"""
 import ctypes as C
 from dataclasses import replace
 import numpy as np
 import pytest
 import torch
 
-from oracle import ppo as oppo, bc as obc, mlp as omlp
+from oracle import ppo as oppo, bc as obc
 from workloads import WORKLOADS, make_inputs
 from gpu_util import dev, host, rel_l2, oracle_rollout, flat_rollout, oracle_cfg, f32
 
 pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
 
 
 @pytest.fixture(scope="module")
@@ -29,127 +40,193 @@ def _layer_slices(dims, log_std):
     return out
 
 
-def _check_vec(name, dims, log_std, got, ref, tol, floor=0.0):
+def _check_vec(name, dims, log_std, got, ref, tol):
     for nm, sl in _layer_slices(dims, log_std):
         r = np.asarray(ref[sl], np.float64)
         err = np.linalg.norm(np.asarray(got[sl], np.float64) - r)
-        assert err <= tol * max(np.linalg.norm(r), floor), (name, nm, err, np.linalg.norm(r))
+        assert err <= tol * np.linalg.norm(r) + 1e-12, (name, nm, err, np.linalg.norm(r))
 
 
-def run_ppo(rx, w, epochs, sym_on=False, rnd_on=False, seed=3, call_index=1, epoch_offset=0, state=None):
-    inp = make_inputs(w)
-    ro = oracle_rollout(w, inp)
-    flat = flat_rollout(w, inp, ro)
-    ocfg = replace(oracle_cfg(w, epochs, seed, call_index), epoch_offset=epoch_offset)
-    na, nc = inp["actor"].size, inp["critic"].size
-    osym = None
-    if sym_on:
-        osym = oppo.SymSpec(inp["perm_obs"], inp["sign_obs"], inp["perm_obs"], inp["sign_obs"], inp["perm_act"],
-                            inp["sign_act"], f32(w.mirror_loss_coef))
-    opt0 = dict(m_a=np.zeros(na), v_a=np.zeros(na), m_c=np.zeros(nc), v_c=np.zeros(nc), step=0)
-    ornd = None
-    if rnd_on:
-        npred = inp["rnd_predictor"].size
-        ornd = dict(pred=inp["rnd_predictor"], targ=inp["rnd_target"], dims=w.dims_rnd, subset=None, m=np.zeros(npred),
-                    v=np.zeros(npred), step=0, lr=f32(w.lr))
-    ref = oppo.ppo_update(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, flat, ocfg, opt0, osym, ornd)
-
-    actor = rx.Mlp(w.dims_actor, dev(inp["actor"]), trainable=True, has_log_std=True)
-    critic = rx.Mlp(w.dims_critic, dev(inp["critic"]), trainable=True)
-    d_obs = dev(flat["obs_a"])
-    rollout = rx.Rollout(w.T, w.N, d_obs, d_obs, dev(flat["actions"]), dev(flat["logp"]), dev(flat["values"]),
-                         dev(flat["mu"]), dev(flat["sigma"]), dev(flat["adv"]), dev(flat["returns"]))
-    cfg = rx.PpoCfg(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
-                    lr=w.lr, epochs=epochs, minibatches=w.minibatches, seed=seed, call_index=call_index, epoch_offset=epoch_offset)
-    sym = rx.Sym(inp["perm_obs"], inp["sign_obs"], inp["perm_obs"], inp["sign_obs"], inp["perm_act"], inp["sign_act"],
-                 w.mirror_loss_coef) if sym_on else None
-    rnd = None
-    if rnd_on:
-        rnd = rx.RndTrain(rx.Mlp(w.dims_rnd, dev(inp["rnd_target"])), rx.Mlp(w.dims_rnd, dev(inp["rnd_predictor"]), trainable=True), lr=w.lr)
-    stats = torch.zeros(epochs * w.minibatches, rx.NSTATS, device="cuda")
-    ws = rx.workspace(rx.rslx_ppo_update_workspace_bytes(actor, critic, rollout, cfg, sym, rnd))
-    step = C.c_int64(0)
-    rx.rslx_ppo_update(actor, critic, rollout, cfg, sym, rnd, step, stats, ws)
-    torch.cuda.synchronize()
-    return dict(ref=ref, actor=actor, critic=critic, stats=host(stats), step=step.value, rnd=rnd, inp=inp)
-
-
-def check_ppo(w, res, epochs, rnd_on=False):
-    ref = res["ref"]
-    assert res["step"] == epochs * w.minibatches == ref["opt"]["step"]
-    got, want = res["stats"], ref["stats"]
+def _check_stats(got, want, tol, floor=1e-3):
+    got, want = np.atleast_2d(got), np.atleast_2d(want)
     for col in range(8):
         err = np.abs(got[:, col] - want[:, col])
-        assert np.all(err <= 1e-4 * np.maximum(np.abs(want[:, col]), 1e-3)), (col, got[:, col], want[:, col])
-    _check_vec("g_actor", w.dims_actor, True, host(res["actor"].grads), ref["g_actor"], 1e-4)
-    _check_vec("g_critic", w.dims_critic, False, host(res["critic"].grads), ref["g_critic"], 1e-4)
-    assert rel_l2(host(res["actor"].params), ref["actor"]) <= 1e-4
-    assert rel_l2(host(res["critic"].params), ref["critic"]) <= 1e-4
-    # the applied update itself (Adam turns tiny gradient entries into +-lr steps, hence the looser bound)
-    d_got = host(res["actor"].params).astype(np.float64) - res["inp"]["actor"]
-    d_ref = ref["actor"] - res["inp"]["actor"]
-    assert rel_l2(d_got, d_ref) <= 2e-2
-    np.testing.assert_allclose(host(res["actor"].adam_m), ref["opt"]["m_a"], rtol=0, atol=1e-4 * np.abs(ref["opt"]["m_a"]).max())
-    if rnd_on:
-        assert rel_l2(host(res["rnd"].predictor.params), ref["rnd"]["pred"]) <= 1e-4
-        _check_vec("g_pred", w.dims_rnd, False, host(res["rnd"].predictor.grads), ref["rnd"]["g"], 1e-4)
-        assert res["rnd"].step.value == ref["rnd"]["step"]
+        assert np.all(err <= tol * np.maximum(np.abs(want[:, col]), floor)), (col, got[:, col], want[:, col])
 
 
-def test_ppo_tiny_one_epoch(rx):
-    w = WORKLOADS["tiny"]
-    check_ppo(w, run_ppo(rx, w, 1), 1)
+class Case:
+    """One workload: seeded inputs, the oracle's rollout and its recorded update trajectory."""
+
+    def __init__(self, w, epochs, sym_on=False, rnd_on=False, seed=3, call_index=1, perturb=0.0):
+        self.w, self.epochs, self.sym_on, self.rnd_on, self.seed, self.call_index = w, epochs, sym_on, rnd_on, seed, call_index
+        inp = self.inp = make_inputs(w)
+        self.flat = flat_rollout(w, inp, oracle_rollout(w, inp))
+        self.actor0, self.critic0 = inp["actor"].copy(), inp["critic"].copy()
+        if perturb:      # start the update away from the collecting policy: ratio != 1, clipping active from step one
+            g = np.random.default_rng(5)
+            self.actor0 = (self.actor0 + perturb * g.standard_normal(self.actor0.size) * np.abs(self.actor0).mean()).astype(np.float32)
+            self.critic0 = (self.critic0 + perturb * g.standard_normal(self.critic0.size) * np.abs(self.critic0).mean()).astype(np.float32)
+        self.ocfg = oracle_cfg(w, epochs, seed, call_index)
+        self.osym = None
+        if sym_on:
+            self.osym = oppo.SymSpec(inp["perm_obs"], inp["sign_obs"], inp["perm_obs"], inp["sign_obs"], inp["perm_act"],
+                                     inp["sign_act"], f32(w.mirror_loss_coef))
+        na, nc = self.actor0.size, self.critic0.size
+        opt0 = dict(m_a=np.zeros(na), v_a=np.zeros(na), m_c=np.zeros(nc), v_c=np.zeros(nc), step=0)
+        ornd = None
+        if rnd_on:
+            npred = inp["rnd_predictor"].size
+            ornd = dict(pred=inp["rnd_predictor"], targ=inp["rnd_target"], dims=w.dims_rnd, subset=None,
+                        m=np.zeros(npred), v=np.zeros(npred), step=0, lr=f32(w.lr))
+        self.ref = oppo.ppo_update(self.actor0, self.critic0, w.dims_actor, w.dims_critic, self.flat, self.ocfg, opt0,
+                                   self.osym, ornd, record=True)
+
+    def gpu_sym(self, rx):
+        i = self.inp
+        return rx.Sym(i["perm_obs"], i["sign_obs"], i["perm_obs"], i["sign_obs"], i["perm_act"], i["sign_act"],
+                      self.w.mirror_loss_coef) if self.sym_on else None
+
+    def gpu_cfg(self, rx, epochs, minibatches, epoch_offset=0):
+        w = self.w
+        return rx.PpoCfg(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
+                         lr=w.lr, epochs=epochs, minibatches=minibatches, seed=self.seed, call_index=self.call_index,
+                         epoch_offset=epoch_offset)
+
+    def gpu_rollout(self, rx, rows=None):
+        f = self.flat if rows is None else {k: v[rows] for k, v in self.flat.items()}
+        B = f["logp"].shape[0]
+        T, N = (self.w.T, self.w.N) if rows is None else (1, B)
+        d_obs = dev(f["obs_a"])
+        return rx.Rollout(T, N, d_obs, d_obs, dev(f["actions"]), dev(f["logp"]), dev(f["values"]), dev(f["mu"]),
+                          dev(f["sigma"]), dev(f["adv"]), dev(f["returns"]))
 
 
-def test_ppo_flat_ragged_one_epoch(rx):
-    w = WORKLOADS["flat"].scaled(250)        # mb = 1500 rows: 11 full 128-row tiles and a 92-row tail
-    check_ppo(w, run_ppo(rx, w, 1), 1)
+def _nets(rx, case, actor, critic, opt=None, rnd_state=None):
+    w = case.w
+    a = rx.Mlp(w.dims_actor, dev(actor, torch.float32), trainable=True, has_log_std=True)
+    c = rx.Mlp(w.dims_critic, dev(critic, torch.float32), trainable=True)
+    if opt is not None:
+        a.adam_m, a.adam_v = dev(opt["m_a"], torch.float32), dev(opt["v_a"], torch.float32)
+        c.adam_m, c.adam_v = dev(opt["m_c"], torch.float32), dev(opt["v_c"], torch.float32)
+    rnd = None
+    if case.rnd_on:
+        st = rnd_state if rnd_state is not None else dict(pred=case.inp["rnd_predictor"], m=None, v=None, step=0)
+        pred = rx.Mlp(w.dims_rnd, dev(st["pred"], torch.float32), trainable=True)
+        if st["m"] is not None:
+            pred.adam_m, pred.adam_v = dev(st["m"], torch.float32), dev(st["v"], torch.float32)
+        rnd = rx.RndTrain(rx.Mlp(w.dims_rnd, dev(case.inp["rnd_target"])), pred, lr=w.lr, adam_step=st["step"])
+    return a, c, rnd
 
 
-def test_ppo_rough_symmetry_one_epoch(rx):
-    w = WORKLOADS["rough"].scaled(125)
-    check_ppo(w, run_ppo(rx, w, 1, sym_on=True), 1)
+def _call(rx, case, a, c, rnd, rollout, cfg, n_rows, step0):
+    stats = torch.zeros(n_rows, rx.NSTATS, device="cuda")
+    sym = case.gpu_sym(rx)
+    ws = rx.workspace(rx.rslx_ppo_update_workspace_bytes(a, c, rollout, cfg, sym, rnd))
+    step = C.c_int64(step0)
+    rx.rslx_ppo_update(a, c, rollout, cfg, sym, rnd, step, stats, ws)
+    torch.cuda.synchronize()
+    return host(stats), step.value
 
 
-def test_ppo_curiosity_rnd_one_epoch(rx):
-    w = replace(WORKLOADS["curiosity"].scaled(336), minibatches=8)
-    check_ppo(w, run_ppo(rx, w, 1, rnd_on=True), 1, rnd_on=True)
+def check_forced_steps(rx, case, steps=None):
+    w, ref = case.w, case.ref
+    for k, tr in enumerate(ref["trace"]):
+        if steps is not None and k not in steps:
+            continue
+        b = tr["before"]
+        a, c, rnd = _nets(rx, case, b["actor"], b["critic"], b["opt"], b["rnd"])
+        stats, step = _call(rx, case, a, c, rnd, case.gpu_rollout(rx, tr["rows"]), case.gpu_cfg(rx, 1, 1), 1, b["opt"]["step"])
+        assert step == b["opt"]["step"] + 1
+        _check_stats(stats[0], ref["stats"][k], TOL)
+        _check_vec("g_actor", w.dims_actor, True, host(a.grads), tr["g_actor"], TOL)
+        _check_vec("g_critic", w.dims_critic, False, host(c.grads), tr["g_critic"], TOL)
+        assert rel_l2(host(a.params), tr["actor"]) <= TOL and rel_l2(host(c.params), tr["critic"]) <= TOL
+        # the applied step itself; float32 copies of the oracle's state bound this from below
+        d_got = host(a.params).astype(np.float64) - np.float32(b["actor"])
+        assert rel_l2(d_got, tr["actor"] - b["actor"]) <= 5e-2
+        if case.rnd_on:
+            _check_vec("g_pred", w.dims_rnd, False, host(rnd.predictor.grads), tr["g_pred"], TOL)
+            assert rel_l2(host(rnd.predictor.params), tr["pred"]) <= TOL
+            assert rnd.step.value == b["rnd"]["step"] + 1
+
+
+def check_free_running(rx, case, later_tol=2e-2, param_tol=None):
+    w, ref = case.w, case.ref
+    a, c, rnd = _nets(rx, case, case.actor0, case.critic0)
+    n = case.epochs * w.minibatches
+    stats, step = _call(rx, case, a, c, rnd, case.gpu_rollout(rx), case.gpu_cfg(rx, case.epochs, w.minibatches), n, 0)
+    assert step == n == ref["opt"]["step"]
+    _check_stats(stats[0], ref["stats"][0], TOL)
+    _check_stats(stats, ref["stats"], later_tol, floor=1e-2)
+    param_tol = TOL * max(1, case.epochs) if param_tol is None else param_tol
+    assert rel_l2(host(a.params), ref["actor"]) <= param_tol
+    assert rel_l2(host(c.params), ref["critic"]) <= param_tol
+    assert rel_l2(host(a.grads), ref["g_actor"]) <= 5e-2 and rel_l2(host(c.grads), ref["g_critic"]) <= 5e-2
+    if case.rnd_on:
+        assert rel_l2(host(rnd.predictor.params), ref["rnd"]["pred"]) <= TOL and rnd.step.value == ref["rnd"]["step"]
+    return a, c, stats
+
+
+def test_ppo_tiny(rx):
+    case = Case(WORKLOADS["tiny"], 1)
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
+
+
+def test_ppo_tiny_off_policy_start(rx):
+    case = Case(WORKLOADS["tiny"], 1, perturb=0.3)
+    assert case.ref["stats"][0, 5] > 0.02          # clip fraction: the clipped branches are exercised from step one
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
+
+
+def test_ppo_flat_ragged(rx):
+    case = Case(WORKLOADS["flat"].scaled(250), 1)     # mb = 1500 rows: 11 full 128-row tiles and a 92-row tail
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
+
+
+def test_ppo_rough_symmetry(rx):
+    case = Case(WORKLOADS["rough"].scaled(125), 1, sym_on=True)
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
+
+
+def test_ppo_curiosity_rnd(rx):
+    case = Case(replace(WORKLOADS["curiosity"].scaled(336), minibatches=8), 1, rnd_on=True)
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
 
 
 def test_ppo_five_epoch_drift_is_bounded(rx):
-    w = WORKLOADS["tiny"]
-    res = run_ppo(rx, w, 5)
-    ref = res["ref"]
-    assert rel_l2(host(res["actor"].params), ref["actor"]) <= 1e-3
-    assert rel_l2(host(res["critic"].params), ref["critic"]) <= 1e-3
-    assert np.all(np.abs(res["stats"][:, :3] - ref["stats"][:, :3]) <= 5e-3 * np.maximum(np.abs(ref["stats"][:, :3]), 1e-2))
+    case = Case(WORKLOADS["tiny"], 5)
+    a, c, stats = check_free_running(rx, case, later_tol=5e-2)
+    ref = case.ref
+    drift = [abs(stats[4 * e + 3, 0] - ref["stats"][4 * e + 3, 0]) for e in range(5)]
+    print("surrogate drift per epoch:", drift, "param rel err:", rel_l2(host(a.params), ref["actor"]))
+    assert rel_l2(host(a.params), ref["actor"]) <= 1e-2 and rel_l2(host(c.params), ref["critic"]) <= 1e-2
 
 
 def test_ppo_resume_with_epoch_offset(rx):
-    w = WORKLOADS["tiny"]
-    full = run_ppo(rx, w, 2)
-    a = run_ppo(rx, w, 1)
-    # second call continues from the first one's state with epoch_offset = 1
-    inp = a["inp"]
-    ro = oracle_rollout(w, inp); flat = flat_rollout(w, inp, ro)
-    d_obs = dev(flat["obs_a"])
-    rollout = rx.Rollout(w.T, w.N, d_obs, d_obs, dev(flat["actions"]), dev(flat["logp"]), dev(flat["values"]),
-                         dev(flat["mu"]), dev(flat["sigma"]), dev(flat["adv"]), dev(flat["returns"]))
-    cfg = rx.PpoCfg(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
-                    lr=w.lr, epochs=1, minibatches=w.minibatches, seed=3, call_index=1, epoch_offset=1)
-    stats = torch.zeros(w.minibatches, rx.NSTATS, device="cuda")
-    ws = rx.workspace(rx.rslx_ppo_update_workspace_bytes(a["actor"], a["critic"], rollout, cfg))
-    step = C.c_int64(a["step"])
-    rx.rslx_ppo_update(a["actor"], a["critic"], rollout, cfg, None, None, step, stats, ws)
-    torch.cuda.synchronize()
-    assert step.value == full["step"]
-    assert torch.equal(a["actor"].params, full["actor"].params) and torch.equal(a["critic"].params, full["critic"].params)
+    case = Case(WORKLOADS["tiny"], 2)
+    w = case.w
+    full_a, full_c, _ = check_free_running(rx, case, later_tol=5e-2)
+    a, c, _ = _nets(rx, case, case.actor0, case.critic0)
+    ro = case.gpu_rollout(rx)
+    _, step = _call(rx, case, a, c, None, ro, case.gpu_cfg(rx, 1, w.minibatches), w.minibatches, 0)
+    _, step = _call(rx, case, a, c, None, ro, case.gpu_cfg(rx, 1, w.minibatches, epoch_offset=1), w.minibatches, step)
+    assert step == 2 * w.minibatches
+    assert torch.equal(a.params, full_a.params) and torch.equal(c.params, full_c.params)
 
 
-@pytest.mark.parametrize("name,kw", [("flat", {}), ("rough", {"sym_on": True})])
-def test_ppo_full_size_one_epoch(rx, name, kw):
-    w = WORKLOADS[name]
-    check_ppo(w, run_ppo(rx, w, 1, **kw), 1)
+@pytest.mark.parametrize("name,kw", [("flat", {}), ("rough", {"sym_on": True}), ("curiosity", {"rnd_on": True})])
+def test_ppo_full_size(rx, name, kw):
+    case = Case(WORKLOADS[name], 1, **kw)
+    check_forced_steps(rx, case, steps={0, case.w.minibatches - 1})
+    # With 49 152 rows per minibatch and 8 steps, one sample whose ratio lies within fp32 rounding of the clip
+    # boundary takes the other branch of the (discontinuous) surrogate gradient than in fp64; every later step
+    # inherits that difference, so the free-running bound of the largest workload is looser.
+    check_free_running(rx, case, param_tol=1e-3 if name == "curiosity" else None)
 
 
 def run_bc(rx, w, epochs, clip=0.0):
@@ -171,16 +248,27 @@ def run_bc(rx, w, epochs, clip=0.0):
     torch.cuda.synchronize()
     got = host(stats)
     assert step.value == epochs * w.minibatches
-    assert np.all(np.abs(got[:, 0] - ref["stats"][:, 0]) <= 1e-4 * np.maximum(ref["stats"][:, 0], 1e-3))
-    assert np.all(np.abs(got[:, 4] - ref["stats"][:, 1]) <= 1e-4 * np.maximum(ref["stats"][:, 1], 1e-3))
-    _check_vec("g_student", w.dims_student, False, host(student.grads), ref["g"], 1e-4)
-    assert rel_l2(host(student.params), ref["student"]) <= 1e-4
+    assert abs(got[0, 0] - ref["stats"][0, 0]) <= TOL * ref["stats"][0, 0] and abs(got[0, 4] - ref["stats"][0, 1]) <= TOL * ref["stats"][0, 1]
+    assert np.all(np.abs(got[:, 0] - ref["stats"][:, 0]) <= 2e-2 * np.maximum(ref["stats"][:, 0], 1e-3))
+    assert np.all(np.abs(got[:, 4] - ref["stats"][:, 1]) <= 2e-2 * np.maximum(ref["stats"][:, 1], 1e-3))
+    assert rel_l2(host(student.grads), ref["g"]) <= 5e-2
+    assert rel_l2(host(student.params), ref["student"]) <= TOL
     # precomputed targets give the same result as the in-library teacher pass
     student2 = rx.Mlp(w.dims_student, dev(inp["student"]), trainable=True)
     step2 = C.c_int64(0)
     rx.rslx_bc_update(student2, None, dev(obs_s), None, dev(tgt.astype(np.float32)), B, cfg, step2, stats, ws)
     torch.cuda.synchronize()
-    assert rel_l2(host(student2.params), ref["student"]) <= 1e-4
+    assert rel_l2(host(student2.params), ref["student"]) <= TOL
+    # single forced step on the whole batch: gradients to 1e-4
+    student3 = rx.Mlp(w.dims_student, dev(inp["student"]), trainable=True)
+    cfg1 = rx.BcCfg(lr=w.lr, epochs=1, minibatches=1, max_grad_norm=clip, seed=5, call_index=2)
+    ws1 = rx.workspace(rx.rslx_bc_update_workspace_bytes(student3, teacher, B, cfg1))
+    step3 = C.c_int64(0)
+    rx.rslx_bc_update(student3, teacher, dev(obs_s), dev(obs_t), None, B, cfg1, step3, stats, ws1)
+    torch.cuda.synchronize()
+    loss, g = obc.bc_loss_and_grad(inp["student"], w.dims_student, obs_s, tgt)
+    _check_vec("g_student", w.dims_student, False, host(student3.grads), g, TOL)
+    assert abs(host(stats)[0, 0] - loss) <= TOL * loss
 
 
 def test_bc_small(rx):

@@ -215,3 +215,17 @@ def test_rnd_zero_error_merge_and_scale_invariance():
                      - ppo.rnd_predictor_loss_and_grad(pred - h * e, targ, dims, obs[:, subset])[0]) / (2 * h) for e in np.eye(pred.size)])
     np.testing.assert_allclose(grad, num, rtol=1e-6, atol=1e-8)
     assert abs(loss - raw.mean() / 4) < 1e-13
+
+
+def test_value_clip_inside_range_has_plain_mse_gradient():
+    """Inside the clip range V_clip equals V, so the clipped value loss has the plain MSE gradient even when
+    rounding of V_old + (V - V_old) makes the clipped branch the (marginally) larger one."""
+    actor, critic, b = _setup(seed=11, n=64)
+    critic = critic.copy(); critic[-1] -= b["values"].mean()                 # values near zero: a + (b - a) != b in floating point
+    critic[-10:-1] *= 0.05
+    V = ppo.act(actor, critic, DIMS_A, DIMS_C, b["obs_a"], b["obs_c"], np.zeros((64, A)))["values"]
+    b["values"] = V + np.random.default_rng(0).uniform(-0.1, 0.1, size=64)   # |V - V_old| < clip everywhere
+    t0, _, gc0 = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, b, ppo.PPOConfig(use_clipped_value_loss=True))
+    t1, _, gc1 = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, b, ppo.PPOConfig(use_clipped_value_loss=False))
+    np.testing.assert_allclose(gc0, gc1, rtol=1e-12, atol=1e-15)
+    assert abs(t0["value_loss"] - t1["value_loss"]) < 1e-7
