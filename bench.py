@@ -1,0 +1,206 @@
+"""Benchmark of the whole PPO hot path on one MI355X.
+
+One step = one training iteration of the "flat" workload (N = 4096 environments, T = 24, obs 48, actions 12,
+actor and critic [512, 256, 128]): T act() calls + the bootstrap value + GAE + the 5-epoch x 4-minibatch PPO
+update, all inputs resident in HBM.  Prints ONE JSON line; `value` is transitions (T*N) per second of the
+whole iteration.  The roofline entry is measured live with HIP events recorded by the library around its
+matrix-core launches; the CPU baseline times the fp64 oracle on a bounded sample of the same workload.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_MFMA_PEAK_TFLOPS = 157.3
+HBM_PEAK_GBS = 8000.0
+
+
+def flops_per_sample_pass(dims_a, dims_c):
+    """Forward + weight gradient + input gradient (none into the observations), 2 flops per multiply-add."""
+    total = 0
+    for dims in (dims_a, dims_c):
+        for l, (i, o) in enumerate(zip(dims[:-1], dims[1:])):
+            total += 2 * i * o * (3 if l > 0 else 2)
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="flat")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (how the path would shard is described in DESIGN.md)")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2509_10771_amd as rx
+    from workloads import WORKLOADS, make_inputs
+
+    rx.rslx_device_check()
+    w = WORKLOADS[args.workload]
+    inp = make_inputs(w)
+    T, N, A, B = w.T, w.N, w.A, w.B
+    dev = lambda x: torch.as_tensor(np.ascontiguousarray(x)).cuda()
+
+    actor = rx.Mlp(w.dims_actor, dev(inp["actor"]), trainable=True, has_log_std=True)
+    critic = rx.Mlp(w.dims_critic, dev(inp["critic"]), trainable=True)
+    obs, rewards, dones = dev(inp["obs"]), dev(inp["rewards"]), dev(inp["dones"])
+    actions, mu, sigma = (torch.empty(T, N, A, device="cuda") for _ in range(3))
+    logp, values, adv, ret = (torch.empty(T, N, device="cuda") for _ in range(4))
+    last = torch.empty(N, device="cuda")
+    sym = rx.Sym(inp["perm_obs"], inp["sign_obs"], inp["perm_obs"], inp["sign_obs"], inp["perm_act"], inp["sign_act"],
+                 w.mirror_loss_coef) if w.symmetry else None
+    rnd = None
+    if w.rnd:
+        rnd_t = rx.Mlp(w.dims_rnd, dev(inp["rnd_target"]))
+        rnd_p = rx.Mlp(w.dims_rnd, dev(inp["rnd_predictor"]), trainable=True)
+        rnd = rx.RndTrain(rnd_t, rnd_p, lr=w.lr)
+        running = dev(np.array([0.0, 1.0, 1e-4], np.float32))
+        r_int = torch.empty(N, device="cuda")
+        rws = rx.workspace(rx.rslx_rnd_workspace_bytes(rnd_t, N))
+        rew_work = torch.empty_like(rewards)
+    rollout = rx.Rollout(T, N, obs[:T], obs[:T], actions, logp, values, mu, sigma, adv, ret)
+    cfg_kw = dict(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
+                  lr=w.lr, epochs=w.epochs, minibatches=w.minibatches, seed=20250910)
+    stats = torch.zeros(w.epochs * w.minibatches, rx.NSTATS, device="cuda")
+    aws = rx.workspace(rx.rslx_act_workspace_bytes(actor, critic, N))
+    gws = rx.workspace(rx.rslx_gae_workspace_bytes(T, N))
+    uws = rx.workspace(rx.rslx_ppo_update_workspace_bytes(actor, critic, rollout, rx.PpoCfg(**cfg_kw), sym, rnd))
+    adam_step = ctypes.c_int64(0)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    phase = {"act": [], "gae": [], "update": []}
+
+    def step(it, timed):
+        e = [ev() for _ in range(4)] if timed else None
+        if timed:
+            e[0].record()
+        rew = rewards
+        if w.rnd:
+            rew_work.copy_(rewards)
+            rew = rew_work
+        for t in range(T):
+            rx.rslx_act(actor, critic, obs[t], obs[t], N, 20250910, it * T + t, None, actions[t], logp[t], values[t],
+                        mu[t], sigma[t], 0, aws)
+            if w.rnd:
+                rx.rslx_rnd(rnd_t, rnd_p, obs[t], N, w.Da, None, w.Da, running, w.rnd_weight, 1, r_int, rew[t], rws)
+        rx.rslx_act(None, critic, None, obs[T], N, 0, 0, None, None, None, last, None, None, rx.ACT_VALUES_ONLY, aws)
+        if timed:
+            e[1].record()
+        rx.rslx_gae(rew, values, last, dones, None, T, N, w.gamma, w.lam, 1, adv, ret, gws)
+        if timed:
+            e[2].record()
+        rx.rslx_ppo_update(actor, critic, rollout, rx.PpoCfg(call_index=it, **cfg_kw), sym, rnd, adam_step, stats, uws)
+        if timed:
+            e[3].record()
+        return e
+
+    for it in range(args.warmup):
+        step(it, False)
+    torch.cuda.synchronize()
+    rx.rslx_trace_begin(1 << 16)
+    t0 = time.perf_counter()
+    evs = [step(args.warmup + it, True) for it in range(args.steps)]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    trace = rx.rslx_trace_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    for e in evs:
+        phase["act"].append(e[0].elapsed_time(e[1])); phase["gae"].append(e[1].elapsed_time(e[2]))
+        phase["update"].append(e[2].elapsed_time(e[3]))
+    med = {k: float(np.median(v)) for k, v in phase.items()}
+    assert torch.isfinite(actor.params).all() and torch.isfinite(stats).all(), "training state became non-finite"
+
+    # ---- roofline of the dominant kernel, from the library's own HIP-event trace of the timed region ----
+    kinds = {}
+    for name, flops, nbytes, ms in trace:
+        k = kinds.setdefault(name, dict(n=0, ms=0.0, flops=0.0, bytes=0.0))
+        k["n"] += 1; k["ms"] += ms; k["flops"] += flops; k["bytes"] += nbytes
+    dom = max(kinds, key=lambda k: kinds[k]["ms"])
+    d = kinds[dom]
+    achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), traffic=None,
+                    launches=d["n"], avg_launch_us=round(d["ms"] * 1e3 / d["n"], 2),
+                    flops_per_launch=d["flops"] / d["n"])
+    breakdown = {k: dict(launches=v["n"], total_ms_per_step=round(v["ms"] / args.steps, 4),
+                         tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["flops"] else None,
+                         gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["bytes"] else None)
+                 for k, v in sorted(kinds.items(), key=lambda kv: -kv[1]["ms"])}
+
+    sample_passes = w.epochs * B * (2 if w.symmetry else 1)
+    upd_flops = flops_per_sample_pass(w.dims_actor, w.dims_critic) * sample_passes
+    result = {
+        "metric": "PPO update transitions/sec + act() env-steps/sec at 4096 envs, 1 GPU",
+        "value": round(B / (ms_per_step * 1e-3), 1),
+        "unit": "transitions/s (whole iteration: 24 act + GAE + 5x4 PPO update)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: N=%d envs, T=%d, obs %d, act %d, actor/critic %s ELU, %d epochs x %d minibatches"
+                   % (w.name, N, T, w.Da, A, list(w.hidden), w.epochs, w.minibatches)},
+        "update_transitions_per_s": round(B / (med["update"] * 1e-3), 1),
+        "update_sample_passes_per_s": round(sample_passes / (med["update"] * 1e-3), 1),
+        "update_tflops": round(upd_flops / (med["update"] * 1e-3) / 1e12, 2),
+        "act_env_steps_per_s": round((T + 1) * N / (med["act"] * 1e-3), 1),
+        "phase_ms": {k: round(v, 4) for k, v in med.items()},
+        "roofline": roofline,
+        "kernels": breakdown,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, inp):
+    """The fp64 oracle on the host cores: the full act loop and GAE, and ONE of the update epochs (scaled up)."""
+    import numpy as np
+    from oracle import ppo as oppo, gae as ogae, rng as orng
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+    except Exception:
+        cores = os.cpu_count()
+    T, N, A, B = w.T, w.N, w.A, w.B
+    t0 = time.perf_counter()
+    acts, logp, vals, mu, sg = [], [], [], [], []
+    for t in range(T):
+        o = oppo.act(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, inp["obs"][t], inp["obs"][t], orng.act_noise(1, t, N, A))
+        acts.append(o["actions"]); logp.append(o["logp"]); vals.append(o["values"]); mu.append(o["mu"]); sg.append(o["sigma"])
+    lastv = oppo.act(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, inp["obs"][T], inp["obs"][T], np.zeros((N, A)))["values"]
+    t_act = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    adv, ret = ogae.gae(inp["rewards"], np.stack(vals), lastv, inp["dones"], w.gamma, w.lam)
+    advn = ogae.normalize_advantages(adv)
+    t_gae = time.perf_counter() - t0
+    flat = dict(obs_a=inp["obs"][:T].reshape(B, -1), obs_c=inp["obs"][:T].reshape(B, -1), actions=np.stack(acts).reshape(B, A),
+                logp=np.stack(logp).reshape(B), values=np.stack(vals).reshape(B), mu=np.stack(mu).reshape(B, A),
+                sigma=np.stack(sg).reshape(B, A), adv=advn.reshape(B), returns=ret.reshape(B))
+    cfg = oppo.PPOConfig(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
+                         lr=w.lr, epochs=1, minibatches=w.minibatches, seed=1)
+    na, nc = inp["actor"].size, inp["critic"].size
+    sym = None
+    if w.symmetry:
+        sym = oppo.SymSpec(inp["perm_obs"], inp["sign_obs"], inp["perm_obs"], inp["sign_obs"], inp["perm_act"], inp["sign_act"], w.mirror_loss_coef)
+    t0 = time.perf_counter()
+    oppo.ppo_update(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, flat, cfg,
+                    dict(m_a=np.zeros(na), v_a=np.zeros(na), m_c=np.zeros(nc), v_c=np.zeros(nc), step=0), sym)
+    t_epoch = time.perf_counter() - t0
+    total = t_act + t_gae + w.epochs * t_epoch
+    return {"value": round(B / total, 1), "unit": "transitions/s (whole iteration)", "cores": int(cores), "kind": "oracle",
+            "sample": "fp64 numpy oracle: full act loop (%.2f s) and GAE (%.3f s) timed; 1 of %d update epochs timed (%.2f s) and multiplied by %d"
+                      % (t_act, t_gae, w.epochs, t_epoch, w.epochs)}
+
+
+if __name__ == "__main__":
+    main()

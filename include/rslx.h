@@ -142,6 +142,25 @@ const char* rslx_last_error(void);
 /* RSLX_OK if the current HIP device is a gfx950 part, RSLX_ERR_UNSUPPORTED / RSLX_ERR_HIP otherwise. */
 int32_t rslx_device_check(void);
 
+/* ---- launch trace (measurement aid) ---------------------------------------------------------- */
+
+/* While a trace is open, every kernel launch of the library is bracketed by a pair of HIP events on
+ * its stream and tagged with its algorithmic work.  rslx_trace_begin clears any earlier trace and
+ * keeps at most max_records launches.  rslx_trace_end stops recording, WAITS on the host for the
+ * recorded events, and copies up to `cap` records (launch order) to `out` (host); *n_out receives the
+ * number recorded.  Calling it with out == NULL only reports the count and keeps the records for a
+ * second call.  `kernel` names a launch site: "gemm_<fwd|dx|dw>_<BM>x<BN>" are the matrix-core
+ * kernels (flops = 2 M N K summed over the grouped problems), the others are streaming kernels
+ * (bytes = algorithmic HBM bytes).  Not thread-safe; tracing costs two event records per launch. */
+typedef struct rslx_trace_record {
+  char kernel[48];
+  double flops;
+  double bytes;
+  float ms;
+} rslx_trace_record;
+int32_t rslx_trace_begin(int32_t max_records);
+int32_t rslx_trace_end(rslx_trace_record* out, int32_t cap, int32_t* n_out);
+
 /* ---- permutation of one epoch (update step U0) --------------------------------------- */
 
 /* Shuffled minibatch order (paper Sec. 2.1: multi-epoch minibatch updates; the generator is this

@@ -10,7 +10,7 @@ __all__ = [
     "rslx_act", "rslx_act_workspace_bytes", "rslx_gae", "rslx_gae_workspace_bytes",
     "rslx_adam_step", "rslx_adam_workspace_bytes", "rslx_ppo_update", "rslx_ppo_update_workspace_bytes",
     "rslx_bc_update", "rslx_bc_update_workspace_bytes", "rslx_sym_augment", "rslx_rnd", "rslx_rnd_workspace_bytes",
-    "ACT_DETERMINISTIC", "ACT_VALUES_ONLY", "EXPORTS",
+    "ACT_DETERMINISTIC", "ACT_VALUES_ONLY", "EXPORTS", "rslx_trace_begin", "rslx_trace_end",
 ]
 
 MAX_LAYERS = 8
@@ -22,7 +22,7 @@ EXPORTS = [
     "rslx_version", "rslx_last_error", "rslx_device_check", "rslx_permutation_workspace_bytes", "rslx_permutation",
     "rslx_act_workspace_bytes", "rslx_act", "rslx_gae_workspace_bytes", "rslx_gae", "rslx_adam_workspace_bytes",
     "rslx_adam_step", "rslx_ppo_update_workspace_bytes", "rslx_ppo_update", "rslx_bc_update_workspace_bytes",
-    "rslx_bc_update", "rslx_sym_augment", "rslx_rnd_workspace_bytes", "rslx_rnd",
+    "rslx_bc_update", "rslx_sym_augment", "rslx_rnd_workspace_bytes", "rslx_rnd", "rslx_trace_begin", "rslx_trace_end",
 ]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librslx.so")
@@ -33,7 +33,7 @@ class RslxError(RuntimeError):
 
 
 if not os.path.exists(_LIB_PATH):
-    raise ImportError("librslx.so is missing at %s: build it with `python -m paper_2509_10771_amd.build`; "
+    raise ImportError("librslx.so is missing at %s: build it with `python paper_2509_10771_amd/build.py`; "
                       "there is no fallback path" % _LIB_PATH)
 lib = C.CDLL(_LIB_PATH)
 
@@ -77,6 +77,10 @@ class _CBcCfg(C.Structure):
                 ("seed", C.c_uint64), ("call_index", C.c_uint64), ("epoch_offset", C.c_int32)]
 
 
+class _CTraceRecord(C.Structure):
+    _fields_ = [("kernel", C.c_char * 48), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
+
+
 def _sig(name, restype, argtypes):
     f = getattr(lib, name)
     f.restype = restype
@@ -109,6 +113,10 @@ _sig("rslx_sym_augment", C.c_int32, [_P(_CSym), _vp, _vp, C.c_int32, C.c_int32, 
 _sig("rslx_rnd_workspace_bytes", C.c_size_t, [_P(_CMlp), C.c_int32])
 _sig("rslx_rnd", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, C.c_int32, C.c_int32, _vp, C.c_int32, _vp, C.c_float, C.c_int32,
                              _vp, _vp, _vp, C.c_size_t, _vp])
+
+
+_sig("rslx_trace_begin", C.c_int32, [C.c_int32])
+_sig("rslx_trace_end", C.c_int32, [_P(_CTraceRecord), C.c_int32, _P(C.c_int32)])
 
 
 def _check(rc, what):
@@ -327,3 +335,16 @@ def rslx_rnd(target, predictor, obs, N, D, subset_idx, n_subset, running, weight
     ct, cp = target.c, predictor.c
     _check(lib.rslx_rnd(_ref(ct), _ref(cp), _ptr(obs), N, D, _ptr(subset_idx), n_subset, _ptr(running), weight,
                         int(update_stats), _ptr(r_int_out), _ptr(rewards_inout), _ptr(ws), ws.numel(), _stream()), "rslx_rnd")
+
+
+def rslx_trace_begin(max_records):
+    _check(lib.rslx_trace_begin(max_records), "rslx_trace_begin")
+
+
+def rslx_trace_end():
+    """Returns [(kernel, flops, bytes, ms)] in launch order."""
+    n = C.c_int32(0)
+    _check(lib.rslx_trace_end(None, 0, C.byref(n)), "rslx_trace_end")
+    buf = (_CTraceRecord * max(n.value, 1))()
+    _check(lib.rslx_trace_end(buf, n.value, C.byref(n)), "rslx_trace_end")
+    return [(buf[i].kernel.decode(), buf[i].flops, buf[i].bytes, buf[i].ms) for i in range(n.value)]

@@ -1,4 +1,5 @@
-"""Compile librslx.so (HIP, gfx950) in-tree.  Run as `python -m paper_2509_10771_amd.build`."""
+"""Compile librslx.so (HIP, gfx950) in-tree.  Run as `python paper_2509_10771_amd/build.py` (the script does not
+import the package, so it also works when no library, or a stale one, is present)."""
 import os
 import subprocess
 import sys

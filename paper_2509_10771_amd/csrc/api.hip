@@ -166,33 +166,61 @@ int32_t forward_nets(const NetJob* jobs, int count, hipStream_t stream) {
   return RSLX_OK;
 }
 
+// Split plan of one trained network's weight gradients: layer l is reduced over `split[l]` row chunks of
+// `chunk[l]` rows; its partial results (W then b, `size[l]` floats per split) start at `part_off[l]`.
+struct SplitPlan {
+  int32_t split[RSLX_MAX_LAYERS];
+  int32_t chunk[RSLX_MAX_LAYERS];
+  int32_t big[RSLX_MAX_LAYERS];
+  int64_t size[RSLX_MAX_LAYERS];
+  int64_t part_off[RSLX_MAX_LAYERS];
+  int64_t total = 0;       // floats
+  int32_t blocks = 0;      // workgroups of the reduction = entries of the squared-norm list
+};
+
+// Enough workgroups to keep about four resident per CU (256 CUs), but at least 128 rows per split.
+constexpr int DW_TARGET_WGS = 1024;
+
+SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group) {
+  SplitPlan p;
+  for (int l = 0; l < n.n_layers; ++l) {
+    const int M = n.dims[l], N = n.dims[l + 1];
+    const int tiles_big = ((M + 127) / 128) * ((N + 127) / 128);
+    p.big[l] = (tiles_big * group >= 16) ? 1 : 0;
+    const int tiles = gemm_dw_tiles(M, N, p.big[l] != 0);
+    int s = (DW_TARGET_WGS + tiles * group - 1) / (tiles * group);
+    const int smax = rows / 128 > 1 ? rows / 128 : 1;
+    if (s > smax) s = smax;
+    if (s < 1) s = 1;
+    int c = (rows + s - 1) / s;
+    c = (c + 15) / 16 * 16;
+    s = (rows + c - 1) / c;            // drop splits that would be empty
+    p.split[l] = s;
+    p.chunk[l] = c;
+    p.size[l] = (int64_t)M * N + N;
+    p.part_off[l] = p.total;
+    p.total += (p.size[l] * s + 3) / 4 * 4;
+    p.blocks += (int32_t)((p.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
+  }
+  return p;
+}
+
 struct BwdJob {
   const rslx_mlp* net;
   XView x;
   int32_t rows;
   NetBufs* bufs;
   const float* d_out;    // [rows, dims[L]]
-  float* partials;       // n_split buffers of split_stride floats, flat gradient layout
-  int64_t split_stride;
+  float* partials;       // split partials, laid out by `plan`
+  const SplitPlan* plan;
 };
-
-int choose_split(int32_t rows) {
-  int s = rows / 1536;
-  if (s < 1) s = 1;
-  if (s > 16) s = 16;
-  return s;
-}
-int chunk_for(int32_t rows, int n_split) {
-  int c = (rows + n_split - 1) / n_split;
-  return (c + 15) / 16 * 16;
-}
 
 // Backward of up to two networks of equal depth: per layer one grouped weight-gradient launch (split over
 // rows, partial sums) and one grouped input-gradient launch.
-int32_t backward_nets(const BwdJob* jobs, int count, int n_split, hipStream_t stream) {
+int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
   if (count == 2 && jobs[0].net->n_layers != jobs[1].net->n_layers) {
-    RSLX_TRY(backward_nets(jobs, 1, n_split, stream));
-    return backward_nets(jobs + 1, 1, n_split, stream);
+    RSLX_TRY(backward_nets(jobs, 1, stream));
+    return backward_nets(jobs + 1, 1, stream);
   }
   const int L = jobs[0].net->n_layers;
   for (int l = L - 1; l >= 0; --l) {
@@ -209,12 +237,14 @@ int32_t backward_nets(const BwdJob* jobs, int count, int n_split, hipStream_t st
         p.lda = n.dims[l];
       }
       p.B = dz; p.ldb = n.dims[l + 1];
-      p.C = jobs[i].partials + layer_offset(n, l); p.ldc = n.dims[l + 1];
+      const SplitPlan& sp = *jobs[i].plan;
+      p.C = jobs[i].partials + sp.part_off[l]; p.ldc = n.dims[l + 1];
       p.M = n.dims[l]; p.N = n.dims[l + 1]; p.K = jobs[i].rows;
-      p.n_split = n_split;
-      p.k_chunk = chunk_for(jobs[i].rows, n_split);
-      p.split_stride = jobs[i].split_stride;
+      p.n_split = sp.split[l];
+      p.k_chunk = sp.chunk[l];
+      p.split_stride = sp.size[l];
       p.bias_off = n.dims[l] * n.dims[l + 1];
+      p.dw_big = sp.big[l];
       p.a_vec = (p.M % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
       p.b_vec = (p.N % 4 == 0 && aligned16(p.B)) ? 1 : 0;
       bw.p[i] = p;
@@ -254,10 +284,71 @@ float bias_correction(float beta, int64_t t) { return (float)(1.0 - std::pow((do
 
 int64_t round4(int64_t n) { return (n + 3) / 4 * 4; }
 
+struct TraceRec {
+  hipEvent_t a, b;
+  char kernel[48];
+  double flops, bytes;
+};
+bool g_trace_on = false;
+size_t g_trace_cap = 0;
+std::vector<TraceRec> g_trace;
+
 }  // namespace
+
+namespace rslx {
+void trace_open(hipStream_t stream, const char* kernel, double flops, double bytes) {
+  if (!g_trace_on || g_trace.size() >= g_trace_cap) return;
+  TraceRec r;
+  if (hipEventCreate(&r.a) != hipSuccess) return;
+  if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+  snprintf(r.kernel, sizeof r.kernel, "%s", kernel);
+  r.flops = flops; r.bytes = bytes;
+  (void)hipEventRecord(r.a, stream);
+  g_trace.push_back(r);
+}
+void trace_close(hipStream_t stream) {
+  if (!g_trace_on || g_trace.empty()) return;
+  (void)hipEventRecord(g_trace.back().b, stream);
+}
+}  // namespace rslx
 
 // ======================================================================================================
 extern "C" {
+
+int32_t rslx_trace_begin(int32_t max_records) {
+  if (max_records < 1) return fail(RSLX_ERR_INVALID_ARG, "rslx_trace_begin: max_records = %d", max_records);
+  for (TraceRec& r : g_trace) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_trace.clear();
+  g_trace.reserve(max_records);
+  g_trace_cap = (size_t)max_records;
+  g_trace_on = true;
+  return RSLX_OK;
+}
+
+int32_t rslx_trace_end(rslx_trace_record* out, int32_t cap, int32_t* n_out) {
+  g_trace_on = false;
+  if (!n_out) return fail(RSLX_ERR_INVALID_ARG, "rslx_trace_end: null n_out");
+  int32_t n = 0;
+  for (TraceRec& r : g_trace) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(r.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+    if (e != hipSuccess) return fail(RSLX_ERR_HIP, "rslx_trace_end: %s", hipGetErrorString(e));
+    if (out && n < cap) {
+      memcpy(out[n].kernel, r.kernel, sizeof r.kernel);
+      out[n].flops = r.flops; out[n].bytes = r.bytes; out[n].ms = ms;
+    }
+    ++n;
+  }
+  *n_out = n;
+  if (out) {
+    for (TraceRec& r : g_trace) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    g_trace.clear();
+  } else {
+    g_trace_on = false;
+  }
+  return RSLX_OK;
+}
 
 int32_t rslx_version(void) { return 100; }
 
@@ -413,13 +504,13 @@ struct TrainBufs {        // per trained network
   NetBufs act;
   float* d_out = nullptr;
   float* partials = nullptr;
-  int64_t stride = 0;
+  SplitPlan plan;
   double* sumsq = nullptr;
   int n_sumsq = 0;
 };
 
 struct PpoPlan {
-  int32_t B, mb, rows, n_split;
+  int32_t B, mb, rows;
   int32_t* perms = nullptr;          // [E, B]
   void* perm_ws = nullptr;
   TrainBufs actor, critic, pred;
@@ -430,12 +521,12 @@ struct PpoPlan {
   size_t bytes = 0;
 };
 
-void carve_train(Carver& c, const rslx_mlp& n, int64_t rows, int n_split, TrainBufs& t) {
+void carve_train(Carver& c, const rslx_mlp& n, int32_t rows, int group, TrainBufs& t) {
   carve_net(c, n, rows, true, t.act);
   t.d_out = c.take<float>((size_t)rows * n.dims[n.n_layers]);
-  t.stride = round4(param_count(n));
-  t.partials = c.take<float>((size_t)t.stride * n_split);
-  t.n_sumsq = reduce_num_blocks(weight_count(n));
+  t.plan = plan_splits(n, rows, group);
+  t.partials = c.take<float>((size_t)t.plan.total);
+  t.n_sumsq = t.plan.blocks;
 }
 
 void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
@@ -443,17 +534,16 @@ void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rs
   p.B = ro->T * ro->N;
   p.mb = p.B / cfg->minibatches;
   p.rows = sym ? 2 * p.mb : p.mb;
-  p.n_split = choose_split(p.rows);
   p.perms = c.take<int32_t>((size_t)cfg->epochs * p.B);
   p.perm_ws = c.take<char>(perm_workspace_bytes(p.B));
-  carve_train(c, *actor, p.rows, p.n_split, p.actor);
-  carve_train(c, *critic, p.rows, p.n_split, p.critic);
+  carve_train(c, *actor, p.rows, 2, p.actor);
+  carve_train(c, *critic, p.rows, 2, p.critic);
   p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 1);
   p.actor.sumsq = p.sumsq_all;
   p.critic.sumsq = p.sumsq_all + p.actor.n_sumsq;
   p.loss_partials = c.take<double>((size_t)ppo_loss_num_blocks(p.mb) * (PPO_NPART_FIXED + ro->A));
   if (rnd) {
-    carve_train(c, *rnd->predictor, p.mb, choose_split(p.mb), p.pred);
+    carve_train(c, *rnd->predictor, p.mb, 1, p.pred);
     p.pred.sumsq = c.take<double>(p.pred.n_sumsq);
     carve_net(c, *rnd->target, p.mb, false, p.targ);
     const int K = rnd->target->dims[rnd->target->n_layers];
@@ -503,8 +593,22 @@ int32_t ppo_validate(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_r
 }
 
 // reduce split partials of one network into grads (weights and biases only) + squared-norm blocks
-int32_t reduce_net(const rslx_mlp& n, const TrainBufs& t, int n_split, hipStream_t s) {
-  RSLX_HIP(launch_reduce_partials(t.partials, n_split, t.stride, weight_count(n), n.grads, t.sumsq, s));
+int32_t reduce_net(const rslx_mlp& n, const TrainBufs& t, hipStream_t s) {
+  ReduceArgs a;
+  memset(&a, 0, sizeof a);
+  a.partials = t.partials; a.grads = n.grads; a.sumsq_blocks = t.sumsq;
+  a.n_layers = n.n_layers;
+  int blocks = 0;
+  for (int l = 0; l < n.n_layers; ++l) {
+    a.split[l] = t.plan.split[l];
+    a.size[l] = t.plan.size[l];
+    a.part_off[l] = t.plan.part_off[l];
+    a.grad_off[l] = layer_offset(n, l);
+    a.block_start[l] = blocks;
+    blocks += (int)((t.plan.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
+  }
+  a.block_start[n.n_layers] = blocks;
+  RSLX_HIP(launch_reduce_partials(a, s));
   return RSLX_OK;
 }
 
@@ -574,11 +678,11 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
                                       cfg->entropy_coef, actor->grads + weight_count(*actor), stats_row,
                                       p.sumsq_all + p.actor.n_sumsq + p.critic.n_sumsq, s));
 
-      BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.partials, p.actor.stride},
-                      BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.partials, p.critic.stride}};
-      RSLX_TRY(backward_nets(bj, 2, p.n_split, s));
-      RSLX_TRY(reduce_net(*actor, p.actor, p.n_split, s));
-      RSLX_TRY(reduce_net(*critic, p.critic, p.n_split, s));
+      BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.partials, &p.actor.plan},
+                      BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.partials, &p.critic.plan}};
+      RSLX_TRY(backward_nets(bj, 2, s));
+      RSLX_TRY(reduce_net(*actor, p.actor, s));
+      RSLX_TRY(reduce_net(*critic, p.critic, s));
 
       const int64_t t = *adam_step + 1;
       AdamArgs aa;
@@ -606,10 +710,9 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
         RSLX_HIP(launch_mse(p.pred.act.out[pr.n_layers - 1], p.targ.out[pr.n_layers - 1], nullptr, p.mb, K,
                             p.pred.d_out, p.mse_partials, s));
         RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)p.mb * K, stats_row + RSLX_STAT_RND_LOSS, s));
-        const int ns = choose_split(p.mb);
-        BwdJob rb{&pr, xr, p.mb, &p.pred.act, p.pred.d_out, p.pred.partials, p.pred.stride};
-        RSLX_TRY(backward_nets(&rb, 1, ns, s));
-        RSLX_TRY(reduce_net(pr, p.pred, ns, s));
+        BwdJob rb{&pr, xr, p.mb, &p.pred.act, p.pred.d_out, p.pred.partials, &p.pred.plan};
+        RSLX_TRY(backward_nets(&rb, 1, s));
+        RSLX_TRY(reduce_net(pr, p.pred, s));
         const int64_t tr = *rnd->adam_step + 1;
         AdamArgs ar;
         memset(&ar, 0, sizeof ar);
@@ -630,7 +733,7 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
 // ---- behaviour cloning ---------------------------------------------------------------------------------------------
 namespace {
 struct BcPlan {
-  int32_t mb, n_split;
+  int32_t mb;
   int32_t* perms = nullptr;
   void* perm_ws = nullptr;
   TrainBufs student;
@@ -642,10 +745,9 @@ struct BcPlan {
 
 void bc_plan(Carver& c, const rslx_mlp* student, const rslx_mlp* teacher, int32_t B, const rslx_bc_cfg* cfg, BcPlan& p) {
   p.mb = B / cfg->minibatches;
-  p.n_split = choose_split(p.mb);
   p.perms = c.take<int32_t>((size_t)cfg->epochs * B);
   p.perm_ws = c.take<char>(perm_workspace_bytes(B));
-  carve_train(c, *student, p.mb, p.n_split, p.student);
+  carve_train(c, *student, p.mb, 1, p.student);
   p.student.sumsq = c.take<double>(p.student.n_sumsq);
   const int A = student->dims[student->n_layers];
   if (teacher) {
@@ -720,9 +822,9 @@ int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* 
       RSLX_TRY(forward_nets(&fj, 1, s));
       RSLX_HIP(launch_mse(p.student.act.out[Ls - 1], targets, idx, p.mb, A, p.student.d_out, p.mse_partials, s));
       RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)p.mb * A, stats_row, s));
-      BwdJob bj{student, xs, p.mb, &p.student.act, p.student.d_out, p.student.partials, p.student.stride};
-      RSLX_TRY(backward_nets(&bj, 1, p.n_split, s));
-      RSLX_TRY(reduce_net(*student, p.student, p.n_split, s));
+      BwdJob bj{student, xs, p.mb, &p.student.act, p.student.d_out, p.student.partials, &p.student.plan};
+      RSLX_TRY(backward_nets(&bj, 1, s));
+      RSLX_TRY(reduce_net(*student, p.student, s));
       const int64_t t = *adam_step + 1;
       AdamArgs aa;
       memset(&aa, 0, sizeof aa);

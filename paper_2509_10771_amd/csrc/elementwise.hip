@@ -123,6 +123,8 @@ hipError_t launch_gae(const float* rewards, const float* values, const float* la
                       float* adv, float* ret, double* partials, hipStream_t stream) {
   const int nb = gae_num_blocks(N);
   double* part = normalize ? partials : nullptr;
+  TraceScope ts(stream, normalize ? "gae_scan+normalize" : "gae_scan", 0.0,
+                (double)T * N * (normalize ? 25.0 : 17.0) + 4.0 * N);
   if (gae_block(N) == 256)
     hipLaunchKernelGGL((gae_scan_kernel<256>), dim3(nb), dim3(256), 0, stream, rewards, values, last_values, dones,
                        timeouts, T, N, gamma, lam, adv, ret, part);
@@ -238,6 +240,7 @@ size_t perm_workspace_bytes(int32_t B) {
 hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, void* ws, hipStream_t stream) {
   if (B <= 0) return hipSuccess;
   PermPlan p = perm_plan(B);
+  TraceScope ts(stream, "permutation", 0.0, 0.0);
   char* w = static_cast<char*>(ws);
   const size_t seg = align_up((size_t)(p.nb + 1) * 4, 256);
   int* counts = reinterpret_cast<int*>(w);
@@ -255,34 +258,61 @@ hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, v
 }
 
 // ---- split-K reduction + squared norm ---------------------------------------------------------------
-constexpr int RED_PER_BLOCK = 1024;  // floats per workgroup
+constexpr int RED_PER_BLOCK = 1024;  // floats per workgroup of the plain squared-norm kernel
 int reduce_num_blocks(int64_t n) { return (int)((n + RED_PER_BLOCK - 1) / RED_PER_BLOCK); }
 
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partials, int n_split,
-                                                              long split_stride, long n, float* __restrict__ grads,
-                                                              double* __restrict__ sumsq_blocks) {
+// One workgroup sums 256 consecutive gradient entries of one layer over all of that layer's splits: 64 lanes
+// cover the 256 floats with one 16-byte load each, the 4 wavefronts take every 4th split, LDS combines them
+// in a fixed order (deterministic result).
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceArgs a) {
+  __shared__ float4 part[4][64];
   __shared__ double smem[4];
-  const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
-  double q = 0.0;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const long i = i0 + c;
-    if (i < n) {
-      float s = 0.f;
-      for (int k = 0; k < n_split; ++k) s += partials[(long)k * split_stride + i];
-      grads[i] = s;
-      q += (double)s * (double)s;
+  int layer = 0;
+  while (layer + 1 < a.n_layers && (int)blockIdx.x >= a.block_start[layer + 1]) ++layer;
+  const long size = a.size[layer];
+  const int n_split = a.split[layer];
+  const float* src = a.partials + a.part_off[layer];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const long j0 = ((long)(blockIdx.x - a.block_start[layer]) * 64 + lane) * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (j0 < size) {
+    if (j0 + 3 < size && ((size & 3) == 0) && ((a.part_off[layer] & 3) == 0)) {
+      for (int k = w; k < n_split; k += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(src + (long)k * size + j0);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
+    } else {
+      float* sp = &s.x;
+      for (int k = w; k < n_split; k += 4)
+        for (int c = 0; c < 4; ++c)
+          if (j0 + c < size) sp[c] += src[(long)k * size + j0 + c];
     }
   }
-  double t = block_sum(q, smem);
-  if (threadIdx.x == 0) sumsq_blocks[blockIdx.x] = t;
+  part[w][lane] = s;
+  __syncthreads();
+  double q = 0.0;
+  if (w == 0 && j0 < size) {
+    float4 t = part[0][lane];
+    for (int g = 1; g < 4; ++g) { t.x += part[g][lane].x; t.y += part[g][lane].y; t.z += part[g][lane].z; t.w += part[g][lane].w; }
+    const float* tp = &t.x;
+    float* dst = a.grads + a.grad_off[layer] + j0;
+    for (int c = 0; c < 4; ++c)
+      if (j0 + c < size) {
+        dst[c] = tp[c];
+        q += (double)tp[c] * (double)tp[c];
+      }
+  }
+  double tot = block_sum(q, smem);
+  if (threadIdx.x == 0) a.sumsq_blocks[blockIdx.x] = tot;
 }
 
-hipError_t launch_reduce_partials(const float* partials, int32_t n_split, int64_t split_stride, int64_t n, float* grads,
-                                  double* sumsq_blocks, hipStream_t stream) {
-  if (n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(reduce_num_blocks(n)), dim3(256), 0, stream, partials, n_split,
-                     (long)split_stride, (long)n, grads, sumsq_blocks);
+hipError_t launch_reduce_partials(const ReduceArgs& a, hipStream_t stream) {
+  const int blocks = a.block_start[a.n_layers];
+  if (blocks <= 0) return hipSuccess;
+  double bytes = 0.0;
+  for (int l = 0; l < a.n_layers; ++l) bytes += 4.0 * (double)a.size[l] * (a.split[l] + 1);
+  TraceScope ts(stream, "reduce_partials", 0.0, bytes);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -358,6 +388,9 @@ hipError_t launch_adam(const AdamArgs& a, hipStream_t stream) {
   int64_t nmax = 0;
   for (int i = 0; i < a.n_seg; ++i) nmax = a.seg[i].n > nmax ? a.seg[i].n : nmax;
   if (nmax <= 0) return hipSuccess;
+  double n_all = 0.0;
+  for (int i = 0; i < a.n_seg; ++i) n_all += (double)a.seg[i].n;
+  TraceScope ts(stream, "adam", 0.0, 28.0 * n_all);
   dim3 grid((unsigned)((nmax + 1023) / 1024), a.n_seg);
   hipLaunchKernelGGL(adam_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
@@ -539,6 +572,7 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(const PpoLossArgs a) {
 }
 
 hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
+  TraceScope ts(stream, "ppo_loss", 0.0, 0.0);
   hipLaunchKernelGGL(ppo_loss_kernel, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
   return hipGetLastError();
 }

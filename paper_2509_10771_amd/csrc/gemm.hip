@@ -2,20 +2,21 @@
 // actor, critic, student, teacher and RND networks: forward, input gradient and weight gradient.
 //
 // Tiling: one workgroup = 4 wavefronts (256 lanes) computes a BM x BN block of C.  Operand tiles of
-// BK = 16 contraction steps are staged through LDS in contraction-major order (As[k][m], Bs[k][n]),
+// BK (16) contraction steps are staged through LDS in contraction-major order (As[k][m], Bs[k][n]),
 // so that the 32 lanes of an MFMA operand row read 32 consecutive words (bank-conflict free), and are
 // double-buffered: global loads of tile k+1 are in flight while tile k feeds the matrix cores.
 //
 // MFMA 32x32x2 fp32 register layout (wave64, lane l, g = l / 32, j = l % 32):
 //   A operand: A[row = j][k = g]      B operand: B[k = g][col = j]
 //   D/C, 16 accumulators r = 0..15:   D[row = 8 * (r / 4) + 4 * g + r % 4][col = j]
+#include <cstdio>
+
 #include "kernels.h"
 
 namespace rslx {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 16;    // contraction steps per LDS tile
 constexpr int PAD = 4;    // LDS row padding (floats); keeps rows 16-byte aligned
 constexpr int NT = 256;   // lanes per workgroup
 
@@ -38,15 +39,17 @@ __device__ __forceinline__ float x_elem(const GemmProblem& P, int r, int c) {
 
 // ---- tile fetch: operand stored with the contraction index contiguous (rows = M or N index) -------
 // Produces R*BK/NT values per lane; element (row, k) lands at lds[k][row].
-template <int R, bool IS_X>
+template <int R, int BK, bool IS_X>
 __device__ __forceinline__ void fetch_kcontig(const GemmProblem& P, const float* __restrict__ base, int ld, bool vec,
                                               int row0, int row_end, int k0, int k_end, float (&reg)[R * BK / NT]) {
   const int tid = threadIdx.x;
   if (vec) {
+    constexpr int LK = BK / 4;       // lanes along the contraction index (one float4 each)
+    constexpr int RP = NT / LK;      // rows per pass
 #pragma unroll
-    for (int p = 0; p < R / 64; ++p) {
-      int row = row0 + p * 64 + tid / 4;
-      int kk = k0 + 4 * (tid % 4);
+    for (int p = 0; p < R / RP; ++p) {
+      int row = row0 + p * RP + tid / LK;
+      int kk = k0 + 4 * (tid % LK);
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (row < row_end && kk < k_end) {
         long sr = IS_X ? (long)src_row(P, row) : (long)row;
@@ -55,10 +58,11 @@ __device__ __forceinline__ void fetch_kcontig(const GemmProblem& P, const float*
       reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
     }
   } else {
+    constexpr int RP = NT / BK;
 #pragma unroll
-    for (int p = 0; p < R / 16; ++p) {
-      int row = row0 + p * 16 + tid / 16;
-      int kk = k0 + tid % 16;
+    for (int p = 0; p < R / RP; ++p) {
+      int row = row0 + p * RP + tid / BK;
+      int kk = k0 + tid % BK;
       float v = 0.f;
       if (row < row_end && kk < k_end) v = IS_X ? x_elem(P, row, kk) : base[(long)row * ld + kk];
       reg[p] = v;
@@ -66,25 +70,28 @@ __device__ __forceinline__ void fetch_kcontig(const GemmProblem& P, const float*
   }
 }
 
-template <int R, int S>
+template <int R, int BK, int S>
 __device__ __forceinline__ void stash_kcontig(bool vec, float (*lds)[S], const float (&reg)[R * BK / NT]) {
   const int tid = threadIdx.x;
   if (vec) {
+    constexpr int LK = BK / 4;
+    constexpr int RP = NT / LK;
 #pragma unroll
-    for (int p = 0; p < R / 64; ++p) {
-      int row = p * 64 + tid / 4;
-      int kq = 4 * (tid % 4);
+    for (int p = 0; p < R / RP; ++p) {
+      int row = p * RP + tid / LK;
+      int kq = 4 * (tid % LK);
 #pragma unroll
       for (int c = 0; c < 4; ++c) lds[kq + c][row] = reg[4 * p + c];
     }
   } else {
+    constexpr int RP = NT / BK;
 #pragma unroll
-    for (int p = 0; p < R / 16; ++p) lds[tid % 16][p * 16 + tid / 16] = reg[p];
+    for (int p = 0; p < R / RP; ++p) lds[tid % BK][p * RP + tid / BK] = reg[p];
   }
 }
 
 // ---- tile fetch: operand stored with the M / N index contiguous (rows = contraction index) --------
-template <int Cw, bool IS_X>
+template <int Cw, int BK, bool IS_X>
 __device__ __forceinline__ void fetch_direct(const GemmProblem& P, const float* __restrict__ base, int ld, bool vec,
                                              int col0, int col_end, int k0, int k_end, float (&reg)[Cw * BK / NT]) {
   const int tid = threadIdx.x;
@@ -115,7 +122,7 @@ __device__ __forceinline__ void fetch_direct(const GemmProblem& P, const float* 
   }
 }
 
-template <int Cw, int S>
+template <int Cw, int BK, int S>
 __device__ __forceinline__ void stash_direct(bool vec, float (*lds)[S], const float (&reg)[Cw * BK / NT]) {
   const int tid = threadIdx.x;
   if (vec) {
@@ -133,7 +140,7 @@ __device__ __forceinline__ void stash_direct(bool vec, float (*lds)[S], const fl
   }
 }
 
-template <int MODE, int BM, int BN, int WM, int WN>
+template <int MODE, int BM, int BN, int WM, int WN, int BK>
 __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
   const int wm = wave / WN, wn = wave % WN;
   const int a_off = wm * (TM * 32) + j, b_off = wn * (TN * 32) + j;
   // 16-byte fetches need at least 64 rows / columns per tile to give every lane a slot
-  const bool avec = P.a_vec != 0 && BM >= 64, bvec = P.b_vec != 0 && BN >= 64;
+  const bool avec = P.a_vec != 0 && BM * BK >= 4 * NT, bvec = P.b_vec != 0 && BN * BK >= 4 * NT;
 
   float ra[BM * BK / NT], rb[BN * BK / NT];
   f32x16 acc[TM][TN];
@@ -175,26 +182,26 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
 
   auto fetch = [&](int k0) {
     if (MODE == GEMM_DW) {
-      fetch_direct<BM, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
-      fetch_direct<BN, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
+      fetch_direct<BM, BK, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
+      fetch_direct<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
     } else if (MODE == GEMM_FWD) {
-      fetch_kcontig<BM, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
-      fetch_direct<BN, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
+      fetch_kcontig<BM, BK, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
+      fetch_direct<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
     } else {
-      fetch_kcontig<BM, false>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
-      fetch_kcontig<BN, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
+      fetch_kcontig<BM, BK, false>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
+      fetch_kcontig<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
     }
   };
   auto stash = [&](int buf) {
     if (MODE == GEMM_DW) {
-      stash_direct<BM, SA>(avec, As[buf], ra);
-      stash_direct<BN, SB>(bvec, Bs[buf], rb);
+      stash_direct<BM, BK, SA>(avec, As[buf], ra);
+      stash_direct<BN, BK, SB>(bvec, Bs[buf], rb);
     } else if (MODE == GEMM_FWD) {
-      stash_kcontig<BM, SA>(avec, As[buf], ra);
-      stash_direct<BN, SB>(bvec, Bs[buf], rb);
+      stash_kcontig<BM, BK, SA>(avec, As[buf], ra);
+      stash_direct<BN, BK, SB>(bvec, Bs[buf], rb);
     } else {
-      stash_kcontig<BM, SA>(avec, As[buf], ra);
-      stash_kcontig<BN, SB>(bvec, Bs[buf], rb);
+      stash_kcontig<BM, BK, SA>(avec, As[buf], ra);
+      stash_kcontig<BN, BK, SB>(bvec, Bs[buf], rb);
     }
   };
 
@@ -206,17 +213,33 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
     if (kt + 1 < nk) fetch(k_begin + (kt + 1) * BK);
+    // operands of step kk + 2 are read from LDS before the matrix-core instructions of step kk issue
+    float a_cur[TM], b_cur[TN], a_nxt[TM], b_nxt[TN];
+#pragma unroll
+    for (int t = 0; t < TM; ++t) a_cur[t] = As[buf][g][a_off + t * 32];
+#pragma unroll
+    for (int t = 0; t < TN; ++t) b_cur[t] = Bs[buf][g][b_off + t * 32];
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float a[TM], b[TN];
+      if (kk + 2 < BK) {
 #pragma unroll
-      for (int t = 0; t < TM; ++t) a[t] = As[buf][kk + g][a_off + t * 32];
+        for (int t = 0; t < TM; ++t) a_nxt[t] = As[buf][kk + 2 + g][a_off + t * 32];
 #pragma unroll
-      for (int t = 0; t < TN; ++t) b[t] = Bs[buf][kk + g][b_off + t * 32];
+        for (int t = 0; t < TN; ++t) b_nxt[t] = Bs[buf][kk + 2 + g][b_off + t * 32];
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of the matrix-core instructions
 #pragma unroll
       for (int x = 0; x < TM; ++x)
 #pragma unroll
-        for (int y = 0; y < TN; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
+        for (int y = 0; y < TN; ++y)
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[x], b_cur[y], acc[x][y], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk + 2 < BK) {
+#pragma unroll
+        for (int t = 0; t < TM; ++t) a_cur[t] = a_nxt[t];
+#pragma unroll
+        for (int t = 0; t < TN; ++t) b_cur[t] = b_nxt[t];
+      }
     }
     if (MODE == GEMM_DW && tm == 0 && tid < BN) {
 #pragma unroll
@@ -259,7 +282,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
   if (MODE == GEMM_DW && tm == 0 && P.bias_off >= 0 && tid < BN && n0 + tid < P.N) Cb[P.bias_off + n0 + tid] = bsum;
 }
 
-template <int MODE, int BM, int BN, int WM, int WN>
+template <int MODE, int BM, int BN, int WM, int WN, int BK = 16>
 static hipError_t launch_cfg(const GemmBatch& batch, hipStream_t stream) {
   int tiles = 0, splits = 1;
   for (int i = 0; i < batch.count; ++i) {
@@ -270,21 +293,55 @@ static hipError_t launch_cfg(const GemmBatch& batch, hipStream_t stream) {
   }
   if (tiles == 0) return hipSuccess;
   dim3 grid(tiles, splits, batch.count);
-  hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN>), grid, dim3(NT), 0, stream, batch);
+  double flops = 0.0;
+  for (int i = 0; i < batch.count; ++i) flops += 2.0 * batch.p[i].M * (double)batch.p[i].N * batch.p[i].K;
+  static const char* const mode_name[3] = {"fwd", "dx", "dw"};
+  char name[48];
+  snprintf(name, sizeof name, "gemm_%s_%dx%d", mode_name[MODE], BM, BN);
+  TraceScope ts(stream, name, flops, 0.0);
+  hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN, BK>), grid, dim3(NT), 0, stream, batch);
   return hipGetLastError();
+}
+
+// Tile selection.  Measured on MI355X: one 128x128 workgroup per CU reaches ~40 % of the matrix-core peak,
+// four resident workgroups per CU reach ~65 %, so the tile shrinks (64x128) whenever 128x128 tiles would leave
+// fewer than about three workgroups per CU, and short contractions (K <= 64, epilogue-bound) also use it.
+enum TileCfg { TILE_128x128, TILE_64x128, TILE_128x64, TILE_128x32 };
+
+static TileCfg pick_tile(GemmMode mode, const GemmBatch& batch) {
+  int maxM = 0, maxN = 0, minK = 1 << 30, dw_big = 1;
+  long tiles128 = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    const GemmProblem& P = batch.p[i];
+    maxM = P.M > maxM ? P.M : maxM;
+    maxN = P.N > maxN ? P.N : maxN;
+    minK = P.K < minK ? P.K : minK;
+    tiles128 += (long)((P.M + 127) / 128) * ((P.N + 127) / 128);
+    dw_big &= P.dw_big;
+  }
+  if (maxN <= 32) return TILE_128x32;
+  if (maxM <= 64) return TILE_64x128;
+  if (maxN <= 64) return TILE_128x64;
+  if (mode == GEMM_DW) return dw_big ? TILE_128x128 : TILE_64x128;
+  if (minK <= 64 || tiles128 < 700) return TILE_64x128;
+  return TILE_128x128;
+}
+
+int gemm_dw_tiles(int32_t M, int32_t N, bool big) {
+  if (N <= 32) return (M + 127) / 128;
+  if (M <= 64 || !big) return ((M + 63) / 64) * ((N + 127) / 128);
+  if (N <= 64) return ((M + 127) / 128) * ((N + 63) / 64);
+  return ((M + 127) / 128) * ((N + 127) / 128);
 }
 
 template <int MODE>
 static hipError_t launch_mode(const GemmBatch& batch, hipStream_t stream) {
-  int maxM = 0, maxN = 0;
-  for (int i = 0; i < batch.count; ++i) {
-    maxM = batch.p[i].M > maxM ? batch.p[i].M : maxM;
-    maxN = batch.p[i].N > maxN ? batch.p[i].N : maxN;
+  switch (pick_tile((GemmMode)MODE, batch)) {
+    case TILE_128x32: return launch_cfg<MODE, 128, 32, 4, 1>(batch, stream);
+    case TILE_64x128: return launch_cfg<MODE, 64, 128, 1, 4>(batch, stream);
+    case TILE_128x64: return launch_cfg<MODE, 128, 64, 2, 2>(batch, stream);
+    default: return launch_cfg<MODE, 128, 128, 2, 2>(batch, stream);
   }
-  if (maxN <= 32) return launch_cfg<MODE, 128, 32, 4, 1>(batch, stream);
-  if (maxM <= 64) return launch_cfg<MODE, 64, 128, 1, 4>(batch, stream);
-  if (maxN <= 64) return launch_cfg<MODE, 128, 64, 2, 2>(batch, stream);
-  return launch_cfg<MODE, 128, 128, 2, 2>(batch, stream);
 }
 
 hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream) {

@@ -8,6 +8,19 @@
 namespace rslx {
 
 // ---------------------------------------------------------------------------------------------
+// Optional launch trace: while enabled, every kernel launch site brackets its launch with a pair of HIP
+// events on the launch stream and tags it with its algorithmic flops / bytes.  Disabled by default
+// (then these calls do nothing).
+// ---------------------------------------------------------------------------------------------
+void trace_open(hipStream_t stream, const char* kernel, double flops, double bytes);
+void trace_close(hipStream_t stream);
+struct TraceScope {
+  hipStream_t s;
+  TraceScope(hipStream_t stream, const char* kernel, double flops, double bytes) : s(stream) { trace_open(s, kernel, flops, bytes); }
+  ~TraceScope() { trace_close(s); }
+};
+
+// ---------------------------------------------------------------------------------------------
 // Dense fp32 contraction on the matrix cores, three operand arrangements of one kernel:
 //   GEMM_FWD  C[r, n]   = act( sum_k X(r, k) W[k, n] + bias[n] )          (layer forward)
 //   GEMM_DX   C[r, kin] = ( sum_n dZ[r, n] W[kin, n] ) * ELU'(H[r, kin])   (input gradient)
@@ -38,6 +51,7 @@ struct GemmProblem {
   int32_t n_split;          // DW: number of splits (grid.y)
   int64_t split_stride;     // DW: floats between consecutive partial buffers
   int32_t bias_off;         // DW: offset of the db partial inside a partial buffer, -1 = none
+  int32_t dw_big;           // DW: 1 = 128x128 tiles were planned for this layer, 0 = 64x128
   int32_t a_vec, b_vec;     // 1 = operand may be fetched with 16-byte loads
 };
 
@@ -47,6 +61,8 @@ struct GemmBatch {
 };
 
 hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream);
+// Number of output tiles the weight-gradient kernel uses for an [M, N] layer (big = 128x128 tiles allowed).
+int gemm_dw_tiles(int32_t M, int32_t N, bool big);
 
 // ---------------------------------------------------------------------------------------------
 // Streaming / reduction kernels (elementwise.hip)
@@ -61,11 +77,24 @@ hipError_t launch_gae(const float* rewards, const float* values, const float* la
 size_t perm_workspace_bytes(int32_t B);
 hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, void* ws, hipStream_t stream);
 
-// Sum the split partials of a flat gradient buffer, write grads, emit per-block sums of squares.
+// Sum the split partials of one network's gradient, layer by layer, into the flat gradient buffer and emit
+// per-block sums of squares.  Layer l owns `split[l]` partial buffers of `size[l]` floats each, stored back to
+// back from `part_off[l]`; its gradient starts at `grad_off[l]`.
+struct ReduceArgs {
+  const float* partials;
+  float* grads;
+  double* sumsq_blocks;
+  int32_t n_layers;
+  int32_t split[8];
+  int64_t size[8];
+  int64_t part_off[8];
+  int64_t grad_off[8];
+  int32_t block_start[9];   // first block of each layer (prefix sums), block_start[n_layers] = total
+};
+constexpr int REDUCE_BLOCK_FLOATS = 256;
+hipError_t launch_reduce_partials(const ReduceArgs& a, hipStream_t stream);
+// Per-block sums of squares of an existing gradient buffer (reduce_num_blocks(n) entries).
 int reduce_num_blocks(int64_t n);
-hipError_t launch_reduce_partials(const float* partials, int32_t n_split, int64_t split_stride, int64_t n,
-                                  float* grads, double* sumsq_blocks, hipStream_t stream);
-// Per-block sums of squares of an existing gradient buffer.
 hipError_t launch_sumsq(const float* g, int64_t n, double* sumsq_blocks, hipStream_t stream);
 
 struct AdamSegment {
