@@ -173,6 +173,7 @@ struct SplitPlan {
   int32_t chunk[RSLX_MAX_LAYERS];
   int32_t big[RSLX_MAX_LAYERS];
   int64_t size[RSLX_MAX_LAYERS];
+  int64_t pitch[RSLX_MAX_LAYERS];     // floats between consecutive split buffers of a layer
   int64_t part_off[RSLX_MAX_LAYERS];
   int64_t total = 0;       // floats
   int32_t blocks = 0;      // workgroups of the reduction = entries of the squared-norm list
@@ -198,8 +199,9 @@ SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group) {
     p.split[l] = s;
     p.chunk[l] = c;
     p.size[l] = (int64_t)M * N + N;
+    p.pitch[l] = (p.size[l] + 3) / 4 * 4;      // 16-byte aligned split buffers
     p.part_off[l] = p.total;
-    p.total += (p.size[l] * s + 3) / 4 * 4;
+    p.total += p.pitch[l] * s;
     p.blocks += (int32_t)((p.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
   }
   return p;
@@ -211,6 +213,7 @@ struct BwdJob {
   int32_t rows;
   NetBufs* bufs;
   const float* d_out;    // [rows, dims[L]]
+  float* wt;             // scratch for the transposed weights (flat parameter layout)
   float* partials;       // split partials, laid out by `plan`
   const SplitPlan* plan;
 };
@@ -223,6 +226,14 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
     return backward_nets(jobs + 1, 1, stream);
   }
   const int L = jobs[0].net->n_layers;
+  TransposeBatch tb;
+  tb.count = 0;
+  for (int i = 0; i < count; ++i)
+    for (int l = 1; l < L; ++l) {
+      const rslx_mlp& n = *jobs[i].net;
+      tb.job[tb.count++] = TransposeJob{n.params + layer_offset(n, l), jobs[i].wt + layer_offset(n, l), n.dims[l], n.dims[l + 1]};
+    }
+  RSLX_HIP(launch_transpose(tb, stream));
   for (int l = L - 1; l >= 0; --l) {
     GemmBatch bw, bx;
     bw.count = bx.count = count;
@@ -242,7 +253,7 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
       p.M = n.dims[l]; p.N = n.dims[l + 1]; p.K = jobs[i].rows;
       p.n_split = sp.split[l];
       p.k_chunk = sp.chunk[l];
-      p.split_stride = sp.size[l];
+      p.split_stride = sp.pitch[l];
       p.bias_off = n.dims[l] * n.dims[l + 1];
       p.dw_big = sp.big[l];
       p.a_vec = (p.M % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
@@ -251,13 +262,13 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
       if (l > 0) {
         GemmProblem q = blank_problem();
         q.A = dz; q.lda = n.dims[l + 1];
-        q.B = n.params + layer_offset(n, l); q.ldb = n.dims[l + 1];
+        q.B = jobs[i].wt + layer_offset(n, l); q.ldb = n.dims[l];
         q.C = jobs[i].bufs->dz[l - 1]; q.ldc = n.dims[l];
         q.aux = jobs[i].bufs->out[l - 1];
         q.M = jobs[i].rows; q.N = n.dims[l]; q.K = n.dims[l + 1];
         q.alpha = n.elu_alpha;
         q.a_vec = (q.K % 4 == 0 && aligned16(q.A)) ? 1 : 0;
-        q.b_vec = (q.K % 4 == 0 && aligned16(q.B)) ? 1 : 0;
+        q.b_vec = (q.N % 4 == 0 && aligned16(q.B)) ? 1 : 0;
         bx.p[i] = q;
       }
     }
@@ -265,6 +276,23 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
     if (l > 0) RSLX_HIP(launch_gemm(GEMM_DX, bx, stream));
   }
   return RSLX_OK;
+}
+
+FusedNet fused_net(const rslx_mlp& n, const float* x, int ldx, const int32_t* col_map, float* out, bool head) {
+  FusedNet f;
+  memset(&f, 0, sizeof f);
+  f.params = n.params; f.x = x; f.ldx = ldx; f.col_map = col_map; f.out = out;
+  f.n_layers = n.n_layers;
+  for (int i = 0; i <= n.n_layers; ++i) f.dims[i] = n.dims[i];
+  f.alpha = n.elu_alpha;
+  f.head = head ? 1 : 0;
+  return f;
+}
+
+int max_dim_of(const rslx_mlp& n) {
+  int m = 0;
+  for (int i = 0; i <= n.n_layers; ++i) m = n.dims[i] > m ? n.dims[i] : m;
+  return m;
 }
 
 bool involution_ok(const int32_t* perm, const float* sign, int n) {
@@ -414,6 +442,27 @@ int32_t rslx_act(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs
   const rslx_mlp* a = values_only ? nullptr : actor;
   if (!ws || ws_bytes < rslx_act_workspace_bytes(a, critic, N)) return fail(RSLX_ERR_WORKSPACE, "rslx_act: workspace too small");
   hipStream_t s = (hipStream_t)stream;
+  // Fast path: one layer-fused launch for both networks and the Gaussian head.
+  {
+    FusedForwardArgs fa;
+    memset(&fa, 0, sizeof fa);
+    fa.n_rows = N;
+    fa.max_dim = max_dim_of(*critic);
+    if (a) {
+      fa.net[fa.n_nets++] = fused_net(*a, obs_actor, a->dims[0], nullptr, mu, true);
+      fa.max_dim = max_dim_of(*a) > fa.max_dim ? max_dim_of(*a) : fa.max_dim;
+    }
+    fa.net[fa.n_nets++] = fused_net(*critic, obs_critic, critic->dims[0], nullptr, values, false);
+    fa.deterministic = (flags & RSLX_ACT_DETERMINISTIC) ? 1 : 0;
+    fa.eps = eps_or_null;
+    fa.noise_base = mix64_host(mix64_host(seed ^ 0xAC7ull) ^ step);
+    fa.actions = actions; fa.logp = logp; fa.sigma = sigma;
+    if (fused_forward_supported(fa)) {
+      RSLX_HIP(launch_fused_forward(fa, s));
+      return RSLX_OK;
+    }
+  }
+  // General path (layers wider than the fused kernel's LDS budget): one grouped launch per layer.
   Carver c(ws);
   NetBufs ba, bc;
   act_carve(c, a, critic, N, &ba, &bc);
@@ -503,6 +552,7 @@ namespace {
 struct TrainBufs {        // per trained network
   NetBufs act;
   float* d_out = nullptr;
+  float* wt = nullptr;
   float* partials = nullptr;
   SplitPlan plan;
   double* sumsq = nullptr;
@@ -524,6 +574,7 @@ struct PpoPlan {
 void carve_train(Carver& c, const rslx_mlp& n, int32_t rows, int group, TrainBufs& t) {
   carve_net(c, n, rows, true, t.act);
   t.d_out = c.take<float>((size_t)rows * n.dims[n.n_layers]);
+  t.wt = c.take<float>((size_t)round4(weight_count(n)));
   t.plan = plan_splits(n, rows, group);
   t.partials = c.take<float>((size_t)t.plan.total);
   t.n_sumsq = t.plan.blocks;
@@ -602,6 +653,7 @@ int32_t reduce_net(const rslx_mlp& n, const TrainBufs& t, hipStream_t s) {
   for (int l = 0; l < n.n_layers; ++l) {
     a.split[l] = t.plan.split[l];
     a.size[l] = t.plan.size[l];
+    a.pitch[l] = t.plan.pitch[l];
     a.part_off[l] = t.plan.part_off[l];
     a.grad_off[l] = layer_offset(n, l);
     a.block_start[l] = blocks;
@@ -678,8 +730,8 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
                                       cfg->entropy_coef, actor->grads + weight_count(*actor), stats_row,
                                       p.sumsq_all + p.actor.n_sumsq + p.critic.n_sumsq, s));
 
-      BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.partials, &p.actor.plan},
-                      BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.partials, &p.critic.plan}};
+      BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.wt, p.actor.partials, &p.actor.plan},
+                      BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.wt, p.critic.partials, &p.critic.plan}};
       RSLX_TRY(backward_nets(bj, 2, s));
       RSLX_TRY(reduce_net(*actor, p.actor, s));
       RSLX_TRY(reduce_net(*critic, p.critic, s));
@@ -710,7 +762,7 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
         RSLX_HIP(launch_mse(p.pred.act.out[pr.n_layers - 1], p.targ.out[pr.n_layers - 1], nullptr, p.mb, K,
                             p.pred.d_out, p.mse_partials, s));
         RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)p.mb * K, stats_row + RSLX_STAT_RND_LOSS, s));
-        BwdJob rb{&pr, xr, p.mb, &p.pred.act, p.pred.d_out, p.pred.partials, &p.pred.plan};
+        BwdJob rb{&pr, xr, p.mb, &p.pred.act, p.pred.d_out, p.pred.wt, p.pred.partials, &p.pred.plan};
         RSLX_TRY(backward_nets(&rb, 1, s));
         RSLX_TRY(reduce_net(pr, p.pred, s));
         const int64_t tr = *rnd->adam_step + 1;
@@ -822,7 +874,7 @@ int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* 
       RSLX_TRY(forward_nets(&fj, 1, s));
       RSLX_HIP(launch_mse(p.student.act.out[Ls - 1], targets, idx, p.mb, A, p.student.d_out, p.mse_partials, s));
       RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)p.mb * A, stats_row, s));
-      BwdJob bj{student, xs, p.mb, &p.student.act, p.student.d_out, p.student.partials, &p.student.plan};
+      BwdJob bj{student, xs, p.mb, &p.student.act, p.student.d_out, p.student.wt, p.student.partials, &p.student.plan};
       RSLX_TRY(backward_nets(&bj, 1, s));
       RSLX_TRY(reduce_net(*student, p.student, s));
       const int64_t t = *adam_step + 1;
@@ -902,9 +954,18 @@ int32_t rslx_rnd(const rslx_mlp* target, const rslx_mlp* predictor, const float*
   XView x;
   x.base = obs; x.ld = D;
   if (subset_idx_or_null) { x.col_map = subset_idx_or_null; x.map_from = 0; }
-  NetJob jobs[2] = {NetJob{predictor, x, N, &bp}, NetJob{target, x, N, &bt}};
-  RSLX_TRY(forward_nets(jobs, 2, s));
   const int L = target->n_layers;
+  FusedForwardArgs fa;
+  memset(&fa, 0, sizeof fa);
+  fa.n_rows = N; fa.n_nets = 2; fa.max_dim = max_dim_of(*target);
+  fa.net[0] = fused_net(*predictor, obs, D, subset_idx_or_null, bp.out[L - 1], false);
+  fa.net[1] = fused_net(*target, obs, D, subset_idx_or_null, bt.out[L - 1], false);
+  if (fused_forward_supported(fa)) {
+    RSLX_HIP(launch_fused_forward(fa, s));
+  } else {
+    NetJob jobs[2] = {NetJob{predictor, x, N, &bp}, NetJob{target, x, N, &bt}};
+    RSLX_TRY(forward_nets(jobs, 2, s));
+  }
   RSLX_HIP(launch_rnd_reward(bp.out[L - 1], bt.out[L - 1], N, target->dims[L], running, weight, update_stats ? 1 : 0,
                              r_int_out, rewards_inout_or_null, partials, s));
   return RSLX_OK;

@@ -275,17 +275,12 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceArgs a
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const long j0 = ((long)(blockIdx.x - a.block_start[layer]) * 64 + lane) * 4;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (j0 < size) {
-    if (j0 + 3 < size && ((size & 3) == 0) && ((a.part_off[layer] & 3) == 0)) {
-      for (int k = w; k < n_split; k += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(src + (long)k * size + j0);
-        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-      }
-    } else {
-      float* sp = &s.x;
-      for (int k = w; k < n_split; k += 4)
-        for (int c = 0; c < 4; ++c)
-          if (j0 + c < size) sp[c] += src[(long)k * size + j0 + c];
+  if (j0 < size) {      // pitch is a multiple of 4, so the 16-byte load stays inside the split buffer's padding
+    const long pitch = a.pitch[layer];
+#pragma unroll 4
+    for (int k = w; k < n_split; k += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(src + (long)k * pitch + j0);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
   }
   part[w][lane] = s;

@@ -152,9 +152,14 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
   const GemmProblem& P = batch.p[blockIdx.z];
   const int tiles_n = (P.N + BN - 1) / BN;
   const int tiles_m = (P.M + BM - 1) / BM;
-  const int tile = blockIdx.x;
+  // Workgroups are handed to the 8 XCDs round-robin by linear id; remap so that neighbours in (tile, split)
+  // order - which share operand rows - run on the same XCD and meet in its L2.
+  int lin = blockIdx.x + gridDim.x * blockIdx.y;
+  const int total = gridDim.x * gridDim.y;
+  if ((total & 7) == 0) lin = (lin & 7) * (total >> 3) + (lin >> 3);
+  const int tile = lin % (int)gridDim.x;
   if (tile >= tiles_m * tiles_n) return;
-  const int split = blockIdx.y;
+  const int split = lin / (int)gridDim.x;
   if (MODE == GEMM_DW && split >= P.n_split) return;
   const int tn = tile % tiles_n, tm = tile / tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
@@ -189,7 +194,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
       fetch_direct<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
     } else {
       fetch_kcontig<BM, BK, false>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
-      fetch_kcontig<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
+      fetch_direct<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
     }
   };
   auto stash = [&](int buf) {
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
       stash_direct<BN, BK, SB>(bvec, Bs[buf], rb);
     } else {
       stash_kcontig<BM, BK, SA>(avec, As[buf], ra);
-      stash_kcontig<BN, BK, SB>(bvec, Bs[buf], rb);
+      stash_direct<BN, BK, SB>(bvec, Bs[buf], rb);
     }
   };
 
@@ -342,6 +347,37 @@ static hipError_t launch_mode(const GemmBatch& batch, hipStream_t stream) {
     case TILE_128x64: return launch_cfg<MODE, 128, 64, 2, 2>(batch, stream);
     default: return launch_cfg<MODE, 128, 128, 2, 2>(batch, stream);
   }
+}
+
+// ---- weight transposition --------------------------------------------------------------------------
+// The input-gradient contraction reads W^T; transposing the (small) weight matrices once per optimiser step
+// lets that kernel fetch both operands the way the forward kernel does instead of transposing W tiles in LDS
+// for every row block.
+__global__ __launch_bounds__(256) void transpose_kernel(const TransposeBatch b) {
+  __shared__ float t[32][33];
+  const TransposeJob& J = b.job[blockIdx.z];
+  const int tiles_c = (J.cols + 31) / 32;
+  const int tiles_r = (J.rows + 31) / 32;
+  if ((int)blockIdx.x >= tiles_c * tiles_r) return;
+  const int r0 = ((int)blockIdx.x / tiles_c) * 32, c0 = ((int)blockIdx.x % tiles_c) * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int i = ty; i < 32; i += 8)
+    if (r0 + i < J.rows && c0 + tx < J.cols) t[i][tx] = J.src[(long)(r0 + i) * J.cols + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8)
+    if (c0 + i < J.cols && r0 + tx < J.rows) J.dst[(long)(c0 + i) * J.rows + r0 + tx] = t[tx][i];
+}
+
+hipError_t launch_transpose(const TransposeBatch& b, hipStream_t stream) {
+  int tiles = 0;
+  for (int i = 0; i < b.count; ++i) {
+    int t = ((b.job[i].rows + 31) / 32) * ((b.job[i].cols + 31) / 32);
+    tiles = t > tiles ? t : tiles;
+  }
+  if (tiles == 0 || b.count == 0) return hipSuccess;
+  TraceScope ts(stream, "transpose_weights", 0.0, 0.0);
+  hipLaunchKernelGGL(transpose_kernel, dim3(tiles, 1, b.count), dim3(256), 0, stream, b);
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream) {

@@ -23,7 +23,8 @@ struct TraceScope {
 // ---------------------------------------------------------------------------------------------
 // Dense fp32 contraction on the matrix cores, three operand arrangements of one kernel:
 //   GEMM_FWD  C[r, n]   = act( sum_k X(r, k) W[k, n] + bias[n] )          (layer forward)
-//   GEMM_DX   C[r, kin] = ( sum_n dZ[r, n] W[kin, n] ) * ELU'(H[r, kin])   (input gradient)
+//   GEMM_DX   C[r, kin] = ( sum_n dZ[r, n] Wt[n, kin] ) * ELU'(H[r, kin])  (input gradient; Wt = W^T,
+//             transposed once per step by launch_transpose)
 //   GEMM_DW   C_s[kin, n] = sum_{r in split s} X(r, kin) dZ[r, n]          (weight gradient, split
 //             over rows; the block row holding kin = 0 also emits the column sums of dZ = db)
 // X(r, c) is a view of a row-major matrix with an optional row gather and column map:
@@ -35,7 +36,7 @@ enum GemmMode : int { GEMM_FWD = 0, GEMM_DX = 1, GEMM_DW = 2 };
 
 struct GemmProblem {
   const float* A;           // FWD/DW: X storage; DX: dZ
-  const float* B;           // FWD/DX: W [K_in, N_out] row-major; DW: dZ
+  const float* B;           // FWD: W [K_in, N_out] row-major; DX: W^T [N_out, K_in] row-major; DW: dZ
   float* C;                 // FWD/DX: output; DW: base of split partial 0
   const float* aux;         // FWD: bias[N] or null; DX: H at C's coordinates (ldc) or null
   const int32_t* row_idx;   // optional row gather for X (device)
@@ -61,8 +62,36 @@ struct GemmBatch {
 };
 
 hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream);
+// Out-of-place transposes of up to 16 row-major matrices in one launch: dst[c, r] = src[r, c].
+struct TransposeJob { const float* src; float* dst; int32_t rows, cols; };
+struct TransposeBatch { TransposeJob job[16]; int32_t count; };
+hipError_t launch_transpose(const TransposeBatch& b, hipStream_t stream);
 // Number of output tiles the weight-gradient kernel uses for an [M, N] layer (big = 128x128 tiles allowed).
 int gemm_dw_tiles(int32_t M, int32_t N, bool big);
+
+// ---------------------------------------------------------------------------------------------
+// Layer-fused inference of up to two networks over the same batch rows (fused_forward.hip).
+// ---------------------------------------------------------------------------------------------
+struct FusedNet {
+  const float* params;      // flat layout; a `head` network's log_std follows its last bias
+  const float* x;           // input matrix [n_rows, ldx] row-major
+  const int32_t* col_map;   // optional: input column k reads x[:, col_map[k]]
+  float* out;               // last layer's output [n_rows, dims[n_layers]]
+  int32_t ldx;
+  int32_t n_layers;
+  int32_t dims[9];
+  float alpha;
+  int32_t head;             // 1: run the Gaussian head on this network's output
+};
+struct FusedForwardArgs {
+  FusedNet net[2];
+  int32_t n_nets, n_rows, max_dim, deterministic;
+  const float* eps;         // optional caller noise [n_rows, A]
+  uint64_t noise_base;
+  float* actions; float* logp; float* sigma;
+};
+bool fused_forward_supported(const FusedForwardArgs& a);
+hipError_t launch_fused_forward(const FusedForwardArgs& a, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
 // Streaming / reduction kernels (elementwise.hip)
@@ -78,8 +107,8 @@ size_t perm_workspace_bytes(int32_t B);
 hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, void* ws, hipStream_t stream);
 
 // Sum the split partials of one network's gradient, layer by layer, into the flat gradient buffer and emit
-// per-block sums of squares.  Layer l owns `split[l]` partial buffers of `size[l]` floats each, stored back to
-// back from `part_off[l]`; its gradient starts at `grad_off[l]`.
+// per-block sums of squares.  Layer l owns `split[l]` partial buffers of `size[l]` floats each, `pitch[l]` floats
+// apart from `part_off[l]` on; its gradient starts at `grad_off[l]`.
 struct ReduceArgs {
   const float* partials;
   float* grads;
@@ -87,6 +116,7 @@ struct ReduceArgs {
   int32_t n_layers;
   int32_t split[8];
   int64_t size[8];
+  int64_t pitch[8];         // floats between consecutive split buffers (multiple of 4)
   int64_t part_off[8];
   int64_t grad_off[8];
   int32_t block_start[9];   // first block of each layer (prefix sums), block_start[n_layers] = total

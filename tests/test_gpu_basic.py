@@ -122,6 +122,15 @@ def test_act_matches_oracle(rx, name, N):
     _act_case(rx, w, inp, N, use_eps=False)
 
 
+def test_act_wide_layers_take_the_layered_path(rx):
+    """Hidden layers wider than 512 do not fit the layer-fused kernel's LDS budget; the per-layer path must agree too."""
+    from dataclasses import replace
+    w = replace(WORKLOADS["tiny"], N=200, hidden=(640, 96))
+    inp = make_inputs(w)
+    _act_case(rx, w, inp, 200, use_eps=True)
+    _act_case(rx, w, inp, 200, use_eps=False)
+
+
 def test_act_noise_distribution(rx):
     w = WORKLOADS["flat"]
     inp = make_inputs(w)
