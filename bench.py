@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="flat")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-trace", action="store_true", help="skip the per-launch HIP-event trace (no roofline entry)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (how the path would shard is described in DESIGN.md)")
@@ -108,16 +109,26 @@ def main():
     for it in range(args.warmup):
         step(it, False)
     torch.cuda.synchronize()
-    rx.rslx_trace_begin(1 << 16)
+    # timed region: K whole iterations, no instrumentation inside the library
     t0 = time.perf_counter()
     evs = [step(args.warmup + it, True) for it in range(args.steps)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    trace = rx.rslx_trace_end()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     for e in evs:
         phase["act"].append(e[0].elapsed_time(e[1])); phase["gae"].append(e[1].elapsed_time(e[2]))
         phase["update"].append(e[2].elapsed_time(e[3]))
+    # the same K iterations again with the library's HIP-event trace on: per-kernel launch durations for the
+    # roofline entry (two event records per launch cost ~10 % of throughput, so `value` comes from the run above)
+    trace, traced_ms = [("untraced", 0.0, 0.0, 1.0)], None
+    if not args.no_trace:
+        rx.rslx_trace_begin(1 << 16)
+        t2 = time.perf_counter()
+        for it in range(args.steps):
+            step(args.warmup + args.steps + it, False)
+        torch.cuda.synchronize()
+        traced_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+        trace = rx.rslx_trace_end()
     med = {k: float(np.median(v)) for k, v in phase.items()}
     assert torch.isfinite(actor.params).all() and torch.isfinite(stats).all(), "training state became non-finite"
 
@@ -153,6 +164,7 @@ def main():
         "update_tflops": round(upd_flops / (med["update"] * 1e-3) / 1e12, 2),
         "act_env_steps_per_s": round((T + 1) * N / (med["act"] * 1e-3), 1),
         "phase_ms": {k: round(v, 4) for k, v in med.items()},
+        "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
         "roofline": roofline,
         "kernels": breakdown,
     }

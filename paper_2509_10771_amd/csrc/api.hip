@@ -404,7 +404,7 @@ int32_t rslx_permutation(uint64_t seed, uint64_t call_index, int32_t epoch, int3
   Carver c(ws);
   void* w = c.take<char>(perm_workspace_bytes(B));
   const uint64_t base = mix64_host(mix64_host(mix64_host(seed) ^ call_index) ^ (uint64_t)epoch);
-  RSLX_HIP(launch_permutation(base, B, perm_out, w, (hipStream_t)stream));
+  RSLX_HIP(launch_permutations(&base, 1, B, perm_out, w, (hipStream_t)stream));
   return RSLX_OK;
 }
 
@@ -687,9 +687,11 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
   if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_ppo_update: workspace %zu < %zu bytes", ws_bytes, p.bytes);
   const int A = ro->A, L_a = actor->n_layers, L_c = critic->n_layers;
 
-  for (int e = 0; e < cfg->epochs; ++e) {
-    const uint64_t base = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
-    RSLX_HIP(launch_permutation(base, p.B, p.perms + (size_t)e * p.B, p.perm_ws, s));
+  {
+    std::vector<uint64_t> bases(cfg->epochs);
+    for (int e = 0; e < cfg->epochs; ++e)
+      bases[e] = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
+    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, p.B, p.perms, p.perm_ws, s));
   }
 
   for (int e = 0; e < cfg->epochs; ++e) {
@@ -859,9 +861,11 @@ int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* 
     }
     targets = p.targets;
   }
-  for (int e = 0; e < cfg->epochs; ++e) {
-    const uint64_t base = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
-    RSLX_HIP(launch_permutation(base, B, p.perms + (size_t)e * B, p.perm_ws, s));
+  {
+    std::vector<uint64_t> bases(cfg->epochs);
+    for (int e = 0; e < cfg->epochs; ++e)
+      bases[e] = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
+    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, B, p.perms, p.perm_ws, s));
   }
   const int nbm = mse_num_blocks((int64_t)p.mb * A);
   for (int e = 0; e < cfg->epochs; ++e) {

@@ -152,6 +152,7 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
 // Keys are uniform 64-bit hashes, so their top bits spread the B items evenly over nb buckets
 // (about 32 per bucket).  Bucket membership is order independent; the order inside a bucket is then
 // fixed by ranking on (key, index), which makes the result independent of atomic scheduling.
+constexpr int PERM_BATCH = 8;   // permutations per launch
 struct PermPlan {
   int32_t nb;      // buckets (power of two)
   int32_t shift;   // key >> shift = bucket
@@ -166,18 +167,26 @@ static PermPlan perm_plan(int32_t B) {
 }
 __device__ __forceinline__ int bucket_of(uint64_t key, int shift) { return shift >= 64 ? 0 : (int)(key >> shift); }
 
-__global__ void perm_zero_kernel(int* counts, int n) {
+// All kernels below process up to PERM_BATCH permutations (epochs) per launch: blockIdx.y selects the epoch,
+// whose scratch arrays sit `*_stride` elements apart.
+struct PermBases { uint64_t base[PERM_BATCH]; };
+
+__global__ void perm_zero_kernel(int* counts, int n, long stride) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) counts[i] = 0;
+  if (i < n) counts[blockIdx.y * stride + i] = 0;
 }
-__global__ void perm_hist_kernel(uint64_t base, int B, int shift, int* counts) {
+__global__ void perm_hist_kernel(const PermBases pb, int B, int shift, int* counts, long stride) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B) atomicAdd(&counts[bucket_of(mix64(base ^ (uint64_t)i), shift)], 1);
+  if (i < B) atomicAdd(&counts[blockIdx.y * stride + bucket_of(mix64(pb.base[blockIdx.y] ^ (uint64_t)i), shift)], 1);
 }
-// Exclusive scan of counts[0..nb) by one workgroup; offsets has nb + 1 entries; cursors are reset.
-__global__ __launch_bounds__(1024) void perm_scan_kernel(const int* counts, int nb, int* offsets, int* cursor) {
+// Exclusive scan of counts[0..nb) by one workgroup per epoch; offsets has nb + 1 entries; cursors are reset.
+__global__ __launch_bounds__(1024) void perm_scan_kernel(const int* counts_all, int nb, int* offsets_all, int* cursor_all,
+                                                         long stride) {
   __shared__ int wsum[16];
   __shared__ int carry;
+  const int* counts = counts_all + blockIdx.y * stride;
+  int* offsets = offsets_all + blockIdx.y * stride;
+  int* cursor = cursor_all + blockIdx.y * stride;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -205,21 +214,27 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(const int* counts, int 
   }
   if (threadIdx.x == 0) offsets[nb] = carry;
 }
-__global__ void perm_scatter_kernel(uint64_t base, int B, int shift, const int* offsets, int* cursor, uint64_t* keys,
-                                    int* idx) {
+__global__ void perm_scatter_kernel(const PermBases pb, int B, int shift, const int* offsets, int* cursor, long stride,
+                                    uint64_t* keys, int* idx, long kstride) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B) return;
-  uint64_t k = mix64(base ^ (uint64_t)i);
+  const int e = blockIdx.y;
+  uint64_t k = mix64(pb.base[e] ^ (uint64_t)i);
   int b = bucket_of(k, shift);
-  int pos = offsets[b] + atomicAdd(&cursor[b], 1);
-  keys[pos] = k;
-  idx[pos] = i;
+  int pos = offsets[e * stride + b] + atomicAdd(&cursor[e * stride + b], 1);
+  keys[e * kstride + pos] = k;
+  idx[e * kstride + pos] = i;
 }
-__global__ void perm_rank_kernel(int B, int shift, const int* offsets, const uint64_t* keys, const int* idx, int* perm) {
-  int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= B) return;
-  const uint64_t k = keys[e];
-  const int i = idx[e];
+__global__ void perm_rank_kernel(int B, int shift, const int* offsets_all, long stride, const uint64_t* keys_all,
+                                 const int* idx_all, long kstride, int* perm_all) {
+  int el = blockIdx.x * blockDim.x + threadIdx.x;
+  if (el >= B) return;
+  const int e = blockIdx.y;
+  const uint64_t* keys = keys_all + e * kstride;
+  const int* idx = idx_all + e * kstride;
+  const int* offsets = offsets_all + e * stride;
+  const uint64_t k = keys[el];
+  const int i = idx[el];
   const int b = bucket_of(k, shift);
   const int s = offsets[b], t = offsets[b + 1];
   int rank = 0;
@@ -227,33 +242,46 @@ __global__ void perm_rank_kernel(int B, int shift, const int* offsets, const uin
     uint64_t ko = keys[o];
     rank += (ko < k || (ko == k && idx[o] < i)) ? 1 : 0;
   }
-  perm[s + rank] = i;
+  perm_all[(long)e * B + s + rank] = i;
 }
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 size_t perm_workspace_bytes(int32_t B) {
   PermPlan p = perm_plan(B);
-  return align_up((size_t)(p.nb + 1) * 4, 256) * 3 + align_up((size_t)B * 8, 256) + align_up((size_t)B * 4, 256);
+  const size_t seg = align_up((size_t)(p.nb + 1) * 4, 256);
+  const size_t kseg = align_up((size_t)B * 8, 256);
+  return (size_t)PERM_BATCH * (3 * seg + kseg + kseg / 2 + 256);
 }
 
-hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, void* ws, hipStream_t stream) {
-  if (B <= 0) return hipSuccess;
-  PermPlan p = perm_plan(B);
+hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_t B, int32_t* perm_out, void* ws,
+                               hipStream_t stream) {
+  if (B <= 0 || n_perm <= 0) return hipSuccess;
   TraceScope ts(stream, "permutation", 0.0, 0.0);
+  PermPlan p = perm_plan(B);
   char* w = static_cast<char*>(ws);
   const size_t seg = align_up((size_t)(p.nb + 1) * 4, 256);
+  const size_t kseg = align_up((size_t)B * 8, 256);
   int* counts = reinterpret_cast<int*>(w);
-  int* offsets = reinterpret_cast<int*>(w + seg);
-  int* cursor = reinterpret_cast<int*>(w + 2 * seg);
-  uint64_t* keys = reinterpret_cast<uint64_t*>(w + 3 * seg);
-  int* idx = reinterpret_cast<int*>(w + 3 * seg + align_up((size_t)B * 8, 256));
+  int* offsets = reinterpret_cast<int*>(w + PERM_BATCH * seg);
+  int* cursor = reinterpret_cast<int*>(w + 2 * PERM_BATCH * seg);
+  uint64_t* keys = reinterpret_cast<uint64_t*>(w + 3 * PERM_BATCH * seg);
+  int* idx = reinterpret_cast<int*>(w + 3 * PERM_BATCH * seg + PERM_BATCH * kseg);
+  const long stride = (long)(seg / 4), kstride = (long)(kseg / 8);
   const unsigned gb = (unsigned)((B + 255) / 256);
-  hipLaunchKernelGGL(perm_zero_kernel, dim3((p.nb + 256) / 256), dim3(256), 0, stream, counts, p.nb + 1);
-  hipLaunchKernelGGL(perm_hist_kernel, dim3(gb), dim3(256), 0, stream, base_key, B, p.shift, counts);
-  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, p.nb, offsets, cursor);
-  hipLaunchKernelGGL(perm_scatter_kernel, dim3(gb), dim3(256), 0, stream, base_key, B, p.shift, offsets, cursor, keys, idx);
-  hipLaunchKernelGGL(perm_rank_kernel, dim3(gb), dim3(256), 0, stream, B, p.shift, offsets, keys, idx, perm_out);
+  for (int e0 = 0; e0 < n_perm; e0 += PERM_BATCH) {
+    const int ne = n_perm - e0 < PERM_BATCH ? n_perm - e0 : PERM_BATCH;
+    PermBases pb;
+    for (int e = 0; e < PERM_BATCH; ++e) pb.base[e] = e < ne ? base_keys[e0 + e] : 0;
+    int32_t* out = perm_out + (size_t)e0 * B;
+    hipLaunchKernelGGL(perm_zero_kernel, dim3((p.nb + 256) / 256, ne), dim3(256), 0, stream, counts, p.nb + 1, stride);
+    hipLaunchKernelGGL(perm_hist_kernel, dim3(gb, ne), dim3(256), 0, stream, pb, B, p.shift, counts, stride);
+    hipLaunchKernelGGL(perm_scan_kernel, dim3(1, ne), dim3(1024), 0, stream, counts, p.nb, offsets, cursor, stride);
+    hipLaunchKernelGGL(perm_scatter_kernel, dim3(gb, ne), dim3(256), 0, stream, pb, B, p.shift, offsets, cursor, stride, keys,
+                       idx, kstride);
+    hipLaunchKernelGGL(perm_rank_kernel, dim3(gb, ne), dim3(256), 0, stream, B, p.shift, offsets, stride, keys, idx, kstride,
+                       out);
+  }
   return hipGetLastError();
 }
 
@@ -477,7 +505,6 @@ __device__ __forceinline__ RowTerms ppo_row(const PpoLossArgs& a, float logp_new
 }
 
 __global__ __launch_bounds__(256) void ppo_loss_kernel(const PpoLossArgs a) {
-  __shared__ double smem[4];
   const int i = blockIdx.x * 256 + threadIdx.x;
   const int A = a.A;
   const bool sym = a.rows > a.mb;
@@ -550,20 +577,22 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(const PpoLossArgs a) {
       }
     }
   }
-  double* out = a.partials + (long)blockIdx.x * (PPO_NPART_FIXED + A);
-  double r;
-  r = block_sum((double)surr, smem);    if (threadIdx.x == 0) out[0] = r;
-  r = block_sum((double)vloss, smem);   if (threadIdx.x == 0) out[1] = r;
-  r = block_sum((double)kl, smem);      if (threadIdx.x == 0) out[2] = r;
-  r = block_sum((double)clipped, smem); if (threadIdx.x == 0) out[3] = r;
-  r = block_sum((double)mirror, smem);  if (threadIdx.x == 0) out[4] = r;
+  // every component: wavefront shuffle reduction, one LDS exchange, then lane c of wavefront 0 adds the four
+  __shared__ double wpart[4][PPO_NPART_FIXED + AMAX];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  auto put = [&](int c, float v) {
+    double r = wave_sum((double)v);
+    if (lane == 0) wpart[w][c] = r;
+  };
+  put(0, surr); put(1, vloss); put(2, kl); put(3, clipped); put(4, mirror);
 #pragma unroll
-  for (int jj = 0; jj < AMAX; ++jj) {
-    if (jj < A) {
-      r = block_sum((double)dls[jj], smem);
-      if (threadIdx.x == 0) out[PPO_NPART_FIXED + jj] = r;
-    }
-  }
+  for (int jj = 0; jj < AMAX; ++jj)
+    if (jj < A) put(PPO_NPART_FIXED + jj, dls[jj]);
+  __syncthreads();
+  const int ncomp = PPO_NPART_FIXED + A;
+  if (threadIdx.x < ncomp)
+    a.partials[(long)blockIdx.x * ncomp + threadIdx.x] =
+        wpart[0][threadIdx.x] + wpart[1][threadIdx.x] + wpart[2][threadIdx.x] + wpart[3][threadIdx.x];
 }
 
 hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
@@ -572,17 +601,25 @@ hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// One wavefront: lane c sums component c over the blocks in block order.
-__global__ __launch_bounds__(64) void ppo_loss_finish_kernel(const double* __restrict__ partials, int blocks, int rows,
-                                                             int mb, int A, const float* __restrict__ log_std,
-                                                             float entropy_coef, float* __restrict__ d_log_std,
-                                                             float* __restrict__ stats_row,
-                                                             double* __restrict__ sumsq_slot) {
-  const int c = threadIdx.x;
+// One workgroup: lane c of every wavefront sums component c over every 4th block, the four partial sums are
+// combined in a fixed order, then wavefront 0 writes the statistics row and the log_std gradient.
+__global__ __launch_bounds__(256) void ppo_loss_finish_kernel(const double* __restrict__ partials, int blocks, int rows,
+                                                              int mb, int A, const float* __restrict__ log_std,
+                                                              float entropy_coef, float* __restrict__ d_log_std,
+                                                              float* __restrict__ stats_row,
+                                                              double* __restrict__ sumsq_slot) {
+  __shared__ double wpart[4][64];
+  const int c = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int ncomp = PPO_NPART_FIXED + A;
-  double s = 0.0;
-  if (c < ncomp)
-    for (int b = 0; b < blocks; ++b) s += partials[(long)b * ncomp + c];
+  double acc = 0.0;
+  if (c < ncomp) {
+#pragma unroll 4
+    for (int b = w; b < blocks; b += 4) acc += partials[(long)b * ncomp + c];
+  }
+  wpart[w][c] = acc;
+  __syncthreads();
+  if (w != 0) return;
+  const double s = wpart[0][c] + wpart[1][c] + wpart[2][c] + wpart[3][c];
   double g2 = 0.0;
   if (c >= PPO_NPART_FIXED && c < ncomp) {
     const float g = (float)s - entropy_coef;
@@ -608,7 +645,7 @@ __global__ __launch_bounds__(64) void ppo_loss_finish_kernel(const double* __res
 hipError_t launch_ppo_loss_finish(const double* partials, int32_t blocks, int32_t rows, int32_t mb, int32_t A,
                                   const float* log_std, float entropy_coef, float* d_log_std, float* stats_row,
                                   double* sumsq_slot, hipStream_t stream) {
-  hipLaunchKernelGGL(ppo_loss_finish_kernel, dim3(1), dim3(64), 0, stream, partials, blocks, rows, mb, A, log_std,
+  hipLaunchKernelGGL(ppo_loss_finish_kernel, dim3(1), dim3(256), 0, stream, partials, blocks, rows, mb, A, log_std,
                      entropy_coef, d_log_std, stats_row, sumsq_slot);
   return hipGetLastError();
 }

@@ -265,9 +265,18 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
       if (col >= P.N) continue;
       float bias = 0.f;
       if (MODE == GEMM_FWD && P.aux) bias = P.aux[col];
+      const int row_base = m0 + wm * (TM * 32) + x * 32 + 4 * g;
+      float hx[16];
+      if (MODE == GEMM_DX && P.aux != nullptr) {   // all 16 loads of a 32x32 block are in flight together
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = min(row_base + 8 * (r / 4) + (r % 4), P.M - 1);
+          hx[r] = P.aux[(long)row * P.ldc + col];
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * (TM * 32) + x * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+        const int row = row_base + 8 * (r / 4) + (r % 4);
         if (row >= P.M) continue;
         float v = acc[x][y][r];
         const long o = (long)row * P.ldc + col;
@@ -275,10 +284,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
           v += bias;
           if (P.elu) v = v > 0.f ? v : P.alpha * expm1f(v);
         } else if (MODE == GEMM_DX) {
-          if (P.aux) {
-            float h = P.aux[o];
-            v *= (h > 0.f) ? 1.0f : (h + P.alpha);
-          }
+          if (P.aux != nullptr) v *= (hx[r] > 0.f) ? 1.0f : (hx[r] + P.alpha);
         }
         Cb[o] = v;
       }
@@ -329,6 +335,7 @@ static TileCfg pick_tile(GemmMode mode, const GemmBatch& batch) {
   if (maxN <= 64) return TILE_128x64;
   if (mode == GEMM_DW) return dw_big ? TILE_128x128 : TILE_64x128;
   if (minK <= 64 || tiles128 < 700) return TILE_64x128;
+  if (mode == GEMM_DX && maxN >= 512) return TILE_64x128;   // wide outputs: the ELU' operand reads favour more, smaller workgroups
   return TILE_128x128;
 }
 

@@ -104,7 +104,9 @@ hipError_t launch_gae(const float* rewards, const float* values, const float* la
 
 // Permutation by sorting 64-bit hash keys (bucket scatter + in-bucket ranking).
 size_t perm_workspace_bytes(int32_t B);
-hipError_t launch_permutation(uint64_t base_key, int32_t B, int32_t* perm_out, void* ws, hipStream_t stream);
+// perm_out [n_perm, B]; base_keys (host) holds one hashed stream key per permutation.
+hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_t B, int32_t* perm_out, void* ws,
+                               hipStream_t stream);
 
 // Sum the split partials of one network's gradient, layer by layer, into the flat gradient buffer and emit
 // per-block sums of squares.  Layer l owns `split[l]` partial buffers of `size[l]` floats each, `pitch[l]` floats
