@@ -169,9 +169,46 @@ def main():
         "kernels": breakdown,
     }
 
+    result["streaming"] = streaming_kernels(rx, torch, T, N, int(actor.params.numel() + critic.params.numel()))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
+
+
+def streaming_kernels(rx, torch, T, N, n_params):
+    """HBM-bound pieces on their own: GAE (+ advantage normalisation) and clip + Adam, at the workload's size
+    (a few MB: cache resident and launch-latency bound) and at a size that shows the achieved HBM bandwidth."""
+    def timeit(f, reps):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    out = {}
+    for label, n_env in (("gae_on_config", N), ("gae_off_config_2^20_envs", 1 << 20)):
+        r = torch.randn(T, n_env, device="cuda"); V = torch.randn(T, n_env, device="cuda"); Vl = torch.randn(n_env, device="cuda")
+        d = (torch.rand(T, n_env, device="cuda") < 0.001).to(torch.uint8)
+        adv = torch.empty(T, n_env, device="cuda"); ret = torch.empty(T, n_env, device="cuda")
+        ws = rx.workspace(rx.rslx_gae_workspace_bytes(T, n_env))
+        ms = timeit(lambda: rx.rslx_gae(r, V, Vl, d, None, T, n_env, 0.99, 0.95, 1, adv, ret, ws), 20)
+        nbytes = 25.0 * T * n_env + 4.0 * n_env       # 17 B/element scan + 8 B/element normalisation pass
+        out[label] = {"us": round(ms * 1e3, 2), "GB/s": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del r, V, Vl, d, adv, ret
+    for label, n in (("adam_on_config", n_params), ("adam_off_config_64M_params", 1 << 26)):
+        p = torch.randn(n, device="cuda"); g = torch.randn(n, device="cuda") * 0.01
+        m = torch.zeros(n, device="cuda"); v = torch.zeros(n, device="cuda")
+        ws = rx.workspace(rx.rslx_adam_workspace_bytes(n)); st = ctypes.c_int64(0)
+        ms = timeit(lambda: rx.rslx_adam_step(p, g, m, v, n, 1e-3, 0.9, 0.999, 1e-8, 1.0, st, None, ws), 10)
+        nbytes = 32.0 * n                               # 4 B/param squared-norm pass + 28 B/param clip + Adam
+        out[label] = {"us": round(ms * 1e3, 2), "GB/s": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del p, g, m, v
+    return out
 
 
 def cpu_baseline(w, inp):

@@ -514,7 +514,7 @@ int32_t rslx_gae(const float* rewards, const float* values, const float* last_va
 }
 
 // ---- Adam ----------------------------------------------------------------------------------------------------
-size_t rslx_adam_workspace_bytes(int64_t n) { return n > 0 ? (size_t)reduce_num_blocks(n) * 8 + 512 : 256; }
+size_t rslx_adam_workspace_bytes(int64_t n) { return n > 0 ? ((size_t)reduce_num_blocks(n) + 1) * 8 + 512 : 256; }
 
 int32_t rslx_adam_step(float* params, const float* grads, float* m, float* v, int64_t n, float lr, float beta1,
                        float beta2, float eps, float max_grad_norm, int64_t* adam_step, float* grad_norm_out, void* ws,
@@ -529,7 +529,7 @@ int32_t rslx_adam_step(float* params, const float* grads, float* m, float* v, in
   hipStream_t s = (hipStream_t)stream;
   Carver c(ws);
   const int nb = reduce_num_blocks(n);
-  double* sumsq = c.take<double>(nb);
+  double* sumsq = c.take<double>((size_t)nb + 1);
   RSLX_HIP(launch_sumsq(grads, n, sumsq, s));
   const int64_t t = *adam_step + 1;
   AdamArgs a;
@@ -589,13 +589,13 @@ void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rs
   p.perm_ws = c.take<char>(perm_workspace_bytes(p.B));
   carve_train(c, *actor, p.rows, 2, p.actor);
   carve_train(c, *critic, p.rows, 2, p.critic);
-  p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 1);
+  p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 2);
   p.actor.sumsq = p.sumsq_all;
   p.critic.sumsq = p.sumsq_all + p.actor.n_sumsq;
   p.loss_partials = c.take<double>((size_t)ppo_loss_num_blocks(p.mb) * (PPO_NPART_FIXED + ro->A));
   if (rnd) {
     carve_train(c, *rnd->predictor, p.mb, 1, p.pred);
-    p.pred.sumsq = c.take<double>(p.pred.n_sumsq);
+    p.pred.sumsq = c.take<double>((size_t)p.pred.n_sumsq + 1);
     carve_net(c, *rnd->target, p.mb, false, p.targ);
     const int K = rnd->target->dims[rnd->target->n_layers];
     p.mse_partials = c.take<double>(mse_num_blocks((int64_t)p.mb * K));
@@ -802,7 +802,7 @@ void bc_plan(Carver& c, const rslx_mlp* student, const rslx_mlp* teacher, int32_
   p.perms = c.take<int32_t>((size_t)cfg->epochs * B);
   p.perm_ws = c.take<char>(perm_workspace_bytes(B));
   carve_train(c, *student, p.mb, 1, p.student);
-  p.student.sumsq = c.take<double>(p.student.n_sumsq);
+  p.student.sumsq = c.take<double>((size_t)p.student.n_sumsq + 1);
   const int A = student->dims[student->n_layers];
   if (teacher) {
     carve_net(c, *teacher, p.mb, false, p.teacher);

@@ -407,7 +407,24 @@ __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
   }
 }
 
-hipError_t launch_adam(const AdamArgs& a, hipStream_t stream) {
+// Long squared-norm lists (large flat buffers) are first folded to one value by a single workgroup, so that the
+// per-block re-reduction in adam_kernel stays short.
+__global__ __launch_bounds__(1024) void sumsq_fold_kernel(const double* __restrict__ in, int n, double* __restrict__ out) {
+  __shared__ double smem[16];
+  double q = 0.0;
+  for (int i = threadIdx.x; i < n; i += 1024) q += in[i];
+  double t = block_sum(q, smem);
+  if (threadIdx.x == 0) *out = t;
+}
+
+hipError_t launch_adam(const AdamArgs& a_in, hipStream_t stream) {
+  AdamArgs a = a_in;
+  if (a.n_sumsq > ADAM_MAX_INLINE_SUMSQ) {     // caller reserved one extra slot behind the list
+    double* total = const_cast<double*>(a.sumsq_blocks) + a.n_sumsq;
+    hipLaunchKernelGGL(sumsq_fold_kernel, dim3(1), dim3(1024), 0, stream, a.sumsq_blocks, a.n_sumsq, total);
+    a.sumsq_blocks = total;
+    a.n_sumsq = 1;
+  }
   int64_t nmax = 0;
   for (int i = 0; i < a.n_seg; ++i) nmax = a.seg[i].n > nmax ? a.seg[i].n : nmax;
   if (nmax <= 0) return hipSuccess;

@@ -143,6 +143,9 @@ struct AdamArgs {
   float bc1, bc2;              // 1 - beta1^t, 1 - beta2^t
   float* grad_norm_out;        // optional device scalar (stats column)
 };
+// Lists longer than this are folded by an extra single-workgroup launch into the slot sumsq_blocks[n_sumsq],
+// which the caller must have reserved.
+constexpr int ADAM_MAX_INLINE_SUMSQ = 4096;
 hipError_t launch_adam(const AdamArgs& a, hipStream_t stream);
 
 // Gaussian head of act(): noise, action, log-density.
