@@ -27,118 +27,155 @@ __device__ __forceinline__ int src_row(const GemmProblem& P, int r) {
   return P.row_idx ? P.row_idx[rr] : rr;
 }
 
-// One element of the gathered / column-mapped view X(r, c).
-__device__ __forceinline__ float x_elem(const GemmProblem& P, int r, int c) {
-  long base = (long)src_row(P, r) * P.lda;
-  if (P.col_map != nullptr && r >= P.map_from) {
-    float s = P.col_sign ? P.col_sign[c] : 1.0f;
-    return s * P.A[base + P.col_map[c]];
-  }
-  return P.A[base + c];
-}
-
-// ---- tile fetch: operand stored with the contraction index contiguous (rows = M or N index) -------
-// Produces R*BK/NT values per lane; element (row, k) lands at lds[k][row].
+// ---- operand with the contraction index contiguous in memory (tile rows = M or N index) ---------------------
+// Everything that does not change along the contraction (row pointers with the gather applied, validity,
+// whether the row uses the column map) is set up once per tile; a k-tile fetch is then loads only.
+// Element (row, k) lands at lds[k][row].
 template <int R, int BK, bool IS_X>
-__device__ __forceinline__ void fetch_kcontig(const GemmProblem& P, const float* __restrict__ base, int ld, bool vec,
-                                              int row0, int row_end, int k0, int k_end, float (&reg)[R * BK / NT]) {
-  const int tid = threadIdx.x;
-  if (vec) {
-    constexpr int LK = BK / 4;       // lanes along the contraction index (one float4 each)
-    constexpr int RP = NT / LK;      // rows per pass
+struct KContig {
+  static constexpr int NREG = R * BK / NT;
+  static constexpr int LK = BK / 4;                 // vector path: lanes along k (one float4 each)
+  static constexpr int RPV = NT / LK;               // vector path: rows per pass
+  static constexpr int RPS = NT / BK;               // scalar path: rows per pass
+  const float* ptr[NREG];                           // row pointers (vector path uses the first R / RPV)
+  bool mapped[NREG];                                // scalar path: row reads through col_map / col_sign
+  bool vec;
+
+  __device__ __forceinline__ void setup(const GemmProblem& P, const float* base, int ld, bool use_vec, int row0, int row_end) {
+    const int tid = threadIdx.x;
+    vec = use_vec;
+    if (vec) {
 #pragma unroll
-    for (int p = 0; p < R / RP; ++p) {
-      int row = row0 + p * RP + tid / LK;
-      int kk = k0 + 4 * (tid % LK);
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row < row_end && kk < k_end) {
-        long sr = IS_X ? (long)src_row(P, row) : (long)row;
-        v = *reinterpret_cast<const float4*>(base + sr * ld + kk);
+      for (int p = 0; p < R / RPV; ++p) {
+        const int row = row0 + p * RPV + tid / LK;
+        ptr[p] = nullptr;
+        if (row < row_end) ptr[p] = base + (long)(IS_X ? src_row(P, row) : row) * ld + 4 * (tid % LK);
       }
-      reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
-    }
-  } else {
-    constexpr int RP = NT / BK;
+    } else {
 #pragma unroll
-    for (int p = 0; p < R / RP; ++p) {
-      int row = row0 + p * RP + tid / BK;
-      int kk = k0 + tid % BK;
-      float v = 0.f;
-      if (row < row_end && kk < k_end) v = IS_X ? x_elem(P, row, kk) : base[(long)row * ld + kk];
-      reg[p] = v;
+      for (int p = 0; p < R / RPS; ++p) {
+        const int row = row0 + p * RPS + tid / BK;
+        ptr[p] = nullptr;
+        mapped[p] = false;
+        if (row < row_end) {
+          ptr[p] = base + (long)(IS_X ? src_row(P, row) : row) * ld;
+          mapped[p] = IS_X && P.col_map != nullptr && row >= P.map_from;
+        }
+      }
     }
   }
-}
 
-template <int R, int BK, int S>
-__device__ __forceinline__ void stash_kcontig(bool vec, float (*lds)[S], const float (&reg)[R * BK / NT]) {
-  const int tid = threadIdx.x;
-  if (vec) {
-    constexpr int LK = BK / 4;
-    constexpr int RP = NT / LK;
+  __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
+    const int tid = threadIdx.x;
+    if (vec) {
+      const bool kok = k0 + 4 * (tid % LK) < k_end;
 #pragma unroll
-    for (int p = 0; p < R / RP; ++p) {
-      int row = p * RP + tid / LK;
-      int kq = 4 * (tid % LK);
+      for (int p = 0; p < R / RPV; ++p) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (kok && ptr[p] != nullptr) v = *reinterpret_cast<const float4*>(ptr[p] + k0);
+        reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
+      }
+    } else {
+      const int c = k0 + tid % BK;
+      const bool kok = c < k_end;
+      int cm = c;
+      float sg = 1.0f;
+      if (IS_X && kok && P.col_map != nullptr) {
+        cm = P.col_map[c];
+        if (P.col_sign != nullptr) sg = P.col_sign[c];
+      }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) lds[kq + c][row] = reg[4 * p + c];
+      for (int p = 0; p < R / RPS; ++p) {
+        float v = 0.f;
+        if (kok && ptr[p] != nullptr) v = mapped[p] ? sg * ptr[p][cm] : ptr[p][c];
+        reg[p] = v;
+      }
     }
-  } else {
-    constexpr int RP = NT / BK;
-#pragma unroll
-    for (int p = 0; p < R / RP; ++p) lds[tid % BK][p * RP + tid / BK] = reg[p];
   }
-}
 
-// ---- tile fetch: operand stored with the M / N index contiguous (rows = contraction index) --------
+  template <int S>
+  __device__ __forceinline__ void stash(float (*lds)[S], const float (&reg)[NREG]) const {
+    const int tid = threadIdx.x;
+    if (vec) {
+#pragma unroll
+      for (int p = 0; p < R / RPV; ++p) {
+        const int row = p * RPV + tid / LK;
+        const int kq = 4 * (tid % LK);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) lds[kq + c][row] = reg[4 * p + c];
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < R / RPS; ++p) lds[tid % BK][p * RPS + tid / BK] = reg[p];
+    }
+  }
+};
+
+// ---- operand with the M / N index contiguous in memory (tile rows = contraction index) ----------------------
+// The column (and its mapped twin for mirrored rows) is fixed per lane; the contraction row changes per k-tile.
 template <int Cw, int BK, bool IS_X>
-__device__ __forceinline__ void fetch_direct(const GemmProblem& P, const float* __restrict__ base, int ld, bool vec,
-                                             int col0, int col_end, int k0, int k_end, float (&reg)[Cw * BK / NT]) {
-  const int tid = threadIdx.x;
-  if (vec) {
-    constexpr int V = Cw / 4;        // float4 per tile row
-    constexpr int RP = NT / V;       // tile rows per pass
-#pragma unroll
-    for (int p = 0; p < BK / RP; ++p) {
-      int kk = k0 + p * RP + tid / V;
-      int col = col0 + 4 * (tid % V);
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (kk < k_end && col < col_end) {
-        long sr = IS_X ? (long)src_row(P, kk) : (long)kk;
-        v = *reinterpret_cast<const float4*>(base + sr * ld + col);
-      }
-      reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
-    }
-  } else {
-    constexpr int RP = NT / Cw;
-#pragma unroll
-    for (int p = 0; p < BK / RP; ++p) {
-      int kk = k0 + p * RP + tid / Cw;
-      int col = col0 + tid % Cw;
-      float v = 0.f;
-      if (kk < k_end && col < col_end) v = IS_X ? x_elem(P, kk, col) : base[(long)kk * ld + col];
-      reg[p] = v;
-    }
-  }
-}
+struct Direct {
+  static constexpr int NREG = Cw * BK / NT;
+  static constexpr int V = Cw / 4;                  // vector path: float4 per tile row
+  static constexpr int RPV = NT / V;                // vector path: tile rows per pass
+  static constexpr int RPS = NT / Cw;               // scalar path: tile rows per pass
+  const float* base;
+  int ld, col, cm;
+  float sg;
+  bool vec, col_ok, has_map;
 
-template <int Cw, int BK, int S>
-__device__ __forceinline__ void stash_direct(bool vec, float (*lds)[S], const float (&reg)[Cw * BK / NT]) {
-  const int tid = threadIdx.x;
-  if (vec) {
-    constexpr int V = Cw / 4;
-    constexpr int RP = NT / V;
-#pragma unroll
-    for (int p = 0; p < BK / RP; ++p) {
-      float4 v = make_float4(reg[4 * p], reg[4 * p + 1], reg[4 * p + 2], reg[4 * p + 3]);
-      *reinterpret_cast<float4*>(&lds[p * RP + tid / V][4 * (tid % V)]) = v;
+  __device__ __forceinline__ void setup(const GemmProblem& P, const float* b, int ld_, bool use_vec, int col0, int col_end) {
+    const int tid = threadIdx.x;
+    base = b; ld = ld_; vec = use_vec;
+    col = vec ? col0 + 4 * (tid % V) : col0 + tid % Cw;
+    col_ok = col < col_end;
+    has_map = false; cm = col; sg = 1.0f;
+    if (IS_X && !vec && col_ok && P.col_map != nullptr) {
+      has_map = true;
+      cm = P.col_map[col];
+      if (P.col_sign != nullptr) sg = P.col_sign[col];
     }
-  } else {
-    constexpr int RP = NT / Cw;
-#pragma unroll
-    for (int p = 0; p < BK / RP; ++p) lds[p * RP + tid / Cw][tid % Cw] = reg[p];
   }
-}
+
+  __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
+    const int tid = threadIdx.x;
+    if (vec) {
+#pragma unroll
+      for (int p = 0; p < BK / RPV; ++p) {
+        const int kk = k0 + p * RPV + tid / V;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (col_ok && kk < k_end) v = *reinterpret_cast<const float4*>(base + (long)(IS_X ? src_row(P, kk) : kk) * ld + col);
+        reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < BK / RPS; ++p) {
+        const int kk = k0 + p * RPS + tid / Cw;
+        float v = 0.f;
+        if (col_ok && kk < k_end) {
+          const float* rowp = base + (long)(IS_X ? src_row(P, kk) : kk) * ld;
+          v = (has_map && kk >= P.map_from) ? sg * rowp[cm] : rowp[col];
+        }
+        reg[p] = v;
+      }
+    }
+  }
+
+  template <int S>
+  __device__ __forceinline__ void stash(float (*lds)[S], const float (&reg)[NREG]) const {
+    const int tid = threadIdx.x;
+    if (vec) {
+#pragma unroll
+      for (int p = 0; p < BK / RPV; ++p) {
+        const float4 v = make_float4(reg[4 * p], reg[4 * p + 1], reg[4 * p + 2], reg[4 * p + 3]);
+        *reinterpret_cast<float4*>(&lds[p * RPV + tid / V][4 * (tid % V)]) = v;
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < BK / RPS; ++p) lds[p * RPS + tid / Cw][tid % Cw] = reg[p];
+    }
+  }
+};
 
 template <int MODE, int BM, int BN, int WM, int WN, int BK>
 __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
@@ -185,29 +222,24 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
   float bsum = 0.f;   // DW: column sum of dZ for the bias gradient
 
+  // operand A: DW reads X rows as contraction rows (M index contiguous); FWD / DX read rows with k contiguous.
+  // operand B: always N index contiguous (W, W^T or dZ).
+  KContig<BM, BK, MODE == GEMM_FWD> a_k;
+  Direct<BM, BK, true> a_d;
+  Direct<BN, BK, false> b_d;
+  if (MODE == GEMM_DW) a_d.setup(P, P.A, P.lda, avec, m0, P.M);
+  else a_k.setup(P, P.A, P.lda, avec, m0, P.M);
+  b_d.setup(P, P.B, P.ldb, bvec, n0, P.N);
+
   auto fetch = [&](int k0) {
-    if (MODE == GEMM_DW) {
-      fetch_direct<BM, BK, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
-      fetch_direct<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
-    } else if (MODE == GEMM_FWD) {
-      fetch_kcontig<BM, BK, true>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
-      fetch_direct<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
-    } else {
-      fetch_kcontig<BM, BK, false>(P, P.A, P.lda, avec, m0, P.M, k0, k_end, ra);
-      fetch_direct<BN, BK, false>(P, P.B, P.ldb, bvec, n0, P.N, k0, k_end, rb);
-    }
+    if (MODE == GEMM_DW) a_d.fetch(P, k0, k_end, ra);
+    else a_k.fetch(P, k0, k_end, ra);
+    b_d.fetch(P, k0, k_end, rb);
   };
   auto stash = [&](int buf) {
-    if (MODE == GEMM_DW) {
-      stash_direct<BM, BK, SA>(avec, As[buf], ra);
-      stash_direct<BN, BK, SB>(bvec, Bs[buf], rb);
-    } else if (MODE == GEMM_FWD) {
-      stash_kcontig<BM, BK, SA>(avec, As[buf], ra);
-      stash_direct<BN, BK, SB>(bvec, Bs[buf], rb);
-    } else {
-      stash_kcontig<BM, BK, SA>(avec, As[buf], ra);
-      stash_direct<BN, BK, SB>(bvec, Bs[buf], rb);
-    }
+    if (MODE == GEMM_DW) a_d.template stash<SA>(As[buf], ra);
+    else a_k.template stash<SA>(As[buf], ra);
+    b_d.template stash<SB>(Bs[buf], rb);
   };
 
   if (nk > 0) {
@@ -282,7 +314,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
         const long o = (long)row * P.ldc + col;
         if (MODE == GEMM_FWD) {
           v += bias;
-          if (P.elu) v = v > 0.f ? v : P.alpha * expm1f(v);
+          if (P.elu) v = v > 0.f ? v : P.alpha * (__expf(v) - 1.0f);
         } else if (MODE == GEMM_DX) {
           if (P.aux != nullptr) v *= (hx[r] > 0.f) ? 1.0f : (hx[r] + P.alpha);
         }
