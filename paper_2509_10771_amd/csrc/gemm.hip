@@ -31,20 +31,21 @@ __device__ __forceinline__ int src_row(const GemmProblem& P, int r) {
 // Everything that does not change along the contraction (row pointers with the gather applied, validity,
 // whether the row uses the column map) is set up once per tile; a k-tile fetch is then loads only.
 // Element (row, k) lands at lds[k][row].
-template <int R, int BK, bool IS_X>
+template <int R, int BK, bool IS_X, bool VEC>
 struct KContig {
   static constexpr int NREG = R * BK / NT;
   static constexpr int LK = BK / 4;                 // vector path: lanes along k (one float4 each)
   static constexpr int RPV = NT / LK;               // vector path: rows per pass
   static constexpr int RPS = NT / BK;               // scalar path: rows per pass
-  const float* ptr[NREG];                           // row pointers (vector path uses the first R / RPV)
-  bool mapped[NREG];                                // scalar path: row reads through col_map / col_sign
-  bool vec;
+  static constexpr int NPTR = VEC ? R / RPV : R / RPS;
+  static constexpr bool vec = VEC;
+  const float* ptr[NPTR];                           // row pointers, gather applied
+  uint32_t mapped;                                  // scalar path, bit p: row of pass p reads through col_map / col_sign
 
-  __device__ __forceinline__ void setup(const GemmProblem& P, const float* base, int ld, bool use_vec, int row0, int row_end) {
+  __device__ __forceinline__ void setup(const GemmProblem& P, const float* base, int ld, int row0, int row_end) {
     const int tid = threadIdx.x;
-    vec = use_vec;
-    if (vec) {
+    mapped = 0;
+    if constexpr (VEC) {
 #pragma unroll
       for (int p = 0; p < R / RPV; ++p) {
         const int row = row0 + p * RPV + tid / LK;
@@ -56,10 +57,9 @@ struct KContig {
       for (int p = 0; p < R / RPS; ++p) {
         const int row = row0 + p * RPS + tid / BK;
         ptr[p] = nullptr;
-        mapped[p] = false;
         if (row < row_end) {
           ptr[p] = base + (long)(IS_X ? src_row(P, row) : row) * ld;
-          mapped[p] = IS_X && P.col_map != nullptr && row >= P.map_from;
+          if (IS_X && P.col_map != nullptr && row >= P.map_from) mapped |= 1u << p;
         }
       }
     }
@@ -67,7 +67,7 @@ struct KContig {
 
   __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
     const int tid = threadIdx.x;
-    if (vec) {
+    if constexpr (VEC) {
       const bool kok = k0 + 4 * (tid % LK) < k_end;
 #pragma unroll
       for (int p = 0; p < R / RPV; ++p) {
@@ -87,7 +87,7 @@ struct KContig {
 #pragma unroll
       for (int p = 0; p < R / RPS; ++p) {
         float v = 0.f;
-        if (kok && ptr[p] != nullptr) v = mapped[p] ? sg * ptr[p][cm] : ptr[p][c];
+        if (kok && ptr[p] != nullptr) v = ((mapped >> p) & 1u) ? sg * ptr[p][cm] : ptr[p][c];
         reg[p] = v;
       }
     }
@@ -96,7 +96,7 @@ struct KContig {
   template <int S>
   __device__ __forceinline__ void stash(float (*lds)[S], const float (&reg)[NREG]) const {
     const int tid = threadIdx.x;
-    if (vec) {
+    if constexpr (VEC) {
 #pragma unroll
       for (int p = 0; p < R / RPV; ++p) {
         const int row = p * RPV + tid / LK;
@@ -113,7 +113,7 @@ struct KContig {
 
 // ---- operand with the M / N index contiguous in memory (tile rows = contraction index) ----------------------
 // The column (and its mapped twin for mirrored rows) is fixed per lane; the contraction row changes per k-tile.
-template <int Cw, int BK, bool IS_X>
+template <int Cw, int BK, bool IS_X, bool VEC>
 struct Direct {
   static constexpr int NREG = Cw * BK / NT;
   static constexpr int V = Cw / 4;                  // vector path: float4 per tile row
@@ -122,11 +122,12 @@ struct Direct {
   const float* base;
   int ld, col, cm;
   float sg;
-  bool vec, col_ok, has_map;
+  bool col_ok, has_map;
+  static constexpr bool vec = VEC;
 
-  __device__ __forceinline__ void setup(const GemmProblem& P, const float* b, int ld_, bool use_vec, int col0, int col_end) {
+  __device__ __forceinline__ void setup(const GemmProblem& P, const float* b, int ld_, int col0, int col_end) {
     const int tid = threadIdx.x;
-    base = b; ld = ld_; vec = use_vec;
+    base = b; ld = ld_;
     col = vec ? col0 + 4 * (tid % V) : col0 + tid % Cw;
     col_ok = col < col_end;
     has_map = false; cm = col; sg = 1.0f;
@@ -139,7 +140,7 @@ struct Direct {
 
   __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
     const int tid = threadIdx.x;
-    if (vec) {
+    if constexpr (VEC) {
 #pragma unroll
       for (int p = 0; p < BK / RPV; ++p) {
         const int kk = k0 + p * RPV + tid / V;
@@ -164,7 +165,7 @@ struct Direct {
   template <int S>
   __device__ __forceinline__ void stash(float (*lds)[S], const float (&reg)[NREG]) const {
     const int tid = threadIdx.x;
-    if (vec) {
+    if constexpr (VEC) {
 #pragma unroll
       for (int p = 0; p < BK / RPV; ++p) {
         const float4 v = make_float4(reg[4 * p], reg[4 * p + 1], reg[4 * p + 2], reg[4 * p + 3]);
@@ -177,8 +178,8 @@ struct Direct {
   }
 };
 
-template <int MODE, int BM, int BN, int WM, int WN, int BK>
-__global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
+template <int MODE, int BM, int BN, int WM, int WN, int BK, bool AVEC, bool BVEC>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void gemm_kernel(const GemmBatch batch) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 block");
@@ -209,8 +210,6 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
   const int g = lane >> 5, j = lane & 31;
   const int wm = wave / WN, wn = wave % WN;
   const int a_off = wm * (TM * 32) + j, b_off = wn * (TN * 32) + j;
-  // 16-byte fetches need at least 64 rows / columns per tile to give every lane a slot
-  const bool avec = P.a_vec != 0 && BM * BK >= 4 * NT, bvec = P.b_vec != 0 && BN * BK >= 4 * NT;
 
   float ra[BM * BK / NT], rb[BN * BK / NT];
   f32x16 acc[TM][TN];
@@ -224,12 +223,12 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
 
   // operand A: DW reads X rows as contraction rows (M index contiguous); FWD / DX read rows with k contiguous.
   // operand B: always N index contiguous (W, W^T or dZ).
-  KContig<BM, BK, MODE == GEMM_FWD> a_k;
-  Direct<BM, BK, true> a_d;
-  Direct<BN, BK, false> b_d;
-  if (MODE == GEMM_DW) a_d.setup(P, P.A, P.lda, avec, m0, P.M);
-  else a_k.setup(P, P.A, P.lda, avec, m0, P.M);
-  b_d.setup(P, P.B, P.ldb, bvec, n0, P.N);
+  KContig<BM, BK, MODE == GEMM_FWD, AVEC> a_k;
+  Direct<BM, BK, true, AVEC> a_d;
+  Direct<BN, BK, false, BVEC> b_d;
+  if (MODE == GEMM_DW) a_d.setup(P, P.A, P.lda, m0, P.M);
+  else a_k.setup(P, P.A, P.lda, m0, P.M);
+  b_d.setup(P, P.B, P.ldb, n0, P.N);
 
   auto fetch = [&](int k0) {
     if (MODE == GEMM_DW) a_d.fetch(P, k0, k_end, ra);
@@ -328,11 +327,15 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmBatch batch) {
 template <int MODE, int BM, int BN, int WM, int WN, int BK = 16>
 static hipError_t launch_cfg(const GemmBatch& batch, hipStream_t stream) {
   int tiles = 0, splits = 1;
+  // 16-byte fetches need every grouped problem to allow them and at least one float4 per lane and tile
+  bool avec = BM * BK >= 4 * NT, bvec = BN * BK >= 4 * NT;
   for (int i = 0; i < batch.count; ++i) {
     const GemmProblem& P = batch.p[i];
     int t = ((P.M + BM - 1) / BM) * ((P.N + BN - 1) / BN);
     tiles = t > tiles ? t : tiles;
     if (MODE == GEMM_DW) splits = P.n_split > splits ? P.n_split : splits;
+    avec = avec && P.a_vec != 0;
+    bvec = bvec && P.b_vec != 0;
   }
   if (tiles == 0) return hipSuccess;
   dim3 grid(tiles, splits, batch.count);
@@ -342,7 +345,10 @@ static hipError_t launch_cfg(const GemmBatch& batch, hipStream_t stream) {
   char name[48];
   snprintf(name, sizeof name, "gemm_%s_%dx%d", mode_name[MODE], BM, BN);
   TraceScope ts(stream, name, flops, 0.0);
-  hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN, BK>), grid, dim3(NT), 0, stream, batch);
+  if (avec && bvec) hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN, BK, true, true>), grid, dim3(NT), 0, stream, batch);
+  else if (avec) hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN, BK, true, false>), grid, dim3(NT), 0, stream, batch);
+  else if (bvec) hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN, BK, false, true>), grid, dim3(NT), 0, stream, batch);
+  else hipLaunchKernelGGL((gemm_kernel<MODE, BM, BN, WM, WN, BK, false, false>), grid, dim3(NT), 0, stream, batch);
   return hipGetLastError();
 }
 
