@@ -132,13 +132,14 @@ struct NetJob {
 };
 
 // Forward of up to two networks of equal depth, one grouped launch per layer.
-int32_t forward_nets(const NetJob* jobs, int count, hipStream_t stream) {
+// With skip_last the output layer is left to the caller (fused output-layer + loss kernel).
+int32_t forward_nets(const NetJob* jobs, int count, hipStream_t stream, bool skip_last = false) {
   if (count == 2 && jobs[0].net->n_layers != jobs[1].net->n_layers) {
-    RSLX_TRY(forward_nets(jobs, 1, stream));
-    return forward_nets(jobs + 1, 1, stream);
+    RSLX_TRY(forward_nets(jobs, 1, stream, skip_last));
+    return forward_nets(jobs + 1, 1, stream, skip_last);
   }
   const int L = jobs[0].net->n_layers;
-  for (int l = 0; l < L; ++l) {
+  for (int l = 0; l < (skip_last ? L - 1 : L); ++l) {
     GemmBatch b;
     b.count = count;
     for (int i = 0; i < count; ++i) {
@@ -220,16 +221,17 @@ struct BwdJob {
 
 // Backward of up to two networks of equal depth: per layer one grouped weight-gradient launch (split over
 // rows, partial sums) and one grouped input-gradient launch.
-int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
+// With skip_last_dx the input gradient of the output layer (dz of the last hidden layer) already exists.
+int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, bool skip_last_dx = false) {
   if (count == 2 && jobs[0].net->n_layers != jobs[1].net->n_layers) {
-    RSLX_TRY(backward_nets(jobs, 1, stream));
-    return backward_nets(jobs + 1, 1, stream);
+    RSLX_TRY(backward_nets(jobs, 1, stream, skip_last_dx));
+    return backward_nets(jobs + 1, 1, stream, skip_last_dx);
   }
   const int L = jobs[0].net->n_layers;
   TransposeBatch tb;
   tb.count = 0;
   for (int i = 0; i < count; ++i)
-    for (int l = 1; l < L; ++l) {
+    for (int l = 1; l < (skip_last_dx ? L - 1 : L); ++l) {
       const rslx_mlp& n = *jobs[i].net;
       tb.job[tb.count++] = TransposeJob{n.params + layer_offset(n, l), jobs[i].wt + layer_offset(n, l), n.dims[l], n.dims[l + 1]};
     }
@@ -259,7 +261,7 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
       p.a_vec = (p.M % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
       p.b_vec = (p.N % 4 == 0 && aligned16(p.B)) ? 1 : 0;
       bw.p[i] = p;
-      if (l > 0) {
+      if (l > 0 && !(skip_last_dx && l == L - 1)) {
         GemmProblem q = blank_problem();
         q.A = dz; q.lda = n.dims[l + 1];
         q.B = jobs[i].wt + layer_offset(n, l); q.ldb = n.dims[l];
@@ -273,7 +275,7 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream) {
       }
     }
     RSLX_HIP(launch_gemm(GEMM_DW, bw, stream));
-    if (l > 0) RSLX_HIP(launch_gemm(GEMM_DX, bx, stream));
+    if (l > 0 && !(skip_last_dx && l == L - 1)) RSLX_HIP(launch_gemm(GEMM_DX, bx, stream));
   }
   return RSLX_OK;
 }
@@ -561,6 +563,8 @@ struct TrainBufs {        // per trained network
 
 struct PpoPlan {
   int32_t B, mb, rows;
+  bool fused_head = false;           // output layers + loss + their input gradient in one launch
+  int32_t loss_blocks = 0;
   int32_t* perms = nullptr;          // [E, B]
   void* perm_ws = nullptr;
   TrainBufs actor, critic, pred;
@@ -592,7 +596,10 @@ void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rs
   p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 2);
   p.actor.sumsq = p.sumsq_all;
   p.critic.sumsq = p.sumsq_all + p.actor.n_sumsq;
-  p.loss_partials = c.take<double>((size_t)ppo_loss_num_blocks(p.mb) * (PPO_NPART_FIXED + ro->A));
+  p.fused_head = actor->n_layers >= 2 && critic->n_layers >= 2 &&
+                 ppo_head_supported(actor->dims[actor->n_layers - 1], critic->dims[critic->n_layers - 1], ro->A);
+  p.loss_blocks = p.fused_head ? ppo_head_num_blocks(p.mb, sym != nullptr) : ppo_loss_num_blocks(p.mb);
+  p.loss_partials = c.take<double>((size_t)p.loss_blocks * (PPO_NPART_FIXED + ro->A));
   if (rnd) {
     carve_train(c, *rnd->predictor, p.mb, 1, p.pred);
     p.pred.sumsq = c.take<double>((size_t)p.pred.n_sumsq + 1);
@@ -709,7 +716,7 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
         xc.col_map = sym->perm_obs_c; xc.col_sign = sym->sign_obs_c;
       }
       NetJob fj[2] = {NetJob{actor, xa, p.rows, &p.actor.act}, NetJob{critic, xc, p.rows, &p.critic.act}};
-      RSLX_TRY(forward_nets(fj, 2, s));
+      RSLX_TRY(forward_nets(fj, 2, s, p.fused_head));
 
       PpoLossArgs la;
       memset(&la, 0, sizeof la);
@@ -727,14 +734,25 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
       la.clipped_value = cfg->use_clipped_value_loss;
       la.d_mu = p.actor.d_out; la.d_v = p.critic.d_out;
       la.partials = p.loss_partials;
-      RSLX_HIP(launch_ppo_loss(la, s));
-      RSLX_HIP(launch_ppo_loss_finish(p.loss_partials, ppo_loss_num_blocks(p.mb), p.rows, p.mb, A, la.log_std,
+      if (p.fused_head) {
+        PpoHeadArgs ha;
+        ha.loss = la;
+        ha.h_a = p.actor.act.out[L_a - 2]; ha.h_c = p.critic.act.out[L_c - 2];
+        ha.w_a = actor->params + layer_offset(*actor, L_a - 1); ha.w_c = critic->params + layer_offset(*critic, L_c - 1);
+        ha.dz_a = p.actor.act.dz[L_a - 2]; ha.dz_c = p.critic.act.dz[L_c - 2];
+        ha.Ha = actor->dims[L_a - 1]; ha.Hc = critic->dims[L_c - 1];
+        ha.alpha_a = actor->elu_alpha; ha.alpha_c = critic->elu_alpha;
+        RSLX_HIP(launch_ppo_head(ha, s));
+      } else {
+        RSLX_HIP(launch_ppo_loss(la, s));
+      }
+      RSLX_HIP(launch_ppo_loss_finish(p.loss_partials, p.loss_blocks, p.rows, p.mb, A, la.log_std,
                                       cfg->entropy_coef, actor->grads + weight_count(*actor), stats_row,
                                       p.sumsq_all + p.actor.n_sumsq + p.critic.n_sumsq, s));
 
       BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.wt, p.actor.partials, &p.actor.plan},
                       BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.wt, p.critic.partials, &p.critic.plan}};
-      RSLX_TRY(backward_nets(bj, 2, s));
+      RSLX_TRY(backward_nets(bj, 2, s, p.fused_head));
       RSLX_TRY(reduce_net(*actor, p.actor, s));
       RSLX_TRY(reduce_net(*critic, p.critic, s));
 

@@ -521,122 +521,361 @@ __device__ __forceinline__ RowTerms ppo_row(const PpoLossArgs& a, float logp_new
   return t;
 }
 
-__global__ __launch_bounds__(256) void ppo_loss_kernel(const PpoLossArgs a) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
+// Per-thread partial sums of the loss head.
+template <int AM>
+struct PpoAcc {
+  float surr = 0.f, vloss = 0.f, kl = 0.f, clipped = 0.f, mirror = 0.f;
+  float dls[AM];
+};
+
+// Rollout quantities of one minibatch row, gathered through the permutation.
+template <int AM>
+struct PpoRowIn {
+  float adv, ret, v_old, logp_old;
+  float act[AM], mu_old[AM], sigma_old[AM];
+  float act_m[AM];     // mirrored action (symmetry only)
+};
+
+template <int AM>
+__device__ __forceinline__ void ppo_row_load(const PpoLossArgs& a, int i, PpoRowIn<AM>& in) {
+  const int A = a.A;
+  const long b = a.idx[i];
+  in.adv = a.adv[b]; in.ret = a.returns[b]; in.v_old = a.v_old[b]; in.logp_old = a.logp_old[b];
+#pragma unroll
+  for (int jj = 0; jj < AM; ++jj) {
+    if (jj < A) {
+      in.act[jj] = a.actions[b * A + jj];
+      in.mu_old[jj] = a.mu_old[b * A + jj];
+      in.sigma_old[jj] = a.sigma_old[b * A + jj];
+      if (a.rows > a.mb) in.act_m[jj] = a.sign_act[jj] * a.actions[b * A + a.perm_act[jj]];
+    }
+  }
+}
+
+// Loss terms and output gradients of one minibatch row (and, with symmetry, of its mirrored twin).  mu / d_mu
+// pointers address one row of A values each (global memory or LDS); v / d_v are scalars.
+template <int AM>
+__device__ __forceinline__ void ppo_loss_row(const PpoLossArgs& a, const PpoRowIn<AM>& in, const float* mu_row,
+                                             const float* mu_twin, float v_row, float v_twin, float* dmu_row,
+                                             float* dmu_twin, float* dv_row, float* dv_twin, PpoAcc<AM>& acc) {
   const int A = a.A;
   const bool sym = a.rows > a.mb;
   const float inv_rows = 1.0f / (float)a.rows;
-  float surr = 0.f, vloss = 0.f, kl = 0.f, clipped = 0.f, mirror = 0.f;
-  float dls[AMAX];
+  const float adv = in.adv, ret = in.ret, v_old = in.v_old, logp_old = in.logp_old;
+  float mu[AM], sg[AM];
+  const float (&act)[AM] = in.act;
+  float zz = 0.f, sum_ls = 0.f;
 #pragma unroll
-  for (int jj = 0; jj < AMAX; ++jj) dls[jj] = 0.f;
-
-  if (i < a.mb) {
-    const long b = a.idx[i];
-    const float adv = a.adv[b], ret = a.returns[b], v_old = a.v_old[b], logp_old = a.logp_old[b];
-    float mu[AMAX], act[AMAX], sg[AMAX];
-    float zz = 0.f, sum_ls = 0.f;
+  for (int jj = 0; jj < AM; ++jj) {
+    if (jj < A) {
+      const float ls = a.log_std[jj];
+      sg[jj] = expf(ls);
+      mu[jj] = mu_row[jj];
+      const float z = (act[jj] - mu[jj]) / sg[jj];
+      zz += z * z;
+      sum_ls += ls;
+      const float so = in.sigma_old[jj], mo = in.mu_old[jj];
+      acc.kl += logf(sg[jj] / so) + (so * so + (mo - mu[jj]) * (mo - mu[jj])) / (2.0f * sg[jj] * sg[jj]) - 0.5f;
+    }
+  }
+  const float logp_new = -0.5f * zz - sum_ls - 0.5f * (float)A * LOG_2PI;
+  float d_logp, d_v;
+  RowTerms t = ppo_row(a, logp_new, logp_old, adv, v_row, v_old, ret, inv_rows, &d_logp, &d_v);
+  acc.surr += t.surr; acc.vloss += t.vloss; acc.clipped += t.clipped;
+  *dv_row = d_v;
 #pragma unroll
-    for (int jj = 0; jj < AMAX; ++jj) {
+  for (int jj = 0; jj < AM; ++jj) {
+    if (jj < A) {
+      const float z = (act[jj] - mu[jj]) / sg[jj];
+      dmu_row[jj] = d_logp * z / sg[jj];
+      acc.dls[jj] += d_logp * (z * z - 1.0f);
+    }
+  }
+  if (sym) {
+    float zz2 = 0.f;
+    float mum[AM], zm[AM];
+#pragma unroll
+    for (int jj = 0; jj < AM; ++jj) {
       if (jj < A) {
-        const float ls = a.log_std[jj];
-        sg[jj] = expf(ls);
-        mu[jj] = a.mu[(long)i * A + jj];
-        act[jj] = a.actions[b * A + jj];
-        const float z = (act[jj] - mu[jj]) / sg[jj];
-        zz += z * z;
-        sum_ls += ls;
-        const float so = a.sigma_old[b * A + jj], mo = a.mu_old[b * A + jj];
-        kl += logf(sg[jj] / so) + (so * so + (mo - mu[jj]) * (mo - mu[jj])) / (2.0f * sg[jj] * sg[jj]) - 0.5f;
+        mum[jj] = mu_twin[jj];
+        const float am = in.act_m[jj];
+        zm[jj] = (am - mum[jj]) / sg[jj];
+        zz2 += zm[jj] * zm[jj];
       }
     }
-    const float logp_new = -0.5f * zz - sum_ls - 0.5f * (float)A * LOG_2PI;
-    float d_logp, d_v;
-    RowTerms t = ppo_row(a, logp_new, logp_old, adv, a.v[i], v_old, ret, inv_rows, &d_logp, &d_v);
-    surr += t.surr; vloss += t.vloss; clipped += t.clipped;
-    a.d_v[i] = d_v;
+    const float logp_m = -0.5f * zz2 - sum_ls - 0.5f * (float)A * LOG_2PI;
+    float d_logp_m, d_v_m;
+    RowTerms tm = ppo_row(a, logp_m, logp_old, adv, v_twin, v_old, ret, inv_rows, &d_logp_m, &d_v_m);
+    acc.surr += tm.surr; acc.vloss += tm.vloss; acc.clipped += tm.clipped;
+    *dv_twin = d_v_m;
+    const float msc = a.mirror_coef * 2.0f / ((float)a.mb * (float)A);
 #pragma unroll
-    for (int jj = 0; jj < AMAX; ++jj) {
+    for (int jj = 0; jj < AM; ++jj) {
       if (jj < A) {
-        const float z = (act[jj] - mu[jj]) / sg[jj];
-        a.d_mu[(long)i * A + jj] = d_logp * z / sg[jj];
-        dls[jj] += d_logp * (z * z - 1.0f);
-      }
-    }
-    if (sym) {
-      const long im = (long)i + a.mb;
-      float zz2 = 0.f;
-      float mum[AMAX], zm[AMAX];
-#pragma unroll
-      for (int jj = 0; jj < AMAX; ++jj) {
-        if (jj < A) {
-          mum[jj] = a.mu[im * A + jj];
-          const float am = a.sign_act[jj] * a.actions[b * A + a.perm_act[jj]];
-          zm[jj] = (am - mum[jj]) / sg[jj];
-          zz2 += zm[jj] * zm[jj];
-        }
-      }
-      const float logp_m = -0.5f * zz2 - sum_ls - 0.5f * (float)A * LOG_2PI;
-      float d_logp_m, d_v_m;
-      RowTerms tm = ppo_row(a, logp_m, logp_old, adv, a.v[im], v_old, ret, inv_rows, &d_logp_m, &d_v_m);
-      surr += tm.surr; vloss += tm.vloss; clipped += tm.clipped;
-      a.d_v[im] = d_v_m;
-      const float msc = a.mirror_coef * 2.0f / ((float)a.mb * (float)A);
-#pragma unroll
-      for (int jj = 0; jj < AMAX; ++jj) {
-        if (jj < A) {
-          const float target = a.sign_act[jj] * a.mu[(long)i * A + a.perm_act[jj]];
-          const float diff = mum[jj] - target;
-          mirror += diff * diff;
-          a.d_mu[im * A + jj] = d_logp_m * zm[jj] / sg[jj] + msc * diff;
-          dls[jj] += d_logp_m * (zm[jj] * zm[jj] - 1.0f);
-        }
+        const float target = a.sign_act[jj] * mu_row[a.perm_act[jj]];
+        const float diff = mum[jj] - target;
+        acc.mirror += diff * diff;
+        dmu_twin[jj] = d_logp_m * zm[jj] / sg[jj] + msc * diff;
+        acc.dls[jj] += d_logp_m * (zm[jj] * zm[jj] - 1.0f);
       }
     }
   }
-  // every component: wavefront shuffle reduction, one LDS exchange, then lane c of wavefront 0 adds the four
-  __shared__ double wpart[4][PPO_NPART_FIXED + AMAX];
+}
+
+// Workgroup reduction of the partial sums: wavefront shuffle reduction, one LDS exchange, then thread c adds the
+// wavefronts' values of component c and writes it to this block's slot.
+template <int AM>
+__device__ __forceinline__ void ppo_acc_reduce(const PpoAcc<AM>& acc, int A, double* block_out) {
+  __shared__ double wpart[4][PPO_NPART_FIXED + AM];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   auto put = [&](int c, float v) {
     double r = wave_sum((double)v);
     if (lane == 0) wpart[w][c] = r;
   };
-  put(0, surr); put(1, vloss); put(2, kl); put(3, clipped); put(4, mirror);
+  put(0, acc.surr); put(1, acc.vloss); put(2, acc.kl); put(3, acc.clipped); put(4, acc.mirror);
 #pragma unroll
-  for (int jj = 0; jj < AMAX; ++jj)
-    if (jj < A) put(PPO_NPART_FIXED + jj, dls[jj]);
+  for (int jj = 0; jj < AM; ++jj)
+    if (jj < A) put(PPO_NPART_FIXED + jj, acc.dls[jj]);
   __syncthreads();
   const int ncomp = PPO_NPART_FIXED + A;
   if (threadIdx.x < ncomp)
-    a.partials[(long)blockIdx.x * ncomp + threadIdx.x] =
-        wpart[0][threadIdx.x] + wpart[1][threadIdx.x] + wpart[2][threadIdx.x] + wpart[3][threadIdx.x];
+    block_out[threadIdx.x] = wpart[0][threadIdx.x] + wpart[1][threadIdx.x] + wpart[2][threadIdx.x] + wpart[3][threadIdx.x];
+}
+
+template <int AM>
+__global__ __launch_bounds__(256) void ppo_loss_kernel(const PpoLossArgs a) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int A = a.A;
+  PpoAcc<AM> acc;
+#pragma unroll
+  for (int jj = 0; jj < AM; ++jj) acc.dls[jj] = 0.f;
+  if (i < a.mb) {
+    const long im = (long)i + a.mb;
+    const bool sym = a.rows > a.mb;
+    PpoRowIn<AM> in;
+    ppo_row_load(a, i, in);
+    ppo_loss_row(a, in, a.mu + (long)i * A, a.mu + im * A, a.v[i], sym ? a.v[im] : 0.f, a.d_mu + (long)i * A,
+                 a.d_mu + im * A, a.d_v + i, a.d_v + im, acc);
+  }
+  ppo_acc_reduce(acc, A, a.partials + (long)blockIdx.x * (PPO_NPART_FIXED + A));
+}
+
+// ---- fused output layer + loss head + input gradient of the output layer --------------------------------------
+// One workgroup owns 32 activation rows (32 minibatch rows, or 16 rows and their 16 mirrored twins): it loads the
+// last hidden activations of actor and critic into LDS, applies both output layers (A + 1 dot products per row),
+// evaluates the PPO loss terms, and back-propagates through the output layers into the pre-activation gradient of
+// the last hidden layer.  Three launches and two passes over the activations collapse into one.
+constexpr int HEAD_ROWS = 32;
+
+template <int AM>
+__global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
+  extern __shared__ float lds[];
+  const PpoLossArgs& a = h.loss;
+  const int A = a.A, Ha = h.Ha, Hc = h.Hc;
+  const bool sym = a.rows > a.mb;
+  const int r_orig = sym ? HEAD_ROWS / 2 : HEAD_ROWS;
+  const int i0 = blockIdx.x * r_orig;
+  const int sa = Ha + 1, sc = Hc + 1;                      // padded LDS row strides
+  float* ha = lds;                                        // [rows][Ha + 1]
+  float* hc = ha + HEAD_ROWS * sa;                        // [rows][Hc + 1]
+  float* wa = hc + HEAD_ROWS * sc;                        // [Ha * A + A]
+  float* wc = wa + Ha * A + A;                            // [Hc + 1]
+  float* mu = wc + Hc + 1;                                // [rows][A]
+  float* dmu = mu + HEAD_ROWS * A;                        // [rows][A]
+  float* vv = dmu + HEAD_ROWS * A;                        // [rows]
+  float* dv = vv + HEAD_ROWS;                             // [rows]
+  float* gat = dv + HEAD_ROWS;                            // [rows][(4 + 3 A) | 1] gathered rollout rows
+  const int tid = threadIdx.x;
+  // local row lr -> activation row (twins live mb rows further down), or -1 past the minibatch
+  auto grow = [&](int lr) -> long {
+    const int o = lr < r_orig ? lr : lr - r_orig;
+    if (i0 + o >= a.mb) return -1;
+    return lr < r_orig ? (long)(i0 + o) : (long)a.mb + i0 + o;
+  };
+
+  // Rollout rows of this block, gathered through the permutation by all lanes together (one value per lane and
+  // pass) into LDS: [row][adv, ret, v_old, logp_old, actions[A], mu_old[A], sigma_old[A]], odd row pitch.
+  const bool loss_lane = tid < r_orig && i0 + tid < a.mb;
+  const int gw = 4 + 3 * A, gp = gw | 1;
+  for (int e = tid; e < r_orig * gw; e += 256) {
+    const int lr = e / gw, c = e - lr * gw;
+    float v = 0.f;
+    if (i0 + lr < a.mb) {
+      const long b = a.idx[i0 + lr];
+      if (c < 4) {
+        const float* src = c == 0 ? a.adv : c == 1 ? a.returns : c == 2 ? a.v_old : a.logp_old;
+        v = src[b];
+      } else {
+        const int q = (c - 4) / A, jj = (c - 4) - q * A;
+        const float* src = q == 0 ? a.actions : q == 1 ? a.mu_old : a.sigma_old;
+        v = src[b * A + jj];
+      }
+    }
+    gat[lr * gp + c] = v;
+  }
+
+  for (int e = tid; e < Ha * A + A; e += 256) wa[e] = h.w_a[e];
+  for (int e = tid; e < Hc + 1; e += 256) wc[e] = h.w_c[e];
+  for (int e = tid; e < HEAD_ROWS * (Ha / 4); e += 256) {
+    const int lr = e / (Ha / 4), c4 = e % (Ha / 4);
+    const long gr = grow(lr);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (gr >= 0) v = *reinterpret_cast<const float4*>(h.h_a + gr * Ha + 4 * c4);
+    float* d = ha + lr * sa + 4 * c4;
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  }
+  for (int e = tid; e < HEAD_ROWS * (Hc / 4); e += 256) {
+    const int lr = e / (Hc / 4), c4 = e % (Hc / 4);
+    const long gr = grow(lr);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (gr >= 0) v = *reinterpret_cast<const float4*>(h.h_c + gr * Hc + 4 * c4);
+    float* d = hc + lr * sc + 4 * c4;
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  }
+  __syncthreads();
+
+  // ---- output layers: lane = row, the 8 half-wavefronts stride over the A + 1 outputs ----
+  {
+    const int lr = tid & (HEAD_ROWS - 1);
+    for (int o = tid / HEAD_ROWS; o <= A; o += 256 / HEAD_ROWS) {
+      float s;
+      if (o < A) {
+        s = wa[Ha * A + o];
+#pragma unroll 16
+        for (int k = 0; k < Ha; ++k) s += ha[lr * sa + k] * wa[k * A + o];
+        mu[lr * A + o] = s;
+      } else {
+        s = wc[Hc];
+#pragma unroll 16
+        for (int k = 0; k < Hc; ++k) s += hc[lr * sc + k] * wc[k];
+        vv[lr] = s;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- loss terms: one lane per original row ----
+  PpoAcc<AM> acc;
+#pragma unroll
+  for (int jj = 0; jj < AM; ++jj) acc.dls[jj] = 0.f;
+  if (loss_lane) {
+    const int lt = tid + r_orig;      // twin's local row (only read with symmetry)
+    PpoRowIn<AM> rin;
+    const float* gr = gat + tid * gp;
+    rin.adv = gr[0]; rin.ret = gr[1]; rin.v_old = gr[2]; rin.logp_old = gr[3];
+#pragma unroll
+    for (int jj = 0; jj < AM; ++jj) {
+      if (jj < A) {
+        rin.act[jj] = gr[4 + jj];
+        rin.mu_old[jj] = gr[4 + A + jj];
+        rin.sigma_old[jj] = gr[4 + 2 * A + jj];
+        if (sym) rin.act_m[jj] = a.sign_act[jj] * gr[4 + a.perm_act[jj]];
+      }
+    }
+    ppo_loss_row(a, rin, mu + tid * A, mu + (sym ? lt : tid) * A, vv[tid], sym ? vv[lt] : 0.f, dmu + tid * A,
+                 dmu + (sym ? lt : tid) * A, dv + tid, dv + (sym ? lt : tid), acc);
+  }
+  ppo_acc_reduce(acc, A, a.partials + (long)blockIdx.x * (PPO_NPART_FIXED + A));   // contains a __syncthreads()
+  __syncthreads();
+
+  // ---- output-layer gradients for the weight-gradient contraction (d_mu, d_v to global memory) ----
+  for (int e = tid; e < HEAD_ROWS * A; e += 256) {
+    const long gr = grow(e / A);
+    if (gr >= 0) a.d_mu[gr * A + e % A] = dmu[e];
+  }
+  if (tid < HEAD_ROWS) {
+    const long gr = grow(tid);
+    if (gr >= 0) a.d_v[gr] = dv[tid];
+  }
+  // ---- input gradient of the output layers, times ELU'(h): lane = hidden unit, its weight row in registers ----
+  {
+    const int k = tid % Ha, rstep = 256 / Ha;
+    float wrow[AM];
+#pragma unroll
+    for (int jj = 0; jj < AM; ++jj) wrow[jj] = jj < A ? wa[k * A + jj] : 0.f;
+#pragma unroll 4
+    for (int lr = tid / Ha; lr < HEAD_ROWS; lr += rstep) {
+      const long gr = grow(lr);
+      if (gr < 0) continue;
+      float s = 0.f;
+#pragma unroll
+      for (int jj = 0; jj < AM; ++jj)
+        if (jj < A) s += dmu[lr * A + jj] * wrow[jj];
+      const float hv = ha[lr * sa + k];
+      h.dz_a[gr * Ha + k] = s * (hv > 0.f ? 1.0f : hv + h.alpha_a);
+    }
+  }
+  {
+    const int k = tid % Hc, rstep = 256 / Hc;
+    const float wk = wc[k];
+#pragma unroll 4
+    for (int lr = tid / Hc; lr < HEAD_ROWS; lr += rstep) {
+      const long gr = grow(lr);
+      if (gr < 0) continue;
+      const float hv = hc[lr * sc + k];
+      h.dz_c[gr * Hc + k] = dv[lr] * wk * (hv > 0.f ? 1.0f : hv + h.alpha_c);
+    }
+  }
+}
+
+size_t ppo_head_lds_bytes(int32_t Ha, int32_t Hc, int32_t A) {
+  return sizeof(float) * ((size_t)HEAD_ROWS * (Ha + 1) + (size_t)HEAD_ROWS * (Hc + 1) + (size_t)Ha * A + A + Hc + 1 +
+                          2 * (size_t)HEAD_ROWS * A + 2 * HEAD_ROWS + (size_t)HEAD_ROWS * ((4 + 3 * A) | 1));
+}
+
+bool ppo_head_supported(int32_t Ha, int32_t Hc, int32_t A) {
+  auto ok = [](int h) { return h == 32 || h == 64 || h == 128 || h == 256; };
+  return ok(Ha) && ok(Hc) && A >= 1 && A <= AMAX && ppo_head_lds_bytes(Ha, Hc, A) <= 150 * 1024;
+}
+
+int ppo_head_num_blocks(int32_t mb, bool sym) { const int r = sym ? HEAD_ROWS / 2 : HEAD_ROWS; return (mb + r - 1) / r; }
+
+hipError_t launch_ppo_head(const PpoHeadArgs& h, hipStream_t stream) {
+  const size_t lds_bytes = ppo_head_lds_bytes(h.Ha, h.Hc, h.loss.A);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ppo_head_kernel<16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(ppo_head_kernel<AMAX>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  TraceScope ts(stream, "ppo_head", 0.0, 0.0);
+  const dim3 grid(ppo_head_num_blocks(h.loss.mb, h.loss.rows > h.loss.mb));
+  if (h.loss.A <= 16) hipLaunchKernelGGL(ppo_head_kernel<16>, grid, dim3(256), lds_bytes, stream, h);
+  else hipLaunchKernelGGL(ppo_head_kernel<AMAX>, grid, dim3(256), lds_bytes, stream, h);
+  return hipGetLastError();
 }
 
 hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
   TraceScope ts(stream, "ppo_loss", 0.0, 0.0);
-  hipLaunchKernelGGL(ppo_loss_kernel, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
+  if (a.A <= 16) hipLaunchKernelGGL(ppo_loss_kernel<16>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(ppo_loss_kernel<AMAX>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
-// One workgroup: lane c of every wavefront sums component c over every 4th block, the four partial sums are
-// combined in a fixed order, then wavefront 0 writes the statistics row and the log_std gradient.
-__global__ __launch_bounds__(256) void ppo_loss_finish_kernel(const double* __restrict__ partials, int blocks, int rows,
-                                                              int mb, int A, const float* __restrict__ log_std,
-                                                              float entropy_coef, float* __restrict__ d_log_std,
-                                                              float* __restrict__ stats_row,
-                                                              double* __restrict__ sumsq_slot) {
-  __shared__ double wpart[4][64];
+// One workgroup of 16 wavefronts: lane c of every wavefront sums component c over every 16th block, the partial
+// sums are combined in a fixed order, then wavefront 0 writes the statistics row and the log_std gradient.
+__global__ __launch_bounds__(1024) void ppo_loss_finish_kernel(const double* __restrict__ partials, int blocks, int rows,
+                                                               int mb, int A, const float* __restrict__ log_std,
+                                                               float entropy_coef, float* __restrict__ d_log_std,
+                                                               float* __restrict__ stats_row,
+                                                               double* __restrict__ sumsq_slot) {
+  __shared__ double wpart[16][64];
   const int c = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int ncomp = PPO_NPART_FIXED + A;
   double acc = 0.0;
   if (c < ncomp) {
-#pragma unroll 4
-    for (int b = w; b < blocks; b += 4) acc += partials[(long)b * ncomp + c];
+#pragma unroll 8
+    for (int b = w; b < blocks; b += 16) acc += partials[(long)b * ncomp + c];
   }
   wpart[w][c] = acc;
   __syncthreads();
   if (w != 0) return;
-  const double s = wpart[0][c] + wpart[1][c] + wpart[2][c] + wpart[3][c];
+  double s = 0.0;
+  for (int k = 0; k < 16; ++k) s += wpart[k][c];
   double g2 = 0.0;
   if (c >= PPO_NPART_FIXED && c < ncomp) {
     const float g = (float)s - entropy_coef;
@@ -662,7 +901,7 @@ __global__ __launch_bounds__(256) void ppo_loss_finish_kernel(const double* __re
 hipError_t launch_ppo_loss_finish(const double* partials, int32_t blocks, int32_t rows, int32_t mb, int32_t A,
                                   const float* log_std, float entropy_coef, float* d_log_std, float* stats_row,
                                   double* sumsq_slot, hipStream_t stream) {
-  hipLaunchKernelGGL(ppo_loss_finish_kernel, dim3(1), dim3(256), 0, stream, partials, blocks, rows, mb, A, log_std,
+  hipLaunchKernelGGL(ppo_loss_finish_kernel, dim3(1), dim3(1024), 0, stream, partials, blocks, rows, mb, A, log_std,
                      entropy_coef, d_log_std, stats_row, sumsq_slot);
   return hipGetLastError();
 }

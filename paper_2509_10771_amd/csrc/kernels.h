@@ -173,6 +173,20 @@ struct PpoLossArgs {
 constexpr int PPO_NPART_FIXED = 5;  // surrogate, value, kl, clip count, mirror ; then A entries of dlog_std
 int ppo_loss_num_blocks(int32_t mb);
 hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream);
+// Fused output layers + loss head + input gradient of the output layers (needs the last hidden widths to be
+// 32, 64, 128 or 256; ppo_head_supported tells).  loss.mu / loss.v are not read; loss.partials needs
+// ppo_head_num_blocks entries.
+struct PpoHeadArgs {
+  PpoLossArgs loss;
+  const float* h_a; const float* h_c;   // last hidden activations [rows, Ha], [rows, Hc]
+  const float* w_a; const float* w_c;   // output layers: W [H, out] row-major followed by the bias
+  float* dz_a; float* dz_c;             // gradients w.r.t. the last hidden pre-activations
+  int32_t Ha, Hc;
+  float alpha_a, alpha_c;
+};
+bool ppo_head_supported(int32_t Ha, int32_t Hc, int32_t A);
+int ppo_head_num_blocks(int32_t mb, bool sym);
+hipError_t launch_ppo_head(const PpoHeadArgs& h, hipStream_t stream);
 // Reduce the loss partials: writes the stats row, the log_std gradient and its squared norm.
 hipError_t launch_ppo_loss_finish(const double* partials, int32_t blocks, int32_t rows, int32_t mb, int32_t A,
                                   const float* log_std, float entropy_coef, float* d_log_std, float* stats_row,

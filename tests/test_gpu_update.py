@@ -180,6 +180,13 @@ def test_ppo_tiny_off_policy_start(rx):
     check_free_running(rx, case)
 
 
+def test_ppo_odd_hidden_width_takes_the_unfused_loss_path(rx):
+    """A last hidden width outside {32, 64, 128, 256} uses the per-layer output GEMMs and the stand-alone loss kernel."""
+    case = Case(replace(WORKLOADS["tiny"], N=50, hidden=(64, 96)), 1, perturb=0.2)
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
+
+
 def test_ppo_flat_ragged(rx):
     case = Case(WORKLOADS["flat"].scaled(250), 1)     # mb = 1500 rows: 11 full 128-row tiles and a 92-row tail
     check_forced_steps(rx, case)
