@@ -19,6 +19,14 @@ if ROOT not in sys.path:
 
 FP32_MFMA_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the matrix-core kernels on the "flat" workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# (2.0 * FETCH + 1.0 * WRITE after calibration against a kernel of known size; profiles/flat_iteration_hbm_traffic.txt).
+HBM_TRAFFIC_BYTES_PER_LAUNCH_FLAT = {
+    "gemm_dx_64x128": 260.2e6,     # algorithmic 252.7e6
+    "gemm_fwd_128x128": 159.6e6,   # algorithmic 151.0e6
+    "gemm_dw_128x128": 218.4e6,    # algorithmic 218.1e6 (incl. 67.1e6 of split partials)
+    "gemm_dx_128x128": 128.2e6,    # algorithmic 126.1e6
+}
 
 
 def flops_per_sample_pass(dims_a, dims_c):
@@ -141,7 +149,8 @@ def main():
     d = kinds[dom]
     achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
     roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), traffic=None,
+                    frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4),
+                    traffic=HBM_TRAFFIC_BYTES_PER_LAUNCH_FLAT.get(dom) if w.name == "flat" else None,
                     launches=d["n"], avg_launch_us=round(d["ms"] * 1e3 / d["n"], 2),
                     flops_per_launch=d["flops"] / d["n"])
     breakdown = {k: dict(launches=v["n"], total_ms_per_step=round(v["ms"] / args.steps, 4),
