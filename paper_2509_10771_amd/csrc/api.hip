@@ -94,6 +94,7 @@ struct XView {
   const float* col_sign = nullptr;
   int idx_mod = INT_MAX;
   int map_from = INT_MAX;
+  int64_t src_rows = 0;     // rows of the matrix behind row_idx
 };
 
 // Per-network activation storage for `rows` rows: out[l] = output of layer l, dz[l] = gradient w.r.t. the
@@ -121,7 +122,7 @@ GemmProblem blank_problem() {
 
 void set_x(GemmProblem& p, const XView& x) {
   p.A = x.base; p.lda = x.ld; p.row_idx = x.row_idx; p.col_map = x.col_map; p.col_sign = x.col_sign;
-  p.idx_mod = x.idx_mod; p.map_from = x.map_from;
+  p.idx_mod = x.idx_mod; p.map_from = x.map_from; p.a_src_rows = x.src_rows;
 }
 
 struct NetJob {
@@ -707,8 +708,8 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
       float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
 
       XView xa, xc;
-      xa.base = ro->obs_actor; xa.ld = ro->Da; xa.row_idx = idx;
-      xc.base = ro->obs_critic; xc.ld = ro->Dc; xc.row_idx = idx;
+      xa.base = ro->obs_actor; xa.ld = ro->Da; xa.row_idx = idx; xa.src_rows = p.B;
+      xc.base = ro->obs_critic; xc.ld = ro->Dc; xc.row_idx = idx; xc.src_rows = p.B;
       if (sym) {
         xa.idx_mod = xc.idx_mod = p.mb;
         xa.map_from = xc.map_from = p.mb;
@@ -774,7 +775,7 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
         const rslx_mlp& pr = *rnd->predictor;
         const int K = pr.dims[pr.n_layers];
         XView xr;
-        xr.base = ro->obs_actor; xr.ld = ro->Da; xr.row_idx = idx;
+        xr.base = ro->obs_actor; xr.ld = ro->Da; xr.row_idx = idx; xr.src_rows = p.B;
         if (rnd->subset_idx) { xr.col_map = rnd->subset_idx; xr.map_from = 0; }
         NetJob rj[2] = {NetJob{&pr, xr, p.mb, &p.pred.act}, NetJob{rnd->target, xr, p.mb, &p.targ}};
         RSLX_TRY(forward_nets(rj, 2, s));
@@ -891,7 +892,7 @@ int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* 
       const int32_t* idx = p.perms + (size_t)e * B + (size_t)m * p.mb;
       float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
       RSLX_HIP(launch_fill(stats_row, RSLX_NSTATS, 0.f, s));
-      XView xs; xs.base = obs_student; xs.ld = student->dims[0]; xs.row_idx = idx;
+      XView xs; xs.base = obs_student; xs.ld = student->dims[0]; xs.row_idx = idx; xs.src_rows = B;
       NetJob fj{student, xs, p.mb, &p.student.act};
       RSLX_TRY(forward_nets(&fj, 1, s));
       RSLX_HIP(launch_mse(p.student.act.out[Ls - 1], targets, idx, p.mb, A, p.student.d_out, p.mse_partials, s));

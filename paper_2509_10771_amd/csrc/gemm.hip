@@ -10,6 +10,7 @@
 //   A operand: A[row = j][k = g]      B operand: B[k = g][col = j]
 //   D/C, 16 accumulators r = 0..15:   D[row = 8 * (r / 4) + 4 * g + r % 4][col = j]
 #include <cstdio>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -39,18 +40,21 @@ struct KContig {
   static constexpr int RPS = NT / BK;               // scalar path: rows per pass
   static constexpr int NPTR = VEC ? R / RPV : R / RPS;
   static constexpr bool vec = VEC;
-  const float* ptr[NPTR];                           // row pointers, gather applied
+  const float* ptr[VEC ? 1 : NPTR];                 // scalar path: row pointers, gather applied
+  uint32_t off[VEC ? NPTR : 1];                     // vector path: element offsets of the rows from `base` (~0u = no row)
+  const float* base;
   uint32_t mapped;                                  // scalar path, bit p: row of pass p reads through col_map / col_sign
 
-  __device__ __forceinline__ void setup(const GemmProblem& P, const float* base, int ld, int row0, int row_end) {
+  __device__ __forceinline__ void setup(const GemmProblem& P, const float* b, int ld, int row0, int row_end) {
     const int tid = threadIdx.x;
     mapped = 0;
+    base = b;
     if constexpr (VEC) {
 #pragma unroll
       for (int p = 0; p < R / RPV; ++p) {
         const int row = row0 + p * RPV + tid / LK;
-        ptr[p] = nullptr;
-        if (row < row_end) ptr[p] = base + (long)(IS_X ? src_row(P, row) : row) * ld + 4 * (tid % LK);
+        off[p] = ~0u;
+        if (row < row_end) off[p] = (uint32_t)(IS_X ? src_row(P, row) : row) * (uint32_t)ld + 4u * (tid % LK);
       }
     } else {
 #pragma unroll
@@ -65,14 +69,17 @@ struct KContig {
     }
   }
 
+  // FULL: the tile lies inside the matrix in both directions, so no lane needs a bounds check.
+  template <bool FULL>
   __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
     const int tid = threadIdx.x;
     if constexpr (VEC) {
-      const bool kok = k0 + 4 * (tid % LK) < k_end;
+      const float* bk = base + k0;                 // uniform; the per-lane part is the 32-bit offset
+      const bool kok = FULL || k0 + 4 * (tid % LK) < k_end;
 #pragma unroll
       for (int p = 0; p < R / RPV; ++p) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (kok && ptr[p] != nullptr) v = *reinterpret_cast<const float4*>(ptr[p] + k0);
+        if (FULL || (kok && off[p] != ~0u)) v = *reinterpret_cast<const float4*>(bk + off[p]);
         reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
       }
     } else {
@@ -123,6 +130,7 @@ struct Direct {
   int ld, col, cm;
   float sg;
   bool col_ok, has_map;
+  uint32_t off[(VEC && !IS_X) ? (BK / RPV > 0 ? BK / RPV : 1) : 1];   // vector path without gather: offsets from row k0
   static constexpr bool vec = VEC;
 
   __device__ __forceinline__ void setup(const GemmProblem& P, const float* b, int ld_, int col0, int col_end) {
@@ -131,6 +139,10 @@ struct Direct {
     col = vec ? col0 + 4 * (tid % V) : col0 + tid % Cw;
     col_ok = col < col_end;
     has_map = false; cm = col; sg = 1.0f;
+    if constexpr (VEC && !IS_X) {
+#pragma unroll
+      for (int p = 0; p < BK / RPV; ++p) off[p] = (uint32_t)(p * RPV + tid / V) * (uint32_t)ld + (uint32_t)col;
+    }
     if (IS_X && !vec && col_ok && P.col_map != nullptr) {
       has_map = true;
       cm = P.col_map[col];
@@ -138,14 +150,19 @@ struct Direct {
     }
   }
 
+  template <bool FULL>
   __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
     const int tid = threadIdx.x;
     if constexpr (VEC) {
+      const float* bk = base + (long)k0 * ld;      // uniform
 #pragma unroll
       for (int p = 0; p < BK / RPV; ++p) {
         const int kk = k0 + p * RPV + tid / V;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (col_ok && kk < k_end) v = *reinterpret_cast<const float4*>(base + (long)(IS_X ? src_row(P, kk) : kk) * ld + col);
+        if (FULL || (col_ok && kk < k_end)) {
+          if constexpr (IS_X) v = *reinterpret_cast<const float4*>(base + (long)src_row(P, kk) * ld + col);
+          else v = *reinterpret_cast<const float4*>(bk + off[p]);
+        }
         reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
       }
     } else {
@@ -230,98 +247,141 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void ge
   else a_k.setup(P, P.A, P.lda, m0, P.M);
   b_d.setup(P, P.B, P.ldb, n0, P.N);
 
-  auto fetch = [&](int k0) {
-    if (MODE == GEMM_DW) a_d.fetch(P, k0, k_end, ra);
-    else a_k.fetch(P, k0, k_end, ra);
-    b_d.fetch(P, k0, k_end, rb);
-  };
   auto stash = [&](int buf) {
     if (MODE == GEMM_DW) a_d.template stash<SA>(As[buf], ra);
     else a_k.template stash<SA>(As[buf], ra);
     b_d.template stash<SB>(Bs[buf], rb);
   };
-
-  if (nk > 0) {
-    fetch(k_begin);
-    stash(0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) fetch(k_begin + (kt + 1) * BK);
-    // operands of step kk + 2 are read from LDS before the matrix-core instructions of step kk issue
-    float a_cur[TM], b_cur[TN], a_nxt[TM], b_nxt[TN];
-#pragma unroll
-    for (int t = 0; t < TM; ++t) a_cur[t] = As[buf][g][a_off + t * 32];
-#pragma unroll
-    for (int t = 0; t < TN; ++t) b_cur[t] = Bs[buf][g][b_off + t * 32];
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-      if (kk + 2 < BK) {
-#pragma unroll
-        for (int t = 0; t < TM; ++t) a_nxt[t] = As[buf][kk + 2 + g][a_off + t * 32];
-#pragma unroll
-        for (int t = 0; t < TN; ++t) b_nxt[t] = Bs[buf][kk + 2 + g][b_off + t * 32];
-      }
-      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of the matrix-core instructions
-#pragma unroll
-      for (int x = 0; x < TM; ++x)
-#pragma unroll
-        for (int y = 0; y < TN; ++y)
-          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[x], b_cur[y], acc[x][y], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (kk + 2 < BK) {
-#pragma unroll
-        for (int t = 0; t < TM; ++t) a_cur[t] = a_nxt[t];
-#pragma unroll
-        for (int t = 0; t < TN; ++t) b_cur[t] = b_nxt[t];
-      }
+  // The loop exists twice: for tiles inside the matrix (no lane checks a bound, loads are base + fixed offset) and
+  // for edge tiles.
+  auto main_loop = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    auto fetch = [&](int k0) {
+      if (MODE == GEMM_DW) a_d.template fetch<FULL>(P, k0, k_end, ra);
+      else a_k.template fetch<FULL>(P, k0, k_end, ra);
+      b_d.template fetch<FULL>(P, k0, k_end, rb);
+    };
+    if (nk > 0) {
+      fetch(k_begin);
+      stash(0);
     }
-    if (MODE == GEMM_DW && tm == 0 && tid < BN) {
-#pragma unroll
-      for (int kk = 0; kk < BK; ++kk) bsum += Bs[buf][kk][tid];
-    }
-    if (kt + 1 < nk) stash(buf ^ 1);
     __syncthreads();
-  }
+    for (int kt = 0; kt < nk; ++kt) {
+      const int buf = kt & 1;
+      if (kt + 1 < nk) fetch(k_begin + (kt + 1) * BK);
+      // operands of step kk + 2 are read from LDS before the matrix-core instructions of step kk issue
+      float a_cur[TM], b_cur[TN], a_nxt[TM], b_nxt[TN];
+#pragma unroll
+      for (int t = 0; t < TM; ++t) a_cur[t] = As[buf][g][a_off + t * 32];
+#pragma unroll
+      for (int t = 0; t < TN; ++t) b_cur[t] = Bs[buf][g][b_off + t * 32];
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 2) {
+        if (kk + 2 < BK) {
+#pragma unroll
+          for (int t = 0; t < TM; ++t) a_nxt[t] = As[buf][kk + 2 + g][a_off + t * 32];
+#pragma unroll
+          for (int t = 0; t < TN; ++t) b_nxt[t] = Bs[buf][kk + 2 + g][b_off + t * 32];
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of the matrix-core instructions
+#pragma unroll
+        for (int x = 0; x < TM; ++x)
+#pragma unroll
+          for (int y = 0; y < TN; ++y)
+            acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[x], b_cur[y], acc[x][y], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk + 2 < BK) {
+#pragma unroll
+          for (int t = 0; t < TM; ++t) a_cur[t] = a_nxt[t];
+#pragma unroll
+          for (int t = 0; t < TN; ++t) b_cur[t] = b_nxt[t];
+        }
+      }
+      if (MODE == GEMM_DW && tm == 0 && tid < BN) {
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) bsum += Bs[buf][kk][tid];
+      }
+      if (kt + 1 < nk) stash(buf ^ 1);
+      __syncthreads();
+    }
+  };
+  const bool interior = AVEC && BVEC && m0 + BM <= P.M && n0 + BN <= P.N && (k_end - k_begin) % BK == 0;
+  if (interior) main_loop(std::true_type{});
+  else main_loop(std::false_type{});
 
   // ---- epilogue -------------------------------------------------------------------------------
+  // Problem fields are copied to registers first: read through the reference they would be fetched again after
+  // every store, since a store may alias them as far as the compiler can tell.
+  const int Mr = P.M, Nc = P.N, ldc = P.ldc;
+  const bool elu = P.elu != 0;
+  const float alpha = P.alpha;
+  const float* aux = P.aux;
+  const int bias_off = P.bias_off;
   float* Cb = P.C;
   if (MODE == GEMM_DW) Cb += (long)split * P.split_stride;
+  const bool full_mn = m0 + BM <= Mr && n0 + BN <= Nc;
 #pragma unroll
   for (int x = 0; x < TM; ++x) {
 #pragma unroll
     for (int y = 0; y < TN; ++y) {
       const int col = n0 + wn * (TN * 32) + y * 32 + j;
-      if (col >= P.N) continue;
-      float bias = 0.f;
-      if (MODE == GEMM_FWD && P.aux) bias = P.aux[col];
       const int row_base = m0 + wm * (TM * 32) + x * 32 + 4 * g;
-      float hx[16];
-      if (MODE == GEMM_DX && P.aux != nullptr) {   // all 16 loads of a 32x32 block are in flight together
+      if (full_mn) {
+        // register r of a 32x32 block sits 8 * (r / 4) + r % 4 rows below row_base: a uniform offset
+        const long o0 = (long)row_base * ldc + col;
+        float* cp = Cb + o0;
+        float hx[16];
+        float bias = 0.f;
+        if (MODE == GEMM_FWD && aux != nullptr) bias = aux[col];
+        if (MODE == GEMM_DX && aux != nullptr) {    // all 16 loads of the block are in flight together
+          const float* hp = aux + o0;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) hx[r] = hp[(8 * (r / 4) + (r % 4)) * ldc];
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = min(row_base + 8 * (r / 4) + (r % 4), P.M - 1);
-          hx[r] = P.aux[(long)row * P.ldc + col];
+          float v = acc[x][y][r];
+          if (MODE == GEMM_FWD) {
+            v += bias;
+            if (elu) {
+              const float e = alpha * (__expf(v) - 1.0f);
+              v = v > 0.f ? v : e;
+            }
+          } else if (MODE == GEMM_DX) {
+            if (aux != nullptr) v *= (hx[r] > 0.f) ? 1.0f : (hx[r] + alpha);
+          }
+          cp[(8 * (r / 4) + (r % 4)) * ldc] = v;
+        }
+        continue;
+      }
+      if (col >= Nc) continue;
+      float bias = 0.f;
+      if (MODE == GEMM_FWD && aux != nullptr) bias = aux[col];
+      float hx[16];
+      if (MODE == GEMM_DX && aux != nullptr) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = min(row_base + 8 * (r / 4) + (r % 4), Mr - 1);
+          hx[r] = aux[(long)row * ldc + col];
         }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + 8 * (r / 4) + (r % 4);
-        if (row >= P.M) continue;
+        if (row >= Mr) continue;
         float v = acc[x][y][r];
-        const long o = (long)row * P.ldc + col;
+        const long o = (long)row * ldc + col;
         if (MODE == GEMM_FWD) {
           v += bias;
-          if (P.elu) v = v > 0.f ? v : P.alpha * (__expf(v) - 1.0f);
+          if (elu) v = v > 0.f ? v : alpha * (__expf(v) - 1.0f);
         } else if (MODE == GEMM_DX) {
-          if (P.aux != nullptr) v *= (hx[r] > 0.f) ? 1.0f : (hx[r] + P.alpha);
+          if (aux != nullptr) v *= (hx[r] > 0.f) ? 1.0f : (hx[r] + alpha);
         }
         Cb[o] = v;
       }
     }
   }
-  if (MODE == GEMM_DW && tm == 0 && P.bias_off >= 0 && tid < BN && n0 + tid < P.N) Cb[P.bias_off + n0 + tid] = bsum;
+  if (MODE == GEMM_DW && tm == 0 && bias_off >= 0 && tid < BN && n0 + tid < Nc) Cb[bias_off + n0 + tid] = bsum;
 }
 
 template <int MODE, int BM, int BN, int WM, int WN, int BK = 16>
@@ -334,8 +394,13 @@ static hipError_t launch_cfg(const GemmBatch& batch, hipStream_t stream) {
     int t = ((P.M + BM - 1) / BM) * ((P.N + BN - 1) / BN);
     tiles = t > tiles ? t : tiles;
     if (MODE == GEMM_DW) splits = P.n_split > splits ? P.n_split : splits;
-    avec = avec && P.a_vec != 0;
-    bvec = bvec && P.b_vec != 0;
+    // the 16-byte paths address rows by 32-bit element offsets from the matrix base
+    const int64_t lim = (int64_t)1 << 32;
+    const int64_t a_rows = P.row_idx != nullptr ? P.a_src_rows : (MODE == GEMM_DW ? P.K : P.M);
+    const bool a_fits = a_rows > 0 && a_rows * (int64_t)P.lda < lim;
+    const bool b_fits = (int64_t)P.K * P.ldb < lim;
+    avec = avec && P.a_vec != 0 && a_fits;
+    bvec = bvec && P.b_vec != 0 && b_fits;
   }
   if (tiles == 0) return hipSuccess;
   dim3 grid(tiles, splits, batch.count);

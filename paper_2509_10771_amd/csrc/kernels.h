@@ -54,6 +54,7 @@ struct GemmProblem {
   int32_t bias_off;         // DW: offset of the db partial inside a partial buffer, -1 = none
   int32_t dw_big;           // DW: 1 = 128x128 tiles were planned for this layer, 0 = 64x128
   int32_t a_vec, b_vec;     // 1 = operand may be fetched with 16-byte loads
+  int64_t a_src_rows;       // rows of the matrix that row_idx gathers from (0 = unknown)
 };
 
 struct GemmBatch {
