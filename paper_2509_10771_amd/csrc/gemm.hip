@@ -247,6 +247,27 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void ge
   else a_k.setup(P, P.A, P.lda, m0, P.M);
   b_d.setup(P, P.B, P.ldb, n0, P.N);
 
+  // DX with at most two 32x32 blocks per wave: the activation values that gate the result (ELU') are fetched
+  // ahead of the contraction loop and wait in registers, so the epilogue does not stall on them.
+  constexpr bool AUX_AHEAD = MODE == GEMM_DX && TM * TN <= 2;
+  float hpre[AUX_AHEAD ? TM * TN * 16 : 1];
+  const bool full_mn = m0 + BM <= P.M && n0 + BN <= P.N;
+  const bool aux_ahead = AUX_AHEAD && full_mn && P.aux != nullptr;
+  auto fetch_aux = [&]() {
+    if constexpr (AUX_AHEAD) {
+      if (aux_ahead) {
+        const int ld = P.ldc;
+#pragma unroll
+        for (int x = 0; x < TM; ++x)
+#pragma unroll
+          for (int y = 0; y < TN; ++y) {
+            const float* hp = P.aux + (long)(m0 + wm * (TM * 32) + x * 32 + 4 * g) * ld + (n0 + wn * (TN * 32) + y * 32 + j);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) hpre[(x * TN + y) * 16 + r] = hp[(8 * (r / 4) + (r % 4)) * ld];
+          }
+      }
+    }
+  };
   auto stash = [&](int buf) {
     if (MODE == GEMM_DW) a_d.template stash<SA>(As[buf], ra);
     else a_k.template stash<SA>(As[buf], ra);
@@ -265,6 +286,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void ge
       fetch(k_begin);
       stash(0);
     }
+    fetch_aux();
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
       const int buf = kt & 1;
@@ -319,7 +341,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void ge
   const int bias_off = P.bias_off;
   float* Cb = P.C;
   if (MODE == GEMM_DW) Cb += (long)split * P.split_stride;
-  const bool full_mn = m0 + BM <= Mr && n0 + BN <= Nc;
 #pragma unroll
   for (int x = 0; x < TM; ++x) {
 #pragma unroll
@@ -333,10 +354,15 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void ge
         float hx[16];
         float bias = 0.f;
         if (MODE == GEMM_FWD && aux != nullptr) bias = aux[col];
-        if (MODE == GEMM_DX && aux != nullptr) {    // all 16 loads of the block are in flight together
-          const float* hp = aux + o0;
+        if (MODE == GEMM_DX && aux != nullptr) {
+          if constexpr (AUX_AHEAD) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) hx[r] = hp[(8 * (r / 4) + (r % 4)) * ldc];
+            for (int r = 0; r < 16; ++r) hx[r] = hpre[(x * TN + y) * 16 + r];
+          } else {                                  // all 16 loads of the block are in flight together
+            const float* hp = aux + o0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) hx[r] = hp[(8 * (r / 4) + (r % 4)) * ldc];
+          }
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
