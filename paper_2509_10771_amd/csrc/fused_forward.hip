@@ -2,15 +2,17 @@
 // batch is a few thousand rows and per-layer launches would cost more than the arithmetic.
 //
 // One workgroup (8 wavefronts, two per SIMD) carries 32 batch rows of one network through every layer.
-// Activations stay in LDS, contraction-major, in two ping-pong buffers; weights are not staged at all: each
-// wavefront owns a contiguous range of output columns and streams its slice of W straight from L2 into the A
-// operand of v_mfma_f32_16x16x4_f32 (16 consecutive columns of four contraction rows per load), one chunk of 32
-// values per lane ahead of the matrix-core instructions that consume it.  A weight value fetched once feeds both
-// 16-row halves of the batch tile.  Feeding W as the A operand makes the accumulator layout [output column]
-// [batch row], so the epilogue (bias, ELU) writes LDS in the layout the next layer reads.
-// The last layer is written to global memory; for the actor the Gaussian head (noise, action, log-density)
-// runs in the same launch, one lane per (row, action component).
+// Activations stay in LDS, contraction-major, in two ping-pong buffers; weights are not staged at all but
+// streamed from L2 into the A operand of v_mfma_f32_16x16x4_f32.  A layer is cut into tasks of 64 output columns;
+// when a layer has fewer than 8 such groups the contraction range of a group is split over 2, 4 or 8 wavefronts,
+// so all 8 stay busy down to the narrow output layer.  Lane (m, kq) of a task owns columns col0 + 4 m .. + 3 at
+// contraction index k + kq: one 16-byte load per step of four indices feeds eight matrix-core instructions (four
+// column blocks x two 16-row halves of the batch tile), and the 16 lanes of a row read 256 contiguous bytes.
+// Partial sums meet in LDS; all 512 lanes then add them up in a fixed order, apply bias and ELU and leave the
+// result in the layout the next layer reads.  The last layer is also written to global memory; for the actor
+// the Gaussian head (noise, action, log-density) runs in the same launch, one lane per (row, action component).
 #include "kernels.h"
+#include <algorithm>
 #include <type_traits>
 
 namespace rslx {
@@ -20,7 +22,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int FF_ROWS = 32;
 constexpr int FF_THREADS = 512;
 constexpr int FF_WAVES = FF_THREADS / 64;
-constexpr int FF_CHUNK = 32;    // weight values per lane held in flight per register buffer
+constexpr int FF_GROUP = 64;                   // output columns per task
+constexpr int FF_STEPS = 8;                    // contraction steps (of four indices) per weight chunk
+constexpr int FF_CHUNK = 4 * FF_STEPS;         // weight values per lane held in flight per register buffer
+constexpr int FF_MAX_DIM = 512;
+constexpr int FF_BUF = FF_MAX_DIM * FF_ROWS;   // floats per LDS buffer: one activation matrix or all partial sums
 constexpr float FF_LOG_2PI = 1.8378770664093453f;
 
 __device__ __forceinline__ uint64_t ff_mix64(uint64_t x) {
@@ -34,190 +40,119 @@ __device__ __forceinline__ uint64_t ff_mix64(uint64_t x) {
 // its B operand for both halves, and 64 lanes read or write 512 contiguous bytes.
 __device__ __forceinline__ int ff_at(int k, int row) { return k * FF_ROWS + ((row & 15) << 1) + (row >> 4); }
 
-// expm1 for the ELU branch (x <= 0): series near zero, where exp(x) - 1 cancels; the hardware exponential elsewhere.
-__device__ __forceinline__ float ff_expm1_neg(float x) {
-  const float p = x * (1.0f + x * (0.5f + x * (0.16666667f + x * (0.041666668f + x * 0.0083333338f))));
-  const float e = __expf(x) - 1.0f;
-  return x > -0.125f ? p : e;
+// ELU with the hardware exponential: alpha (e^x - 1) for x <= 0.  The absolute error (about 1e-7) is what
+// matters for a value that feeds the next layer's sums; the relative error near zero does not.
+__device__ __forceinline__ float ff_elu(float x, float alpha) { return x > 0.f ? x : alpha * (__expf(x) - 1.0f); }
+
+// Work of one wavefront in one layer: 64 columns from col0 and contraction steps [s_begin, s_end), a step being
+// four contraction indices.  Every part spans a whole number of chunk pairs (16 steps); the last one of a group
+// runs into zero activations (the LDS rows from K up to the next multiple of 64 are kept at zero), so no chunk
+// needs a partial form.
+struct FfTask {
+  int col0, kpart, parts, s_begin, s_end;   // parts: how many wavefronts share a group's contraction
+  bool active;
+};
+
+__host__ __device__ inline int ff_groups(int N) { return (N + FF_GROUP - 1) / FF_GROUP; }
+
+// The split of a layer is planned on the host (it needs integer divisions): see FusedNet::split_*.
+__device__ __forceinline__ FfTask ff_task(const FusedNet& net, int l, int wave) {
+  const int K = net.dims[l], N = net.dims[l + 1];
+  const int shift = net.split_shift[l], per = net.split_steps[l];
+  FfTask t;
+  const int group = wave >> shift;
+  t.kpart = wave & ((1 << shift) - 1);
+  t.col0 = group * FF_GROUP;
+  t.parts = net.split_parts[l];
+  const int steps = (K + 3) / 4;
+  t.s_begin = min(steps, t.kpart * per);
+  t.s_end = min(steps, t.s_begin + per);
+  t.active = group < ff_groups(N) && t.kpart < t.parts;
+  return t;
 }
 
-// The contraction of a column group runs in steps of four indices.  Weight chunk c holds steps [c S, (c + 1) S),
-// S = FF_CHUNK / CB: register s * CB + cb of lane (m, kq) is W[4 (c S + s) + kq][col0 + 16 cb + m].  A chunk is
-// fetched as the matrix pointer plus a 32-bit offset: a fixed lane part and a uniform part per step.  Steps past
-// the last whole one (K / 4) are skipped under a uniform test; the K % 4 indices that remain form one ragged step with clamped rows.  Columns are clamped into the matrix: columns past N only feed
-// accumulator rows the epilogue drops.
-template <int CB>
+// Weight stream of a task.  Register 4 s + cb of the chunk at step s0 is W[4 (s0 + s) + kq][col0 + 4 m + cb].
+// Rows and columns are clamped into the matrix: rows past K meet zero activations, columns past N only feed
+// accumulator rows that are dropped later.
 struct FfWeights {
-  static constexpr int S = FF_CHUNK / CB;
   const float* W;
-  int ldw, K, N, col0, m, kq, steps;
-  unsigned lo[CB];      // byte offset of W[kq][col0 + 16 cb + m]
+  int ldw, K, N, m, kq;
+  bool vec;             // rows are 16-byte aligned and N % 4 == 0: one 16-byte load per step
+  int col[4];           // clamped columns col0 + 4 m + cb
 
-  __device__ __forceinline__ void setup(const float* W_, int K_, int N_, int col0_, int m_, int kq_) {
-    W = W_; ldw = N_; K = K_; N = N_; col0 = col0_; m = m_; kq = kq_; steps = K_ / 4;
+  __device__ __forceinline__ void setup(const float* W_, int K_, int N_, int col0, int m_, int kq_) {
+    W = W_; ldw = N_; K = K_; N = N_; m = m_; kq = kq_;
+    vec = (N_ & 3) == 0 && (reinterpret_cast<uintptr_t>(W_) & 15) == 0;
+    const int c = vec ? min(col0 + 4 * m, N - 4) : col0 + 4 * m;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) lo[cb] = (unsigned)(kq * ldw + min(col0 + 16 * cb + m, N - 1)) * 4u;
+    for (int cb = 0; cb < 4; ++cb) col[cb] = min(c + cb, N - 1);
   }
-  __device__ __forceinline__ int chunks() const { return (steps + S - 1) / S; }
-  __device__ __forceinline__ bool whole(int c) const { return (c + 1) * S <= steps; }
-
-  // Step (c, s): uniform byte offset of its four rows, made opaque so that every address is formed next to its
-  // load (one add) instead of living in a register of its own across the whole contraction.
-  __device__ __forceinline__ unsigned step_off(int c, int s) const {
-    return __builtin_amdgcn_readfirstlane((unsigned)((c * S + s) * 4 * ldw) * 4u);
-  }
-
-  __device__ __forceinline__ void load(int c, float (&dst)[FF_CHUNK]) const {
-    if (c * S >= steps) return;                 // past the end: never consumed
-    const char* wb = reinterpret_cast<const char*>(W);
-    if (whole(c)) {
+  template <bool VEC>
+  __device__ __forceinline__ void load(int s0, float (&dst)[FF_CHUNK]) const {
+    if constexpr (VEC) {
 #pragma unroll
-      for (int s = 0; s < S; ++s) {
-        const unsigned so = step_off(c, s);
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) dst[s * CB + cb] = *reinterpret_cast<const float*>(wb + (lo[cb] + so));
+      for (int s = 0; s < FF_STEPS; ++s) {
+        const int row = min(4 * (s0 + s) + kq, K - 1);
+        const float4 v = *reinterpret_cast<const float4*>(W + (long)row * ldw + col[0]);
+        dst[4 * s + 0] = v.x; dst[4 * s + 1] = v.y; dst[4 * s + 2] = v.z; dst[4 * s + 3] = v.w;
       }
     } else {
 #pragma unroll
-      for (int s = 0; s < S; ++s) {
-        if (c * S + s < steps) {
-          const unsigned so = step_off(c, s);
+      for (int s = 0; s < FF_STEPS; ++s) {
+        const float* wr = W + (long)min(4 * (s0 + s) + kq, K - 1) * ldw;
 #pragma unroll
-          for (int cb = 0; cb < CB; ++cb) dst[s * CB + cb] = *reinterpret_cast<const float*>(wb + (lo[cb] + so));
-        }
+        for (int cb = 0; cb < 4; ++cb) dst[4 * s + cb] = wr[col[cb]];
       }
     }
   }
 };
 
-// acc[cb][h] += W[:, col0 + 16 cb .. + 15]^T (A operand) x activations of row half h (B operand), cb < CB.
-// Lane (m = lane % 16, kq = lane / 16) supplies column col0 + 16 cb + m and batch rows m, 16 + m at contraction
-// index k + kq.  `w0` arrives holding chunk 0, fetched by the caller ahead of time.  Two register buffers
-// alternate without copies so that the loads of chunk c + 1 stay in flight under the matrix-core instructions of
-// chunk c.
-template <int CB>
-__device__ __forceinline__ void ff_contract(const FfWeights<CB>& wt, const float* actIn, float (&w0)[FF_CHUNK],
-                                            f32x4 (&acc)[CB][2]) {
-  constexpr int S = FF_CHUNK / CB;      // 4-wide contraction steps per chunk
-  constexpr int SB = S < 8 ? S : 8;     // steps whose activation operands are read from LDS together
-  const int m = wt.m, kq = wt.kq;
+// acc[cb][h] += W[:, col0 + 4 m + cb]^T (A operand) x activations of row half h (B operand) over the task's
+// contraction range.  `w0` arrives holding the task's first chunk, fetched by the caller ahead of time.  Two
+// register buffers alternate without copies so that the loads of chunk c + 1 stay in flight under the matrix-core
+// instructions of chunk c.
+template <bool VEC>
+__device__ __forceinline__ void ff_contract(const FfWeights& wt, const FfTask& task, const float* actIn,
+                                            float (&w0)[FF_CHUNK], f32x4 (&acc)[4][2]) {
   float w1[FF_CHUNK];
-  auto mfma_step = [&](const float* wv, float2 b) {
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-      acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[cb], b.x, acc[cb][0], 0, 0, 0);
-      acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[cb], b.y, acc[cb][1], 0, 0, 0);
-    }
-  };
+  const float* bp = actIn + (task.s_begin * 4 + wt.kq) * FF_ROWS + 2 * wt.m;
   auto compute = [&](int c, const float (&src)[FF_CHUNK]) {
-    const float* bp = actIn + (c * (4 * S) + kq) * FF_ROWS + 2 * m;
-    if (wt.whole(c)) {
+    float2 b[FF_STEPS];
 #pragma unroll
-      for (int s0 = 0; s0 < S; s0 += SB) {
-        float2 b[SB];
+    for (int s = 0; s < FF_STEPS; ++s) b[s] = *reinterpret_cast<const float2*>(bp + (c * FF_STEPS + s) * 4 * FF_ROWS);
 #pragma unroll
-        for (int s = 0; s < SB; ++s) b[s] = *reinterpret_cast<const float2*>(bp + 4 * (s0 + s) * FF_ROWS);
+    for (int s = 0; s < FF_STEPS; ++s)
 #pragma unroll
-        for (int s = 0; s < SB; ++s) mfma_step(&src[(s0 + s) * CB], b[s]);
+      for (int cb = 0; cb < 4; ++cb) {
+        acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(src[4 * s + cb], b[s].x, acc[cb][0], 0, 0, 0);
+        acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(src[4 * s + cb], b[s].y, acc[cb][1], 0, 0, 0);
       }
-    } else {
-#pragma unroll
-      for (int s = 0; s < S; ++s)
-        if (c * S + s < wt.steps) mfma_step(&src[s * CB], *reinterpret_cast<const float2*>(bp + 4 * s * FF_ROWS));
-    }
   };
-  const int nch = wt.chunks();
+  // A task spans an even number of chunks (see the split plan), and the fetch of the following chunk is issued
+  // without a test (rows are clamped: a chunk past the range reads valid memory and is not used).  The loop body
+  // is therefore free of branches, and the compiler's count of the loads in flight is exact: the matrix-core
+  // instructions of one buffer wait for that buffer's loads only, not for the ones just issued into the other.
+  const int nch = (task.s_end - task.s_begin + FF_STEPS - 1) / FF_STEPS;
   for (int c = 0; c < nch; c += 2) {
-    wt.load(c + 1, w1);
+    wt.load<VEC>(task.s_begin + (c + 1) * FF_STEPS, w1);
+    __builtin_amdgcn_sched_barrier(0);      // the fetches stay ahead of the other buffer's arithmetic
     compute(c, w0);
-    if (c + 1 < nch) {
-      wt.load(c + 2, w0);
-      compute(c + 1, w1);
-    }
-  }
-  if (wt.K & 3) {     // ragged last step: rows clamped, activations past K read as zero
-    const int ka = 4 * wt.steps + kq;
-    float wv[CB];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-      wv[cb] = wt.W[(long)min(ka, wt.K - 1) * wt.ldw + min(wt.col0 + 16 * cb + m, wt.N - 1)];
-    float2 b = *reinterpret_cast<const float2*>(actIn + min(ka, wt.K - 1) * FF_ROWS + 2 * m);
-    if (ka >= wt.K) b = make_float2(0.f, 0.f);
-    mfma_step(wv, b);
+    __builtin_amdgcn_sched_barrier(0);
+    wt.load<VEC>(task.s_begin + (c + 2) * FF_STEPS, w0);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(c + 1, w1);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-// bias + activation, store to LDS and, for the last layer, to global ([row][n]).  Accumulator register r of lane
-// (m, kq) holds output column col0 + 16 cb + 4 kq + r for batch rows m (half 0) and 16 + m (half 1).
-template <int CB>
-__device__ __forceinline__ void ff_epilogue(const f32x4 (&acc)[CB][2], const float (&bv)[CB][4], int N,
-                                            int col0, bool elu, float alpha, float* actOut, float* __restrict__ gout,
-                                            int ldo, int row0, int n_rows, int m, int kq) {
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int n = col0 + 16 * cb + 4 * kq + r;
-      float v0 = acc[cb][0][r] + bv[cb][r], v1 = acc[cb][1][r] + bv[cb][r];
-      if (elu) {
-        v0 = v0 > 0.f ? v0 : alpha * ff_expm1_neg(v0);
-        v1 = v1 > 0.f ? v1 : alpha * ff_expm1_neg(v1);
-      }
-      if (n < N) {
-        *reinterpret_cast<float2*>(actOut + n * FF_ROWS + 2 * m) = make_float2(v0, v1);
-        if (gout != nullptr) {
-          if (row0 + m < n_rows) gout[(long)(row0 + m) * ldo + n] = v0;
-          if (row0 + 16 + m < n_rows) gout[(long)(row0 + 16 + m) * ldo + n] = v1;
-        }
-      }
-    }
-  }
-}
-
-// Column-tile group of one wavefront in a layer: `count` (4, 2 or 1) 16-column tiles from column col0; 0 = none.
-struct FfGroup {
-  int col0, count;
-};
-
-__device__ __forceinline__ FfGroup ff_group(int N, int wave, int t_done) {
-  const int tiles = (N + 15) / 16;
-  const int tpw = (tiles + FF_WAVES - 1) / FF_WAVES;   // 16-column tiles per wavefront, contiguous
-  const int t0 = wave * tpw + t_done;
-  const int left = min(tiles, (wave + 1) * tpw) - t0;
-  FfGroup gr;
-  gr.col0 = t0 * 16;
-  gr.count = left >= 4 ? 4 : left >= 2 ? 2 : left >= 1 ? 1 : 0;
-  return gr;
-}
-
-// First weight chunk of a group, in the register order ff_contract<count> expects.
-__device__ __forceinline__ void ff_first_chunk(const float* __restrict__ W, int K, int N, FfGroup gr, int m, int kq,
-                                               float (&w)[FF_CHUNK]) {
-  if (gr.count == 4) {
-    FfWeights<4> wt; wt.setup(W, K, N, gr.col0, m, kq); wt.load(0, w);
-  } else if (gr.count == 2) {
-    FfWeights<2> wt; wt.setup(W, K, N, gr.col0, m, kq); wt.load(0, w);
-  } else if (gr.count == 1) {
-    FfWeights<1> wt; wt.setup(W, K, N, gr.col0, m, kq); wt.load(0, w);
-  }
-}
-
-template <int CB>
-__device__ __forceinline__ void ff_tile(const float* __restrict__ W, const float* __restrict__ bias, int K, int N,
-                                        int col0, const float* in, float (&w0)[FF_CHUNK], f32x4 (&acc)[CB][2],
-                                        float (&bv)[CB][4], int m, int kq) {
-  // the bias values travel with the weight stream, long before the epilogue needs them
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) bv[cb][r] = bias[min(col0 + 16 * cb + 4 * kq + r, N - 1)];
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) acc[cb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-  FfWeights<CB> wt;
-  wt.setup(W, K, N, col0, m, kq);
-  ff_contract<CB>(wt, in, w0, acc);
+// First weight chunk of a task.
+__device__ __forceinline__ void ff_first_chunk(const float* __restrict__ W, int K, int N, const FfTask& task, int m,
+                                               int kq, float (&w)[FF_CHUNK]) {
+  if (!task.active) return;
+  FfWeights wt;
+  wt.setup(W, K, N, task.col0, m, kq);
+  if (wt.vec) wt.load<true>(task.s_begin, w);
+  else wt.load<false>(task.s_begin, w);
 }
 
 __global__ __launch_bounds__(FF_THREADS) void fused_forward_kernel(const FusedForwardArgs args) {
@@ -225,16 +160,19 @@ __global__ __launch_bounds__(FF_THREADS) void fused_forward_kernel(const FusedFo
   const FusedNet& net = args.net[blockIdx.y];
   const int row0 = blockIdx.x * FF_ROWS;
   if (row0 >= args.n_rows) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // the wavefront index decides which columns and contraction range a wavefront works on: held in a scalar
+  // register, every test on it is a scalar branch
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m = lane & 15, kq = lane >> 4;
   float* bufA = lds;
-  float* bufB = lds + args.max_dim * FF_ROWS;
+  float* bufB = lds + FF_BUF;
 
   // The first weight chunk of the first layer and the head's per-component inputs do not depend on any
   // activation: they are requested before the input rows, so their latency passes under the staging.
   float wpre[FF_CHUNK];
-  FfGroup gr = ff_group(net.dims[1], wave, 0);
-  ff_first_chunk(net.params, net.dims[0], net.dims[1], gr, m, kq, wpre);
+  FfTask task = ff_task(net, 0, wave);
+  ff_first_chunk(net.params, net.dims[0], net.dims[1], task, m, kq, wpre);
   const int A = net.dims[net.n_layers];
   float head_ls = 0.f, head_eps = 0.f;
   if (net.head && tid < FF_ROWS * A) {
@@ -245,18 +183,46 @@ __global__ __launch_bounds__(FF_THREADS) void fused_forward_kernel(const FusedFo
     if (!args.deterministic && args.eps != nullptr && n < args.n_rows) head_eps = args.eps[n * A + (tid >> 5)];
   }
 
-  // ---- input rows -> LDS (lanes run over rows) ----
+  // ---- input rows -> LDS; rows from K0 to the next multiple of 64 are zero ----
   {
     const int K0 = net.dims[0];
-    const int r = tid & 31;
-    const int row = row0 + r;
-    for (int k = tid >> 5; k < K0; k += FF_THREADS / 32) {
-      float v = 0.f;
-      if (row < args.n_rows) {
-        const int c = net.col_map ? net.col_map[k] : k;
-        v = net.x[(long)row * net.ldx + c];
+    const int Kp = (K0 + 63) & ~63;
+    if (net.col_map == nullptr && (net.ldx & 3) == 0 && (K0 & 3) == 0 && (reinterpret_cast<uintptr_t>(net.x) & 15) == 0) {
+      // 16-byte loads, lanes along a row; every load is issued before the first one is used
+      const int q4 = K0 >> 2;                           // float4 per row
+      constexpr int PASS = FF_MAX_DIM * FF_ROWS / 4 / FF_THREADS;
+      float4 v[PASS];
+#pragma unroll
+      for (int i = 0; i < PASS; ++i) {
+        const int e = tid + FF_THREADS * i;
+        if (FF_THREADS * i >= FF_ROWS * q4) break;
+        const int r = e / q4, c4 = e - r * q4;
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (e < FF_ROWS * q4 && row0 + r < args.n_rows)
+          v[i] = *reinterpret_cast<const float4*>(net.x + (long)(row0 + r) * net.ldx + 4 * c4);
       }
-      bufA[ff_at(k, r)] = v;
+#pragma unroll
+      for (int i = 0; i < PASS; ++i) {
+        const int e = tid + FF_THREADS * i;
+        if (FF_THREADS * i >= FF_ROWS * q4) break;
+        if (e < FF_ROWS * q4) {
+          const int r = e / q4, c4 = e - r * q4;
+          bufA[ff_at(4 * c4 + 0, r)] = v[i].x; bufA[ff_at(4 * c4 + 1, r)] = v[i].y;
+          bufA[ff_at(4 * c4 + 2, r)] = v[i].z; bufA[ff_at(4 * c4 + 3, r)] = v[i].w;
+        }
+      }
+      for (int e = tid; e < (Kp - K0) * FF_ROWS; e += FF_THREADS) bufA[K0 * FF_ROWS + e] = 0.f;
+    } else {
+      const int r = tid & 31;
+      const int row = row0 + r;
+      for (int k = tid >> 5; k < Kp; k += FF_THREADS / 32) {
+        float v = 0.f;
+        if (row < args.n_rows && k < K0) {
+          const int c = net.col_map ? net.col_map[k] : k;
+          v = net.x[(long)row * net.ldx + c];
+        }
+        bufA[ff_at(k, r)] = v;
+      }
     }
   }
   __syncthreads();
@@ -270,39 +236,108 @@ __global__ __launch_bounds__(FF_THREADS) void fused_forward_kernel(const FusedFo
     const float* bias = W + (long)K * N;
     const bool last = (l + 1 == net.n_layers);
     float* gout = last ? net.out : nullptr;
-    // weights of the group that follows the current one: the next group of this layer, else the first group of
-    // the next layer; its first chunk is requested before the current group's epilogue
-    int t_done = 0;
-    while (gr.count > 0) {
-      t_done += gr.count;
-      FfGroup nx = ff_group(N, wave, t_done);
-      const float* Wn = W;
-      int Kn = K, Nn = N;
-      if (nx.count == 0 && !last) {
-        Wn = bias + N; Kn = N; Nn = net.dims[l + 2];
-        nx = ff_group(Nn, wave, 0);
+    const int plane = ff_groups(N) * FF_GROUP * FF_ROWS;     // floats between the partial sums of two parts
+
+    // bias values of the outputs this lane finishes, requested ahead of the contraction: with the contraction of
+    // a group shared among wavefronts, the sums are finished by all lanes after an exchange through LDS (lane ->
+    // outputs tid + 512 i); otherwise each wavefront finishes its own accumulators in registers
+    const bool shared = task.parts > 1;
+    constexpr int FIN = FF_MAX_DIM * (FF_ROWS / 2) / FF_THREADS;   // outputs (column, row pair) per lane at most
+    float bfin[FIN];
+    if (shared) {
+#pragma unroll
+      for (int i = 0; i < FIN; ++i) {
+        if (FF_THREADS * i >= N * 16) break;
+        const int e = tid + FF_THREADS * i;
+        bfin[i] = bias[min(e >> 4, N - 1)];
       }
-      auto run = [&](auto cb_tag) {
-        constexpr int CB = decltype(cb_tag)::value;
-        f32x4 acc[CB][2];
-        float bv[CB][4];
-        ff_tile<CB>(W, bias, K, N, gr.col0, in, wpre, acc, bv, m, kq);
-        ff_first_chunk(Wn, Kn, Nn, nx, m, kq, wpre);
-        ff_epilogue<CB>(acc, bv, N, gr.col0, !last, net.alpha, out, gout, N, row0, args.n_rows, m, kq);
-      };
-      if (gr.count == 4) run(std::integral_constant<int, 4>{});
-      else if (gr.count == 2) run(std::integral_constant<int, 2>{});
-      else run(std::integral_constant<int, 1>{});
-      if (Wn != W) break;          // nx belongs to the next layer
-      gr = nx;
+    } else if (task.active) {
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bfin[4 * cb + r] = bias[min(task.col0 + 16 * kq + 4 * r + cb, N - 1)];
     }
-    if (gr.count == 0 && !last) {  // this wavefront had no columns in this layer: fetch for the next one now
-      gr = ff_group(net.dims[l + 2], wave, 0);
-      ff_first_chunk(bias + N, N, net.dims[l + 2], gr, m, kq, wpre);
+    const FfTask next = last ? task : ff_task(net, l + 1, wave);
+    if (task.active) {
+      f32x4 acc[4][2];
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) acc[cb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+      FfWeights wt;
+      wt.setup(W, K, N, task.col0, m, kq);
+      if (wt.vec) ff_contract<true>(wt, task, in, wpre, acc);
+      else ff_contract<false>(wt, task, in, wpre, acc);
+      // the next layer's first chunk is requested before this layer's sums are exchanged
+      if (!last) ff_first_chunk(bias + N, N, net.dims[l + 2], next, m, kq, wpre);
+      // accumulator register r of block cb: column col0 + 16 kq + 4 r + cb, batch rows m (half 0) and 16 + m
+      float* part = out + task.kpart * plane;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int c = task.col0 + 16 * kq + 4 * r + cb;
+          float2 v = make_float2(acc[cb][0][r], acc[cb][1][r]);
+          if (!shared) {
+            v.x += bfin[4 * cb + r]; v.y += bfin[4 * cb + r];
+            if (!last) {
+              v.x = ff_elu(v.x, net.alpha);
+              v.y = ff_elu(v.y, net.alpha);
+            }
+            if (gout != nullptr && c < N) {
+              if (row0 + m < args.n_rows) gout[(long)(row0 + m) * N + c] = v.x;
+              if (row0 + 16 + m < args.n_rows) gout[(long)(row0 + 16 + m) * N + c] = v.y;
+            }
+          }
+          *reinterpret_cast<float2*>(part + c * FF_ROWS + 2 * m) = v;
+        }
     } else if (!last) {
-      gr = ff_group(net.dims[l + 2], wave, 0);
+      ff_first_chunk(bias + N, N, net.dims[l + 2], next, m, kq, wpre);
     }
     __syncthreads();
+
+    // ---- all lanes: sum the parts in order, bias, activation; result in place of part 0 ----
+    // (reads first, then arithmetic, then writes: the LDS latency is paid once, not per output)
+    const int parts = task.parts;
+    if (shared) {
+      float2 fv[FIN];
+#pragma unroll
+      for (int i = 0; i < FIN; ++i) {
+        if (FF_THREADS * i >= N * 16) break;
+        const int e = min(tid + FF_THREADS * i, N * 16 - 1);
+        const float* p0 = out + (e >> 4) * FF_ROWS + 2 * (e & 15);
+        float2 v = *reinterpret_cast<const float2*>(p0);
+        for (int p = 1; p < parts; ++p) {
+          const float2 u = *reinterpret_cast<const float2*>(p0 + p * plane);
+          v.x += u.x; v.y += u.y;
+        }
+        fv[i] = v;
+      }
+#pragma unroll
+      for (int i = 0; i < FIN; ++i) {
+        if (FF_THREADS * i >= N * 16) break;
+        const int e = tid + FF_THREADS * i;
+        if (e < N * 16) {
+          const int c = e >> 4, mp = e & 15;
+          float2 v = fv[i];
+          v.x += bfin[i]; v.y += bfin[i];
+          if (!last) {
+            v.x = ff_elu(v.x, net.alpha);
+            v.y = ff_elu(v.y, net.alpha);
+          }
+          *reinterpret_cast<float2*>(out + c * FF_ROWS + 2 * mp) = v;
+          if (gout != nullptr) {
+            if (row0 + mp < args.n_rows) gout[(long)(row0 + mp) * N + c] = v.x;
+            if (row0 + 16 + mp < args.n_rows) gout[(long)(row0 + 16 + mp) * N + c] = v.y;
+          }
+        }
+      }
+    }
+    // rows from N to the next multiple of 64 are the zero padding the next layer's last chunks run into
+    for (int e = tid; e < (((N + 63) & ~63) - N) * 16; e += FF_THREADS)
+      *reinterpret_cast<float2*>(out + (N + (e >> 4)) * FF_ROWS + 2 * (e & 15)) = make_float2(0.f, 0.f);
+    __syncthreads();
+    task = next;
     float* tmp = in; in = out; out = tmp;
     woff += (long)K * N + N;
   }
@@ -354,17 +389,17 @@ __global__ __launch_bounds__(FF_THREADS) void fused_forward_kernel(const FusedFo
 }
 
 bool fused_forward_supported(const FusedForwardArgs& a) {
-  if (a.max_dim > 512 || a.n_nets < 1 || a.n_nets > 2) return false;
+  if (a.max_dim > FF_MAX_DIM || a.n_nets < 1 || a.n_nets > 2) return false;
   return true;
 }
 
 hipError_t launch_fused_forward(const FusedForwardArgs& a, hipStream_t stream) {
   if (a.n_rows <= 0) return hipSuccess;
-  const size_t lds_bytes = (size_t)2 * a.max_dim * FF_ROWS * sizeof(float);
+  const size_t lds_bytes = (size_t)2 * FF_BUF * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 512 * FF_ROWS * (int)sizeof(float));
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * FF_BUF * (int)sizeof(float));
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -372,8 +407,19 @@ hipError_t launch_fused_forward(const FusedForwardArgs& a, hipStream_t stream) {
   for (int i = 0; i < a.n_nets; ++i)
     for (int l = 0; l < a.net[i].n_layers; ++l) flops += 2.0 * a.n_rows * a.net[i].dims[l] * (double)a.net[i].dims[l + 1];
   TraceScope ts(stream, "fused_forward", flops, 0.0);
-  dim3 grid((a.n_rows + FF_ROWS - 1) / FF_ROWS, a.n_nets);
-  hipLaunchKernelGGL(fused_forward_kernel, grid, dim3(FF_THREADS), lds_bytes, stream, a);
+  FusedForwardArgs b = a;
+  for (int i = 0; i < b.n_nets; ++i)
+    for (int l = 0; l < b.net[i].n_layers; ++l) {
+      const int g = ff_groups(b.net[i].dims[l + 1]);
+      const int shift = g > FF_WAVES / 2 ? 0 : g > FF_WAVES / 4 ? 1 : g > FF_WAVES / 8 ? 2 : 3;
+      const int steps = (b.net[i].dims[l] + 3) / 4;
+      const int per = (((steps + (1 << shift) - 1) >> shift) + 2 * FF_STEPS - 1) / (2 * FF_STEPS) * (2 * FF_STEPS);
+      b.net[i].split_shift[l] = shift;
+      b.net[i].split_steps[l] = per;
+      b.net[i].split_parts[l] = std::max(1, (steps + per - 1) / per);
+    }
+  dim3 grid((b.n_rows + FF_ROWS - 1) / FF_ROWS, b.n_nets);
+  hipLaunchKernelGGL(fused_forward_kernel, grid, dim3(FF_THREADS), lds_bytes, stream, b);
   return hipGetLastError();
 }
 

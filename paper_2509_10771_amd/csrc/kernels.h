@@ -83,6 +83,9 @@ struct FusedNet {
   int32_t dims[9];
   float alpha;
   int32_t head;             // 1: run the Gaussian head on this network's output
+  // per-layer work split, filled in by launch_fused_forward: a layer's 64-column groups are shared by
+  // 1 << split_shift wavefronts each, `split_steps` contraction steps apiece, of which `split_parts` have work
+  int32_t split_shift[8], split_steps[8], split_parts[8];
 };
 struct FusedForwardArgs {
   FusedNet net[2];

@@ -131,6 +131,18 @@ def test_act_wide_layers_take_the_layered_path(rx):
     _act_case(rx, w, inp, 200, use_eps=False)
 
 
+@pytest.mark.parametrize("Da,hidden,A", [(45, (100, 36), 7), (3, (8,), 1), (130, (192, 320, 20), 5), (48, (512, 512), 33)])
+def test_act_odd_shapes_in_the_fused_kernel(rx, Da, hidden, A):
+    """Widths that are no multiple of 4 or 64: ragged contraction tails, unaligned rows (scalar weight loads),
+    column groups that end inside a 64-column task, contraction ranges that split unevenly over wavefronts."""
+    from dataclasses import replace
+    w = replace(WORKLOADS["tiny"], N=77, Da=Da, Dc=Da, A=A, hidden=hidden)
+    inp = make_inputs(w)
+    inp["actor"][-w.A:] = np.random.default_rng(1).normal(scale=0.3, size=w.A).astype(np.float32)
+    _act_case(rx, w, inp, 77, use_eps=True)
+    _act_case(rx, w, inp, 77, use_eps=False)
+
+
 def test_act_noise_distribution(rx):
     w = WORKLOADS["flat"]
     inp = make_inputs(w)
