@@ -652,22 +652,26 @@ int32_t ppo_validate(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_r
 }
 
 // reduce split partials of one network into grads (weights and biases only) + squared-norm blocks
+// Appends one network's layers to a reduce launch; the network's sumsq blocks must start at entry a.blocks of
+// a.sumsq_blocks.
+void reduce_add_net(ReduceArgs& a, const rslx_mlp& n, const TrainBufs& t) {
+  for (int l = 0; l < n.n_layers; ++l) {
+    ReduceSeg& sg = a.seg[a.n_seg++];
+    sg.partials = t.partials + t.plan.part_off[l];
+    sg.grads = n.grads + layer_offset(n, l);
+    sg.size = t.plan.size[l];
+    sg.pitch = t.plan.pitch[l];
+    sg.split = t.plan.split[l];
+    sg.block_start = a.blocks;
+    a.blocks += (int)((t.plan.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
+  }
+}
+
 int32_t reduce_net(const rslx_mlp& n, const TrainBufs& t, hipStream_t s) {
   ReduceArgs a;
   memset(&a, 0, sizeof a);
-  a.partials = t.partials; a.grads = n.grads; a.sumsq_blocks = t.sumsq;
-  a.n_layers = n.n_layers;
-  int blocks = 0;
-  for (int l = 0; l < n.n_layers; ++l) {
-    a.split[l] = t.plan.split[l];
-    a.size[l] = t.plan.size[l];
-    a.pitch[l] = t.plan.pitch[l];
-    a.part_off[l] = t.plan.part_off[l];
-    a.grad_off[l] = layer_offset(n, l);
-    a.block_start[l] = blocks;
-    blocks += (int)((t.plan.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
-  }
-  a.block_start[n.n_layers] = blocks;
+  a.sumsq_blocks = t.sumsq;
+  reduce_add_net(a, n, t);
   RSLX_HIP(launch_reduce_partials(a, s));
   return RSLX_OK;
 }
@@ -747,15 +751,23 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
       } else {
         RSLX_HIP(launch_ppo_loss(la, s));
       }
-      RSLX_HIP(launch_ppo_loss_finish(p.loss_partials, p.loss_blocks, p.rows, p.mb, A, la.log_std,
-                                      cfg->entropy_coef, actor->grads + weight_count(*actor), stats_row,
-                                      p.sumsq_all + p.actor.n_sumsq + p.critic.n_sumsq, s));
-
       BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.wt, p.actor.partials, &p.actor.plan},
                       BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.wt, p.critic.partials, &p.critic.plan}};
       RSLX_TRY(backward_nets(bj, 2, s, p.fused_head));
-      RSLX_TRY(reduce_net(*actor, p.actor, s));
-      RSLX_TRY(reduce_net(*critic, p.critic, s));
+      {   // one launch: both networks' split sums and the loss head's sums
+        ReduceArgs ra;
+        memset(&ra, 0, sizeof ra);
+        ra.sumsq_blocks = p.sumsq_all;
+        reduce_add_net(ra, *actor, p.actor);
+        reduce_add_net(ra, *critic, p.critic);
+        ra.finish.partials = p.loss_partials; ra.finish.blocks = p.loss_blocks;
+        ra.finish.rows = p.rows; ra.finish.mb = p.mb; ra.finish.A = A;
+        ra.finish.log_std = la.log_std; ra.finish.entropy_coef = cfg->entropy_coef;
+        ra.finish.d_log_std = actor->grads + weight_count(*actor);
+        ra.finish.stats_row = stats_row;
+        ra.finish.sumsq_slot = p.sumsq_all + p.actor.n_sumsq + p.critic.n_sumsq;
+        RSLX_HIP(launch_reduce_partials(ra, s));
+      }
 
       const int64_t t = *adam_step + 1;
       AdamArgs aa;

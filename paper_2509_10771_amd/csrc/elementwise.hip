@@ -9,6 +9,8 @@ namespace rslx {
 constexpr int WAVE = 64;
 
 // ---- reductions -----------------------------------------------------------------------------------
+constexpr float LOG_2PI = 1.8378770664093453f;
+
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
   for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_down(v, o, WAVE);
@@ -289,22 +291,66 @@ hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_
 constexpr int RED_PER_BLOCK = 1024;  // floats per workgroup of the plain squared-norm kernel
 int reduce_num_blocks(int64_t n) { return (int)((n + RED_PER_BLOCK - 1) / RED_PER_BLOCK); }
 
+// Sums the per-block partial sums of the PPO loss head in a fixed order (lane c of every wavefront takes
+// component c over every 4th block), then wavefront 0 writes the statistics row and the log_std gradient.
+__device__ void loss_finish_block(const LossFinishArgs& f) {
+  __shared__ double wpart[4][64];
+  const int c = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int A = f.A, ncomp = PPO_NPART_FIXED + A;
+  double acc = 0.0;
+  if (c < ncomp) {
+#pragma unroll 8
+    for (int b = w; b < f.blocks; b += 4) acc += f.partials[(long)b * ncomp + c];
+  }
+  wpart[w][c] = acc;
+  __syncthreads();
+  if (w != 0) return;
+  const double s = wpart[0][c] + wpart[1][c] + wpart[2][c] + wpart[3][c];
+  double g2 = 0.0;
+  if (c >= PPO_NPART_FIXED && c < ncomp) {
+    const float g = (float)s - f.entropy_coef;
+    f.d_log_std[c - PPO_NPART_FIXED] = g;
+    g2 = (double)g * (double)g;
+  }
+  g2 = wave_sum(g2);
+  double ent = 0.0;
+  if (c < A) ent = 0.5 + 0.5 * (double)LOG_2PI + (double)f.log_std[c];
+  ent = wave_sum(ent);
+  const int rows = f.rows, mb = f.mb;
+  if (c == 0) {
+    *f.sumsq_slot = g2;
+    f.stats_row[0] = (float)(s / rows);
+    f.stats_row[2] = (float)ent;
+  }
+  if (c == 1) f.stats_row[1] = (float)(s / rows);
+  if (c == 2) f.stats_row[3] = (float)(s / mb);
+  if (c == 3) f.stats_row[5] = (float)(s / rows);
+  if (c == 4) f.stats_row[6] = rows > mb ? (float)(s / ((double)mb * A)) : 0.f;
+  if (c == 5) f.stats_row[7] = 0.f;
+}
+
 // One workgroup sums 256 consecutive gradient entries of one layer over all of that layer's splits: 64 lanes
 // cover the 256 floats with one 16-byte load each, the 4 wavefronts take every 4th split, LDS combines them
-// in a fixed order (deterministic result).
+// in a fixed order (deterministic result).  The layers of all networks trained in a step share one launch; its
+// last workgroup finishes the loss sums instead.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceArgs a) {
+  if ((int)blockIdx.x == a.blocks) {
+    loss_finish_block(a.finish);
+    return;
+  }
   __shared__ float4 part[4][64];
   __shared__ double smem[4];
-  int layer = 0;
-  while (layer + 1 < a.n_layers && (int)blockIdx.x >= a.block_start[layer + 1]) ++layer;
-  const long size = a.size[layer];
-  const int n_split = a.split[layer];
-  const float* src = a.partials + a.part_off[layer];
+  int si = 0;
+  while (si + 1 < a.n_seg && (int)blockIdx.x >= a.seg[si + 1].block_start) ++si;
+  const ReduceSeg& sg = a.seg[si];
+  const long size = sg.size;
+  const int n_split = sg.split;
+  const float* src = sg.partials;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const long j0 = ((long)(blockIdx.x - a.block_start[layer]) * 64 + lane) * 4;
+  const long j0 = ((long)(blockIdx.x - sg.block_start) * 64 + lane) * 4;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (j0 < size) {      // pitch is a multiple of 4, so the 16-byte load stays inside the split buffer's padding
-    const long pitch = a.pitch[layer];
+    const long pitch = sg.pitch;
 #pragma unroll 4
     for (int k = w; k < n_split; k += 4) {
       const float4 v = *reinterpret_cast<const float4*>(src + (long)k * pitch + j0);
@@ -318,7 +364,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceArgs a
     float4 t = part[0][lane];
     for (int g = 1; g < 4; ++g) { t.x += part[g][lane].x; t.y += part[g][lane].y; t.z += part[g][lane].z; t.w += part[g][lane].w; }
     const float* tp = &t.x;
-    float* dst = a.grads + a.grad_off[layer] + j0;
+    float* dst = sg.grads + j0;
     for (int c = 0; c < 4; ++c)
       if (j0 + c < size) {
         dst[c] = tp[c];
@@ -330,12 +376,12 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceArgs a
 }
 
 hipError_t launch_reduce_partials(const ReduceArgs& a, hipStream_t stream) {
-  const int blocks = a.block_start[a.n_layers];
-  if (blocks <= 0) return hipSuccess;
+  const int extra = a.finish.blocks > 0 ? 1 : 0;
+  if (a.blocks + extra <= 0) return hipSuccess;
   double bytes = 0.0;
-  for (int l = 0; l < a.n_layers; ++l) bytes += 4.0 * (double)a.size[l] * (a.split[l] + 1);
+  for (int i = 0; i < a.n_seg; ++i) bytes += 4.0 * (double)a.seg[i].size * (a.seg[i].split + 1);
   TraceScope ts(stream, "reduce_partials", 0.0, bytes);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, stream, a);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(a.blocks + extra), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -437,7 +483,6 @@ hipError_t launch_adam(const AdamArgs& a_in, hipStream_t stream) {
 }
 
 // ---- Gaussian head of act() -------------------------------------------------------------------------
-constexpr float LOG_2PI = 1.8378770664093453f;
 
 __global__ __launch_bounds__(256) void act_head_kernel(const float* __restrict__ mu_in, const float* __restrict__ log_std,
                                                        const float* __restrict__ eps_in, uint64_t noise_base, int N,
@@ -853,56 +898,6 @@ hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
   TraceScope ts(stream, "ppo_loss", 0.0, 0.0);
   if (a.A <= 16) hipLaunchKernelGGL(ppo_loss_kernel<16>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
   else hipLaunchKernelGGL(ppo_loss_kernel<AMAX>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
-  return hipGetLastError();
-}
-
-// One workgroup of 16 wavefronts: lane c of every wavefront sums component c over every 16th block, the partial
-// sums are combined in a fixed order, then wavefront 0 writes the statistics row and the log_std gradient.
-__global__ __launch_bounds__(1024) void ppo_loss_finish_kernel(const double* __restrict__ partials, int blocks, int rows,
-                                                               int mb, int A, const float* __restrict__ log_std,
-                                                               float entropy_coef, float* __restrict__ d_log_std,
-                                                               float* __restrict__ stats_row,
-                                                               double* __restrict__ sumsq_slot) {
-  __shared__ double wpart[16][64];
-  const int c = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int ncomp = PPO_NPART_FIXED + A;
-  double acc = 0.0;
-  if (c < ncomp) {
-#pragma unroll 8
-    for (int b = w; b < blocks; b += 16) acc += partials[(long)b * ncomp + c];
-  }
-  wpart[w][c] = acc;
-  __syncthreads();
-  if (w != 0) return;
-  double s = 0.0;
-  for (int k = 0; k < 16; ++k) s += wpart[k][c];
-  double g2 = 0.0;
-  if (c >= PPO_NPART_FIXED && c < ncomp) {
-    const float g = (float)s - entropy_coef;
-    d_log_std[c - PPO_NPART_FIXED] = g;
-    g2 = (double)g * (double)g;
-  }
-  g2 = wave_sum(g2);
-  double ent = 0.0;
-  if (c < A) ent = 0.5 + 0.5 * (double)LOG_2PI + (double)log_std[c];
-  ent = wave_sum(ent);
-  if (c == 0) {
-    *sumsq_slot = g2;
-    stats_row[0] = (float)(s / rows);
-    stats_row[2] = (float)ent;
-  }
-  if (c == 1) stats_row[1] = (float)(s / rows);
-  if (c == 2) stats_row[3] = (float)(s / mb);
-  if (c == 3) stats_row[5] = (float)(s / rows);
-  if (c == 4) stats_row[6] = rows > mb ? (float)(s / ((double)mb * A)) : 0.f;
-  if (c == 5) stats_row[7] = 0.f;
-}
-
-hipError_t launch_ppo_loss_finish(const double* partials, int32_t blocks, int32_t rows, int32_t mb, int32_t A,
-                                  const float* log_std, float entropy_coef, float* d_log_std, float* stats_row,
-                                  double* sumsq_slot, hipStream_t stream) {
-  hipLaunchKernelGGL(ppo_loss_finish_kernel, dim3(1), dim3(1024), 0, stream, partials, blocks, rows, mb, A, log_std,
-                     entropy_coef, d_log_std, stats_row, sumsq_slot);
   return hipGetLastError();
 }
 

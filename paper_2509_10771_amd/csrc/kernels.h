@@ -115,17 +115,31 @@ hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_
 // Sum the split partials of one network's gradient, layer by layer, into the flat gradient buffer and emit
 // per-block sums of squares.  Layer l owns `split[l]` partial buffers of `size[l]` floats each, `pitch[l]` floats
 // apart from `part_off[l]` on; its gradient starts at `grad_off[l]`.
+// Sums of the PPO loss partials: stats row, log_std gradient and its squared norm (see launch_reduce_partials).
+struct LossFinishArgs {
+  const double* partials;   // [blocks][5 + A]; blocks == 0: nothing to finish
+  int32_t blocks, rows, mb, A;
+  const float* log_std;
+  float entropy_coef;
+  float* d_log_std;
+  float* stats_row;
+  double* sumsq_slot;
+};
+// One segment = the split-buffers of one layer of one network.
+struct ReduceSeg {
+  const float* partials;    // first split buffer of the layer
+  float* grads;             // the layer's slice of the flat gradient
+  int64_t size;             // floats per split (W then b)
+  int64_t pitch;            // floats between consecutive split buffers (multiple of 4)
+  int32_t split;
+  int32_t block_start;      // first workgroup of the segment
+};
 struct ReduceArgs {
-  const float* partials;
-  float* grads;
+  ReduceSeg seg[16];
+  int32_t n_seg;
+  int32_t blocks;           // workgroups over all segments; block b writes sumsq_blocks[b]
   double* sumsq_blocks;
-  int32_t n_layers;
-  int32_t split[8];
-  int64_t size[8];
-  int64_t pitch[8];         // floats between consecutive split buffers (multiple of 4)
-  int64_t part_off[8];
-  int64_t grad_off[8];
-  int32_t block_start[9];   // first block of each layer (prefix sums), block_start[n_layers] = total
+  LossFinishArgs finish;    // handled by one extra workgroup of the same launch
 };
 constexpr int REDUCE_BLOCK_FLOATS = 256;
 hipError_t launch_reduce_partials(const ReduceArgs& a, hipStream_t stream);
@@ -191,10 +205,6 @@ struct PpoHeadArgs {
 bool ppo_head_supported(int32_t Ha, int32_t Hc, int32_t A);
 int ppo_head_num_blocks(int32_t mb, bool sym);
 hipError_t launch_ppo_head(const PpoHeadArgs& h, hipStream_t stream);
-// Reduce the loss partials: writes the stats row, the log_std gradient and its squared norm.
-hipError_t launch_ppo_loss_finish(const double* partials, int32_t blocks, int32_t rows, int32_t mb, int32_t A,
-                                  const float* log_std, float entropy_coef, float* d_log_std, float* stats_row,
-                                  double* sumsq_slot, hipStream_t stream);
 
 // Mean-squared-error head: d = 2 (y - target) / (rows * width), block partial sums of squared error.
 int mse_num_blocks(int64_t n);
