@@ -710,27 +710,72 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(const PpoLossArgs a) {
 // last hidden activations of actor and critic into LDS, applies both output layers (A + 1 dot products per row),
 // evaluates the PPO loss terms, and back-propagates through the output layers into the pre-activation gradient of
 // the last hidden layer.  Three launches and two passes over the activations collapse into one.
+// Every phase spreads over all 256 lanes: global loads are issued together before the first one is used, the
+// output-layer dot products are cut into 8 contraction ranges per row, the loss runs on (row, action component)
+// pairs with the row sums taken through LDS in a fixed order, and the input gradient reads a row's d_mu with
+// 16-byte broadcasts.
 constexpr int HEAD_ROWS = 32;
+constexpr int HEAD_KPARTS = 8;      // lanes that share one row's output-layer dot products (and: 256 / HEAD_ROWS)
+constexpr int HEAD_PAD = 4;         // LDS row padding of the activations: rows stay 16-byte aligned, and the lanes
+                                    // (row, part) of the output-layer phase spread evenly over the banks
+
+// LDS plan (floats), shared by the kernel and the host-side size check.
+struct HeadLds {
+  int A4, gp;
+  int ha, hc, wa, wc, mu, dmu, vv, dv, gat, bidx, pact, cst, dlp, scr, dls, total;
+  // A4: padded number of action components = the kernel's template width (rows of W, mu, d_mu in LDS)
+  __host__ __device__ HeadLds(int Ha, int Hc, int A, int AP) {
+    A4 = AP;
+    gp = (4 + 3 * A) | 1;
+    int o = 0;
+    auto take = [&](int n) { const int r = o; o += (n + 3) & ~3; return r; };
+    ha = take(HEAD_ROWS * (Ha + HEAD_PAD));
+    hc = take(HEAD_ROWS * (Hc + HEAD_PAD));
+    wa = take(Ha * AP + AP);            // W rows padded with zeros to AP, then the bias
+    wc = take(Hc + 1);
+    mu = take(HEAD_ROWS * A4);
+    dmu = take(HEAD_ROWS * A4);
+    vv = take(HEAD_ROWS);
+    dv = take(HEAD_ROWS);
+    gat = take(HEAD_ROWS * gp);
+    bidx = take(HEAD_ROWS);
+    pact = take(A4);                    // mirror map of the action components
+    cst = take(4 * A4);                 // per component: log_std, 1 / sigma, 1 / (2 sigma^2), mirror sign
+    dlp = take(2 * HEAD_ROWS);          // d loss / d log-prob of the rows (and of their twins)
+    scr = take(2 * A4 * HEAD_ROWS);     // squared standard scores of rows and twins
+    dls = take(2 * A4);
+    total = o;
+  }
+};
 
 template <int AM>
 __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
   extern __shared__ float lds[];
   const PpoLossArgs& a = h.loss;
   const int A = a.A, Ha = h.Ha, Hc = h.Hc;
+  const HeadLds L(Ha, Hc, A, AM);
+  constexpr int A4 = AM;
+  const int gp = L.gp;
   const bool sym = a.rows > a.mb;
   const int r_orig = sym ? HEAD_ROWS / 2 : HEAD_ROWS;
   const int i0 = blockIdx.x * r_orig;
-  const int sa = Ha + 1, sc = Hc + 1;                      // padded LDS row strides
-  float* ha = lds;                                        // [rows][Ha + 1]
-  float* hc = ha + HEAD_ROWS * sa;                        // [rows][Hc + 1]
-  float* wa = hc + HEAD_ROWS * sc;                        // [Ha * A + A]
-  float* wc = wa + Ha * A + A;                            // [Hc + 1]
-  float* mu = wc + Hc + 1;                                // [rows][A]
-  float* dmu = mu + HEAD_ROWS * A;                        // [rows][A]
-  float* vv = dmu + HEAD_ROWS * A;                        // [rows]
-  float* dv = vv + HEAD_ROWS;                             // [rows]
-  float* gat = dv + HEAD_ROWS;                            // [rows][(4 + 3 A) | 1] gathered rollout rows
-  const int tid = threadIdx.x;
+  const int sa = Ha + HEAD_PAD, sc = Hc + HEAD_PAD;         // padded LDS row strides
+  float* ha = lds + L.ha;
+  float* hc = lds + L.hc;
+  float* wa = lds + L.wa;
+  float* wc = lds + L.wc;
+  float* mu = lds + L.mu;
+  float* dmu = lds + L.dmu;
+  float* vv = lds + L.vv;
+  float* dv = lds + L.dv;
+  float* gat = lds + L.gat;       // [row][adv, ret, v_old, logp_old, actions[A], mu_old[A], sigma_old[A]]
+  int* bidx = reinterpret_cast<int*>(lds + L.bidx);
+  int* pact = reinterpret_cast<int*>(lds + L.pact);
+  float* cst = lds + L.cst;
+  float* dlp = lds + L.dlp;
+  float* scr = lds + L.scr;
+  float* dls_out = lds + L.dls;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // local row lr -> activation row (twins live mb rows further down), or -1 past the minibatch
   auto grow = [&](int lr) -> long {
     const int o = lr < r_orig ? lr : lr - r_orig;
@@ -738,115 +783,271 @@ __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
     return lr < r_orig ? (long)(i0 + o) : (long)a.mb + i0 + o;
   };
 
-  // Rollout rows of this block, gathered through the permutation by all lanes together (one value per lane and
-  // pass) into LDS: [row][adv, ret, v_old, logp_old, actions[A], mu_old[A], sigma_old[A]], odd row pitch.
-  const bool loss_lane = tid < r_orig && i0 + tid < a.mb;
-  const int gw = 4 + 3 * A, gp = gw | 1;
-  for (int e = tid; e < r_orig * gw; e += 256) {
-    const int lr = e / gw, c = e - lr * gw;
-    float v = 0.f;
-    if (i0 + lr < a.mb) {
-      const long b = a.idx[i0 + lr];
-      if (c < 4) {
-        const float* src = c == 0 ? a.adv : c == 1 ? a.returns : c == 2 ? a.v_old : a.logp_old;
-        v = src[b];
-      } else {
-        const int q = (c - 4) / A, jj = (c - 4) - q * A;
-        const float* src = q == 0 ? a.actions : q == 1 ? a.mu_old : a.sigma_old;
-        v = src[b * A + jj];
-      }
+  // ---- phase 1: every global read of the block, issued before any of them is consumed ----
+  int my_b = -1;
+  if (tid < r_orig && i0 + tid < a.mb) my_b = a.idx[i0 + tid];
+  constexpr int HP = 8;                                   // 16-byte pieces per lane and network (H <= 256)
+  float4 ra[HP], rc[HP];
+  const int pa = Ha >> 2, pc = Hc >> 2;                   // pieces per row (powers of two)
+  const int sha = __ffs(pa) - 1, shc = __ffs(pc) - 1;
+#pragma unroll
+  for (int i = 0; i < HP; ++i) {
+    const int e = tid + 256 * i;
+    ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    rc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (e < HEAD_ROWS * pa) {
+      const long gr = grow(e >> sha);
+      if (gr >= 0) ra[i] = *reinterpret_cast<const float4*>(h.h_a + gr * Ha + 4 * (e & (pa - 1)));
     }
-    gat[lr * gp + c] = v;
+    if (e < HEAD_ROWS * pc) {
+      const long gr = grow(e >> shc);
+      if (gr >= 0) rc[i] = *reinterpret_cast<const float4*>(h.h_c + gr * Hc + 4 * (e & (pc - 1)));
+    }
   }
-
-  for (int e = tid; e < Ha * A + A; e += 256) wa[e] = h.w_a[e];
+  for (int e0 = 0; e0 < (Ha + 1) * AM; e0 += 256 * 8) {   // 8 loads in flight per lane; rows padded with zeros
+    float wv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = e0 + tid + 256 * i;
+      const int k = e / AM, jj = e - k * AM;
+      wv[i] = (e < (Ha + 1) * AM && jj < A) ? h.w_a[k * A + jj] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = e0 + tid + 256 * i;
+      if (e < (Ha + 1) * AM) wa[e] = wv[i];
+    }
+  }
   for (int e = tid; e < Hc + 1; e += 256) wc[e] = h.w_c[e];
-  for (int e = tid; e < HEAD_ROWS * (Ha / 4); e += 256) {
-    const int lr = e / (Ha / 4), c4 = e % (Ha / 4);
-    const long gr = grow(lr);
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (gr >= 0) v = *reinterpret_cast<const float4*>(h.h_a + gr * Ha + 4 * c4);
-    float* d = ha + lr * sa + 4 * c4;
-    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  if (tid < A) {
+    const float ls = a.log_std[tid];
+    const float inv = expf(-ls);
+    cst[4 * tid + 0] = ls; cst[4 * tid + 1] = inv; cst[4 * tid + 2] = 0.5f * inv * inv;
+    cst[4 * tid + 3] = sym ? a.sign_act[tid] : 1.0f;
+    pact[tid] = sym ? a.perm_act[tid] : tid;
   }
-  for (int e = tid; e < HEAD_ROWS * (Hc / 4); e += 256) {
-    const int lr = e / (Hc / 4), c4 = e % (Hc / 4);
-    const long gr = grow(lr);
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (gr >= 0) v = *reinterpret_cast<const float4*>(h.h_c + gr * Hc + 4 * c4);
-    float* d = hc + lr * sc + 4 * c4;
-    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-  }
+  for (int e = tid; e < HEAD_ROWS * A4; e += 256) dmu[e] = 0.f;    // also the padding the 16-byte reads touch
+  if (tid < HEAD_ROWS) bidx[tid] = my_b;
   __syncthreads();
-
-  // ---- output layers: lane = row, the 8 half-wavefronts stride over the A + 1 outputs ----
+  // rollout rows, gathered through the permutation: wavefront w takes rows w, w + 4, ..; lanes run over the row;
+  // the loads of all 8 rows are in flight together
   {
-    const int lr = tid & (HEAD_ROWS - 1);
-    for (int o = tid / HEAD_ROWS; o <= A; o += 256 / HEAD_ROWS) {
-      float s;
-      if (o < A) {
-        s = wa[Ha * A + o];
-#pragma unroll 16
-        for (int k = 0; k < Ha; ++k) s += ha[lr * sa + k] * wa[k * A + o];
-        mu[lr * A + o] = s;
+    const int gw = 4 + 3 * A;
+    for (int c = lane; c < gw; c += 64) {
+      const float* src; int stride = 1, off = 0;
+      if (c < 4) {
+        src = c == 0 ? a.adv : c == 1 ? a.returns : c == 2 ? a.v_old : a.logp_old;
       } else {
-        s = wc[Hc];
-#pragma unroll 16
-        for (int k = 0; k < Hc; ++k) s += hc[lr * sc + k] * wc[k];
-        vv[lr] = s;
+        const int q = (c - 4) / A;
+        src = q == 0 ? a.actions : q == 1 ? a.mu_old : a.sigma_old;
+        stride = A; off = (c - 4) - q * A;
       }
+      float gv[HEAD_ROWS / 4];
+#pragma unroll
+      for (int i = 0; i < HEAD_ROWS / 4; ++i) {
+        const int r = wave + 4 * i;
+        const long b = r < r_orig ? bidx[r] : -1;
+        gv[i] = b >= 0 ? src[b * stride + off] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < HEAD_ROWS / 4; ++i) {
+        const int r = wave + 4 * i;
+        if (r < r_orig) gat[r * gp + c] = gv[i];
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < HP; ++i) {
+    const int e = tid + 256 * i;
+    if (e < HEAD_ROWS * pa) {
+      *reinterpret_cast<float4*>(ha + (e >> sha) * sa + 4 * (e & (pa - 1))) = ra[i];
+    }
+    if (e < HEAD_ROWS * pc) {
+      *reinterpret_cast<float4*>(hc + (e >> shc) * sc + 4 * (e & (pc - 1))) = rc[i];
     }
   }
   __syncthreads();
 
-  // ---- loss terms: one lane per original row ----
-  PpoAcc<AM> acc;
+  // ---- phase 2: output layers.  The 8 lanes (row, p) of a row take every 8th hidden unit each and form the
+  //      A + 1 dot products over them; a butterfly over the 8 lanes adds the parts in a fixed order ----
+  {
+    const int p8 = lane & (HEAD_KPARTS - 1), row = wave * 8 + (lane >> 3);
+    float acc[AM + 1];
 #pragma unroll
-  for (int jj = 0; jj < AM; ++jj) acc.dls[jj] = 0.f;
-  if (loss_lane) {
-    const int lt = tid + r_orig;      // twin's local row (only read with symmetry)
-    PpoRowIn<AM> rin;
-    const float* gr = gat + tid * gp;
-    rin.adv = gr[0]; rin.ret = gr[1]; rin.v_old = gr[2]; rin.logp_old = gr[3];
+    for (int jj = 0; jj <= AM; ++jj) acc[jj] = 0.f;
+    // trip counts are uniform (the lane only shifts the start), so the loops carry no lane mask
+#pragma unroll 4
+    for (int i = 0; i < Ha / HEAD_KPARTS; ++i) {
+      const int k = HEAD_KPARTS * i + p8;
+      const float hv = ha[row * sa + k];
+      const float4* wr = reinterpret_cast<const float4*>(wa + k * AM);
 #pragma unroll
-    for (int jj = 0; jj < AM; ++jj) {
-      if (jj < A) {
-        rin.act[jj] = gr[4 + jj];
-        rin.mu_old[jj] = gr[4 + A + jj];
-        rin.sigma_old[jj] = gr[4 + 2 * A + jj];
-        if (sym) rin.act_m[jj] = a.sign_act[jj] * gr[4 + a.perm_act[jj]];
+      for (int q = 0; q < AM / 4; ++q) {
+        const float4 w4 = wr[q];
+        acc[4 * q] += hv * w4.x; acc[4 * q + 1] += hv * w4.y; acc[4 * q + 2] += hv * w4.z; acc[4 * q + 3] += hv * w4.w;
       }
     }
-    ppo_loss_row(a, rin, mu + tid * A, mu + (sym ? lt : tid) * A, vv[tid], sym ? vv[lt] : 0.f, dmu + tid * A,
-                 dmu + (sym ? lt : tid) * A, dv + tid, dv + (sym ? lt : tid), acc);
+#pragma unroll 4
+    for (int i = 0; i < Hc / HEAD_KPARTS; ++i) {
+      const int k = HEAD_KPARTS * i + p8;
+      acc[AM] += hc[row * sc + k] * wc[k];
+    }
+    // butterfly over the 8 lanes of a row; all exchanges of a step are issued together
+#pragma unroll
+    for (int off = 1; off < HEAD_KPARTS; off <<= 1) {
+      float t[AM + 1];
+#pragma unroll
+      for (int jj = 0; jj <= AM; ++jj) t[jj] = __shfl_xor(acc[jj], off, 64);
+#pragma unroll
+      for (int jj = 0; jj <= AM; ++jj) acc[jj] += t[jj];
+    }
+    if (p8 == 0) {
+#pragma unroll
+      for (int jj = 0; jj < AM; ++jj) mu[row * A4 + jj] = acc[jj] + wa[Ha * AM + jj];
+      vv[row] = acc[AM] + wc[Hc];
+    }
   }
-  ppo_acc_reduce(acc, A, a.partials + (long)blockIdx.x * (PPO_NPART_FIXED + A));   // contains a __syncthreads()
   __syncthreads();
 
-  // ---- output-layer gradients for the weight-gradient contraction (d_mu, d_v to global memory) ----
+  // ---- phase 3: loss.  Lane (row, jg) handles components jg, jg + 8, .. of a row (and of its twin) ----
+  constexpr int JPT = (AM + HEAD_KPARTS - 1) / HEAD_KPARTS;
+  const int lr = tid & (HEAD_ROWS - 1), jg = tid >> 5;
+  const bool row_ok = lr < r_orig && i0 + lr < a.mb;
+  const int lt = lr + r_orig;                       // twin's local row (symmetry only)
+  float* z2 = scr;                                  // [A4][32] rows, then [A4][32] twins
+  float* z2m = scr + A4 * HEAD_ROWS;
+  float zj[JPT], zmj[JPT], diffj[JPT];
+  double kl_acc = 0.0, mir_acc = 0.0;
+#pragma unroll
+  for (int t = 0; t < JPT; ++t) {
+    const int jj = jg + HEAD_KPARTS * t;
+    zj[t] = 0.f; zmj[t] = 0.f; diffj[t] = 0.f;
+    if (jj < A) {
+      float zz = 0.f, zzm = 0.f;
+      if (row_ok) {
+        const float* gr = gat + lr * gp;
+        const float ls = cst[4 * jj], inv = cst[4 * jj + 1], inv2 = cst[4 * jj + 2];
+        const float act = gr[4 + jj], mo = gr[4 + A + jj], so = gr[4 + 2 * A + jj];
+        const float m_ = mu[lr * A4 + jj];
+        const float z = (act - m_) * inv;
+        zj[t] = z; zz = z * z;
+        kl_acc += (double)((ls - logf(so)) + (so * so + (mo - m_) * (mo - m_)) * inv2 - 0.5f);
+        if (sym) {
+          const float sgn = cst[4 * jj + 3];
+          const int pj = pact[jj];
+          const float am = sgn * gr[4 + pj];
+          const float mm = mu[lt * A4 + jj];
+          const float zm = (am - mm) * inv;
+          zmj[t] = zm; zzm = zm * zm;
+          const float target = sgn * mu[lr * A4 + pj];
+          diffj[t] = mm - target;
+          mir_acc += (double)(diffj[t] * diffj[t]);
+        }
+      }
+      z2[jj * HEAD_ROWS + lr] = zz;
+      if (sym) z2m[jj * HEAD_ROWS + lr] = zzm;
+    }
+  }
+  __syncthreads();
+  double surr_acc = 0.0, vl_acc = 0.0, clip_acc = 0.0;
+  if (tid < HEAD_ROWS) {
+    float dl = 0.f, dlm = 0.f;
+    if (row_ok) {
+      const float* gr = gat + lr * gp;
+      const float inv_rows = 1.0f / (float)a.rows;
+      float zz = 0.f, zzm = 0.f, sum_ls = 0.f;
+      for (int jj = 0; jj < A; ++jj) {
+        zz += z2[jj * HEAD_ROWS + lr];
+        if (sym) zzm += z2m[jj * HEAD_ROWS + lr];
+        sum_ls += cst[4 * jj];
+      }
+      const float cl = sum_ls + 0.5f * (float)A * LOG_2PI;
+      float d_v;
+      RowTerms t = ppo_row(a, -0.5f * zz - cl, gr[3], gr[0], vv[lr], gr[2], gr[1], inv_rows, &dl, &d_v);
+      surr_acc = t.surr; vl_acc = t.vloss; clip_acc = t.clipped;
+      dv[lr] = d_v;
+      if (sym) {
+        float d_vm;
+        RowTerms tm = ppo_row(a, -0.5f * zzm - cl, gr[3], gr[0], vv[lt], gr[2], gr[1], inv_rows, &dlm, &d_vm);
+        surr_acc += tm.surr; vl_acc += tm.vloss; clip_acc += tm.clipped;
+        dv[lt] = d_vm;
+      }
+    } else if (lr < r_orig) {
+      dv[lr] = 0.f;
+      if (sym) dv[lt] = 0.f;
+    }
+    dlp[lr] = dl;
+    dlp[HEAD_ROWS + lr] = dlm;
+  }
+  __syncthreads();
+  {
+    const float dl = dlp[lr], dlm = dlp[HEAD_ROWS + lr];
+    const float msc = sym ? a.mirror_coef * 2.0f / ((float)a.mb * (float)A) : 0.f;
+#pragma unroll
+    for (int t = 0; t < JPT; ++t) {
+      const int jj = jg + HEAD_KPARTS * t;
+      double g = 0.0;
+      if (jj < A && lr < r_orig) {
+        const float inv = cst[4 * jj + 1];
+        dmu[lr * A4 + jj] = dl * zj[t] * inv;
+        float gl = dl * (zj[t] * zj[t] - 1.0f);
+        if (sym) {
+          dmu[lt * A4 + jj] = dlm * zmj[t] * inv + msc * diffj[t];
+          gl += dlm * (zmj[t] * zmj[t] - 1.0f);
+        }
+        g = row_ok ? (double)gl : 0.0;
+      }
+      // lanes of a half-wavefront share jj and run over the rows: sum them, one value per component
+      for (int off = 16; off > 0; off >>= 1) g += __shfl_xor(g, off, 64);
+      if ((lane & 31) == 0 && jj < A) reinterpret_cast<double*>(dls_out)[jj] = g;
+    }
+  }
+  {
+    __shared__ double wpart[4][PPO_NPART_FIXED];
+    const double v5[PPO_NPART_FIXED] = {surr_acc, vl_acc, kl_acc, clip_acc, mir_acc};
+#pragma unroll
+    for (int c = 0; c < PPO_NPART_FIXED; ++c) {
+      const double r = wave_sum(v5[c]);
+      if (lane == 0) wpart[wave][c] = r;
+    }
+    __syncthreads();
+    double* block_out = a.partials + (long)blockIdx.x * (PPO_NPART_FIXED + A);
+    if (tid < PPO_NPART_FIXED) block_out[tid] = wpart[0][tid] + wpart[1][tid] + wpart[2][tid] + wpart[3][tid];
+    else if (tid < PPO_NPART_FIXED + A) block_out[tid] = reinterpret_cast<const double*>(dls_out)[tid - PPO_NPART_FIXED];
+  }
+
+  // ---- phase 4: output-layer gradients for the weight-gradient contraction (d_mu, d_v to global memory) ----
   for (int e = tid; e < HEAD_ROWS * A; e += 256) {
-    const long gr = grow(e / A);
-    if (gr >= 0) a.d_mu[gr * A + e % A] = dmu[e];
+    const int r = e / A, jj = e - r * A;
+    const long gr = grow(r);
+    if (gr >= 0) a.d_mu[gr * A + jj] = dmu[r * A4 + jj];
   }
   if (tid < HEAD_ROWS) {
     const long gr = grow(tid);
     if (gr >= 0) a.d_v[gr] = dv[tid];
   }
-  // ---- input gradient of the output layers, times ELU'(h): lane = hidden unit, its weight row in registers ----
+  // ---- input gradient of the output layers, times ELU'(h): lane = hidden unit, its weight row in registers, a
+  //      row's d_mu read with 16-byte broadcasts ----
   {
     const int k = tid % Ha, rstep = 256 / Ha;
     float wrow[AM];
 #pragma unroll
-    for (int jj = 0; jj < AM; ++jj) wrow[jj] = jj < A ? wa[k * A + jj] : 0.f;
+    for (int q = 0; q < AM / 4; ++q) {
+      const float4 w4 = *reinterpret_cast<const float4*>(wa + k * AM + 4 * q);
+      wrow[4 * q] = w4.x; wrow[4 * q + 1] = w4.y; wrow[4 * q + 2] = w4.z; wrow[4 * q + 3] = w4.w;
+    }
 #pragma unroll 4
-    for (int lr = tid / Ha; lr < HEAD_ROWS; lr += rstep) {
-      const long gr = grow(lr);
+    for (int i = 0; i < HEAD_ROWS / rstep; ++i) {      // uniform trip count; the lane only shifts the first row
+      const int r = tid / Ha + i * rstep;
+      const long gr = grow(r);
       if (gr < 0) continue;
       float s = 0.f;
 #pragma unroll
-      for (int jj = 0; jj < AM; ++jj)
-        if (jj < A) s += dmu[lr * A + jj] * wrow[jj];
-      const float hv = ha[lr * sa + k];
+      for (int q = 0; q < AM / 4; ++q) {
+        const float4 d = *reinterpret_cast<const float4*>(dmu + r * A4 + 4 * q);
+        s += d.x * wrow[4 * q] + d.y * wrow[4 * q + 1] + d.z * wrow[4 * q + 2] + d.w * wrow[4 * q + 3];
+      }
+      const float hv = ha[r * sa + k];
       h.dz_a[gr * Ha + k] = s * (hv > 0.f ? 1.0f : hv + h.alpha_a);
     }
   }
@@ -854,44 +1055,53 @@ __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
     const int k = tid % Hc, rstep = 256 / Hc;
     const float wk = wc[k];
 #pragma unroll 4
-    for (int lr = tid / Hc; lr < HEAD_ROWS; lr += rstep) {
-      const long gr = grow(lr);
+    for (int i = 0; i < HEAD_ROWS / rstep; ++i) {
+      const int r = tid / Hc + i * rstep;
+      const long gr = grow(r);
       if (gr < 0) continue;
-      const float hv = hc[lr * sc + k];
-      h.dz_c[gr * Hc + k] = dv[lr] * wk * (hv > 0.f ? 1.0f : hv + h.alpha_c);
+      const float hv = hc[r * sc + k];
+      h.dz_c[gr * Hc + k] = dv[r] * wk * (hv > 0.f ? 1.0f : hv + h.alpha_c);
     }
   }
 }
 
+static int head_width(int A) { return A <= 4 ? 4 : A <= 8 ? 8 : A <= 12 ? 12 : A <= 16 ? 16 : 32; }
+
 size_t ppo_head_lds_bytes(int32_t Ha, int32_t Hc, int32_t A) {
-  return sizeof(float) * ((size_t)HEAD_ROWS * (Ha + 1) + (size_t)HEAD_ROWS * (Hc + 1) + (size_t)Ha * A + A + Hc + 1 +
-                          2 * (size_t)HEAD_ROWS * A + 2 * HEAD_ROWS + (size_t)HEAD_ROWS * ((4 + 3 * A) | 1));
+  return sizeof(float) * (size_t)HeadLds(Ha, Hc, A, head_width(A)).total;
 }
 
 bool ppo_head_supported(int32_t Ha, int32_t Hc, int32_t A) {
   auto ok = [](int h) { return h == 32 || h == 64 || h == 128 || h == 256; };
-  return ok(Ha) && ok(Hc) && A >= 1 && A <= AMAX && ppo_head_lds_bytes(Ha, Hc, A) <= 150 * 1024;
+  return ok(Ha) && ok(Hc) && A >= 1 && A <= 32 && ppo_head_lds_bytes(Ha, Hc, A) <= 150 * 1024;
 }
 
 int ppo_head_num_blocks(int32_t mb, bool sym) { const int r = sym ? HEAD_ROWS / 2 : HEAD_ROWS; return (mb + r - 1) / r; }
 
-hipError_t launch_ppo_head(const PpoHeadArgs& h, hipStream_t stream) {
-  const size_t lds_bytes = ppo_head_lds_bytes(h.Ha, h.Hc, h.loss.A);
+template <int AM>
+static hipError_t launch_ppo_head_width(const PpoHeadArgs& h, size_t lds_bytes, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ppo_head_kernel<16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ppo_head_kernel<AM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(ppo_head_kernel<AMAX>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  TraceScope ts(stream, "ppo_head", 0.0, 0.0);
   const dim3 grid(ppo_head_num_blocks(h.loss.mb, h.loss.rows > h.loss.mb));
-  if (h.loss.A <= 16) hipLaunchKernelGGL(ppo_head_kernel<16>, grid, dim3(256), lds_bytes, stream, h);
-  else hipLaunchKernelGGL(ppo_head_kernel<AMAX>, grid, dim3(256), lds_bytes, stream, h);
+  hipLaunchKernelGGL(ppo_head_kernel<AM>, grid, dim3(256), lds_bytes, stream, h);
   return hipGetLastError();
+}
+
+hipError_t launch_ppo_head(const PpoHeadArgs& h, hipStream_t stream) {
+  const size_t lds_bytes = ppo_head_lds_bytes(h.Ha, h.Hc, h.loss.A);
+  TraceScope ts(stream, "ppo_head", 0.0, 0.0);
+  switch (head_width(h.loss.A)) {
+    case 4: return launch_ppo_head_width<4>(h, lds_bytes, stream);
+    case 8: return launch_ppo_head_width<8>(h, lds_bytes, stream);
+    case 12: return launch_ppo_head_width<12>(h, lds_bytes, stream);
+    case 16: return launch_ppo_head_width<16>(h, lds_bytes, stream);
+    default: return launch_ppo_head_width<32>(h, lds_bytes, stream);
+  }
 }
 
 hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
