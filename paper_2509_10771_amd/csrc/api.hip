@@ -181,8 +181,10 @@ struct SplitPlan {
   int32_t blocks = 0;      // workgroups of the reduction = entries of the squared-norm list
 };
 
-// Enough workgroups to keep about four resident per CU (256 CUs), but at least 128 rows per split.
+// Enough workgroups to fill the 256 CUs once, but at least 128 rows per split: four 64-row-tile workgroups per CU,
+// three of the 128x128 ones (measured: 768 of those beat 1024, and a quarter of the partial sums goes away).
 constexpr int DW_TARGET_WGS = 1024;
+constexpr int DW_TARGET_WGS_BIG = 768;
 
 SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group) {
   SplitPlan p;
@@ -191,7 +193,8 @@ SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group) {
     const int tiles_big = ((M + 127) / 128) * ((N + 127) / 128);
     p.big[l] = (tiles_big * group >= 16) ? 1 : 0;
     const int tiles = gemm_dw_tiles(M, N, p.big[l] != 0);
-    int s = (DW_TARGET_WGS + tiles * group - 1) / (tiles * group);
+    const int target = p.big[l] ? DW_TARGET_WGS_BIG : DW_TARGET_WGS;
+    int s = (target + tiles * group - 1) / (tiles * group);
     const int smax = rows / 128 > 1 ? rows / 128 : 1;
     if (s > smax) s = smax;
     if (s < 1) s = 1;
