@@ -187,6 +187,22 @@ def test_ppo_odd_hidden_width_takes_the_unfused_loss_path(rx):
     check_free_running(rx, case)
 
 
+@pytest.mark.parametrize("base,N,A,hidden,sym_on", [
+    ("tiny", 40, 3, (64, 32), False),        # padded action width 4
+    ("rough", 30, 7, (96, 64), True),        # width 8, mirrored twins, 16 + 16 rows per workgroup
+    ("tiny", 50, 16, (128, 128), False),     # width 16, no padding
+    ("tiny", 36, 20, (64, 256), False),      # width 32, widest hidden layer of the fused head
+    ("rough", 20, 12, (64, 128), True),      # width 12 with symmetry
+])
+def test_ppo_fused_head_widths(rx, base, N, A, hidden, sym_on):
+    """The fused output-layer + loss kernel exists once per padded action width; every width, with and without
+    mirrored rows, must agree with the oracle like the default one."""
+    w = replace(WORKLOADS[base].scaled(N), A=A, hidden=hidden)
+    case = Case(w, 1, sym_on=sym_on, perturb=0.2)
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
+
+
 def test_ppo_flat_ragged(rx):
     case = Case(WORKLOADS["flat"].scaled(250), 1)     # mb = 1500 rows: 11 full 128-row tiles and a 92-row tail
     check_forced_steps(rx, case)
