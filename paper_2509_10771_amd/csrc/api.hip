@@ -182,9 +182,12 @@ struct SplitPlan {
 };
 
 // Enough workgroups to fill the 256 CUs once, but at least 128 rows per split: four 64-row-tile workgroups per CU,
-// three of the 128x128 ones (measured: 768 of those beat 1024, and a quarter of the partial sums goes away).
+// three of the 128x128 ones (measured: 768 of those beat 1024).  A 128x128 weight gradient that shares its launch
+// with the layer's input gradient (every layer but the first) only needs two per CU - the input gradient's
+// workgroups take the other slots - which also halves its partial sums.
 constexpr int DW_TARGET_WGS = 1024;
 constexpr int DW_TARGET_WGS_BIG = 768;
+constexpr int DW_TARGET_WGS_BIG_PAIRED = 512;
 
 SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group) {
   SplitPlan p;
@@ -193,7 +196,7 @@ SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group) {
     const int tiles_big = ((M + 127) / 128) * ((N + 127) / 128);
     p.big[l] = (tiles_big * group >= 16) ? 1 : 0;
     const int tiles = gemm_dw_tiles(M, N, p.big[l] != 0);
-    const int target = p.big[l] ? DW_TARGET_WGS_BIG : DW_TARGET_WGS;
+    const int target = p.big[l] ? (l > 0 ? DW_TARGET_WGS_BIG_PAIRED : DW_TARGET_WGS_BIG) : DW_TARGET_WGS;
     int s = (target + tiles * group - 1) / (tiles * group);
     const int smax = rows / 128 > 1 ? rows / 128 : 1;
     if (s > smax) s = smax;
@@ -278,8 +281,8 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, bool sk
         bx.p[i] = q;
       }
     }
-    RSLX_HIP(launch_gemm(GEMM_DW, bw, stream));
-    if (l > 0 && !(skip_last_dx && l == L - 1)) RSLX_HIP(launch_gemm(GEMM_DX, bx, stream));
+    if (l > 0 && !(skip_last_dx && l == L - 1)) RSLX_HIP(launch_gemm_dw_dx(bw, bx, stream));
+    else RSLX_HIP(launch_gemm(GEMM_DW, bw, stream));
   }
   return RSLX_OK;
 }

@@ -195,26 +195,29 @@ struct Direct {
   }
 };
 
+// LDS floats of one tile configuration: two buffers of BK x (BM + PAD) and BK x (BN + PAD).
+template <int BM, int BN, int BK>
+constexpr int gemm_lds_floats() { return 2 * BK * (BM + PAD) + 2 * BK * (BN + PAD); }
+
+// One output tile (one split of it for the weight gradient) of problem P.  `lin` numbers the workgroups of the
+// problem's grid of gx tiles x (total / gx) splits; `smem` holds gemm_lds_floats<BM, BN, BK>() floats.
 template <int MODE, int BM, int BN, int WM, int WN, int BK, bool AVEC, bool BVEC>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void gemm_kernel(const GemmBatch batch) {
+__device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const int total, const int gx, float* smem) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 block");
   constexpr int SA = BM + PAD, SB = BN + PAD;
-  __shared__ __align__(16) float As[2][BK][SA];
-  __shared__ __align__(16) float Bs[2][BK][SB];
+  float (*As)[BK][SA] = reinterpret_cast<float (*)[BK][SA]>(smem);
+  float (*Bs)[BK][SB] = reinterpret_cast<float (*)[BK][SB]>(smem + 2 * BK * SA);
 
-  const GemmProblem& P = batch.p[blockIdx.z];
   const int tiles_n = (P.N + BN - 1) / BN;
   const int tiles_m = (P.M + BM - 1) / BM;
   // Workgroups are handed to the 8 XCDs round-robin by linear id; remap so that neighbours in (tile, split)
   // order - which share operand rows - run on the same XCD and meet in its L2.
-  int lin = blockIdx.x + gridDim.x * blockIdx.y;
-  const int total = gridDim.x * gridDim.y;
   if ((total & 7) == 0) lin = (lin & 7) * (total >> 3) + (lin >> 3);
-  const int tile = lin % (int)gridDim.x;
+  const int tile = lin % gx;
   if (tile >= tiles_m * tiles_n) return;
-  const int split = lin / (int)gridDim.x;
+  const int split = lin / gx;
   if (MODE == GEMM_DW && split >= P.n_split) return;
   const int tn = tile % tiles_n, tm = tile / tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
@@ -410,6 +413,35 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void ge
   if (MODE == GEMM_DW && tm == 0 && bias_off >= 0 && tid < BN && n0 + tid < Nc) Cb[bias_off + n0 + tid] = bsum;
 }
 
+template <int MODE, int BM, int BN, int WM, int WN, int BK, bool AVEC, bool BVEC>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void gemm_kernel(const GemmBatch batch) {
+  __shared__ __align__(16) float smem[gemm_lds_floats<BM, BN, BK>()];
+  gemm_tile<MODE, BM, BN, WM, WN, BK, AVEC, BVEC>(batch.p[blockIdx.z], blockIdx.x + gridDim.x * blockIdx.y,
+                                                  gridDim.x * gridDim.y, gridDim.x, smem);
+}
+
+// Weight gradient and input gradient of one layer in one launch (both read the same dZ and neither reads the
+// other's result): the workgroups of the second fill the CUs as those of the first drain, so one launch tail and
+// one output phase disappear.  Workgroups [0, nw) belong to the weight gradient (gw tiles x sw splits per
+// problem), the rest to the input gradient (gx tiles per problem).  16-byte operand paths only.
+template <int WBM, int WBN, int WWM, int WWN, int XBM, int XBN, int XWM, int XWN, int BK>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void gemm_pair_kernel(
+    const GemmBatch bw, const GemmBatch bx, const int gw, const int sw, const int gx) {
+  constexpr int LW = gemm_lds_floats<WBM, WBN, BK>(), LX = gemm_lds_floats<XBM, XBN, BK>();
+  __shared__ __align__(16) float smem[LW > LX ? LW : LX];
+  const int per_w = gw * sw;
+  const int nw = bw.count * per_w;
+  const int b = blockIdx.x;
+  if (b < nw) {
+    const int z = b / per_w;
+    gemm_tile<GEMM_DW, WBM, WBN, WWM, WWN, BK, true, true>(bw.p[z], b - z * per_w, per_w, gw, smem);
+  } else {
+    const int c = b - nw;
+    const int z = c / gx;
+    gemm_tile<GEMM_DX, XBM, XBN, XWM, XWN, BK, true, true>(bx.p[z], c - z * gx, gx, gx, smem);
+  }
+}
+
 template <int MODE, int BM, int BN, int WM, int WN, int BK = 16>
 static hipError_t launch_cfg(const GemmBatch& batch, hipStream_t stream) {
   int tiles = 0, splits = 1;
@@ -514,6 +546,59 @@ hipError_t launch_transpose(const TransposeBatch& b, hipStream_t stream) {
   TraceScope ts(stream, "transpose_weights", 0.0, 0.0);
   hipLaunchKernelGGL(transpose_kernel, dim3(tiles, 1, b.count), dim3(256), 0, stream, b);
   return hipGetLastError();
+}
+
+// Grid geometry of a batch for a tile shape and whether every problem may use the 16-byte operand paths.
+struct BatchGeom {
+  int tiles = 0, splits = 1;
+  bool vec = true;
+  double flops = 0.0;
+};
+
+static BatchGeom batch_geom(GemmMode mode, const GemmBatch& batch, int BM, int BN) {
+  BatchGeom g;
+  for (int i = 0; i < batch.count; ++i) {
+    const GemmProblem& P = batch.p[i];
+    const int t = ((P.M + BM - 1) / BM) * ((P.N + BN - 1) / BN);
+    g.tiles = t > g.tiles ? t : g.tiles;
+    if (mode == GEMM_DW) g.splits = P.n_split > g.splits ? P.n_split : g.splits;
+    const int64_t lim = (int64_t)1 << 32;
+    const int64_t a_rows = P.row_idx != nullptr ? P.a_src_rows : (mode == GEMM_DW ? P.K : P.M);
+    g.vec = g.vec && P.a_vec != 0 && P.b_vec != 0 && a_rows > 0 && a_rows * (int64_t)P.lda < lim &&
+            (int64_t)P.K * P.ldb < lim;
+    g.flops += 2.0 * P.M * (double)P.N * P.K;
+  }
+  return g;
+}
+
+template <int WBM, int WBN, int WWM, int WWN, int XBM, int XBN, int XWM, int XWN>
+static hipError_t launch_pair_cfg(const GemmBatch& bw, const GemmBatch& bx, const BatchGeom& gw, const BatchGeom& gx,
+                                  hipStream_t stream) {
+  char name[48];
+  snprintf(name, sizeof name, "gemm_dwdx_%dx%d_%dx%d", WBM, WBN, XBM, XBN);
+  TraceScope ts(stream, name, gw.flops + gx.flops, 0.0);
+  const int blocks = bw.count * gw.tiles * gw.splits + bx.count * gx.tiles;
+  hipLaunchKernelGGL((gemm_pair_kernel<WBM, WBN, WWM, WWN, XBM, XBN, XWM, XWN, 16>), dim3(blocks), dim3(NT), 0, stream,
+                     bw, bx, gw.tiles, gw.splits, gx.tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_dw_dx(const GemmBatch& bw, const GemmBatch& bx, hipStream_t stream) {
+  const TileCfg tw = pick_tile(GEMM_DW, bw), tx = pick_tile(GEMM_DX, bx);
+  const bool w_ok = tw == TILE_128x128 || tw == TILE_64x128, x_ok = tx == TILE_128x128 || tx == TILE_64x128;
+  if (w_ok && x_ok && bw.count > 0 && bx.count > 0) {
+    const BatchGeom gw = batch_geom(GEMM_DW, bw, tw == TILE_128x128 ? 128 : 64, 128);
+    const BatchGeom gx = batch_geom(GEMM_DX, bx, tx == TILE_128x128 ? 128 : 64, 128);
+    if (gw.vec && gx.vec && gw.tiles > 0 && gx.tiles > 0) {
+      if (tw == TILE_128x128 && tx == TILE_128x128) return launch_pair_cfg<128, 128, 2, 2, 128, 128, 2, 2>(bw, bx, gw, gx, stream);
+      if (tw == TILE_128x128) return launch_pair_cfg<128, 128, 2, 2, 64, 128, 1, 4>(bw, bx, gw, gx, stream);
+      if (tx == TILE_128x128) return launch_pair_cfg<64, 128, 1, 4, 128, 128, 2, 2>(bw, bx, gw, gx, stream);
+      return launch_pair_cfg<64, 128, 1, 4, 64, 128, 1, 4>(bw, bx, gw, gx, stream);
+    }
+  }
+  hipError_t e = launch_gemm(GEMM_DW, bw, stream);
+  if (e != hipSuccess) return e;
+  return launch_gemm(GEMM_DX, bx, stream);
 }
 
 hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream) {

@@ -63,6 +63,8 @@ struct GemmBatch {
 };
 
 hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream);
+// Weight gradient (bw) and input gradient (bx) of one layer; one launch when both fit the paired kernel.
+hipError_t launch_gemm_dw_dx(const GemmBatch& bw, const GemmBatch& bx, hipStream_t stream);
 // Out-of-place transposes of up to 16 row-major matrices in one launch: dst[c, r] = src[r, c].
 struct TransposeJob { const float* src; float* dst; int32_t rows, cols; };
 struct TransposeBatch { TransposeJob job[16]; int32_t count; };
