@@ -657,7 +657,6 @@ int32_t ppo_validate(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_r
   return RSLX_OK;
 }
 
-// reduce split partials of one network into grads (weights and biases only) + squared-norm blocks
 // Appends one network's layers to a reduce launch; the network's sumsq blocks must start at entry a.blocks of
 // a.sumsq_blocks.
 void reduce_add_net(ReduceArgs& a, const rslx_mlp& n, const TrainBufs& t) {
