@@ -15,7 +15,7 @@ import pytest
 import torch
 
 from oracle import ppo as oppo, bc as obc
-from workloads import WORKLOADS, make_inputs
+from workloads import WORKLOADS, make_inputs, xavier_mlp
 from gpu_util import dev, host, rel_l2, oracle_rollout, flat_rollout, oracle_cfg, f32
 
 pytestmark = pytest.mark.gpu
@@ -57,9 +57,15 @@ def _check_stats(got, want, tol, floor=1e-3):
 class Case:
     """One workload: seeded inputs, the oracle's rollout and its recorded update trajectory."""
 
-    def __init__(self, w, epochs, sym_on=False, rnd_on=False, seed=3, call_index=1, perturb=0.0):
+    def __init__(self, w, epochs, sym_on=False, rnd_on=False, seed=3, call_index=1, perturb=0.0, rnd_subset=0):
         self.w, self.epochs, self.sym_on, self.rnd_on, self.seed, self.call_index = w, epochs, sym_on, rnd_on, seed, call_index
         inp = self.inp = make_inputs(w)
+        self.rnd_dims, self.rnd_sub = w.dims_rnd if rnd_on else None, None
+        if rnd_on and rnd_subset:      # RND nets that read a strict subset of the observation columns
+            g = np.random.default_rng(11)
+            self.rnd_sub = np.sort(g.choice(w.Da, size=rnd_subset, replace=False)).astype(np.int32)
+            self.rnd_dims = (rnd_subset,) + tuple(w.dims_rnd[1:])
+            inp["rnd_target"], inp["rnd_predictor"] = xavier_mlp(g, self.rnd_dims), xavier_mlp(g, self.rnd_dims)
         self.flat = flat_rollout(w, inp, oracle_rollout(w, inp))
         self.actor0, self.critic0 = inp["actor"].copy(), inp["critic"].copy()
         if perturb:      # start the update away from the collecting policy: ratio != 1, clipping active from step one
@@ -76,7 +82,7 @@ class Case:
         ornd = None
         if rnd_on:
             npred = inp["rnd_predictor"].size
-            ornd = dict(pred=inp["rnd_predictor"], targ=inp["rnd_target"], dims=w.dims_rnd, subset=None,
+            ornd = dict(pred=inp["rnd_predictor"], targ=inp["rnd_target"], dims=self.rnd_dims, subset=self.rnd_sub,
                         m=np.zeros(npred), v=np.zeros(npred), step=0, lr=f32(w.lr))
         self.ref = oppo.ppo_update(self.actor0, self.critic0, w.dims_actor, w.dims_critic, self.flat, self.ocfg, opt0,
                                    self.osym, ornd, record=True)
@@ -111,10 +117,11 @@ def _nets(rx, case, actor, critic, opt=None, rnd_state=None):
     rnd = None
     if case.rnd_on:
         st = rnd_state if rnd_state is not None else dict(pred=case.inp["rnd_predictor"], m=None, v=None, step=0)
-        pred = rx.Mlp(w.dims_rnd, dev(st["pred"], torch.float32), trainable=True)
+        pred = rx.Mlp(case.rnd_dims, dev(st["pred"], torch.float32), trainable=True)
         if st["m"] is not None:
             pred.adam_m, pred.adam_v = dev(st["m"], torch.float32), dev(st["v"], torch.float32)
-        rnd = rx.RndTrain(rx.Mlp(w.dims_rnd, dev(case.inp["rnd_target"])), pred, lr=w.lr, adam_step=st["step"])
+        rnd = rx.RndTrain(rx.Mlp(case.rnd_dims, dev(case.inp["rnd_target"])), pred,
+                          subset_idx=None if case.rnd_sub is None else dev(case.rnd_sub), lr=w.lr, adam_step=st["step"])
     return a, c, rnd
 
 
@@ -145,7 +152,7 @@ def check_forced_steps(rx, case, steps=None):
         d_got = host(a.params).astype(np.float64) - np.float32(b["actor"])
         assert rel_l2(d_got, tr["actor"] - b["actor"]) <= 5e-2
         if case.rnd_on:
-            _check_vec("g_pred", w.dims_rnd, False, host(rnd.predictor.grads), tr["g_pred"], TOL)
+            _check_vec("g_pred", case.rnd_dims, False, host(rnd.predictor.grads), tr["g_pred"], TOL)
             assert rel_l2(host(rnd.predictor.params), tr["pred"]) <= TOL
             assert rnd.step.value == b["rnd"]["step"] + 1
 
@@ -219,6 +226,14 @@ def test_ppo_curiosity_rnd(rx):
     case = Case(replace(WORKLOADS["curiosity"].scaled(336), minibatches=8), 1, rnd_on=True)
     check_forced_steps(rx, case)
     check_free_running(rx, case)
+
+
+def test_ppo_curiosity_rnd_state_subset(rx):
+    """The RND networks read 20 of the 48 observation columns (strict subset): the column map rides in the first
+    layer's operand loads of the forward and of the weight-gradient contraction."""
+    case = Case(replace(WORKLOADS["curiosity"].scaled(168), minibatches=4), 1, rnd_on=True, rnd_subset=20)
+    check_forced_steps(rx, case)
+    check_free_running(rx, case, param_tol=1e-3, grad_tol=0.25)
 
 
 def test_ppo_five_epoch_drift_is_bounded(rx):
