@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--workload", default="flat")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-trace", action="store_true", help="skip the per-launch HIP-event trace (no roofline entry)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same iteration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (how the path would shard is described in DESIGN.md)")
@@ -136,6 +137,37 @@ def main():
         torch.cuda.synchronize()
         traced_ms = (time.perf_counter() - t2) * 1e3 / args.steps
         trace = rx.rslx_trace_end()
+    # the same iteration recorded once as a HIP graph (entry points on device-resident counters) and replayed K times
+    graph_ms = None
+    if not args.no_graph:
+        ctr = rx.dev_counters(act_step=(args.warmup + 2 * args.steps) * T, call_index=args.warmup + 2 * args.steps,
+                              adam_step=adam_step.value, rnd_adam_step=rnd.step.value if rnd else 0)
+
+        def step_dc():
+            rew = rewards
+            if w.rnd:
+                rew_work.copy_(rewards)
+                rew = rew_work
+            for t in range(T):
+                rx.rslx_act_dc(actor, critic, obs[t], obs[t], N, 20250910, ctr, None, actions[t], logp[t], values[t],
+                               mu[t], sigma[t], 0, aws)
+                if w.rnd:
+                    rx.rslx_rnd(rnd_t, rnd_p, obs[t], N, w.Da, None, w.Da, running, w.rnd_weight, 1, r_int, rew[t], rws)
+            rx.rslx_act_dc(None, critic, None, obs[T], N, 0, ctr, None, None, None, last, None, None, rx.ACT_VALUES_ONLY, aws)
+            rx.rslx_gae(rew, values, last, dones, None, T, N, w.gamma, w.lam, 1, adv, ret, gws)
+            rx.rslx_ppo_update_dc(actor, critic, rollout, rx.PpoCfg(**cfg_kw), sym, rnd, ctr, stats, uws)
+
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step_dc()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t3) * 1e3 / args.steps
     med = {k: float(np.median(v)) for k, v in phase.items()}
     assert torch.isfinite(actor.params).all() and torch.isfinite(stats).all(), "training state became non-finite"
 
@@ -173,6 +205,8 @@ def main():
         "act_env_steps_per_s": round((T + 1) * N / (med["act"] * 1e-3), 1),
         "phase_ms": {k: round(v, 4) for k, v in med.items()},
         "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
+        "graph_replay": None if graph_ms is None else {"ms_per_step": round(graph_ms, 4),
+                                                       "value": round(B / (graph_ms * 1e-3), 1)},
         "roofline": roofline,
         "kernels": breakdown,
     }

@@ -238,6 +238,37 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
                         const rslx_rnd_train* rnd_or_null, int64_t* adam_step, float* stats,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* ---- replayable variants: call-to-call counters in device memory ----------------------- */
+
+/* The iteration of paper Sec. 3 (T x act, advantage estimation, update) is a fixed sequence of
+ * launches; a caller that records it once (HIP graph) and replays it needs every value that
+ * changes between iterations to live in device memory.  rslx_dev_counters (device, 32 bytes)
+ * holds them; the *_dc entry points read it in their kernels and advance it with a kernel of
+ * their own, so host arguments are the same for every replay:
+ *   act_step       noise stream position: rslx_act_dc draws with step = act_step, then act_step += 1
+ *                  (not with RSLX_ACT_VALUES_ONLY, which draws nothing)
+ *   call_index     permutation stream of rslx_ppo_update_dc (cfg->call_index is ignored), += 1 per call
+ *   adam_step      optimiser steps of actor + critic so far, += epochs * minibatches per call
+ *   rnd_adam_step  the same for the RND predictor (rnd->adam_step is ignored)
+ * Everything else is as in rslx_act / rslx_ppo_update; the bias corrections 1 - beta^t are formed
+ * in fp64 on the device.  The caller initialises the struct (e.g. zeros) and must not run two
+ * calls that share it concurrently. */
+typedef struct rslx_dev_counters {
+  int64_t act_step;
+  uint64_t call_index;
+  int64_t adam_step;
+  int64_t rnd_adam_step;
+} rslx_dev_counters;
+
+int32_t rslx_act_dc(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor,
+                    const float* obs_critic, int32_t N, uint64_t seed, rslx_dev_counters* counters,
+                    const float* eps_or_null, float* actions, float* logp, float* values, float* mu,
+                    float* sigma, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+int32_t rslx_ppo_update_dc(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* ro,
+                           const rslx_ppo_cfg* cfg, const rslx_sym* sym_or_null,
+                           const rslx_rnd_train* rnd_or_null, rslx_dev_counters* counters,
+                           float* stats, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- behaviour cloning update (paper Sec. 2.1) ---------------------------------------- */
 
 /* targets = teacher(obs_teacher) (once; or the caller's precomputed `targets_or_null` [B, A]);

@@ -11,6 +11,7 @@ __all__ = [
     "rslx_adam_step", "rslx_adam_workspace_bytes", "rslx_ppo_update", "rslx_ppo_update_workspace_bytes",
     "rslx_bc_update", "rslx_bc_update_workspace_bytes", "rslx_sym_augment", "rslx_rnd", "rslx_rnd_workspace_bytes",
     "ACT_DETERMINISTIC", "ACT_VALUES_ONLY", "EXPORTS", "rslx_trace_begin", "rslx_trace_end",
+    "dev_counters", "rslx_act_dc", "rslx_ppo_update_dc",
 ]
 
 MAX_LAYERS = 8
@@ -23,6 +24,7 @@ EXPORTS = [
     "rslx_act_workspace_bytes", "rslx_act", "rslx_gae_workspace_bytes", "rslx_gae", "rslx_adam_workspace_bytes",
     "rslx_adam_step", "rslx_ppo_update_workspace_bytes", "rslx_ppo_update", "rslx_bc_update_workspace_bytes",
     "rslx_bc_update", "rslx_sym_augment", "rslx_rnd_workspace_bytes", "rslx_rnd", "rslx_trace_begin", "rslx_trace_end",
+    "rslx_act_dc", "rslx_ppo_update_dc",
 ]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librslx.so")
@@ -97,6 +99,8 @@ _sig("rslx_permutation", C.c_int32, [C.c_uint64, C.c_uint64, C.c_int32, C.c_int3
 _sig("rslx_act_workspace_bytes", C.c_size_t, [_P(_CMlp), _P(_CMlp), C.c_int32])
 _sig("rslx_act", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, C.c_int32, C.c_uint64, C.c_uint64, _vp, _vp, _vp, _vp, _vp,
                              _vp, C.c_uint32, _vp, C.c_size_t, _vp])
+_sig("rslx_act_dc", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, C.c_int32, C.c_uint64, _vp, _vp, _vp, _vp, _vp, _vp,
+                                _vp, C.c_uint32, _vp, C.c_size_t, _vp])
 _sig("rslx_gae_workspace_bytes", C.c_size_t, [C.c_int32, C.c_int32])
 _sig("rslx_gae", C.c_int32, [_vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_int32, _vp, _vp,
                              _vp, C.c_size_t, _vp])
@@ -106,6 +110,8 @@ _sig("rslx_adam_step", C.c_int32, [_vp, _vp, _vp, _vp, C.c_int64, C.c_float, C.c
 _sig("rslx_ppo_update_workspace_bytes", C.c_size_t, [_P(_CMlp), _P(_CMlp), _P(_CRollout), _P(_CPpoCfg), _P(_CSym), _P(_CRndTrain)])
 _sig("rslx_ppo_update", C.c_int32, [_P(_CMlp), _P(_CMlp), _P(_CRollout), _P(_CPpoCfg), _P(_CSym), _P(_CRndTrain),
                                     _P(C.c_int64), _vp, _vp, C.c_size_t, _vp])
+_sig("rslx_ppo_update_dc", C.c_int32, [_P(_CMlp), _P(_CMlp), _P(_CRollout), _P(_CPpoCfg), _P(_CSym), _P(_CRndTrain),
+                                       _vp, _vp, _vp, C.c_size_t, _vp])
 _sig("rslx_bc_update_workspace_bytes", C.c_size_t, [_P(_CMlp), _P(_CMlp), C.c_int32, _P(_CBcCfg)])
 _sig("rslx_bc_update", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, _vp, C.c_int32, _P(_CBcCfg), _P(C.c_int64), _vp, _vp,
                                    C.c_size_t, _vp])
@@ -265,6 +271,20 @@ def rslx_act(actor, critic, obs_actor, obs_critic, N, seed, step, eps, actions, 
                         _ptr(logp), _ptr(values), _ptr(mu), _ptr(sigma), flags, _ptr(ws), ws.numel(), _stream()), "rslx_act")
 
 
+def dev_counters(act_step=0, call_index=0, adam_step=0, rnd_adam_step=0, device="cuda"):
+    """rslx_dev_counters in device memory: int64 tensor [act_step, call_index, adam_step, rnd_adam_step]."""
+    return torch.tensor([act_step, call_index, adam_step, rnd_adam_step], dtype=torch.int64, device=device)
+
+
+def rslx_act_dc(actor, critic, obs_actor, obs_critic, N, seed, counters, eps, actions, logp, values, mu, sigma, flags, ws):
+    """counters: int64 device tensor of 4 (dev_counters())."""
+    ca = actor.c if actor is not None else None
+    cc = critic.c
+    _check(lib.rslx_act_dc(_ref(ca), _ref(cc), _ptr(obs_actor), _ptr(obs_critic), N, seed, _ptr(counters), _ptr(eps),
+                           _ptr(actions), _ptr(logp), _ptr(values), _ptr(mu), _ptr(sigma), flags, _ptr(ws), ws.numel(),
+                           _stream()), "rslx_act_dc")
+
+
 def rslx_gae_workspace_bytes(T, N):
     return lib.rslx_gae_workspace_bytes(T, N)
 
@@ -302,6 +322,15 @@ def rslx_ppo_update(actor, critic, rollout, cfg, sym, rnd, adam_step, stats, ws)
     cn = rnd.c() if rnd is not None else None
     _check(lib.rslx_ppo_update(_ref(ca), _ref(cc), _ref(cr), _ref(cfg.c), _ref(cs), _ref(cn), C.byref(adam_step),
                                _ptr(stats), _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "rslx_ppo_update")
+
+
+def rslx_ppo_update_dc(actor, critic, rollout, cfg, sym, rnd, counters, stats, ws):
+    """counters: int64 device tensor of 4 (dev_counters()), advanced by the call's own kernels."""
+    ca, cc, cr = actor.c, critic.c, rollout.c
+    cs = sym.c if sym is not None else None
+    cn = rnd.c() if rnd is not None else None
+    _check(lib.rslx_ppo_update_dc(_ref(ca), _ref(cc), _ref(cr), _ref(cfg.c), _ref(cs), _ref(cn), _ptr(counters),
+                                  _ptr(stats), _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "rslx_ppo_update_dc")
 
 
 def rslx_bc_update_workspace_bytes(student, teacher, B, cfg):

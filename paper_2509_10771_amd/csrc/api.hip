@@ -433,10 +433,23 @@ size_t rslx_act_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* critic, i
   return act_carve(c, actor, critic, N, nullptr, nullptr);
 }
 
-int32_t rslx_act(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
-                 int32_t N, uint64_t seed, uint64_t step, const float* eps_or_null, float* actions, float* logp,
-                 float* values, float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+static_assert(sizeof(rslx_dev_counters) == 4 * sizeof(int64_t), "rslx_dev_counters is four 64-bit words");
+hipError_t advance_counters(rslx_dev_counters* c, int64_t act, int64_t call, int64_t adam, int64_t rnd, hipStream_t s) {
+  const int64_t d[4] = {act, call, adam, rnd};
+  return launch_counter_add(reinterpret_cast<int64_t*>(c), d, 4, s);
+}
+
+// Shared body of rslx_act and rslx_act_dc: with `counters` the noise position comes from device memory.
+int32_t act_impl(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
+                 int32_t N, uint64_t seed, uint64_t step, rslx_dev_counters* counters, const float* eps_or_null,
+                 float* actions, float* logp, float* values, float* mu, float* sigma, uint32_t flags, void* ws,
+                 size_t ws_bytes, void* stream) {
   const bool values_only = (flags & RSLX_ACT_VALUES_ONLY) != 0;
+  const int64_t* step_dev = counters ? &counters->act_step : nullptr;
+  const uint64_t noise_pre = mix64_host(seed ^ 0xAC7ull);
   if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_act: N = %d", N);
   RSLX_TRY(check_mlp(critic, "rslx_act critic", false));
   if (critic->dims[critic->n_layers] != 1) return fail(RSLX_ERR_SHAPE, "rslx_act: critic output width must be 1");
@@ -464,10 +477,12 @@ int32_t rslx_act(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs
     fa.net[fa.n_nets++] = fused_net(*critic, obs_critic, critic->dims[0], nullptr, values, false);
     fa.deterministic = (flags & RSLX_ACT_DETERMINISTIC) ? 1 : 0;
     fa.eps = eps_or_null;
-    fa.noise_base = mix64_host(mix64_host(seed ^ 0xAC7ull) ^ step);
+    fa.noise_base = mix64_host(noise_pre ^ step);
+    fa.step_dev = step_dev; fa.noise_pre = noise_pre;
     fa.actions = actions; fa.logp = logp; fa.sigma = sigma;
     if (fused_forward_supported(fa)) {
       RSLX_HIP(launch_fused_forward(fa, s));
+      if (counters && !values_only) RSLX_HIP(advance_counters(counters, 1, 0, 0, 0, s));
       return RSLX_OK;
     }
   }
@@ -488,11 +503,31 @@ int32_t rslx_act(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs
   RSLX_TRY(forward_nets(jobs, nj, s));
   if (a) {
     const int A = a->dims[a->n_layers];
-    const uint64_t base = mix64_host(mix64_host(seed ^ 0xAC7ull) ^ step);
+    const uint64_t base = mix64_host(noise_pre ^ step);
     RSLX_HIP(launch_act_head(mu, a->params + weight_count(*a), eps_or_null, base, N, A,
-                             (flags & RSLX_ACT_DETERMINISTIC) ? 1 : 0, actions, logp, mu, sigma, s));
+                             (flags & RSLX_ACT_DETERMINISTIC) ? 1 : 0, actions, logp, mu, sigma, s, step_dev, noise_pre));
+    if (counters) RSLX_HIP(advance_counters(counters, 1, 0, 0, 0, s));
   }
   return RSLX_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t rslx_act(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
+                 int32_t N, uint64_t seed, uint64_t step, const float* eps_or_null, float* actions, float* logp,
+                 float* values, float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+  return act_impl(actor, critic, obs_actor, obs_critic, N, seed, step, nullptr, eps_or_null, actions, logp, values, mu,
+                  sigma, flags, ws, ws_bytes, stream);
+}
+
+int32_t rslx_act_dc(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
+                    int32_t N, uint64_t seed, rslx_dev_counters* counters, const float* eps_or_null, float* actions,
+                    float* logp, float* values, float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes,
+                    void* stream) {
+  if (!counters) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_dc: null counters");
+  return act_impl(actor, critic, obs_actor, obs_critic, N, seed, 0, counters, eps_or_null, actions, logp, values, mu,
+                  sigma, flags, ws, ws_bytes, stream);
 }
 
 // ---- GAE -----------------------------------------------------------------------------------------------------
@@ -652,7 +687,6 @@ int32_t ppo_validate(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_r
       if (rnd->target->dims[i] != rnd->predictor->dims[i]) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: rnd nets differ in shape");
     if (rnd->n_subset != rnd->target->dims[0] || (!rnd->subset_idx && rnd->n_subset != ro->Da))
       return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: rnd subset width");
-    if (need_buffers && !rnd->adam_step) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: rnd adam_step null");
   }
   return RSLX_OK;
 }
@@ -692,11 +726,20 @@ size_t rslx_ppo_update_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* cr
   return p.bytes;
 }
 
-int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
-                        const rslx_sym* sym, const rslx_rnd_train* rnd, int64_t* adam_step, float* stats, void* ws,
-                        size_t ws_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// Shared body of rslx_ppo_update and rslx_ppo_update_dc: with `counters` the permutation stream index and the
+// optimiser step counts are read from device memory by the kernels and advanced at the end of the call.
+int32_t ppo_update_impl(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
+                        const rslx_sym* sym, const rslx_rnd_train* rnd, int64_t* adam_step, rslx_dev_counters* counters,
+                        float* stats, void* ws, size_t ws_bytes, void* stream) {
   RSLX_TRY(ppo_validate(actor, critic, ro, cfg, sym, rnd, true));
-  if (!adam_step || !stats) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null adam_step or stats");
+  if ((!adam_step && !counters) || !stats) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null adam_step or stats");
+  int64_t host_step = 0, host_rnd_step = 0;      // stand-ins for the host counters in the device-counter variant
+  if (counters) adam_step = &host_step;
+  int64_t* rnd_step = rnd ? (counters ? &host_rnd_step : rnd->adam_step) : nullptr;
+  if (rnd && !rnd_step) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: rnd adam_step null");
   hipStream_t s = (hipStream_t)stream;
   Carver c(ws);
   PpoPlan p;
@@ -708,7 +751,8 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
     std::vector<uint64_t> bases(cfg->epochs);
     for (int e = 0; e < cfg->epochs; ++e)
       bases[e] = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
-    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, p.B, p.perms, p.perm_ws, s));
+    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, p.B, p.perms, p.perm_ws, s, mix64_host(cfg->seed),
+                                 counters ? &counters->call_index : nullptr, cfg->epoch_offset));
   }
 
   for (int e = 0; e < cfg->epochs; ++e) {
@@ -784,6 +828,7 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
       aa.max_grad_norm = cfg->max_grad_norm;
       aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;
       aa.bc1 = bias_correction(cfg->beta1, t); aa.bc2 = bias_correction(cfg->beta2, t);
+      if (counters) { aa.step_dev = &counters->adam_step; aa.step_off = (int32_t)t; }
       aa.grad_norm_out = stats_row + RSLX_STAT_GRAD_NORM;
       RSLX_HIP(launch_adam(aa, s));
       *adam_step = t;
@@ -803,7 +848,7 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
         BwdJob rb{&pr, xr, p.mb, &p.pred.act, p.pred.d_out, p.pred.wt, p.pred.partials, &p.pred.plan};
         RSLX_TRY(backward_nets(&rb, 1, s));
         RSLX_TRY(reduce_net(pr, p.pred, s));
-        const int64_t tr = *rnd->adam_step + 1;
+        const int64_t tr = *rnd_step + 1;
         AdamArgs ar;
         memset(&ar, 0, sizeof ar);
         ar.seg[0] = AdamSegment{pr.params, pr.grads, pr.adam_m, pr.adam_v, param_count(pr)};
@@ -812,12 +857,31 @@ int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
         ar.max_grad_norm = 0.f;
         ar.lr = rnd->lr; ar.beta1 = cfg->beta1; ar.beta2 = cfg->beta2; ar.eps = cfg->adam_eps;
         ar.bc1 = bias_correction(cfg->beta1, tr); ar.bc2 = bias_correction(cfg->beta2, tr);
+        if (counters) { ar.step_dev = &counters->rnd_adam_step; ar.step_off = (int32_t)tr; }
         RSLX_HIP(launch_adam(ar, s));
-        *rnd->adam_step = tr;
+        *rnd_step = tr;
       }
     }
   }
+  if (counters) RSLX_HIP(advance_counters(counters, 0, 1, host_step, host_rnd_step, s));
   return RSLX_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t rslx_ppo_update(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
+                        const rslx_sym* sym, const rslx_rnd_train* rnd, int64_t* adam_step, float* stats, void* ws,
+                        size_t ws_bytes, void* stream) {
+  if (!adam_step) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null adam_step or stats");
+  return ppo_update_impl(actor, critic, ro, cfg, sym, rnd, adam_step, nullptr, stats, ws, ws_bytes, stream);
+}
+
+int32_t rslx_ppo_update_dc(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
+                           const rslx_sym* sym, const rslx_rnd_train* rnd, rslx_dev_counters* counters, float* stats,
+                           void* ws, size_t ws_bytes, void* stream) {
+  if (!counters) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_dc: null counters");
+  return ppo_update_impl(actor, critic, ro, cfg, sym, rnd, nullptr, counters, stats, ws, ws_bytes, stream);
 }
 
 // ---- behaviour cloning ---------------------------------------------------------------------------------------------

@@ -171,7 +171,16 @@ __device__ __forceinline__ int bucket_of(uint64_t key, int shift) { return shift
 
 // All kernels below process up to PERM_BATCH permutations (epochs) per launch: blockIdx.y selects the epoch,
 // whose scratch arrays sit `*_stride` elements apart.
-struct PermBases { uint64_t base[PERM_BATCH]; };
+struct PermBases {
+  uint64_t base[PERM_BATCH];
+  uint64_t seed_mixed;           // with call_dev: base of entry e = mix64(mix64(seed_mixed ^ *call_dev) ^ epoch[e])
+  const uint64_t* call_dev;
+  int32_t epoch[PERM_BATCH];
+};
+__device__ __forceinline__ uint64_t perm_base(const PermBases& pb, int e) {
+  if (pb.call_dev == nullptr) return pb.base[e];
+  return mix64(mix64(pb.seed_mixed ^ *pb.call_dev) ^ (uint64_t)pb.epoch[e]);
+}
 
 __global__ void perm_zero_kernel(int* counts, int n, long stride) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -179,7 +188,7 @@ __global__ void perm_zero_kernel(int* counts, int n, long stride) {
 }
 __global__ void perm_hist_kernel(const PermBases pb, int B, int shift, int* counts, long stride) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B) atomicAdd(&counts[blockIdx.y * stride + bucket_of(mix64(pb.base[blockIdx.y] ^ (uint64_t)i), shift)], 1);
+  if (i < B) atomicAdd(&counts[blockIdx.y * stride + bucket_of(mix64(perm_base(pb, blockIdx.y) ^ (uint64_t)i), shift)], 1);
 }
 // Exclusive scan of counts[0..nb) by one workgroup per epoch; offsets has nb + 1 entries; cursors are reset.
 __global__ __launch_bounds__(1024) void perm_scan_kernel(const int* counts_all, int nb, int* offsets_all, int* cursor_all,
@@ -221,7 +230,7 @@ __global__ void perm_scatter_kernel(const PermBases pb, int B, int shift, const 
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B) return;
   const int e = blockIdx.y;
-  uint64_t k = mix64(pb.base[e] ^ (uint64_t)i);
+  uint64_t k = mix64(perm_base(pb, e) ^ (uint64_t)i);
   int b = bucket_of(k, shift);
   int pos = offsets[e * stride + b] + atomicAdd(&cursor[e * stride + b], 1);
   keys[e * kstride + pos] = k;
@@ -257,7 +266,7 @@ size_t perm_workspace_bytes(int32_t B) {
 }
 
 hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_t B, int32_t* perm_out, void* ws,
-                               hipStream_t stream) {
+                               hipStream_t stream, uint64_t seed_mixed, const uint64_t* call_index_dev, int32_t epoch0) {
   if (B <= 0 || n_perm <= 0) return hipSuccess;
   TraceScope ts(stream, "permutation", 0.0, 0.0);
   PermPlan p = perm_plan(B);
@@ -274,7 +283,12 @@ hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_
   for (int e0 = 0; e0 < n_perm; e0 += PERM_BATCH) {
     const int ne = n_perm - e0 < PERM_BATCH ? n_perm - e0 : PERM_BATCH;
     PermBases pb;
-    for (int e = 0; e < PERM_BATCH; ++e) pb.base[e] = e < ne ? base_keys[e0 + e] : 0;
+    pb.seed_mixed = seed_mixed;
+    pb.call_dev = call_index_dev;
+    for (int e = 0; e < PERM_BATCH; ++e) {
+      pb.base[e] = (e < ne && call_index_dev == nullptr) ? base_keys[e0 + e] : 0;
+      pb.epoch[e] = epoch0 + e0 + e;
+    }
     int32_t* out = perm_out + (size_t)e0 * B;
     hipLaunchKernelGGL(perm_zero_kernel, dim3((p.nb + 256) / 256, ne), dim3(256), 0, stream, counts, p.nb + 1, stride);
     hipLaunchKernelGGL(perm_hist_kernel, dim3(gb, ne), dim3(256), 0, stream, pb, B, p.shift, counts, stride);
@@ -407,11 +421,18 @@ hipError_t launch_sumsq(const float* g, int64_t n, double* sumsq_blocks, hipStre
 // scale is identical everywhere and no extra launch or atomic is needed.
 __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
   __shared__ double smem[4];
-  __shared__ float s_scale;
+  __shared__ float s_scale, s_bc1, s_bc2;
   double q = 0.0;
   for (int i = threadIdx.x; i < a.n_sumsq; i += 256) q += a.sumsq_blocks[i];
   double tot = block_sum(q, smem);
   if (threadIdx.x == 0) {
+    float bc1 = a.bc1, bc2 = a.bc2;
+    if (a.step_dev != nullptr) {          // step counter in device memory: bias corrections formed here
+      const double t = (double)(*a.step_dev + a.step_off);
+      bc1 = (float)(1.0 - pow((double)a.beta1, t));
+      bc2 = (float)(1.0 - pow((double)a.beta2, t));
+    }
+    s_bc1 = bc1; s_bc2 = bc2;
     float norm = (float)sqrt(tot);
     float s = 1.0f;
     if (a.max_grad_norm > 0.f && a.max_grad_norm < 3.0e38f) s = fminf(1.0f, a.max_grad_norm / (norm + 1e-6f));
@@ -422,7 +443,7 @@ __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
   const float scale = s_scale;
   const AdamSegment& sg = a.seg[blockIdx.y];
   const float ob1 = 1.0f - a.beta1, ob2 = 1.0f - a.beta2;
-  const float inv_bc1 = 1.0f / a.bc1, inv_bc2 = 1.0f / a.bc2;
+  const float inv_bc1 = 1.0f / s_bc1, inv_bc2 = 1.0f / s_bc2;
   const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i0 >= sg.n) return;
   if (i0 + 3 < sg.n) {
@@ -488,9 +509,11 @@ __global__ __launch_bounds__(256) void act_head_kernel(const float* __restrict__
                                                        const float* __restrict__ eps_in, uint64_t noise_base, int N,
                                                        int A, int deterministic, float* __restrict__ actions,
                                                        float* __restrict__ logp, float* __restrict__ mu_out,
-                                                       float* __restrict__ sigma_out) {
+                                                       float* __restrict__ sigma_out, const int64_t* __restrict__ step_dev,
+                                                       uint64_t noise_pre) {
   const int n = blockIdx.x * 256 + threadIdx.x;
   if (n >= N) return;
+  if (step_dev != nullptr) noise_base = mix64(noise_pre ^ (uint64_t)*step_dev);
   float acc = 0.f, sum_ls = 0.f;
   for (int jj = 0; jj < A; ++jj) {
     const long o = (long)n * A + jj;
@@ -521,9 +544,21 @@ __global__ __launch_bounds__(256) void act_head_kernel(const float* __restrict__
 
 hipError_t launch_act_head(const float* mu_in, const float* log_std, const float* eps, uint64_t noise_base, int32_t N,
                            int32_t A, int32_t deterministic, float* actions, float* logp, float* mu_out,
-                           float* sigma_out, hipStream_t stream) {
+                           float* sigma_out, hipStream_t stream, const int64_t* step_dev, uint64_t noise_pre) {
   hipLaunchKernelGGL(act_head_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, mu_in, log_std, eps, noise_base, N, A,
-                     deterministic, actions, logp, mu_out, sigma_out);
+                     deterministic, actions, logp, mu_out, sigma_out, step_dev, noise_pre);
+  return hipGetLastError();
+}
+
+// counters[i] += delta.d[i] for i < n: advances the call-to-call counters that live in device memory.
+struct CounterDeltas { int64_t d[4]; };
+__global__ void counter_add_kernel(int64_t* counters, CounterDeltas delta, int n) {
+  if (blockIdx.x == 0 && (int)threadIdx.x < n) counters[threadIdx.x] += delta.d[threadIdx.x];
+}
+hipError_t launch_counter_add(int64_t* counters, const int64_t* delta, int32_t n, hipStream_t stream) {
+  CounterDeltas cd{};
+  for (int i = 0; i < n && i < 4; ++i) cd.d[i] = delta[i];
+  hipLaunchKernelGGL(counter_add_kernel, dim3(1), dim3(64), 0, stream, counters, cd, n < 4 ? n : 4);
   return hipGetLastError();
 }
 

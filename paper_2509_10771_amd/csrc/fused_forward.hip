@@ -363,7 +363,8 @@ __global__ __launch_bounds__(FF_THREADS) void fused_forward_kernel(const FusedFo
         } else if (args.eps != nullptr) {
           eps = e == tid ? head_eps : args.eps[o];
         } else {
-          const uint64_t h = ff_mix64(args.noise_base ^ (uint64_t)o);
+          const uint64_t nb = args.step_dev != nullptr ? ff_mix64(args.noise_pre ^ (uint64_t)*args.step_dev) : args.noise_base;
+          const uint64_t h = ff_mix64(nb ^ (uint64_t)o);
           const float u1 = (float)((uint32_t)(h >> 40) + 1u) * 5.9604644775390625e-08f;
           const float u2 = (float)((uint32_t)(h >> 8) & 0xFFFFFFu) * 5.9604644775390625e-08f;
           eps = sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2);

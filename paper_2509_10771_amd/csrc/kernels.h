@@ -94,6 +94,8 @@ struct FusedForwardArgs {
   int32_t n_nets, n_rows, max_dim, deterministic;
   const float* eps;         // optional caller noise [n_rows, A]
   uint64_t noise_base;
+  const int64_t* step_dev;  // optional device counter: noise_base = mix64(noise_pre ^ *step_dev)
+  uint64_t noise_pre;
   float* actions; float* logp; float* sigma;
 };
 bool fused_forward_supported(const FusedForwardArgs& a);
@@ -111,8 +113,11 @@ hipError_t launch_gae(const float* rewards, const float* values, const float* la
 // Permutation by sorting 64-bit hash keys (bucket scatter + in-bucket ranking).
 size_t perm_workspace_bytes(int32_t B);
 // perm_out [n_perm, B]; base_keys (host) holds one hashed stream key per permutation.
+// call_index_dev != null: base_keys[e] is ignored and the key base of permutation e is
+// mix64(mix64(seed_mixed ^ *call_index_dev) ^ (epoch0 + e)), formed in the kernels.
 hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_t B, int32_t* perm_out, void* ws,
-                               hipStream_t stream);
+                               hipStream_t stream, uint64_t seed_mixed = 0, const uint64_t* call_index_dev = nullptr,
+                               int32_t epoch0 = 0);
 
 // Sum the split partials of one network's gradient, layer by layer, into the flat gradient buffer and emit
 // per-block sums of squares.  Layer l owns `split[l]` partial buffers of `size[l]` floats each, `pitch[l]` floats
@@ -160,7 +165,9 @@ struct AdamArgs {
   int32_t n_sumsq;
   float max_grad_norm;         // <= 0: no clipping
   float lr, beta1, beta2, eps;
-  float bc1, bc2;              // 1 - beta1^t, 1 - beta2^t
+  float bc1, bc2;              // 1 - beta1^t, 1 - beta2^t (used when step_dev is null)
+  const int64_t* step_dev;     // optional device counter: t = *step_dev + step_off, corrections formed in the kernel
+  int32_t step_off;
   float* grad_norm_out;        // optional device scalar (stats column)
 };
 // Lists longer than this are folded by an extra single-workgroup launch into the slot sumsq_blocks[n_sumsq],
@@ -169,9 +176,12 @@ constexpr int ADAM_MAX_INLINE_SUMSQ = 4096;
 hipError_t launch_adam(const AdamArgs& a, hipStream_t stream);
 
 // Gaussian head of act(): noise, action, log-density.
+// step_dev != null: the noise base is mix64(noise_pre ^ *step_dev) instead of noise_base.
 hipError_t launch_act_head(const float* mu_in, const float* log_std, const float* eps, uint64_t noise_base,
                            int32_t N, int32_t A, int32_t deterministic, float* actions, float* logp, float* mu_out,
-                           float* sigma_out, hipStream_t stream);
+                           float* sigma_out, hipStream_t stream, const int64_t* step_dev = nullptr, uint64_t noise_pre = 0);
+// counters[i] += delta[i] for i < n <= 4 (one small launch); for callers whose counters live in device memory.
+hipError_t launch_counter_add(int64_t* counters, const int64_t* delta, int32_t n, hipStream_t stream);
 hipError_t launch_copy_column(const float* src, int32_t n, float* dst, hipStream_t stream);
 
 // PPO loss head: per-row loss terms, d loss / d mu and d loss / d V, block partial sums.
