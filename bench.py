@@ -65,6 +65,8 @@ def main():
     actor = rx.Mlp(w.dims_actor, dev(inp["actor"]), trainable=True, has_log_std=True)
     critic = rx.Mlp(w.dims_critic, dev(inp["critic"]), trainable=True)
     obs, rewards, dones = dev(inp["obs"]), dev(inp["rewards"]), dev(inp["dones"])
+    timeouts = dev(inp["timeouts"]) if "timeouts" in inp else None
+    rnd_sub = dev(inp["rnd_subset_idx"]) if "rnd_subset_idx" in inp else None
     actions, mu, sigma = (torch.empty(T, N, A, device="cuda") for _ in range(3))
     logp, values, adv, ret = (torch.empty(T, N, device="cuda") for _ in range(4))
     last = torch.empty(N, device="cuda")
@@ -74,7 +76,7 @@ def main():
     if w.rnd:
         rnd_t = rx.Mlp(w.dims_rnd, dev(inp["rnd_target"]))
         rnd_p = rx.Mlp(w.dims_rnd, dev(inp["rnd_predictor"]), trainable=True)
-        rnd = rx.RndTrain(rnd_t, rnd_p, lr=w.lr)
+        rnd = rx.RndTrain(rnd_t, rnd_p, subset_idx=rnd_sub, lr=w.lr)
         running = dev(np.array([0.0, 1.0, 1e-4], np.float32))
         r_int = torch.empty(N, device="cuda")
         rws = rx.workspace(rx.rslx_rnd_workspace_bytes(rnd_t, N))
@@ -102,11 +104,11 @@ def main():
             rx.rslx_act(actor, critic, obs[t], obs[t], N, 20250910, it * T + t, None, actions[t], logp[t], values[t],
                         mu[t], sigma[t], 0, aws)
             if w.rnd:
-                rx.rslx_rnd(rnd_t, rnd_p, obs[t], N, w.Da, None, w.Da, running, w.rnd_weight, 1, r_int, rew[t], rws)
+                rx.rslx_rnd(rnd_t, rnd_p, obs[t], N, w.Da, rnd_sub, w.dims_rnd[0], running, w.rnd_weight, 1, r_int, rew[t], rws)
         rx.rslx_act(None, critic, None, obs[T], N, 0, 0, None, None, None, last, None, None, rx.ACT_VALUES_ONLY, aws)
         if timed:
             e[1].record()
-        rx.rslx_gae(rew, values, last, dones, None, T, N, w.gamma, w.lam, 1, adv, ret, gws)
+        rx.rslx_gae(rew, values, last, dones, timeouts, T, N, w.gamma, w.lam, 1, adv, ret, gws)
         if timed:
             e[2].record()
         rx.rslx_ppo_update(actor, critic, rollout, rx.PpoCfg(call_index=it, **cfg_kw), sym, rnd, adam_step, stats, uws)
@@ -152,9 +154,9 @@ def main():
                 rx.rslx_act_dc(actor, critic, obs[t], obs[t], N, 20250910, ctr, None, actions[t], logp[t], values[t],
                                mu[t], sigma[t], 0, aws)
                 if w.rnd:
-                    rx.rslx_rnd(rnd_t, rnd_p, obs[t], N, w.Da, None, w.Da, running, w.rnd_weight, 1, r_int, rew[t], rws)
+                    rx.rslx_rnd(rnd_t, rnd_p, obs[t], N, w.Da, rnd_sub, w.dims_rnd[0], running, w.rnd_weight, 1, r_int, rew[t], rws)
             rx.rslx_act_dc(None, critic, None, obs[T], N, 0, ctr, None, None, None, last, None, None, rx.ACT_VALUES_ONLY, aws)
-            rx.rslx_gae(rew, values, last, dones, None, T, N, w.gamma, w.lam, 1, adv, ret, gws)
+            rx.rslx_gae(rew, values, last, dones, timeouts, T, N, w.gamma, w.lam, 1, adv, ret, gws)
             rx.rslx_ppo_update_dc(actor, critic, rollout, rx.PpoCfg(**cfg_kw), sym, rnd, ctr, stats, uws)
 
         graph = torch.cuda.CUDAGraph()
@@ -194,7 +196,7 @@ def main():
     result = {
         "metric": "PPO update transitions/sec + act() env-steps/sec at 4096 envs, 1 GPU",
         "value": round(B / (ms_per_step * 1e-3), 1),
-        "unit": "transitions/s (whole iteration: 24 act + GAE + 5x4 PPO update)",
+        "unit": "transitions/s (whole iteration: %d act + GAE + %dx%d PPO update)" % (T, w.epochs, w.minibatches),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: N=%d envs, T=%d, obs %d, act %d, actor/critic %s ELU, %d epochs x %d minibatches"
@@ -271,7 +273,7 @@ def cpu_baseline(w, inp):
     lastv = oppo.act(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, inp["obs"][T], inp["obs"][T], np.zeros((N, A)))["values"]
     t_act = time.perf_counter() - t0
     t0 = time.perf_counter()
-    adv, ret = ogae.gae(inp["rewards"], np.stack(vals), lastv, inp["dones"], w.gamma, w.lam)
+    adv, ret = ogae.gae(inp["rewards"], np.stack(vals), lastv, inp["dones"], w.gamma, w.lam, timeouts=inp.get("timeouts"))
     advn = ogae.normalize_advantages(adv)
     t_gae = time.perf_counter() - t0
     flat = dict(obs_a=inp["obs"][:T].reshape(B, -1), obs_c=inp["obs"][:T].reshape(B, -1), actions=np.stack(acts).reshape(B, A),

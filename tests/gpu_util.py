@@ -36,7 +36,8 @@ def oracle_rollout(w, inp, seed=7, normalize=True):
     f32 = lambda x: np.ascontiguousarray(np.asarray(x, np.float32))
     ro = dict(actions=f32(np.stack(acts)), logp=f32(np.stack(logp)), values=f32(np.stack(vals)), mu=f32(np.stack(mu)),
               sigma=f32(np.stack(sg)), last_values=f32(last))
-    adv, ret = ogae.gae(inp["rewards"], ro["values"], ro["last_values"], inp["dones"], w.gamma, w.lam)
+    adv, ret = ogae.gae(inp["rewards"], ro["values"], ro["last_values"], inp["dones"], w.gamma, w.lam,
+                        timeouts=inp.get("timeouts"))
     ro["adv_raw"], ro["returns"] = f32(adv), f32(ret)
     ro["adv"] = f32(ogae.normalize_advantages(adv)) if normalize else f32(adv)
     return ro

@@ -60,7 +60,7 @@ class Case:
     def __init__(self, w, epochs, sym_on=False, rnd_on=False, seed=3, call_index=1, perturb=0.0, rnd_subset=0):
         self.w, self.epochs, self.sym_on, self.rnd_on, self.seed, self.call_index = w, epochs, sym_on, rnd_on, seed, call_index
         inp = self.inp = make_inputs(w)
-        self.rnd_dims, self.rnd_sub = w.dims_rnd if rnd_on else None, None
+        self.rnd_dims, self.rnd_sub = w.dims_rnd if rnd_on else None, inp.get("rnd_subset_idx") if rnd_on else None
         if rnd_on and rnd_subset:      # RND nets that read a strict subset of the observation columns
             g = np.random.default_rng(11)
             self.rnd_sub = np.sort(g.choice(w.Da, size=rnd_subset, replace=False)).astype(np.int32)

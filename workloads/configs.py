@@ -44,6 +44,8 @@ class Workload:
     rnd_hidden: tuple = ()
     rnd_out: int = 0
     rnd_weight: float = 0.5
+    rnd_subset: int = 0             # > 0: the RND networks read this many of the Da observation columns
+    timeout_p: float = 0.0          # per-step probability that an episode ends by time limit (also sets done)
 
     @property
     def B(self):
@@ -63,7 +65,7 @@ class Workload:
 
     @property
     def dims_rnd(self):
-        return (self.Da,) + tuple(self.rnd_hidden) + (self.rnd_out,)
+        return (self.rnd_subset or self.Da,) + tuple(self.rnd_hidden) + (self.rnd_out,)
 
     def scaled(self, N):
         """Same workload at another environment count (parity tests at oracle-friendly sizes)."""
@@ -81,6 +83,13 @@ WORKLOADS = {
                         epochs=2, minibatches=4),
     "curiosity": Workload("curiosity", 5, N=16384, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128),
                           heavy_tail=True, rnd=True, rnd_hidden=(256, 256), rnd_out=64, minibatches=8),
+    # the two variants below exercise paths the five configurations above leave cold: episodes cut by a time limit
+    # (value bootstrap through the reward) next to early terminations, and RND on a strict subset of the state
+    "flat_timeouts": Workload("flat_timeouts", 6, N=4096, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128),
+                              heavy_tail=True, done_p=0.01, timeout_p=0.02),
+    "curiosity_subset": Workload("curiosity_subset", 7, N=16384, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128),
+                                 heavy_tail=True, rnd=True, rnd_hidden=(256, 256), rnd_out=64, minibatches=8,
+                                 rnd_subset=24),
 }
 
 
@@ -136,7 +145,7 @@ def make_inputs(w, seed=None):
     """All seeded arrays of one workload.
 
     obs        [T+1, N, Da] float32 (slab T feeds the bootstrap value); the critic reads the same tensor
-    rewards    [T, N] float32, dones [T, N] uint8
+    rewards    [T, N] float32, dones [T, N] uint8 (timeouts [T, N] uint8, a subset of dones, if the workload has them)
     actor/critic/...  flat float32 parameter vectors
     """
     gen = np.random.Generator(np.random.PCG64(MASTER_SEED + w.cfg_id if seed is None else seed))
@@ -165,6 +174,11 @@ def make_inputs(w, seed=None):
         out["teacher"] = xavier_mlp(gen, w.dims_actor)
         out["student"] = xavier_mlp(gen, w.dims_student)
     if w.rnd:
+        if w.rnd_subset:
+            out["rnd_subset_idx"] = np.sort(gen.choice(w.Da, size=w.rnd_subset, replace=False)).astype(np.int32)
         out["rnd_target"] = xavier_mlp(gen, w.dims_rnd)
         out["rnd_predictor"] = xavier_mlp(gen, w.dims_rnd)
+    if w.timeout_p > 0.0:
+        out["timeouts"] = (gen.random((T, N)) < w.timeout_p).astype(np.uint8)
+        out["dones"] = out["dones"] | out["timeouts"]
     return out
