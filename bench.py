@@ -62,6 +62,10 @@ def main():
     T, N, A, B = w.T, w.N, w.A, w.B
     dev = lambda x: torch.as_tensor(np.ascontiguousarray(x)).cuda()
 
+    if w.bc:
+        print(json.dumps(distill_iteration(args, rx, torch, np, w, inp)))
+        return
+
     actor = rx.Mlp(w.dims_actor, dev(inp["actor"]), trainable=True, has_log_std=True)
     critic = rx.Mlp(w.dims_critic, dev(inp["critic"]), trainable=True)
     obs, rewards, dones = dev(inp["obs"]), dev(inp["rewards"]), dev(inp["dones"])
@@ -173,23 +177,7 @@ def main():
     med = {k: float(np.median(v)) for k, v in phase.items()}
     assert torch.isfinite(actor.params).all() and torch.isfinite(stats).all(), "training state became non-finite"
 
-    # ---- roofline of the dominant kernel, from the library's own HIP-event trace of the timed region ----
-    kinds = {}
-    for name, flops, nbytes, ms in trace:
-        k = kinds.setdefault(name, dict(n=0, ms=0.0, flops=0.0, bytes=0.0))
-        k["n"] += 1; k["ms"] += ms; k["flops"] += flops; k["bytes"] += nbytes
-    dom = max(kinds, key=lambda k: kinds[k]["ms"])
-    d = kinds[dom]
-    achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4),
-                    traffic=HBM_TRAFFIC_BYTES_PER_LAUNCH_FLAT.get(dom) if w.name == "flat" else None,
-                    launches=d["n"], avg_launch_us=round(d["ms"] * 1e3 / d["n"], 2),
-                    flops_per_launch=d["flops"] / d["n"])
-    breakdown = {k: dict(launches=v["n"], total_ms_per_step=round(v["ms"] / args.steps, 4),
-                         tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["flops"] else None,
-                         gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["bytes"] else None)
-                 for k, v in sorted(kinds.items(), key=lambda kv: -kv[1]["ms"])}
+    roofline, breakdown = summarize_trace(trace, w, args.steps)
 
     sample_passes = w.epochs * B * (2 if w.symmetry else 1)
     upd_flops = flops_per_sample_pass(w.dims_actor, w.dims_critic) * sample_passes
@@ -217,6 +205,114 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
+
+
+def distill_iteration(args, rx, torch, np, w, inp):
+    """One iteration of the distillation loop: T collection steps (student acts, teacher relabels) and the
+    behaviour-cloning update on the collected targets."""
+    T, N, A, B = w.T, w.N, w.A, w.B
+    dev = lambda x: torch.as_tensor(np.ascontiguousarray(x)).cuda()
+    student = rx.Mlp(w.dims_student, dev(inp["student"]), trainable=True)
+    teacher = rx.Mlp(w.dims_actor, dev(inp["teacher"]))
+    obs_s, obs_t = dev(inp["obs_student"]), dev(inp["obs"][:T])
+    actions, targets = torch.empty(T, N, A, device="cuda"), torch.empty(T, N, A, device="cuda")
+    cfg_kw = dict(lr=w.lr, epochs=w.epochs, minibatches=w.minibatches, seed=20250910)
+    stats = torch.zeros(w.epochs * w.minibatches, rx.NSTATS, device="cuda")
+    cws = rx.workspace(rx.rslx_bc_collect_workspace_bytes(student, teacher, N))
+    uws = rx.workspace(rx.rslx_bc_update_workspace_bytes(student, None, B, rx.BcCfg(**cfg_kw)))
+    adam_step = ctypes.c_int64(0)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(it, timed, ctr=None):
+        e = [ev() for _ in range(3)] if timed else None
+        if timed:
+            e[0].record()
+        for t in range(T):
+            rx.rslx_bc_collect(student, teacher, obs_s[t], obs_t[t], N, actions[t], targets[t], cws)
+        if timed:
+            e[1].record()
+        if ctr is None:
+            rx.rslx_bc_update(student, None, obs_s, None, targets, B, rx.BcCfg(call_index=it, **cfg_kw), adam_step, stats, uws)
+        else:
+            rx.rslx_bc_update_dc(student, None, obs_s, None, targets, B, rx.BcCfg(**cfg_kw), ctr, stats, uws)
+        if timed:
+            e[2].record()
+        return e
+
+    for it in range(args.warmup):
+        step(it, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs = [step(args.warmup + it, True) for it in range(args.steps)]
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    med = {"collect": float(np.median([e[0].elapsed_time(e[1]) for e in evs])),
+           "update": float(np.median([e[1].elapsed_time(e[2]) for e in evs]))}
+    roofline, breakdown, traced_ms = None, None, None
+    if not args.no_trace:
+        rx.rslx_trace_begin(1 << 16)
+        t2 = time.perf_counter()
+        for it in range(args.steps):
+            step(args.warmup + args.steps + it, False)
+        torch.cuda.synchronize()
+        traced_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+        roofline, breakdown = summarize_trace(rx.rslx_trace_end(), w, args.steps)
+    graph_ms = None
+    if not args.no_graph:
+        ctr = rx.dev_counters(call_index=args.warmup + 2 * args.steps, adam_step=adam_step.value)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(0, False, ctr)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t3) * 1e3 / args.steps
+    assert torch.isfinite(student.params).all() and torch.isfinite(stats).all(), "training state became non-finite"
+    fwd = lambda dims: sum(2 * i * o for i, o in zip(dims[:-1], dims[1:]))
+    upd_flops = (3 * fwd(w.dims_student) - 2 * w.dims_student[0] * w.dims_student[1]) * B * w.epochs
+    col_flops = (fwd(w.dims_student) + fwd(w.dims_actor)) * B
+    return {
+        "metric": "BC (distillation) transitions/sec: collection (student acts, teacher relabels) + update, 1 GPU",
+        "value": round(B / (ms_per_step * 1e-3), 1),
+        "unit": "transitions/s (whole iteration: %d collect + %dx%d BC update)" % (T, w.epochs, w.minibatches),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: N=%d envs, T=%d, teacher %s, student %s ELU, %d epochs x %d minibatches"
+                   % (w.name, N, T, list(w.dims_actor), list(w.dims_student), w.epochs, w.minibatches)},
+        "phase_ms": {k: round(v, 4) for k, v in med.items()},
+        "collect_tflops": round(col_flops / (med["collect"] * 1e-3) / 1e12, 2),
+        "update_tflops": round(upd_flops / (med["update"] * 1e-3) / 1e12, 2),
+        "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
+        "graph_replay": None if graph_ms is None else {"ms_per_step": round(graph_ms, 4),
+                                                       "value": round(B / (graph_ms * 1e-3), 1)},
+        "roofline": roofline, "kernels": breakdown,
+    }
+
+
+def summarize_trace(trace, w, steps):
+    """Roofline of the dominant kernel and the per-kernel breakdown, from the library's own HIP-event trace."""
+    kinds = {}
+    for name, flops, nbytes, ms in trace:
+        k = kinds.setdefault(name, dict(n=0, ms=0.0, flops=0.0, bytes=0.0))
+        k["n"] += 1; k["ms"] += ms; k["flops"] += flops; k["bytes"] += nbytes
+    dom = max(kinds, key=lambda k: kinds[k]["ms"])
+    d = kinds[dom]
+    achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4),
+                    traffic=HBM_TRAFFIC_BYTES_PER_LAUNCH_FLAT.get(dom) if w.name == "flat" else None,
+                    launches=d["n"], avg_launch_us=round(d["ms"] * 1e3 / d["n"], 2),
+                    flops_per_launch=d["flops"] / d["n"])
+    breakdown = {k: dict(launches=v["n"], total_ms_per_step=round(v["ms"] / steps, 4),
+                         tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["flops"] else None,
+                         gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["bytes"] else None)
+                 for k, v in sorted(kinds.items(), key=lambda kv: -kv[1]["ms"])}
+
+    return roofline, breakdown
 
 
 def streaming_kernels(rx, torch, T, N, n_params):

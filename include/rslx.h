@@ -282,6 +282,25 @@ int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* 
                        const rslx_bc_cfg* cfg, int64_t* adam_step, float* stats, void* ws,
                        size_t ws_bytes, void* stream);
 
+/* As rslx_bc_update with the permutation stream (counters->call_index, += 1) and the optimiser step
+ * count (counters->adam_step, += epochs * minibatches) in device memory; cfg->call_index is ignored.
+ * See rslx_dev_counters. */
+int32_t rslx_bc_update_dc(rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student,
+                          const float* obs_teacher, const float* targets_or_null, int32_t B,
+                          const rslx_bc_cfg* cfg, rslx_dev_counters* counters, float* stats, void* ws,
+                          size_t ws_bytes, void* stream);
+
+/* One collection step of the distillation loop (paper Sec. 2.1: the student is rolled out, the
+ * expert relabels what it visits): actions = student(obs_student) (mean action, no noise) and
+ * targets = teacher(obs_teacher) for the same N states, one launch for both networks.
+ * obs_student [N, Ds], obs_teacher [N, Dt], actions [N, A], targets [N, A]; all device.  The
+ * targets written over a rollout are what rslx_bc_update takes as `targets_or_null`.
+ * RSLX_ERR_SHAPE if the two networks' output widths differ. */
+size_t rslx_bc_collect_workspace_bytes(const rslx_mlp* student, const rslx_mlp* teacher, int32_t N);
+int32_t rslx_bc_collect(const rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student,
+                        const float* obs_teacher, int32_t N, float* actions, float* targets, void* ws,
+                        size_t ws_bytes, void* stream);
+
 /* ---- symmetry augmentation (paper Sec. 2.2) -------------------------------------------- */
 
 /* obs_out[0:B] = obs_in, obs_out[B:2B][:, j] = sign_obs_a[j] * obs_in[:, perm_obs_a[j]]; the same

@@ -36,6 +36,13 @@ def teacher_targets(teacher_flat, dims_t, obs_teacher, alpha=1.0):
     return out
 
 
+def collect_step(student_flat, dims_s, teacher_flat, dims_t, obs_student, obs_teacher, alpha=1.0):
+    """One collection step of the loop of Sec. 2.1: the student's (mean) action on its own observations, which
+    drives the roll-out, and the expert's action on the same states, which becomes the regression target."""
+    actions, _ = mlp.forward(mlp.unpack(student_flat, dims_s), obs_student, alpha)
+    return actions, teacher_targets(teacher_flat, dims_t, obs_teacher, alpha)
+
+
 def bc_loss_and_grad(student_flat, dims_s, obs_student, targets, alpha=1.0):
     layers = mlp.unpack(student_flat, dims_s)
     y, cache = mlp.forward(layers, obs_student, alpha)

@@ -11,7 +11,8 @@ __all__ = [
     "rslx_adam_step", "rslx_adam_workspace_bytes", "rslx_ppo_update", "rslx_ppo_update_workspace_bytes",
     "rslx_bc_update", "rslx_bc_update_workspace_bytes", "rslx_sym_augment", "rslx_rnd", "rslx_rnd_workspace_bytes",
     "ACT_DETERMINISTIC", "ACT_VALUES_ONLY", "EXPORTS", "rslx_trace_begin", "rslx_trace_end",
-    "dev_counters", "rslx_act_dc", "rslx_ppo_update_dc",
+    "dev_counters", "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes",
+    "rslx_bc_collect",
 ]
 
 MAX_LAYERS = 8
@@ -24,7 +25,7 @@ EXPORTS = [
     "rslx_act_workspace_bytes", "rslx_act", "rslx_gae_workspace_bytes", "rslx_gae", "rslx_adam_workspace_bytes",
     "rslx_adam_step", "rslx_ppo_update_workspace_bytes", "rslx_ppo_update", "rslx_bc_update_workspace_bytes",
     "rslx_bc_update", "rslx_sym_augment", "rslx_rnd_workspace_bytes", "rslx_rnd", "rslx_trace_begin", "rslx_trace_end",
-    "rslx_act_dc", "rslx_ppo_update_dc",
+    "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes", "rslx_bc_collect",
 ]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librslx.so")
@@ -115,6 +116,10 @@ _sig("rslx_ppo_update_dc", C.c_int32, [_P(_CMlp), _P(_CMlp), _P(_CRollout), _P(_
 _sig("rslx_bc_update_workspace_bytes", C.c_size_t, [_P(_CMlp), _P(_CMlp), C.c_int32, _P(_CBcCfg)])
 _sig("rslx_bc_update", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, _vp, C.c_int32, _P(_CBcCfg), _P(C.c_int64), _vp, _vp,
                                    C.c_size_t, _vp])
+_sig("rslx_bc_update_dc", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, _vp, C.c_int32, _P(_CBcCfg), _vp, _vp, _vp,
+                                      C.c_size_t, _vp])
+_sig("rslx_bc_collect_workspace_bytes", C.c_size_t, [_P(_CMlp), _P(_CMlp), C.c_int32])
+_sig("rslx_bc_collect", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp, C.c_size_t, _vp])
 _sig("rslx_sym_augment", C.c_int32, [_P(_CSym), _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, _vp])
 _sig("rslx_rnd_workspace_bytes", C.c_size_t, [_P(_CMlp), C.c_int32])
 _sig("rslx_rnd", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, C.c_int32, C.c_int32, _vp, C.c_int32, _vp, C.c_float, C.c_int32,
@@ -348,6 +353,26 @@ def rslx_bc_update(student, teacher, obs_student, obs_teacher, targets, B, cfg, 
     _check(lib.rslx_bc_update(_ref(cs), _ref(ct), _ptr(obs_student), _ptr(obs_teacher), _ptr(targets), B, _ref(cfg.c),
                               C.byref(adam_step), _ptr(stats), _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
            "rslx_bc_update")
+
+
+def rslx_bc_update_dc(student, teacher, obs_student, obs_teacher, targets, B, cfg, counters, stats, ws):
+    """counters: int64 device tensor of 4 (dev_counters()); call_index and adam_step are used."""
+    cs = student.c
+    ct = teacher.c if teacher is not None else None
+    _check(lib.rslx_bc_update_dc(_ref(cs), _ref(ct), _ptr(obs_student), _ptr(obs_teacher), _ptr(targets), B, _ref(cfg.c),
+                                 _ptr(counters), _ptr(stats), _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
+           "rslx_bc_update_dc")
+
+
+def rslx_bc_collect_workspace_bytes(student, teacher, N):
+    return lib.rslx_bc_collect_workspace_bytes(_ref(student.c), _ref(teacher.c), N)
+
+
+def rslx_bc_collect(student, teacher, obs_student, obs_teacher, N, actions, targets, ws):
+    cs = student.c if student is not None else None
+    ct = teacher.c if teacher is not None else None
+    _check(lib.rslx_bc_collect(_ref(cs), _ref(ct), _ptr(obs_student), _ptr(obs_teacher), N, _ptr(actions), _ptr(targets),
+                               _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "rslx_bc_collect")
 
 
 def rslx_sym_augment(sym, obs_in, act_in, B, D, A, obs_out, act_out):

@@ -934,13 +934,19 @@ size_t rslx_bc_update_workspace_bytes(const rslx_mlp* student, const rslx_mlp* t
   return p.bytes;
 }
 
-int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student, const float* obs_teacher,
-                       const float* targets_or_null, int32_t B, const rslx_bc_cfg* cfg, int64_t* adam_step, float* stats,
-                       void* ws, size_t ws_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// Shared body of rslx_bc_update and rslx_bc_update_dc (permutation stream and Adam step count from device memory).
+int32_t bc_update_impl(rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student, const float* obs_teacher,
+                       const float* targets_or_null, int32_t B, const rslx_bc_cfg* cfg, int64_t* adam_step,
+                       rslx_dev_counters* counters, float* stats, void* ws, size_t ws_bytes, void* stream) {
+  int64_t host_step = 0;
+  if (counters) adam_step = &host_step;
   const rslx_mlp* tch = targets_or_null ? nullptr : teacher;
   if (!targets_or_null && !teacher) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: need a teacher or precomputed targets");
   RSLX_TRY(bc_validate(student, tch, B, cfg, true));
-  if (!obs_student || !adam_step || !stats) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: null pointer");
+  if (!obs_student || !stats) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: null pointer");
   if (tch && !obs_teacher) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: null teacher observations");
   hipStream_t s = (hipStream_t)stream;
   Carver c(ws);
@@ -965,7 +971,8 @@ int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* 
     std::vector<uint64_t> bases(cfg->epochs);
     for (int e = 0; e < cfg->epochs; ++e)
       bases[e] = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
-    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, B, p.perms, p.perm_ws, s));
+    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, B, p.perms, p.perm_ws, s, mix64_host(cfg->seed),
+                                 counters ? &counters->call_index : nullptr, cfg->epoch_offset));
   }
   const int nbm = mse_num_blocks((int64_t)p.mb * A);
   for (int e = 0; e < cfg->epochs; ++e) {
@@ -990,13 +997,79 @@ int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* 
       aa.max_grad_norm = cfg->max_grad_norm;
       aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;
       aa.bc1 = bias_correction(cfg->beta1, t); aa.bc2 = bias_correction(cfg->beta2, t);
+      if (counters) { aa.step_dev = &counters->adam_step; aa.step_off = (int32_t)t; }
       aa.grad_norm_out = stats_row + RSLX_STAT_GRAD_NORM;
       RSLX_HIP(launch_adam(aa, s));
       *adam_step = t;
     }
   }
+  if (counters) RSLX_HIP(advance_counters(counters, 0, 1, host_step, 0, s));
   return RSLX_OK;
 }
+}  // namespace
+
+extern "C" {
+
+int32_t rslx_bc_update(rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student, const float* obs_teacher,
+                       const float* targets_or_null, int32_t B, const rslx_bc_cfg* cfg, int64_t* adam_step, float* stats,
+                       void* ws, size_t ws_bytes, void* stream) {
+  if (!adam_step) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update: null pointer");
+  return bc_update_impl(student, teacher, obs_student, obs_teacher, targets_or_null, B, cfg, adam_step, nullptr, stats, ws,
+                        ws_bytes, stream);
+}
+
+int32_t rslx_bc_update_dc(rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student, const float* obs_teacher,
+                          const float* targets_or_null, int32_t B, const rslx_bc_cfg* cfg, rslx_dev_counters* counters,
+                          float* stats, void* ws, size_t ws_bytes, void* stream) {
+  if (!counters) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update_dc: null counters");
+  return bc_update_impl(student, teacher, obs_student, obs_teacher, targets_or_null, B, cfg, nullptr, counters, stats, ws,
+                        ws_bytes, stream);
+}
+
+// ---- one collection step of the distillation loop ---------------------------------------------------------------------
+size_t rslx_bc_collect_workspace_bytes(const rslx_mlp* student, const rslx_mlp* teacher, int32_t N) {
+  if (N <= 0 || !student || !teacher) return 256;
+  Carver c(nullptr);
+  return act_carve(c, student, teacher, N, nullptr, nullptr);
+}
+
+int32_t rslx_bc_collect(const rslx_mlp* student, const rslx_mlp* teacher, const float* obs_student, const float* obs_teacher,
+                        int32_t N, float* actions, float* targets, void* ws, size_t ws_bytes, void* stream) {
+  if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_bc_collect: N = %d", N);
+  RSLX_TRY(check_mlp(student, "rslx_bc_collect student", false));
+  RSLX_TRY(check_mlp(teacher, "rslx_bc_collect teacher", false));
+  if (student->dims[student->n_layers] != teacher->dims[teacher->n_layers])
+    return fail(RSLX_ERR_SHAPE, "rslx_bc_collect: student and teacher action widths differ");
+  if (!obs_student || !obs_teacher || !actions || !targets) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_collect: null pointer");
+  if (N == 0) return RSLX_OK;
+  if (!ws || ws_bytes < rslx_bc_collect_workspace_bytes(student, teacher, N))
+    return fail(RSLX_ERR_WORKSPACE, "rslx_bc_collect: workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  {
+    FusedForwardArgs fa;
+    memset(&fa, 0, sizeof fa);
+    fa.n_rows = N;
+    fa.n_nets = 2;
+    fa.max_dim = max_dim_of(*student) > max_dim_of(*teacher) ? max_dim_of(*student) : max_dim_of(*teacher);
+    fa.net[0] = fused_net(*student, obs_student, student->dims[0], nullptr, actions, false);
+    fa.net[1] = fused_net(*teacher, obs_teacher, teacher->dims[0], nullptr, targets, false);
+    if (fused_forward_supported(fa)) {
+      RSLX_HIP(launch_fused_forward(fa, s));
+      return RSLX_OK;
+    }
+  }
+  Carver c(ws);
+  NetBufs bs, bt;
+  act_carve(c, student, teacher, N, &bs, &bt);
+  bs.out[student->n_layers - 1] = actions;
+  bt.out[teacher->n_layers - 1] = targets;
+  XView xs; xs.base = obs_student; xs.ld = student->dims[0];
+  XView xt; xt.base = obs_teacher; xt.ld = teacher->dims[0];
+  NetJob jobs[2] = {NetJob{student, xs, N, &bs}, NetJob{teacher, xt, N, &bt}};
+  RSLX_TRY(forward_nets(jobs, 2, s));
+  return RSLX_OK;
+}
+
 
 // ---- symmetry augmentation ---------------------------------------------------------------------------------------------
 int32_t rslx_sym_augment(const rslx_sym* sym, const float* obs_in, const float* act_in, int32_t B, int32_t D, int32_t A,

@@ -184,6 +184,27 @@ def test_bc_zero_loss_and_normal_equation_gradient():
     assert res["opt"]["step"] == 4 and res["stats"].shape == (4, 2)
 
 
+def test_bc_collect_step_special_cases():
+    """Collection step of the distillation loop: a student that is the teacher (same observations) produces the
+    targets themselves, and the update on such data has nothing to do; a linear student's action is the affine map
+    of ITS observations (not the teacher's), the target is independent of the student."""
+    g = np.random.default_rng(3)
+    dims = (4, 6, 3)
+    teacher = g.normal(size=mlp.n_params(dims)); x_t = g.normal(size=(10, 4))
+    a, tgt = bc.collect_step(teacher, dims, teacher, dims, x_t, x_t)
+    assert np.array_equal(a, tgt)
+    loss, grad = bc.bc_loss_and_grad(teacher, dims, x_t, tgt)
+    assert loss == 0.0 and np.all(grad == 0.0)
+    dl = (2, 3)
+    student = g.normal(size=mlp.n_params(dl)); x_s = g.normal(size=(10, 2))
+    a, tgt2 = bc.collect_step(student, dl, teacher, dims, x_s, x_t)
+    W, b = student[:6].reshape(2, 3), student[6:]
+    for n in range(10):
+        for j in range(3):
+            assert abs(a[n, j] - (x_s[n, 0] * W[0, j] + x_s[n, 1] * W[1, j] + b[j])) < 1e-14
+    assert np.array_equal(tgt2, tgt)
+
+
 def test_rnd_zero_error_merge_and_scale_invariance():
     g = np.random.default_rng(0)
     dims = (5, 8, 4)
