@@ -1,4 +1,4 @@
-"""CPU oracle for the PPO / BC / symmetry / RND hot path (fp64, numpy).
+"""CPU oracle for the PPO / BC / symmetry / RND hot path and its recurrent variant (fp64, numpy).
 
 TEST INFRASTRUCTURE ONLY.  This package is a plain, slow, obviously-correct
 statement of what the GPU library computes.  It is imported by the tests, by
@@ -24,4 +24,11 @@ tests/test_oracle_*.py):
   symmetry.* ............................ pinned (involution, equivariant net, identity map)
   bc.* .................................. pinned (zero loss, normal-equation gradient)
   rnd.* ................................. pinned (two-pass mean/var, zero error)
+  gru.cell / sequence_forward ........... pinned (library GRU cell and GRU in fp64, closed forms,
+                                          separately run episodes for the resets)
+  gru.cell_backward / sequence_backward . pinned (finite differences, library autodiff, per-episode
+                                          brute force)
+  recurrent.act / minibatch_loss_and_grads / ppo_update
+                                          pinned (act == sequence re-run, on-policy identities, finite
+                                          differences of the scalar loss, column-wise minibatches)
 """

@@ -57,7 +57,7 @@ def act(actor_flat, critic_flat, dims_a, dims_c, obs_a, obs_c, eps, alpha=1.0):
     return dict(actions=a, logp=gaussian.log_prob(a, mu, sigma), values=V[:, 0], mu=mu, sigma=sigma)
 
 
-def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg, sym=None):
+def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg, sym=None, input_grads=False):
     """Loss terms and flat gradients for one minibatch.
 
     batch: dict of row-gathered arrays obs_a, obs_c, actions, logp, adv, returns,
@@ -65,6 +65,8 @@ def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg
     With `sym`, the mb rows are followed by their mirrored copies (observations
     and actions mirrored; advantages, returns, old values, old log-densities
     copied) and every mean runs over the 2*mb rows.
+    With input_grads the derivatives of the loss w.r.t. obs_a and obs_c are returned as well (a recurrent
+    memory in front of the networks needs them).
     """
     alpha = cfg.elu_alpha
     layers_a, log_std = mlp.unpack(actor_flat, dims_a, log_std=True)
@@ -116,8 +118,8 @@ def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg
         d_mu[mb:] += sym.mirror_loss_coef * d_mirror
         loss += sym.mirror_loss_coef * mirror_l
 
-    grads_a, _ = mlp.backward(layers_a, cache_a, d_mu, alpha)
-    grads_c, _ = mlp.backward(layers_c, cache_c, (cfg.value_coef * dV)[:, None], alpha)
+    grads_a, dx_a = mlp.backward(layers_a, cache_a, d_mu, alpha)
+    grads_c, dx_c = mlp.backward(layers_c, cache_c, (cfg.value_coef * dV)[:, None], alpha)
     g_actor = mlp.pack(grads_a, d_log_std)
     g_critic = mlp.pack(grads_c)
 
@@ -125,6 +127,8 @@ def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg
     kl = np.mean(gaussian.kl_old_new(mu_old, sigma_old, mu[:mb], np.broadcast_to(sigma, mu_old.shape)))
     terms = dict(loss=float(loss), surrogate=float(surrogate), value_loss=float(value_loss), entropy=float(H),
                  kl=float(kl), clip_frac=float(np.mean(np.abs(ratio - 1.0) > cfg.clip)), mirror_loss=float(mirror_l))
+    if input_grads:
+        return terms, g_actor, g_critic, dx_a, dx_c
     return terms, g_actor, g_critic
 
 

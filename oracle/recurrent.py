@@ -1,0 +1,104 @@
+"""Recurrent actor-critic: act() with carried hidden states and the PPO update with back-propagation through
+time (fp64).
+
+Sec. 3 of the paper: recurrent networks are supported for the RL and the distillation setting by managing the
+hidden states across roll-outs and back-propagating through time.  The model here: actor and critic each own a
+GRU memory (oracle.gru) whose state feeds their MLP (oracle.mlp),
+
+    h^a_t = GRU_a(obs^a_t, hin^a_t),  mu_t = actor_mlp(h^a_t);    h^c_t = GRU_c(obs^c_t, hin^c_t),  V_t = critic_mlp(h^c_t)
+
+Hidden-state management: the state is zeroed for an environment whose episode ended on the previous step, it
+is carried from one roll-out into the next, and the roll-out stores the state it started from (h0, after any
+reset) so that the update can re-run the sequence exactly.
+
+Update: minibatches are sets of whole environment columns (all T steps of N / M environments, environments
+shuffled per epoch); each is re-run through the memory from its stored h0 with the same resets, the PPO loss
+(oracle.ppo.minibatch_loss_and_grads, means over the T * N / M samples) is back-propagated through the MLPs
+into the hidden states and from there through time (truncated at the roll-out start, never across an episode
+boundary).  One gradient norm over all four parameter sets, one Adam step counter.
+
+A network's flat parameter vector is the GRU layout followed by the MLP layout (log_std last for the actor).
+
+Oracle code: test infrastructure only.
+"""
+import numpy as np
+
+from . import gru, adam, rng
+from . import ppo as _ppo
+
+
+def split(flat, D, H):
+    """(gru part, mlp part) of a recurrent network's flat parameter vector."""
+    k = gru.n_params(D, H)
+    flat = np.asarray(flat, np.float64)
+    return flat[:k], flat[k:]
+
+
+def act(actor, critic, D_a, D_c, H, dims_a, dims_c, obs_a, obs_c, h_a, h_c, reset, eps, alpha=1.0):
+    """One roll-out step.  reset [N] (0/1): environments whose episode ended on the previous step start from a
+    zero state.  Returns the outputs of ppo.act plus the new states h_a, h_c and the states the step started
+    from (hin_a, hin_c)."""
+    ga, ma = split(actor, D_a, H)
+    gc, mc = split(critic, D_c, H)
+    keep = (1.0 - np.asarray(reset, np.float64))[:, None]
+    hin_a, hin_c = np.asarray(h_a, np.float64) * keep, np.asarray(h_c, np.float64) * keep
+    ha, _ = gru.cell(gru.unpack(ga, D_a, H), obs_a, hin_a)
+    hc, _ = gru.cell(gru.unpack(gc, D_c, H), obs_c, hin_c)
+    out = _ppo.act(ma, mc, dims_a, dims_c, ha, hc, eps, alpha)
+    out.update(h_a=ha, h_c=hc, hin_a=hin_a, hin_c=hin_c)
+    return out
+
+
+def minibatch_loss_and_grads(actor, critic, D_a, D_c, H, dims_a, dims_c, batch, cfg):
+    """batch: arrays with leading [T, nb]: obs_a, obs_c, actions, logp, adv, returns, values, mu, sigma, dones,
+    and h0_a, h0_c [nb, H].  Returns (terms, g_actor, g_critic) in the flat layouts."""
+    ga, ma = split(actor, D_a, H)
+    gc, mc = split(critic, D_c, H)
+    pa, pc = gru.unpack(ga, D_a, H), gru.unpack(gc, D_c, H)
+    dones = np.asarray(batch["dones"])
+    T, nb = dones.shape
+    Ha, cache_a = gru.sequence_forward(pa, batch["obs_a"], batch["h0_a"], dones)
+    Hc, cache_c = gru.sequence_forward(pc, batch["obs_c"], batch["h0_c"], dones)
+    rows = {k: np.asarray(batch[k]).reshape((T * nb,) + np.asarray(batch[k]).shape[2:])
+            for k in ("actions", "logp", "adv", "returns", "values", "mu", "sigma")}
+    rows["obs_a"], rows["obs_c"] = Ha.reshape(T * nb, H), Hc.reshape(T * nb, H)
+    terms, g_ma, g_mc, dHa, dHc = _ppo.minibatch_loss_and_grads(ma, mc, dims_a, dims_c, rows, cfg, None, input_grads=True)
+    g_ga, _ = gru.sequence_backward(pa, cache_a, dones, dHa.reshape(T, nb, H))
+    g_gc, _ = gru.sequence_backward(pc, cache_c, dones, dHc.reshape(T, nb, H))
+    return terms, np.concatenate([g_ga, g_ma]), np.concatenate([g_gc, g_mc])
+
+
+def ppo_update(actor, critic, D_a, D_c, H, dims_a, dims_c, rollout, cfg, opt, record=False):
+    """E epochs x M minibatches of whole environment columns.
+
+    rollout: arrays [T, N, ...] obs_a, obs_c, actions, logp, adv, returns, values, mu, sigma, dones and
+    h0_a, h0_c [N, H].  opt: m_a, v_a, m_c, v_c, step.  Environment order of epoch e:
+    rng.permutation(seed, call_index, e + epoch_offset, N); minibatch m takes the m-th contiguous slice.
+    """
+    actor = np.asarray(actor, np.float64).copy(); critic = np.asarray(critic, np.float64).copy()
+    opt = {k: (np.asarray(v, np.float64).copy() if k != "step" else int(v)) for k, v in opt.items()}
+    N = np.asarray(rollout["dones"]).shape[1]
+    assert N % cfg.minibatches == 0
+    nb = N // cfg.minibatches
+    stats, perms, trace = [], [], []
+    g_a = g_c = None
+    for e in range(cfg.epochs):
+        perm = rng.permutation(cfg.seed, cfg.call_index, e + cfg.epoch_offset, N)
+        perms.append(perm)
+        for m in range(cfg.minibatches):
+            envs = perm[m * nb:(m + 1) * nb]
+            batch = {k: (np.asarray(v)[envs] if k in ("h0_a", "h0_c") else np.asarray(v)[:, envs]) for k, v in rollout.items()}
+            before = dict(actor=actor.copy(), critic=critic.copy(),
+                          opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()}) if record else None
+            terms, g_a, g_c = minibatch_loss_and_grads(actor, critic, D_a, D_c, H, dims_a, dims_c, batch, cfg)
+            norm = adam.global_norm([g_a, g_c])
+            s = adam.clip_scale(norm, cfg.max_grad_norm)
+            t0 = opt["step"]
+            actor, opt["m_a"], opt["v_a"], _ = adam.adam_step(actor, s * g_a, opt["m_a"], opt["v_a"], t0, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
+            critic, opt["m_c"], opt["v_c"], opt["step"] = adam.adam_step(critic, s * g_c, opt["m_c"], opt["v_c"], t0, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
+            if record:
+                trace.append(dict(envs=envs, before=before, g_actor=g_a, g_critic=g_c, actor=actor.copy(), critic=critic.copy()))
+            stats.append([terms["surrogate"], terms["value_loss"], terms["entropy"], terms["kl"], norm,
+                          terms["clip_frac"], 0.0, 0.0])
+    return dict(actor=actor, critic=critic, opt=opt, stats=np.array(stats), g_actor=g_a, g_critic=g_c,
+                perms=np.array(perms), trace=trace)
