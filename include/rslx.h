@@ -269,6 +269,61 @@ int32_t rslx_ppo_update_dc(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout
                            const rslx_rnd_train* rnd_or_null, rslx_dev_counters* counters,
                            float* stats, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- recurrent actor-critic (paper Sec. 3: hidden states managed across roll-outs, BPTT) ---- */
+
+/* A gated recurrent unit in front of an MLP (Cho et al. 2014; the reset gate multiplies the
+ * hidden-side candidate term, bias included):
+ *   gi = x W_ih + b_ih,  gh = h W_hh + b_hh        (3H wide, gate order r, z, n)
+ *   r = sigmoid(gi_r + gh_r), z = sigmoid(gi_z + gh_z), n = tanh(gi_n + r gh_n), h' = (1-z) n + z h
+ * Flat device layout: W_ih [in_dim, 3H] row-major, b_ih [3H], W_hh [H, 3H] row-major, b_hh [3H].
+ * hidden must be a multiple of 4; buffers 16-byte aligned; grads/adam_* NULL for inference. */
+typedef struct rslx_gru {
+  int32_t in_dim, hidden;
+  float* params;
+  float* grads;
+  float* adam_m;
+  float* adam_v;
+} rslx_gru;
+
+/* One roll-out step of a recurrent actor-critic: each network is a GRU whose new state feeds its
+ * MLP (mlp.dims[0] == gru.hidden).  For every environment n:
+ *   hin = reset[n] ? 0 : h[n];   h[n] <- GRU(obs[n], hin);   mu, V = MLPs(h[n]);  then as rslx_act.
+ * reset_or_null (device uint8 [N]) carries the previous step's episode-end flags.  h_actor
+ * [N, H_a] and h_critic [N, H_c] (device) are updated in place; when h0_actor_out / h0_critic_out
+ * are not NULL they receive hin, the state the step started from - the roll-out's first step
+ * stores it for rslx_ppo_update_recurrent.  With RSLX_ACT_VALUES_ONLY only the critic runs and
+ * NO state is written (the bootstrap value of the observation that opens the next roll-out).
+ * Everything else (noise, outputs, flags, errors) is as in rslx_act. */
+size_t rslx_act_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor,
+                                          const rslx_gru* gru_critic, const rslx_mlp* critic, int32_t N);
+int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+                           const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
+                           int32_t N, float* h_actor, float* h_critic, const uint8_t* reset_or_null,
+                           float* h0_actor_out, float* h0_critic_out, uint64_t seed, uint64_t step,
+                           const float* eps_or_null, float* actions, float* logp, float* values,
+                           float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/* PPO update of a recurrent actor-critic with back-propagation through time.  Minibatches are
+ * whole environment columns: per epoch the N environments are shuffled (the permutation stream of
+ * rslx_ppo_update, over N instead of T*N) and minibatch m takes the m-th slice of N / minibatches
+ * environments with all T steps, rows ordered step-major.  Each minibatch is re-run through both
+ * memories from h0 (the states the roll-out's first step started from, [N, H]) with the state
+ * zeroed after every step whose `dones` flag is set; the loss of rslx_ppo_update (means over the
+ * T * N / minibatches samples) is back-propagated through the MLPs into the hidden states and
+ * through time, truncated at the roll-out start and never across an episode end.  One gradient
+ * norm over the four parameter sets, one Adam step counter.  ro->Da / ro->Dc are the GRU input
+ * widths.  dones: device uint8 [T, N].  N % minibatches != 0 is RSLX_ERR_SHAPE.  Symmetry and RND
+ * are not available here.  grads of all four hold the last minibatch's gradient on return. */
+size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor,
+                                                 const rslx_gru* gru_critic, const rslx_mlp* critic,
+                                                 const rslx_rollout* ro, const rslx_ppo_cfg* cfg);
+int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru* gru_critic,
+                                  rslx_mlp* critic, const rslx_rollout* ro, const uint8_t* dones,
+                                  const float* h0_actor, const float* h0_critic, const rslx_ppo_cfg* cfg,
+                                  int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
+                                  void* stream);
+
 /* ---- behaviour cloning update (paper Sec. 2.1) ---------------------------------------- */
 
 /* targets = teacher(obs_teacher) (once; or the caller's precomputed `targets_or_null` [B, A]);

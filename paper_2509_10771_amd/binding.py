@@ -12,7 +12,8 @@ __all__ = [
     "rslx_bc_update", "rslx_bc_update_workspace_bytes", "rslx_sym_augment", "rslx_rnd", "rslx_rnd_workspace_bytes",
     "ACT_DETERMINISTIC", "ACT_VALUES_ONLY", "EXPORTS", "rslx_trace_begin", "rslx_trace_end",
     "dev_counters", "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes",
-    "rslx_bc_collect",
+    "rslx_bc_collect", "Gru", "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent",
+    "rslx_ppo_update_recurrent_workspace_bytes", "rslx_ppo_update_recurrent",
 ]
 
 MAX_LAYERS = 8
@@ -26,6 +27,8 @@ EXPORTS = [
     "rslx_adam_step", "rslx_ppo_update_workspace_bytes", "rslx_ppo_update", "rslx_bc_update_workspace_bytes",
     "rslx_bc_update", "rslx_sym_augment", "rslx_rnd_workspace_bytes", "rslx_rnd", "rslx_trace_begin", "rslx_trace_end",
     "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes", "rslx_bc_collect",
+    "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent", "rslx_ppo_update_recurrent_workspace_bytes",
+    "rslx_ppo_update_recurrent",
 ]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librslx.so")
@@ -47,6 +50,11 @@ _vp = C.c_void_p
 class _CMlp(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("dims", C.c_int32 * (MAX_LAYERS + 1)), ("elu_alpha", C.c_float),
                 ("has_log_std", C.c_int32), ("params", _vp), ("grads", _vp), ("adam_m", _vp), ("adam_v", _vp)]
+
+
+class _CGru(C.Structure):
+    _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("params", _vp), ("grads", _vp), ("adam_m", _vp),
+                ("adam_v", _vp)]
 
 
 class _CRollout(C.Structure):
@@ -120,6 +128,14 @@ _sig("rslx_bc_update_dc", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, _vp, C.c_i
                                       C.c_size_t, _vp])
 _sig("rslx_bc_collect_workspace_bytes", C.c_size_t, [_P(_CMlp), _P(_CMlp), C.c_int32])
 _sig("rslx_bc_collect", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp, C.c_size_t, _vp])
+_sig("rslx_act_recurrent_workspace_bytes", C.c_size_t, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), C.c_int32])
+_sig("rslx_act_recurrent", C.c_int32, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp,
+                                       _vp, C.c_uint64, C.c_uint64, _vp, _vp, _vp, _vp, _vp, _vp, C.c_uint32, _vp,
+                                       C.c_size_t, _vp])
+_sig("rslx_ppo_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), _P(_CRollout),
+                                                               _P(_CPpoCfg)])
+_sig("rslx_ppo_update_recurrent", C.c_int32, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), _P(_CRollout), _vp, _vp, _vp,
+                                              _P(_CPpoCfg), _P(C.c_int64), _vp, _vp, C.c_size_t, _vp])
 _sig("rslx_sym_augment", C.c_int32, [_P(_CSym), _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, _vp])
 _sig("rslx_rnd_workspace_bytes", C.c_size_t, [_P(_CMlp), C.c_int32])
 _sig("rslx_rnd", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, C.c_int32, C.c_int32, _vp, C.c_int32, _vp, C.c_float, C.c_int32,
@@ -180,6 +196,22 @@ class Mlp:
         s.adam_m = _ptr(self.adam_m)
         s.adam_v = _ptr(self.adam_v)
         return s
+
+
+class Gru:
+    """GRU memory over a flat device buffer: W_ih [in, 3H], b_ih [3H], W_hh [H, 3H], b_hh [3H]."""
+
+    def __init__(self, in_dim, hidden, params, trainable=False):
+        self.in_dim, self.hidden = int(in_dim), int(hidden)
+        assert params.numel() == 3 * self.hidden * (self.in_dim + self.hidden + 2)
+        self.params = params
+        self.grads = torch.zeros_like(params) if trainable else None
+        self.adam_m = torch.zeros_like(params) if trainable else None
+        self.adam_v = torch.zeros_like(params) if trainable else None
+
+    @property
+    def c(self):
+        return _CGru(self.in_dim, self.hidden, _ptr(self.params), _ptr(self.grads), _ptr(self.adam_m), _ptr(self.adam_v))
 
 
 class Rollout:
@@ -373,6 +405,38 @@ def rslx_bc_collect(student, teacher, obs_student, obs_teacher, N, actions, targ
     ct = teacher.c if teacher is not None else None
     _check(lib.rslx_bc_collect(_ref(cs), _ref(ct), _ptr(obs_student), _ptr(obs_teacher), N, _ptr(actions), _ptr(targets),
                                _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "rslx_bc_collect")
+
+
+def rslx_act_recurrent_workspace_bytes(gru_actor, actor, gru_critic, critic, N):
+    ga = gru_actor.c if gru_actor is not None else None
+    ca = actor.c if actor is not None else None
+    return lib.rslx_act_recurrent_workspace_bytes(_ref(ga), _ref(ca), _ref(gru_critic.c), _ref(critic.c), N)
+
+
+def rslx_act_recurrent(gru_actor, actor, gru_critic, critic, obs_actor, obs_critic, N, h_actor, h_critic, reset, h0_actor_out,
+                       h0_critic_out, seed, step, eps, actions, logp, values, mu, sigma, flags, ws):
+    ga = gru_actor.c if gru_actor is not None else None
+    ca = actor.c if actor is not None else None
+    _check(lib.rslx_act_recurrent(_ref(ga), _ref(ca), _ref(gru_critic.c), _ref(critic.c), _ptr(obs_actor), _ptr(obs_critic), N,
+                                  _ptr(h_actor), _ptr(h_critic), _ptr(reset), _ptr(h0_actor_out), _ptr(h0_critic_out), seed,
+                                  step, _ptr(eps), _ptr(actions), _ptr(logp), _ptr(values), _ptr(mu), _ptr(sigma), flags,
+                                  _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "rslx_act_recurrent")
+
+
+def rslx_ppo_update_recurrent_workspace_bytes(gru_actor, actor, gru_critic, critic, rollout, cfg):
+    n = lib.rslx_ppo_update_recurrent_workspace_bytes(_ref(gru_actor.c), _ref(actor.c), _ref(gru_critic.c), _ref(critic.c),
+                                                      _ref(rollout.c), _ref(cfg.c))
+    if n == 0:
+        raise RslxError("rslx_ppo_update_recurrent_workspace_bytes: %s" % lib.rslx_last_error().decode())
+    return n
+
+
+def rslx_ppo_update_recurrent(gru_actor, actor, gru_critic, critic, rollout, dones, h0_actor, h0_critic, cfg, adam_step, stats, ws):
+    """adam_step: ctypes.c_int64, updated in place."""
+    _check(lib.rslx_ppo_update_recurrent(_ref(gru_actor.c), _ref(actor.c), _ref(gru_critic.c), _ref(critic.c), _ref(rollout.c),
+                                         _ptr(dones), _ptr(h0_actor), _ptr(h0_critic), _ref(cfg.c), C.byref(adam_step),
+                                         _ptr(stats), _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
+           "rslx_ppo_update_recurrent")
 
 
 def rslx_sym_augment(sym, obs_in, act_in, B, D, A, obs_out, act_out):

@@ -189,29 +189,31 @@ constexpr int DW_TARGET_WGS = 1024;
 constexpr int DW_TARGET_WGS_BIG = 768;
 constexpr int DW_TARGET_WGS_BIG_PAIRED = 512;
 
-SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group) {
+// Plans layer l (an [M, N] weight reduced over `rows` rows) and appends it to p.
+void plan_layer(SplitPlan& p, int l, int M, int N, int32_t rows, int group, bool paired) {
+  const int tiles_big = ((M + 127) / 128) * ((N + 127) / 128);
+  p.big[l] = (tiles_big * group >= 16) ? 1 : 0;
+  const int tiles = gemm_dw_tiles(M, N, p.big[l] != 0);
+  const int target = p.big[l] ? (paired ? DW_TARGET_WGS_BIG_PAIRED : DW_TARGET_WGS_BIG) : DW_TARGET_WGS;
+  int s = (target + tiles * group - 1) / (tiles * group);
+  const int smax = rows / 128 > 1 ? rows / 128 : 1;
+  if (s > smax) s = smax;
+  if (s < 1) s = 1;
+  int c = (rows + s - 1) / s;
+  c = (c + 15) / 16 * 16;
+  s = (rows + c - 1) / c;            // drop splits that would be empty
+  p.split[l] = s;
+  p.chunk[l] = c;
+  p.size[l] = (int64_t)M * N + N;
+  p.pitch[l] = (p.size[l] + 3) / 4 * 4;      // 16-byte aligned split buffers
+  p.part_off[l] = p.total;
+  p.total += p.pitch[l] * s;
+  p.blocks += (int32_t)((p.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
+}
+
+SplitPlan plan_splits(const rslx_mlp& n, int32_t rows, int group, bool first_has_dx = false) {
   SplitPlan p;
-  for (int l = 0; l < n.n_layers; ++l) {
-    const int M = n.dims[l], N = n.dims[l + 1];
-    const int tiles_big = ((M + 127) / 128) * ((N + 127) / 128);
-    p.big[l] = (tiles_big * group >= 16) ? 1 : 0;
-    const int tiles = gemm_dw_tiles(M, N, p.big[l] != 0);
-    const int target = p.big[l] ? (l > 0 ? DW_TARGET_WGS_BIG_PAIRED : DW_TARGET_WGS_BIG) : DW_TARGET_WGS;
-    int s = (target + tiles * group - 1) / (tiles * group);
-    const int smax = rows / 128 > 1 ? rows / 128 : 1;
-    if (s > smax) s = smax;
-    if (s < 1) s = 1;
-    int c = (rows + s - 1) / s;
-    c = (c + 15) / 16 * 16;
-    s = (rows + c - 1) / c;            // drop splits that would be empty
-    p.split[l] = s;
-    p.chunk[l] = c;
-    p.size[l] = (int64_t)M * N + N;
-    p.pitch[l] = (p.size[l] + 3) / 4 * 4;      // 16-byte aligned split buffers
-    p.part_off[l] = p.total;
-    p.total += p.pitch[l] * s;
-    p.blocks += (int32_t)((p.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
-  }
+  for (int l = 0; l < n.n_layers; ++l) plan_layer(p, l, n.dims[l], n.dims[l + 1], rows, group, l > 0 || first_has_dx);
   return p;
 }
 
@@ -224,6 +226,7 @@ struct BwdJob {
   float* wt;             // scratch for the transposed weights (flat parameter layout)
   float* partials;       // split partials, laid out by `plan`
   const SplitPlan* plan;
+  float* dx0 = nullptr;  // optional [rows, dims[0]]: gradient w.r.t. the network input (a memory in front of it)
 };
 
 // Backward of up to two networks of equal depth: per layer one grouped weight-gradient launch (split over
@@ -237,8 +240,9 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, bool sk
   const int L = jobs[0].net->n_layers;
   TransposeBatch tb;
   tb.count = 0;
+  const bool dx_in = jobs[0].dx0 != nullptr;     // all jobs of a call agree on this
   for (int i = 0; i < count; ++i)
-    for (int l = 1; l < (skip_last_dx ? L - 1 : L); ++l) {
+    for (int l = dx_in ? 0 : 1; l < (skip_last_dx ? L - 1 : L); ++l) {
       const rslx_mlp& n = *jobs[i].net;
       tb.job[tb.count++] = TransposeJob{n.params + layer_offset(n, l), jobs[i].wt + layer_offset(n, l), n.dims[l], n.dims[l + 1]};
     }
@@ -268,12 +272,12 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, bool sk
       p.a_vec = (p.M % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
       p.b_vec = (p.N % 4 == 0 && aligned16(p.B)) ? 1 : 0;
       bw.p[i] = p;
-      if (l > 0 && !(skip_last_dx && l == L - 1)) {
+      if ((l > 0 || dx_in) && !(skip_last_dx && l == L - 1)) {
         GemmProblem q = blank_problem();
         q.A = dz; q.lda = n.dims[l + 1];
         q.B = jobs[i].wt + layer_offset(n, l); q.ldb = n.dims[l];
-        q.C = jobs[i].bufs->dz[l - 1]; q.ldc = n.dims[l];
-        q.aux = jobs[i].bufs->out[l - 1];
+        q.C = l > 0 ? jobs[i].bufs->dz[l - 1] : jobs[i].dx0; q.ldc = n.dims[l];
+        q.aux = l > 0 ? jobs[i].bufs->out[l - 1] : nullptr;      // the network input is not an ELU output
         q.M = jobs[i].rows; q.N = n.dims[l]; q.K = n.dims[l + 1];
         q.alpha = n.elu_alpha;
         q.a_vec = (q.K % 4 == 0 && aligned16(q.A)) ? 1 : 0;
@@ -281,7 +285,7 @@ int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, bool sk
         bx.p[i] = q;
       }
     }
-    if (l > 0 && !(skip_last_dx && l == L - 1)) RSLX_HIP(launch_gemm_dw_dx(bw, bx, stream));
+    if ((l > 0 || dx_in) && !(skip_last_dx && l == L - 1)) RSLX_HIP(launch_gemm_dw_dx(bw, bx, stream));
     else RSLX_HIP(launch_gemm(GEMM_DW, bw, stream));
   }
   return RSLX_OK;
@@ -617,11 +621,11 @@ struct PpoPlan {
   size_t bytes = 0;
 };
 
-void carve_train(Carver& c, const rslx_mlp& n, int32_t rows, int group, TrainBufs& t) {
+void carve_train(Carver& c, const rslx_mlp& n, int32_t rows, int group, TrainBufs& t, bool first_has_dx = false) {
   carve_net(c, n, rows, true, t.act);
   t.d_out = c.take<float>((size_t)rows * n.dims[n.n_layers]);
   t.wt = c.take<float>((size_t)round4(weight_count(n)));
-  t.plan = plan_splits(n, rows, group);
+  t.plan = plan_splits(n, rows, group, first_has_dx);
   t.partials = c.take<float>((size_t)t.plan.total);
   t.n_sumsq = t.plan.blocks;
 }
@@ -1145,6 +1149,487 @@ int32_t rslx_rnd(const rslx_mlp* target, const rslx_mlp* predictor, const float*
   }
   RSLX_HIP(launch_rnd_reward(bp.out[L - 1], bt.out[L - 1], N, target->dims[L], running, weight, update_stats ? 1 : 0,
                              r_int_out, rewards_inout_or_null, partials, s));
+  return RSLX_OK;
+}
+
+}  // extern "C"
+
+// ======================================================================================================
+// Recurrent actor-critic: GRU memories in front of the MLPs, back-propagation through time.
+// ======================================================================================================
+namespace {
+
+int64_t gru_off_bih(const rslx_gru& g) { return (int64_t)g.in_dim * 3 * g.hidden; }
+int64_t gru_off_whh(const rslx_gru& g) { return gru_off_bih(g) + 3 * g.hidden; }
+int64_t gru_off_bhh(const rslx_gru& g) { return gru_off_whh(g) + (int64_t)g.hidden * 3 * g.hidden; }
+int64_t gru_count(const rslx_gru& g) { return gru_off_bhh(g) + 3 * g.hidden; }
+
+int32_t check_gru(const rslx_gru* g, const char* name, bool trainable) {
+  if (!g) return fail(RSLX_ERR_INVALID_ARG, "%s: null memory", name);
+  if (g->in_dim < 1 || g->in_dim > (1 << 20) || g->hidden < 4 || g->hidden > (1 << 16) || g->hidden % 4 != 0)
+    return fail(RSLX_ERR_SHAPE, "%s: in_dim = %d, hidden = %d (hidden must be a multiple of 4)", name, g->in_dim, g->hidden);
+  if (!g->params || !aligned16(g->params)) return fail(RSLX_ERR_INVALID_ARG, "%s: params null or not 16-byte aligned", name);
+  if (trainable) {
+    if (!g->grads || !g->adam_m || !g->adam_v) return fail(RSLX_ERR_INVALID_ARG, "%s: grads / adam_m / adam_v required", name);
+    if (!aligned16(g->grads) || !aligned16(g->adam_m) || !aligned16(g->adam_v))
+      return fail(RSLX_ERR_INVALID_ARG, "%s: optimiser buffers not 16-byte aligned", name);
+  }
+  return RSLX_OK;
+}
+
+// C[M, 3H] = X W + b for one side of a memory's gates (X given as a view or as a plain matrix).
+GemmProblem gate_problem(const XView& x, int K, const float* W, const float* b, float* C, int M, int H3) {
+  GemmProblem p = blank_problem();
+  set_x(p, x);
+  p.B = W; p.ldb = H3; p.aux = b;
+  p.C = C; p.ldc = H3;
+  p.M = M; p.N = H3; p.K = K;
+  p.elu = 0; p.alpha = 1.f;
+  p.a_vec = (K % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
+  p.b_vec = (H3 % 4 == 0 && aligned16(W)) ? 1 : 0;
+  return p;
+}
+
+XView plain_view(const float* base, int ld) {
+  XView x;
+  x.base = base; x.ld = ld;
+  return x;
+}
+
+struct StepBufs {     // one memory's buffers of a single act step
+  float* hin = nullptr;
+  float* gi = nullptr;
+  float* gh = nullptr;
+  float* hnew = nullptr;    // values-only: the state is not written back
+};
+
+size_t act_recurrent_carve(Carver& c, const rslx_gru* ga, const rslx_gru* gc, int32_t N, StepBufs* ba, StepBufs* bc) {
+  const rslx_gru* g[2] = {ga, gc};
+  StepBufs* b[2] = {ba, bc};
+  for (int k = 0; k < 2; ++k) {
+    if (!g[k]) continue;
+    StepBufs t;
+    t.hin = c.take<float>((size_t)N * g[k]->hidden);
+    t.gi = c.take<float>((size_t)N * 3 * g[k]->hidden);
+    t.gh = c.take<float>((size_t)N * 3 * g[k]->hidden);
+    t.hnew = c.take<float>((size_t)N * g[k]->hidden);
+    if (b[k]) *b[k] = t;
+  }
+  return c.off;
+}
+
+// hin -> gi, gh -> new state, for the memories listed (1 or 2), each with its own input matrix.
+int32_t gru_step(const rslx_gru* const* g, const float* const* obs, const StepBufs* b, float* const* h_out, int count,
+                 int32_t N, hipStream_t s) {
+  GemmBatch bi, bh;
+  bi.count = bh.count = count;
+  GruFwdArgs ga;
+  memset(&ga, 0, sizeof ga);
+  ga.n_nets = count; ga.nb = N;
+  for (int k = 0; k < count; ++k) {
+    const rslx_gru& m = *g[k];
+    const int H3 = 3 * m.hidden;
+    bi.p[k] = gate_problem(plain_view(obs[k], m.in_dim), m.in_dim, m.params, m.params + gru_off_bih(m), b[k].gi, N, H3);
+    bh.p[k] = gate_problem(plain_view(b[k].hin, m.hidden), m.hidden, m.params + gru_off_whh(m), m.params + gru_off_bhh(m),
+                           b[k].gh, N, H3);
+    ga.net[k] = GruFwdNet{b[k].gi, b[k].gh, b[k].hin, h_out[k], nullptr, m.hidden};
+  }
+  RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
+  RSLX_HIP(launch_gemm(GEMM_FWD, bh, s));
+  RSLX_HIP(launch_gru_gates_fwd(ga, s));
+  return RSLX_OK;
+}
+
+int32_t act_recurrent_validate(const rslx_gru* ga, const rslx_mlp* actor, const rslx_gru* gc, const rslx_mlp* critic,
+                               bool values_only) {
+  RSLX_TRY(check_gru(gc, "rslx_act_recurrent critic memory", false));
+  RSLX_TRY(check_mlp(critic, "rslx_act_recurrent critic", false));
+  if (critic->dims[0] != gc->hidden) return fail(RSLX_ERR_SHAPE, "rslx_act_recurrent: critic input width != memory width");
+  if (!values_only) {
+    RSLX_TRY(check_gru(ga, "rslx_act_recurrent actor memory", false));
+    RSLX_TRY(check_mlp(actor, "rslx_act_recurrent actor", false));
+    if (actor->dims[0] != ga->hidden) return fail(RSLX_ERR_SHAPE, "rslx_act_recurrent: actor input width != memory width");
+  }
+  return RSLX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rslx_act_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+                                          const rslx_mlp* critic, int32_t N) {
+  if (N <= 0 || !gru_critic || !critic) return 256;
+  Carver c(nullptr);
+  act_recurrent_carve(c, gru_actor, gru_critic, N, nullptr, nullptr);
+  return (c.off + 255) / 256 * 256 + rslx_act_workspace_bytes(actor, critic, N);
+}
+
+int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+                           const rslx_mlp* critic, const float* obs_actor, const float* obs_critic, int32_t N,
+                           float* h_actor, float* h_critic, const uint8_t* reset_or_null, float* h0_actor_out,
+                           float* h0_critic_out, uint64_t seed, uint64_t step, const float* eps_or_null, float* actions,
+                           float* logp, float* values, float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes,
+                           void* stream) {
+  const bool values_only = (flags & RSLX_ACT_VALUES_ONLY) != 0;
+  if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_act_recurrent: N = %d", N);
+  RSLX_TRY(act_recurrent_validate(gru_actor, actor, gru_critic, critic, values_only));
+  if (!obs_critic || !h_critic || !values) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: null critic input / state / output");
+  if (!values_only && (!obs_actor || !h_actor)) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: null actor input / state");
+  if (!aligned16(h_critic) || (!values_only && !aligned16(h_actor)) || (h0_actor_out && !aligned16(h0_actor_out)) ||
+      (h0_critic_out && !aligned16(h0_critic_out)))
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: state buffers not 16-byte aligned");
+  if (N == 0) return RSLX_OK;
+  const rslx_gru* ga = values_only ? nullptr : gru_actor;
+  const rslx_mlp* a = values_only ? nullptr : actor;
+  if (!ws || ws_bytes < rslx_act_recurrent_workspace_bytes(ga, a, gru_critic, critic, N))
+    return fail(RSLX_ERR_WORKSPACE, "rslx_act_recurrent: workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  StepBufs ba, bc;
+  act_recurrent_carve(c, ga, gru_critic, N, &ba, &bc);
+  const size_t used = (c.off + 255) / 256 * 256;
+
+  RowGatherArgs rg;
+  memset(&rg, 0, sizeof rg);
+  rg.nb = N; rg.reset = reset_or_null;
+  if (ga) rg.job[rg.n_jobs++] = RowGatherJob{h_actor, ba.hin, values_only ? nullptr : h0_actor_out, ga->hidden};
+  rg.job[rg.n_jobs++] = RowGatherJob{h_critic, bc.hin, values_only ? nullptr : h0_critic_out, gru_critic->hidden};
+  RSLX_HIP(launch_row_gather(rg, s));
+
+  const float* h_in_actor_mlp = h_actor;
+  const float* h_in_critic_mlp = values_only ? bc.hnew : h_critic;
+  if (ga) {
+    const rslx_gru* g[2] = {ga, gru_critic};
+    const float* obs[2] = {obs_actor, obs_critic};
+    const StepBufs b[2] = {ba, bc};
+    float* out[2] = {h_actor, h_critic};
+    RSLX_TRY(gru_step(g, obs, b, out, 2, N, s));
+  } else {
+    const rslx_gru* g[1] = {gru_critic};
+    const float* obs[1] = {obs_critic};
+    const StepBufs b[1] = {bc};
+    float* out[1] = {bc.hnew};
+    RSLX_TRY(gru_step(g, obs, b, out, 1, N, s));
+  }
+  return act_impl(a, critic, h_in_actor_mlp, h_in_critic_mlp, N, seed, step, nullptr, eps_or_null, actions, logp, values,
+                  mu, sigma, flags, static_cast<char*>(ws) + used, ws_bytes - used, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+struct RnnBufs {          // per memory, one column-wise minibatch (rows = T * nb)
+  float* gi = nullptr; float* gh = nullptr; float* dgi = nullptr; float* dgh = nullptr;   // [rows, 3H]
+  float* hin = nullptr;   // [rows, H] state every step starts from
+  float* hs = nullptr;    // [rows, H] new states = input of the MLP
+  float* dh = nullptr;    // [rows, H] gradient from the MLP
+  float* back = nullptr;  // [nb, H]
+  float* direct = nullptr;  // [nb, H]
+  float* whh_t = nullptr;   // [3H, H]
+  SplitPlan plan;           // layer 0: W_ih / b_ih, layer 1: W_hh / b_hh
+  float* partials = nullptr;
+};
+
+struct RnnPlan {
+  int32_t T, N, nb, rows;
+  bool fused_head = false;
+  int32_t loss_blocks = 0;
+  int32_t* perms = nullptr;      // [E, N]
+  void* perm_ws = nullptr;
+  int32_t* rows_all = nullptr;   // [E, M, T, nb] roll-out rows of every minibatch
+  TrainBufs actor, critic;
+  RnnBufs ma, mc;
+  double* sumsq_all = nullptr;
+  int32_t n_sumsq = 0;
+  double* loss_partials = nullptr;
+  size_t bytes = 0;
+};
+
+void carve_memory(Carver& c, const rslx_gru& g, int32_t rows, int32_t nb, RnnBufs& b) {
+  const size_t H = g.hidden;
+  b.gi = c.take<float>(rows * 3 * H); b.gh = c.take<float>(rows * 3 * H);
+  b.dgi = c.take<float>(rows * 3 * H); b.dgh = c.take<float>(rows * 3 * H);
+  b.hin = c.take<float>(rows * H); b.hs = c.take<float>(rows * H); b.dh = c.take<float>(rows * H);
+  b.back = c.take<float>(nb * H); b.direct = c.take<float>(nb * H);
+  b.whh_t = c.take<float>(3 * H * H);
+  plan_layer(b.plan, 0, g.in_dim, 3 * g.hidden, rows, 2, false);
+  plan_layer(b.plan, 1, g.hidden, 3 * g.hidden, rows, 2, false);
+  b.partials = c.take<float>((size_t)b.plan.total);
+}
+
+void rnn_plan(Carver& c, const rslx_gru* ga, const rslx_mlp* actor, const rslx_gru* gc, const rslx_mlp* critic,
+              const rslx_rollout* ro, const rslx_ppo_cfg* cfg, RnnPlan& p) {
+  p.T = ro->T; p.N = ro->N;
+  p.nb = ro->N / cfg->minibatches;
+  p.rows = p.T * p.nb;
+  p.perms = c.take<int32_t>((size_t)cfg->epochs * p.N);
+  p.perm_ws = c.take<char>(perm_workspace_bytes(p.N));
+  p.rows_all = c.take<int32_t>((size_t)cfg->epochs * p.T * p.N);
+  carve_train(c, *actor, p.rows, 2, p.actor, true);
+  carve_train(c, *critic, p.rows, 2, p.critic, true);
+  carve_memory(c, *ga, p.rows, p.nb, p.ma);
+  carve_memory(c, *gc, p.rows, p.nb, p.mc);
+  p.n_sumsq = p.actor.n_sumsq + p.critic.n_sumsq + p.ma.plan.blocks + p.mc.plan.blocks + 1;
+  p.sumsq_all = c.take<double>((size_t)p.n_sumsq + 1);
+  p.fused_head = actor->n_layers >= 2 && critic->n_layers >= 2 &&
+                 ppo_head_supported(actor->dims[actor->n_layers - 1], critic->dims[critic->n_layers - 1], ro->A);
+  p.loss_blocks = p.fused_head ? ppo_head_num_blocks(p.rows, false) : ppo_loss_num_blocks(p.rows);
+  p.loss_partials = c.take<double>((size_t)p.loss_blocks * (PPO_NPART_FIXED + ro->A));
+  p.bytes = c.off + 256;
+}
+
+int32_t rnn_validate(const rslx_gru* ga, const rslx_mlp* actor, const rslx_gru* gc, const rslx_mlp* critic,
+                     const rslx_rollout* ro, const rslx_ppo_cfg* cfg, bool need_buffers) {
+  if (!ro || !cfg) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: null rollout or cfg");
+  RSLX_TRY(check_gru(ga, "rslx_ppo_update_recurrent actor memory", need_buffers));
+  RSLX_TRY(check_gru(gc, "rslx_ppo_update_recurrent critic memory", need_buffers));
+  RSLX_TRY(check_mlp(actor, "rslx_ppo_update_recurrent actor", need_buffers));
+  RSLX_TRY(check_mlp(critic, "rslx_ppo_update_recurrent critic", need_buffers));
+  if (!actor->has_log_std) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: actor needs log_std");
+  if (ro->T < 1 || ro->N < 1 || (int64_t)ro->T * ro->N > (1 << 30))
+    return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: T = %d, N = %d", ro->T, ro->N);
+  if (ro->Da != ga->in_dim || ro->Dc != gc->in_dim || actor->dims[0] != ga->hidden || critic->dims[0] != gc->hidden ||
+      ro->A != actor->dims[actor->n_layers] || critic->dims[critic->n_layers] != 1)
+    return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: rollout, memory and network widths do not match");
+  if (ro->A > 32) return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: action width %d > 32", ro->A);
+  if (actor->n_layers + critic->n_layers + 4 > 16)
+    return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: more than 12 MLP layers in total");
+  if (cfg->epochs < 0 || cfg->minibatches < 1) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: epochs / minibatches");
+  if (ro->N % cfg->minibatches != 0)
+    return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: N = %d is not a multiple of minibatches = %d", ro->N, cfg->minibatches);
+  if (need_buffers && (!ro->obs_actor || !ro->obs_critic || !ro->actions || !ro->logp || !ro->values || !ro->mu ||
+                       !ro->sigma || !ro->advantages || !ro->returns))
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: null rollout buffer");
+  return RSLX_OK;
+}
+
+// Weight-gradient problem of one side of a memory's gates: partials[l] = X^T dG over the row splits.
+GemmProblem gate_dw_problem(const XView& x, int M, const float* dG, int H3, int32_t rows, const RnnBufs& b, int l) {
+  GemmProblem p = blank_problem();
+  set_x(p, x);
+  p.B = dG; p.ldb = H3;
+  p.C = b.partials + b.plan.part_off[l]; p.ldc = H3;
+  p.M = M; p.N = H3; p.K = rows;
+  p.n_split = b.plan.split[l];
+  p.k_chunk = b.plan.chunk[l];
+  p.split_stride = b.plan.pitch[l];
+  p.bias_off = M * H3;
+  p.dw_big = b.plan.big[l];
+  p.a_vec = (M % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
+  p.b_vec = (H3 % 4 == 0 && aligned16(dG)) ? 1 : 0;
+  return p;
+}
+
+void reduce_add_memory(ReduceArgs& a, const rslx_gru& g, const RnnBufs& b) {
+  for (int l = 0; l < 2; ++l) {
+    ReduceSeg& sg = a.seg[a.n_seg++];
+    sg.partials = b.partials + b.plan.part_off[l];
+    sg.grads = g.grads + (l == 0 ? 0 : gru_off_whh(g));
+    sg.size = b.plan.size[l];
+    sg.pitch = b.plan.pitch[l];
+    sg.split = b.plan.split[l];
+    sg.block_start = a.blocks;
+    a.blocks += (int)((b.plan.size[l] + REDUCE_BLOCK_FLOATS - 1) / REDUCE_BLOCK_FLOATS);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+                                                 const rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg) {
+  if (rnn_validate(gru_actor, actor, gru_critic, critic, ro, cfg, false) != RSLX_OK) return 0;
+  Carver c(nullptr);
+  RnnPlan p;
+  rnn_plan(c, gru_actor, actor, gru_critic, critic, ro, cfg, p);
+  return p.bytes;
+}
+
+int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru* gru_critic, rslx_mlp* critic,
+                                  const rslx_rollout* ro, const uint8_t* dones, const float* h0_actor, const float* h0_critic,
+                                  const rslx_ppo_cfg* cfg, int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
+                                  void* stream) {
+  RSLX_TRY(rnn_validate(gru_actor, actor, gru_critic, critic, ro, cfg, true));
+  if (!dones || !h0_actor || !h0_critic || !adam_step || !stats)
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: null dones, h0, adam_step or stats");
+  if (!aligned16(h0_actor) || !aligned16(h0_critic)) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: h0 not 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  RnnPlan p;
+  rnn_plan(c, gru_actor, actor, gru_critic, critic, ro, cfg, p);
+  if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_ppo_update_recurrent: workspace %zu < %zu bytes", ws_bytes, p.bytes);
+  const int A = ro->A, L_a = actor->n_layers, L_c = critic->n_layers;
+  const int T = p.T, nb = p.nb, rows = p.rows;
+  const rslx_gru* mem[2] = {gru_actor, gru_critic};
+  RnnBufs* mb[2] = {&p.ma, &p.mc};
+  const float* obs[2] = {ro->obs_actor, ro->obs_critic};
+  const float* h0[2] = {h0_actor, h0_critic};
+
+  {
+    std::vector<uint64_t> bases(cfg->epochs);
+    for (int e = 0; e < cfg->epochs; ++e)
+      bases[e] = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
+    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, p.N, p.perms, p.perm_ws, s));
+    RSLX_HIP(launch_column_rows(p.perms, cfg->epochs, cfg->minibatches, T, p.N, p.rows_all, s));
+  }
+
+  for (int e = 0; e < cfg->epochs; ++e) {
+    for (int m = 0; m < cfg->minibatches; ++m) {
+      const int32_t* envs = p.perms + (size_t)e * p.N + (size_t)m * nb;
+      const int32_t* ridx = p.rows_all + ((size_t)e * cfg->minibatches + m) * rows;
+      float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
+
+      // ---- memories forward: input-side gates for all steps at once, then step by step ----
+      {
+        RowGatherArgs rg;
+        memset(&rg, 0, sizeof rg);
+        rg.n_jobs = 2; rg.nb = nb; rg.idx = envs;
+        for (int k = 0; k < 2; ++k) rg.job[k] = RowGatherJob{h0[k], mb[k]->hin, nullptr, mem[k]->hidden};
+        RSLX_HIP(launch_row_gather(rg, s));
+        GemmBatch bi;
+        bi.count = 2;
+        for (int k = 0; k < 2; ++k) {
+          XView x;
+          x.base = obs[k]; x.ld = mem[k]->in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * p.N;
+          bi.p[k] = gate_problem(x, mem[k]->in_dim, mem[k]->params, mem[k]->params + gru_off_bih(*mem[k]), mb[k]->gi, rows,
+                                 3 * mem[k]->hidden);
+        }
+        RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
+      }
+      for (int t = 0; t < T; ++t) {
+        GemmBatch bh;
+        bh.count = 2;
+        GruFwdArgs ga;
+        memset(&ga, 0, sizeof ga);
+        ga.n_nets = 2; ga.nb = nb; ga.done = dones; ga.done_idx = ridx + (size_t)t * nb;
+        for (int k = 0; k < 2; ++k) {
+          const rslx_gru& g = *mem[k];
+          const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
+          bh.p[k] = gate_problem(plain_view(mb[k]->hin + o, g.hidden), g.hidden, g.params + gru_off_whh(g),
+                                 g.params + gru_off_bhh(g), mb[k]->gh + o3, nb, 3 * g.hidden);
+          ga.net[k] = GruFwdNet{mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->hs + o,
+                                t + 1 < T ? mb[k]->hin + o + (size_t)nb * H : nullptr, g.hidden};
+        }
+        RSLX_HIP(launch_gemm(GEMM_FWD, bh, s));
+        RSLX_HIP(launch_gru_gates_fwd(ga, s));
+      }
+
+      // ---- MLPs on the hidden states, loss head, MLP backward down to the hidden states ----
+      XView xa = plain_view(p.ma.hs, gru_actor->hidden), xc = plain_view(p.mc.hs, gru_critic->hidden);
+      NetJob fj[2] = {NetJob{actor, xa, rows, &p.actor.act}, NetJob{critic, xc, rows, &p.critic.act}};
+      RSLX_TRY(forward_nets(fj, 2, s, p.fused_head));
+      PpoLossArgs la;
+      memset(&la, 0, sizeof la);
+      la.mu = p.actor.act.out[L_a - 1];
+      la.v = p.critic.act.out[L_c - 1];
+      la.log_std = actor->params + weight_count(*actor);
+      la.idx = ridx;
+      la.actions = ro->actions; la.logp_old = ro->logp; la.adv = ro->advantages; la.returns = ro->returns;
+      la.v_old = ro->values; la.mu_old = ro->mu; la.sigma_old = ro->sigma;
+      la.mb = rows; la.rows = rows; la.A = A;
+      la.clip = cfg->clip; la.value_coef = cfg->value_coef; la.entropy_coef = cfg->entropy_coef;
+      la.clipped_value = cfg->use_clipped_value_loss;
+      la.d_mu = p.actor.d_out; la.d_v = p.critic.d_out;
+      la.partials = p.loss_partials;
+      if (p.fused_head) {
+        PpoHeadArgs ha;
+        ha.loss = la;
+        ha.h_a = p.actor.act.out[L_a - 2]; ha.h_c = p.critic.act.out[L_c - 2];
+        ha.w_a = actor->params + layer_offset(*actor, L_a - 1); ha.w_c = critic->params + layer_offset(*critic, L_c - 1);
+        ha.dz_a = p.actor.act.dz[L_a - 2]; ha.dz_c = p.critic.act.dz[L_c - 2];
+        ha.Ha = actor->dims[L_a - 1]; ha.Hc = critic->dims[L_c - 1];
+        ha.alpha_a = actor->elu_alpha; ha.alpha_c = critic->elu_alpha;
+        RSLX_HIP(launch_ppo_head(ha, s));
+      } else {
+        RSLX_HIP(launch_ppo_loss(la, s));
+      }
+      BwdJob bj[2] = {BwdJob{actor, xa, rows, &p.actor.act, p.actor.d_out, p.actor.wt, p.actor.partials, &p.actor.plan, p.ma.dh},
+                      BwdJob{critic, xc, rows, &p.critic.act, p.critic.d_out, p.critic.wt, p.critic.partials, &p.critic.plan, p.mc.dh}};
+      RSLX_TRY(backward_nets(bj, 2, s, p.fused_head));
+
+      // ---- back-propagation through time ----
+      {
+        TransposeBatch tb;
+        tb.count = 2;
+        for (int k = 0; k < 2; ++k)
+          tb.job[k] = TransposeJob{mem[k]->params + gru_off_whh(*mem[k]), mb[k]->whh_t, mem[k]->hidden, 3 * mem[k]->hidden};
+        RSLX_HIP(launch_transpose(tb, s));
+      }
+      for (int t = T - 1; t >= 0; --t) {
+        GruBwdArgs gb;
+        memset(&gb, 0, sizeof gb);
+        gb.n_nets = 2; gb.nb = nb; gb.done = dones; gb.done_idx = ridx + (size_t)t * nb;
+        GemmBatch bx;
+        bx.count = 2;
+        for (int k = 0; k < 2; ++k) {
+          const rslx_gru& g = *mem[k];
+          const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
+          const bool last = t == T - 1;
+          gb.net[k] = GruBwdNet{mb[k]->dh + o, last ? nullptr : mb[k]->back, last ? nullptr : mb[k]->direct,
+                                mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3, mb[k]->dgh + o3,
+                                mb[k]->direct, g.hidden};
+          GemmProblem q = blank_problem();
+          q.A = mb[k]->dgh + o3; q.lda = 3 * g.hidden;
+          q.B = mb[k]->whh_t; q.ldb = g.hidden;
+          q.C = mb[k]->back; q.ldc = g.hidden;
+          q.M = nb; q.N = g.hidden; q.K = 3 * g.hidden;
+          q.alpha = 1.f;
+          q.a_vec = aligned16(q.A) ? 1 : 0;
+          q.b_vec = aligned16(q.B) ? 1 : 0;
+          bx.p[k] = q;
+        }
+        RSLX_HIP(launch_gru_gates_bwd(gb, s));
+        if (t > 0) RSLX_HIP(launch_gemm(GEMM_DX, bx, s));
+      }
+      {   // weight gradients of both sides of the gates, all steps at once
+        GemmBatch bwi, bwh;
+        bwi.count = bwh.count = 2;
+        for (int k = 0; k < 2; ++k) {
+          const rslx_gru& g = *mem[k];
+          XView x;
+          x.base = obs[k]; x.ld = g.in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * p.N;
+          bwi.p[k] = gate_dw_problem(x, g.in_dim, mb[k]->dgi, 3 * g.hidden, rows, *mb[k], 0);
+          bwh.p[k] = gate_dw_problem(plain_view(mb[k]->hin, g.hidden), g.hidden, mb[k]->dgh, 3 * g.hidden, rows, *mb[k], 1);
+        }
+        RSLX_HIP(launch_gemm(GEMM_DW, bwi, s));
+        RSLX_HIP(launch_gemm(GEMM_DW, bwh, s));
+      }
+      {   // one launch: every split sum and the loss head's sums
+        ReduceArgs ra;
+        memset(&ra, 0, sizeof ra);
+        ra.sumsq_blocks = p.sumsq_all;
+        reduce_add_net(ra, *actor, p.actor);
+        reduce_add_net(ra, *critic, p.critic);
+        reduce_add_memory(ra, *gru_actor, p.ma);
+        reduce_add_memory(ra, *gru_critic, p.mc);
+        ra.finish.partials = p.loss_partials; ra.finish.blocks = p.loss_blocks;
+        ra.finish.rows = rows; ra.finish.mb = rows; ra.finish.A = A;
+        ra.finish.log_std = la.log_std; ra.finish.entropy_coef = cfg->entropy_coef;
+        ra.finish.d_log_std = actor->grads + weight_count(*actor);
+        ra.finish.stats_row = stats_row;
+        ra.finish.sumsq_slot = p.sumsq_all + (p.n_sumsq - 1);
+        RSLX_HIP(launch_reduce_partials(ra, s));
+      }
+      const int64_t t1 = *adam_step + 1;
+      AdamArgs aa;
+      memset(&aa, 0, sizeof aa);
+      aa.seg[0] = AdamSegment{actor->params, actor->grads, actor->adam_m, actor->adam_v, param_count(*actor)};
+      aa.seg[1] = AdamSegment{critic->params, critic->grads, critic->adam_m, critic->adam_v, param_count(*critic)};
+      aa.seg[2] = AdamSegment{gru_actor->params, gru_actor->grads, gru_actor->adam_m, gru_actor->adam_v, gru_count(*gru_actor)};
+      aa.seg[3] = AdamSegment{gru_critic->params, gru_critic->grads, gru_critic->adam_m, gru_critic->adam_v, gru_count(*gru_critic)};
+      aa.n_seg = 4;
+      aa.sumsq_blocks = p.sumsq_all; aa.n_sumsq = p.n_sumsq;
+      aa.max_grad_norm = cfg->max_grad_norm;
+      aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;
+      aa.bc1 = bias_correction(cfg->beta1, t1); aa.bc2 = bias_correction(cfg->beta2, t1);
+      aa.grad_norm_out = stats_row + RSLX_STAT_GRAD_NORM;
+      RSLX_HIP(launch_adam(aa, s));
+      *adam_step = t1;
+    }
+  }
   return RSLX_OK;
 }
 

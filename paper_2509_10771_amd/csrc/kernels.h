@@ -159,7 +159,7 @@ struct AdamSegment {
   int64_t n;
 };
 struct AdamArgs {
-  AdamSegment seg[2];
+  AdamSegment seg[4];
   int32_t n_seg;
   const double* sumsq_blocks;  // per-block sums of squares covering every clipped tensor
   int32_t n_sumsq;
@@ -233,5 +233,64 @@ hipError_t launch_rnd_reward(const float* yp, const float* yt, int32_t N, int32_
                              int32_t update_stats, float* r_int, float* rewards, double* partials, hipStream_t stream);
 
 hipError_t launch_fill(float* p, int64_t n, float value, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------
+// Gated recurrent unit (recurrent.hip): the element-wise gate stages around the hidden-side contractions.
+//   gi = x W_ih + b_ih, gh = hin W_hh + b_hh ([*, 3H], gate order r, z, n; both from the GEMM kernel)
+//   r = sigmoid(gi_r + gh_r), z = sigmoid(gi_z + gh_z), n = tanh(gi_n + r gh_n), h = (1 - z) n + z hin
+// Up to two networks (actor, critic memories) per launch; H % 4 == 0.
+// ---------------------------------------------------------------------------------------------
+struct GruFwdNet {
+  const float* gi;        // [nb, 3H] this step's rows
+  const float* gh;        // [nb, 3H]
+  const float* hin;       // [nb, H]
+  float* h_out;           // [nb, H]
+  float* hin_next;        // [nb, H] or null: h_out * (1 - done), the state the next step starts from
+  int32_t H;
+};
+struct GruFwdArgs {
+  GruFwdNet net[2];
+  int32_t n_nets, nb;
+  const uint8_t* done;      // episode-end flags (null = none); row i reads done[done_idx ? done_idx[i] : i]
+  const int32_t* done_idx;
+};
+hipError_t launch_gru_gates_fwd(const GruFwdArgs& a, hipStream_t stream);
+
+// One step of back-propagation through time, element-wise part: with
+//   dh = dh_ext + (1 - done) (back + direct)        (back/direct: what step t + 1 sent to its input state)
+// it writes dgi = [dr_pre, dz_pre, dn_pre], dgh = [dr_pre, dz_pre, dn_pre r] and direct_out = dh z; the
+// caller then forms back = dgh W_hh^T with the GEMM kernel.
+struct GruBwdNet {
+  const float* dh_ext;    // [nb, H] gradient arriving from the layers above
+  const float* back;      // [nb, H] or null (last step)
+  const float* direct_in; // [nb, H] or null (last step)
+  const float* gi; const float* gh; const float* hin;
+  float* dgi; float* dgh; // [nb, 3H]
+  float* direct_out;      // [nb, H]
+  int32_t H;
+};
+struct GruBwdArgs {
+  GruBwdNet net[2];
+  int32_t n_nets, nb;
+  const uint8_t* done;      // flags of THIS step (they gate what step t + 1 sends back); null = none
+  const int32_t* done_idx;
+};
+hipError_t launch_gru_gates_bwd(const GruBwdArgs& a, hipStream_t stream);
+
+// dst[i, :] = src[idx ? idx[i] : i, :] * (reset && reset[i] ? 0 : 1) for up to two [*, H] matrices; a second
+// copy of the result goes to dst2 when it is not null.
+struct RowGatherJob { const float* src; float* dst; float* dst2; int32_t H; };
+struct RowGatherArgs {
+  RowGatherJob job[2];
+  int32_t n_jobs, nb;
+  const int32_t* idx;
+  const uint8_t* reset;
+};
+hipError_t launch_row_gather(const RowGatherArgs& a, hipStream_t stream);
+
+// rows_out[((e * M + m) * T + t) * nb + i] = t * N + perm[e * N + m * nb + i]: the roll-out rows of every
+// column-wise minibatch, step-major.
+hipError_t launch_column_rows(const int32_t* perm, int32_t E, int32_t M, int32_t T, int32_t N, int32_t* rows_out,
+                              hipStream_t stream);
 
 }  // namespace rslx

@@ -46,6 +46,7 @@ class Workload:
     rnd_weight: float = 0.5
     rnd_subset: int = 0             # > 0: the RND networks read this many of the Da observation columns
     timeout_p: float = 0.0          # per-step probability that an episode ends by time limit (also sets done)
+    memory_hidden: int = 0          # > 0: actor and critic each have a GRU memory of this width in front of their MLP
 
     @property
     def B(self):
@@ -53,11 +54,11 @@ class Workload:
 
     @property
     def dims_actor(self):
-        return (self.Da,) + tuple(self.hidden) + (self.A,)
+        return (self.memory_hidden or self.Da,) + tuple(self.hidden) + (self.A,)
 
     @property
     def dims_critic(self):
-        return (self.Dc,) + tuple(self.hidden) + (1,)
+        return (self.memory_hidden or self.Dc,) + tuple(self.hidden) + (1,)
 
     @property
     def dims_student(self):
@@ -90,6 +91,10 @@ WORKLOADS = {
     "curiosity_subset": Workload("curiosity_subset", 7, N=16384, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128),
                                  heavy_tail=True, rnd=True, rnd_hidden=(256, 256), rnd_out=64, minibatches=8,
                                  rnd_subset=24),
+    # recurrent actor-critic: a 256-wide GRU memory per network, episodes end often enough that every roll-out
+    # holds resets
+    "recurrent": Workload("recurrent", 8, N=4096, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128), heavy_tail=True,
+                          done_p=0.01, memory_hidden=256),
 }
 
 
@@ -104,6 +109,12 @@ def xavier_mlp(gen, dims, log_std=False):
     if log_std:
         parts.append(np.zeros(dims[-1], np.float32))
     return np.concatenate(parts)
+
+
+def uniform_gru(gen, D, H):
+    """Flat float32 GRU parameters W_ih [D, 3H], b_ih [3H], W_hh [H, 3H], b_hh [3H], all ~ U(-1/sqrt(H), 1/sqrt(H))."""
+    a = 1.0 / np.sqrt(H)
+    return gen.uniform(-a, a, size=3 * H * (D + H + 2)).astype(np.float32)
 
 
 def random_involution(gen, n, p_fixed=0.2):
@@ -178,6 +189,12 @@ def make_inputs(w, seed=None):
             out["rnd_subset_idx"] = np.sort(gen.choice(w.Da, size=w.rnd_subset, replace=False)).astype(np.int32)
         out["rnd_target"] = xavier_mlp(gen, w.dims_rnd)
         out["rnd_predictor"] = xavier_mlp(gen, w.dims_rnd)
+    if w.memory_hidden:
+        H = w.memory_hidden
+        out["gru_actor"], out["gru_critic"] = uniform_gru(gen, w.Da, H), uniform_gru(gen, w.Dc, H)
+        out["h_actor"] = (0.5 * gen.standard_normal((N, H))).astype(np.float32)     # states carried in from before
+        out["h_critic"] = (0.5 * gen.standard_normal((N, H))).astype(np.float32)
+        out["reset0"] = (gen.random(N) < w.done_p).astype(np.uint8)                  # episode ends of the step before
     if w.timeout_p > 0.0:
         out["timeouts"] = (gen.random((T, N)) < w.timeout_p).astype(np.uint8)
         out["dones"] = out["dones"] | out["timeouts"]
