@@ -65,6 +65,9 @@ def main():
     if w.bc:
         print(json.dumps(distill_iteration(args, rx, torch, np, w, inp)))
         return
+    if w.memory_hidden:
+        print(json.dumps(recurrent_iteration(args, rx, torch, np, w, inp)))
+        return
 
     actor = rx.Mlp(w.dims_actor, dev(inp["actor"]), trainable=True, has_log_std=True)
     critic = rx.Mlp(w.dims_critic, dev(inp["critic"]), trainable=True)
@@ -289,6 +292,95 @@ def distill_iteration(args, rx, torch, np, w, inp):
         "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
         "graph_replay": None if graph_ms is None else {"ms_per_step": round(graph_ms, 4),
                                                        "value": round(B / (graph_ms * 1e-3), 1)},
+        "roofline": roofline, "kernels": breakdown,
+    }
+
+
+def recurrent_iteration(args, rx, torch, np, w, inp):
+    """One iteration with GRU memories: T recurrent act steps (states carried across iterations, reset at episode
+    ends), bootstrap value, GAE, and the column-wise PPO update with back-propagation through time."""
+    T, N, A, B, H = w.T, w.N, w.A, w.B, w.memory_hidden
+    dev = lambda x: torch.as_tensor(np.ascontiguousarray(x)).cuda()
+    nets = []
+    for which, D, dims, log_std in (("actor", w.Da, w.dims_actor, True), ("critic", w.Dc, w.dims_critic, False)):
+        nets.append(rx.Gru(D, H, dev(inp["gru_" + which]), trainable=True))
+        nets.append(rx.Mlp(dims, dev(inp[which]), trainable=True, has_log_std=log_std))
+    ga, ma, gc, mc = nets
+    obs, rewards, dones = dev(inp["obs"]), dev(inp["rewards"]), dev(inp["dones"])
+    h_a, h_c, reset0 = dev(inp["h_actor"]), dev(inp["h_critic"]), dev(inp["reset0"])
+    h0_a, h0_c = torch.empty(N, H, device="cuda"), torch.empty(N, H, device="cuda")
+    actions, mu, sigma = (torch.empty(T, N, A, device="cuda") for _ in range(3))
+    logp, values, adv, ret = (torch.empty(T, N, device="cuda") for _ in range(4))
+    last = torch.empty(N, device="cuda")
+    rollout = rx.Rollout(T, N, obs[:T], obs[:T], actions, logp, values, mu, sigma, adv, ret)
+    cfg_kw = dict(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
+                  lr=w.lr, epochs=w.epochs, minibatches=w.minibatches, seed=20250910)
+    stats = torch.zeros(w.epochs * w.minibatches, rx.NSTATS, device="cuda")
+    aws = rx.workspace(rx.rslx_act_recurrent_workspace_bytes(ga, ma, gc, mc, N))
+    gws = rx.workspace(rx.rslx_gae_workspace_bytes(T, N))
+    uws = rx.workspace(rx.rslx_ppo_update_recurrent_workspace_bytes(ga, ma, gc, mc, rollout, rx.PpoCfg(**cfg_kw)))
+    adam_step = ctypes.c_int64(0)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(it, timed):
+        e = [ev() for _ in range(4)] if timed else None
+        if timed:
+            e[0].record()
+        for t in range(T):
+            reset = dones[t - 1] if t > 0 else (reset0 if it == 0 else dones[T - 1])
+            rx.rslx_act_recurrent(ga, ma, gc, mc, obs[t], obs[t], N, h_a, h_c, reset, h0_a if t == 0 else None,
+                                  h0_c if t == 0 else None, 20250910, it * T + t, None, actions[t], logp[t], values[t], mu[t],
+                                  sigma[t], 0, aws)
+        rx.rslx_act_recurrent(None, None, gc, mc, None, obs[T], N, None, h_c, dones[T - 1], None, None, 0, 0, None, None, None,
+                              last, None, None, rx.ACT_VALUES_ONLY, aws)
+        if timed:
+            e[1].record()
+        rx.rslx_gae(rewards, values, last, dones, None, T, N, w.gamma, w.lam, 1, adv, ret, gws)
+        if timed:
+            e[2].record()
+        rx.rslx_ppo_update_recurrent(ga, ma, gc, mc, rollout, dones, h0_a, h0_c, rx.PpoCfg(call_index=it, **cfg_kw), adam_step,
+                                     stats, uws)
+        if timed:
+            e[3].record()
+        return e
+
+    for it in range(args.warmup):
+        step(it, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs = [step(args.warmup + it, True) for it in range(args.steps)]
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    med = {k: float(np.median([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, k in enumerate(("act", "gae", "update"))}
+    roofline, breakdown, traced_ms = None, None, None
+    if not args.no_trace:
+        rx.rslx_trace_begin(1 << 17)
+        t2 = time.perf_counter()
+        for it in range(args.steps):
+            step(args.warmup + args.steps + it, False)
+        torch.cuda.synchronize()
+        traced_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+        roofline, breakdown = summarize_trace(rx.rslx_trace_end(), w, args.steps)
+    assert torch.isfinite(ma.params).all() and torch.isfinite(ga.params).all() and torch.isfinite(stats).all()
+    fwd = lambda dims: sum(2 * i * o for i, o in zip(dims[:-1], dims[1:]))
+    gru_fwd = lambda D: 2 * (D + H) * 3 * H
+    gru_bwd = lambda D: 2 * D * 3 * H + 2 * 2 * H * 3 * H
+    per_sample = 3 * (fwd(w.dims_actor) + fwd(w.dims_critic)) + gru_fwd(w.Da) + gru_fwd(w.Dc) + gru_bwd(w.Da) + gru_bwd(w.Dc)
+    act_flops = fwd(w.dims_actor) + fwd(w.dims_critic) + gru_fwd(w.Da) + gru_fwd(w.Dc)
+    return {
+        "metric": "recurrent PPO (GRU memories, BPTT) transitions/sec: act + GAE + update, 1 GPU",
+        "value": round(B / (ms_per_step * 1e-3), 1),
+        "unit": "transitions/s (whole iteration: %d act + GAE + %dx%d PPO update)" % (T, w.epochs, w.minibatches),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: N=%d envs, T=%d, obs %d, act %d, GRU %d + MLP %s ELU per network, %d epochs x %d minibatches "
+                               "of %d environment columns" % (w.name, N, T, w.Da, A, H, list(w.hidden), w.epochs, w.minibatches,
+                                                             N // w.minibatches)},
+        "phase_ms": {k: round(v, 4) for k, v in med.items()},
+        "update_tflops": round(per_sample * B * w.epochs / (med["update"] * 1e-3) / 1e12, 2),
+        "act_tflops": round(act_flops * (T + 1) * N / (med["act"] * 1e-3) / 1e12, 2),
+        "act_env_steps_per_s": round((T + 1) * N / (med["act"] * 1e-3), 1),
+        "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
         "roofline": roofline, "kernels": breakdown,
     }
 

@@ -1199,7 +1199,6 @@ XView plain_view(const float* base, int ld) {
 struct StepBufs {     // one memory's buffers of a single act step
   float* hin = nullptr;
   float* gi = nullptr;
-  float* gh = nullptr;
   float* hnew = nullptr;    // values-only: the state is not written back
 };
 
@@ -1211,32 +1210,28 @@ size_t act_recurrent_carve(Carver& c, const rslx_gru* ga, const rslx_gru* gc, in
     StepBufs t;
     t.hin = c.take<float>((size_t)N * g[k]->hidden);
     t.gi = c.take<float>((size_t)N * 3 * g[k]->hidden);
-    t.gh = c.take<float>((size_t)N * 3 * g[k]->hidden);
     t.hnew = c.take<float>((size_t)N * g[k]->hidden);
     if (b[k]) *b[k] = t;
   }
   return c.off;
 }
 
-// hin -> gi, gh -> new state, for the memories listed (1 or 2), each with its own input matrix.
+// hin -> gi -> new state (hidden-side contraction fused with the gates), for the memories listed (1 or 2), each with its own input matrix.
 int32_t gru_step(const rslx_gru* const* g, const float* const* obs, const StepBufs* b, float* const* h_out, int count,
                  int32_t N, hipStream_t s) {
-  GemmBatch bi, bh;
-  bi.count = bh.count = count;
-  GruFwdArgs ga;
-  memset(&ga, 0, sizeof ga);
-  ga.n_nets = count; ga.nb = N;
+  GemmBatch bi;
+  bi.count = count;
+  GruStepFwdArgs sa;
+  memset(&sa, 0, sizeof sa);
+  sa.n_nets = count; sa.nb = N;
   for (int k = 0; k < count; ++k) {
     const rslx_gru& m = *g[k];
-    const int H3 = 3 * m.hidden;
-    bi.p[k] = gate_problem(plain_view(obs[k], m.in_dim), m.in_dim, m.params, m.params + gru_off_bih(m), b[k].gi, N, H3);
-    bh.p[k] = gate_problem(plain_view(b[k].hin, m.hidden), m.hidden, m.params + gru_off_whh(m), m.params + gru_off_bhh(m),
-                           b[k].gh, N, H3);
-    ga.net[k] = GruFwdNet{b[k].gi, b[k].gh, b[k].hin, h_out[k], nullptr, m.hidden};
+    bi.p[k] = gate_problem(plain_view(obs[k], m.in_dim), m.in_dim, m.params, m.params + gru_off_bih(m), b[k].gi, N, 3 * m.hidden);
+    sa.net[k] = GruFwdNet{b[k].gi, b[k].hin, h_out[k], nullptr, m.params + gru_off_whh(m), m.params + gru_off_bhh(m),
+                          nullptr, m.hidden};
   }
   RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
-  RSLX_HIP(launch_gemm(GEMM_FWD, bh, s));
-  RSLX_HIP(launch_gru_gates_fwd(ga, s));
+  RSLX_HIP(launch_gru_step_fwd(sa, s));
   return RSLX_OK;
 }
 
@@ -1325,7 +1320,6 @@ struct RnnBufs {          // per memory, one column-wise minibatch (rows = T * n
   float* hin = nullptr;   // [rows, H] state every step starts from
   float* hs = nullptr;    // [rows, H] new states = input of the MLP
   float* dh = nullptr;    // [rows, H] gradient from the MLP
-  float* back = nullptr;  // [nb, H]
   float* direct = nullptr;  // [nb, H]
   float* whh_t = nullptr;   // [3H, H]
   SplitPlan plan;           // layer 0: W_ih / b_ih, layer 1: W_hh / b_hh
@@ -1352,7 +1346,7 @@ void carve_memory(Carver& c, const rslx_gru& g, int32_t rows, int32_t nb, RnnBuf
   b.gi = c.take<float>(rows * 3 * H); b.gh = c.take<float>(rows * 3 * H);
   b.dgi = c.take<float>(rows * 3 * H); b.dgh = c.take<float>(rows * 3 * H);
   b.hin = c.take<float>(rows * H); b.hs = c.take<float>(rows * H); b.dh = c.take<float>(rows * H);
-  b.back = c.take<float>(nb * H); b.direct = c.take<float>(nb * H);
+  b.direct = c.take<float>(nb * H);
   b.whh_t = c.take<float>(3 * H * H);
   plan_layer(b.plan, 0, g.in_dim, 3 * g.hidden, rows, 2, false);
   plan_layer(b.plan, 1, g.hidden, 3 * g.hidden, rows, 2, false);
@@ -1500,21 +1494,17 @@ int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru
         RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
       }
       for (int t = 0; t < T; ++t) {
-        GemmBatch bh;
-        bh.count = 2;
-        GruFwdArgs ga;
-        memset(&ga, 0, sizeof ga);
-        ga.n_nets = 2; ga.nb = nb; ga.done = dones; ga.done_idx = ridx + (size_t)t * nb;
+        GruStepFwdArgs sa;
+        memset(&sa, 0, sizeof sa);
+        sa.n_nets = 2; sa.nb = nb; sa.done = dones; sa.done_idx = ridx + (size_t)t * nb;
         for (int k = 0; k < 2; ++k) {
           const rslx_gru& g = *mem[k];
           const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
-          bh.p[k] = gate_problem(plain_view(mb[k]->hin + o, g.hidden), g.hidden, g.params + gru_off_whh(g),
-                                 g.params + gru_off_bhh(g), mb[k]->gh + o3, nb, 3 * g.hidden);
-          ga.net[k] = GruFwdNet{mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->hs + o,
-                                t + 1 < T ? mb[k]->hin + o + (size_t)nb * H : nullptr, g.hidden};
+          sa.net[k] = GruFwdNet{mb[k]->gi + o3, mb[k]->hin + o, mb[k]->hs + o,
+                                t + 1 < T ? mb[k]->hin + o + (size_t)nb * H : nullptr, g.params + gru_off_whh(g),
+                                g.params + gru_off_bhh(g), mb[k]->gh + o3, g.hidden};
         }
-        RSLX_HIP(launch_gemm(GEMM_FWD, bh, s));
-        RSLX_HIP(launch_gru_gates_fwd(ga, s));
+        RSLX_HIP(launch_gru_step_fwd(sa, s));
       }
 
       // ---- MLPs on the hidden states, loss head, MLP backward down to the hidden states ----
@@ -1559,30 +1549,18 @@ int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru
         RSLX_HIP(launch_transpose(tb, s));
       }
       for (int t = T - 1; t >= 0; --t) {
-        GruBwdArgs gb;
-        memset(&gb, 0, sizeof gb);
-        gb.n_nets = 2; gb.nb = nb; gb.done = dones; gb.done_idx = ridx + (size_t)t * nb;
-        GemmBatch bx;
-        bx.count = 2;
+        GruStepBwdArgs sb;
+        memset(&sb, 0, sizeof sb);
+        sb.n_nets = 2; sb.nb = nb; sb.done = dones; sb.done_idx = ridx + (size_t)t * nb;
         for (int k = 0; k < 2; ++k) {
           const rslx_gru& g = *mem[k];
           const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
           const bool last = t == T - 1;
-          gb.net[k] = GruBwdNet{mb[k]->dh + o, last ? nullptr : mb[k]->back, last ? nullptr : mb[k]->direct,
-                                mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3, mb[k]->dgh + o3,
-                                mb[k]->direct, g.hidden};
-          GemmProblem q = blank_problem();
-          q.A = mb[k]->dgh + o3; q.lda = 3 * g.hidden;
-          q.B = mb[k]->whh_t; q.ldb = g.hidden;
-          q.C = mb[k]->back; q.ldc = g.hidden;
-          q.M = nb; q.N = g.hidden; q.K = 3 * g.hidden;
-          q.alpha = 1.f;
-          q.a_vec = aligned16(q.A) ? 1 : 0;
-          q.b_vec = aligned16(q.B) ? 1 : 0;
-          bx.p[k] = q;
+          sb.net[k] = GruBwdNet{mb[k]->dh + o, last ? nullptr : mb[k]->dgh + o3 + (size_t)nb * 3 * H, mb[k]->direct,
+                                mb[k]->whh_t, mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3,
+                                mb[k]->dgh + o3, mb[k]->direct, g.hidden};
         }
-        RSLX_HIP(launch_gru_gates_bwd(gb, s));
-        if (t > 0) RSLX_HIP(launch_gemm(GEMM_DX, bx, s));
+        RSLX_HIP(launch_gru_step_bwd(sb, s));
       }
       {   // weight gradients of both sides of the gates, all steps at once
         GemmBatch bwi, bwh;

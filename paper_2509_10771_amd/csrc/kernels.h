@@ -235,47 +235,52 @@ hipError_t launch_rnd_reward(const float* yp, const float* yt, int32_t N, int32_
 hipError_t launch_fill(float* p, int64_t n, float value, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
-// Gated recurrent unit (recurrent.hip): the element-wise gate stages around the hidden-side contractions.
-//   gi = x W_ih + b_ih, gh = hin W_hh + b_hh ([*, 3H], gate order r, z, n; both from the GEMM kernel)
+// Gated recurrent unit (recurrent.hip), one time step per launch for up to two networks (the actor's and the
+// critic's memory); H % 4 == 0.
+//   gi = x W_ih + b_ih (from the GEMM kernel),  gh = hin W_hh + b_hh   ([*, 3H], gate order r, z, n)
 //   r = sigmoid(gi_r + gh_r), z = sigmoid(gi_z + gh_z), n = tanh(gi_n + r gh_n), h = (1 - z) n + z hin
-// Up to two networks (actor, critic memories) per launch; H % 4 == 0.
+// Forward: gh is formed tile by tile on the matrix cores (and stored when gh_out is set: the backward pass reads
+// it), the gates are the epilogue.
 // ---------------------------------------------------------------------------------------------
 struct GruFwdNet {
   const float* gi;        // [nb, 3H] this step's rows
-  const float* gh;        // [nb, 3H]
   const float* hin;       // [nb, H]
   float* h_out;           // [nb, H]
   float* hin_next;        // [nb, H] or null: h_out * (1 - done), the state the next step starts from
+  const float* w_hh;      // [H, 3H] row-major
+  const float* b_hh;      // [3H]
+  float* gh_out;          // [nb, 3H] or null
   int32_t H;
 };
-struct GruFwdArgs {
+struct GruStepFwdArgs {
   GruFwdNet net[2];
   int32_t n_nets, nb;
   const uint8_t* done;      // episode-end flags (null = none); row i reads done[done_idx ? done_idx[i] : i]
   const int32_t* done_idx;
 };
-hipError_t launch_gru_gates_fwd(const GruFwdArgs& a, hipStream_t stream);
+hipError_t launch_gru_step_fwd(const GruStepFwdArgs& a, hipStream_t stream);
 
-// One step of back-propagation through time, element-wise part: with
-//   dh = dh_ext + (1 - done) (back + direct)        (back/direct: what step t + 1 sent to its input state)
-// it writes dgi = [dr_pre, dz_pre, dn_pre], dgh = [dr_pre, dz_pre, dn_pre r] and direct_out = dh z; the
-// caller then forms back = dgh W_hh^T with the GEMM kernel.
+// One step of back-propagation through time.  back = dgh_next W_hh^T (what step t + 1 sends to its input state
+// through the hidden-side contraction) is formed tile by tile and never stored; with
+//   dh = dh_ext + (1 - done) (back + direct_in)
+// the epilogue writes dgi = [dr_pre, dz_pre, dn_pre], dgh = [dr_pre, dz_pre, dn_pre r] and direct_out = dh z.
 struct GruBwdNet {
   const float* dh_ext;    // [nb, H] gradient arriving from the layers above
-  const float* back;      // [nb, H] or null (last step)
-  const float* direct_in; // [nb, H] or null (last step)
+  const float* dgh_next;  // [nb, 3H] this network's dgh of step t + 1, null on the last step
+  const float* direct_in; // [nb, H] direct_out of step t + 1 (may alias direct_out), unused on the last step
+  const float* whh_t;     // [3H, H] row-major (W_hh transposed)
   const float* gi; const float* gh; const float* hin;
   float* dgi; float* dgh; // [nb, 3H]
   float* direct_out;      // [nb, H]
   int32_t H;
 };
-struct GruBwdArgs {
+struct GruStepBwdArgs {
   GruBwdNet net[2];
   int32_t n_nets, nb;
   const uint8_t* done;      // flags of THIS step (they gate what step t + 1 sends back); null = none
   const int32_t* done_idx;
 };
-hipError_t launch_gru_gates_bwd(const GruBwdArgs& a, hipStream_t stream);
+hipError_t launch_gru_step_bwd(const GruStepBwdArgs& a, hipStream_t stream);
 
 // dst[i, :] = src[idx ? idx[i] : i, :] * (reset && reset[i] ? 0 : 1) for up to two [*, H] matrices; a second
 // copy of the result goes to dst2 when it is not null.

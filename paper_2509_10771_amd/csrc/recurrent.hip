@@ -1,5 +1,6 @@
-// Element-wise stages of the gated recurrent unit (forward gates, back-propagation through time) and the
-// index plumbing of column-wise minibatches.  The contractions around them run in the GEMM kernel.
+// Gated recurrent unit, one time step per launch: the hidden-side contraction on the matrix cores with the gate
+// stage (forward) or the gate derivatives (back-propagation through time) as its epilogue, and the index plumbing
+// of column-wise minibatches.  The input-side contractions and the weight gradients run in the GEMM kernel.
 #include "kernels.h"
 
 namespace rslx {
@@ -18,64 +19,244 @@ __device__ __forceinline__ float tanhf_(float a) {
 __device__ __forceinline__ f4 ld4(const float* p) { return *reinterpret_cast<const f4*>(p); }
 __device__ __forceinline__ void st4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
 
-__global__ __launch_bounds__(256) void gru_gates_fwd_kernel(const GruFwdArgs a) {
-  const GruFwdNet& n = a.net[blockIdx.y];
-  const int H = n.H, q = H >> 2;
-  const long e = (long)blockIdx.x * 256 + threadIdx.x;
-  if (e >= (long)a.nb * q) return;
-  const int i = (int)(e / q), j = (int)(e - (long)i * q) * 4;
-  const float* gi = n.gi + (long)i * 3 * H + j;
-  const float* gh = n.gh + (long)i * 3 * H + j;
-  const f4 gir = ld4(gi), giz = ld4(gi + H), gin = ld4(gi + 2 * H);
-  const f4 ghr = ld4(gh), ghz = ld4(gh + H), ghn = ld4(gh + 2 * H);
-  const f4 hin = ld4(n.hin + (long)i * H + j);
-  float keep = 1.0f;
-  if (n.hin_next != nullptr && a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[i] : i] ? 0.0f : 1.0f;
-  f4 h;
+// ---- fused step kernels ----------------------------------------------------------------------------------
+// A workgroup of 2 x 2 wavefronts owns 32 rows and 32 hidden units: wavefront (wr, wj) takes rows 16 wr .. 16 wr + 15
+// and hidden units 16 wj .. 16 wj + 15 and accumulates NTW tiles of 16 output columns with
+// v_mfma_f32_16x16x4_f32, D[row, col] += sum_k A[row, k] B[k, col(tile)]; the tiles' columns come from `col0[]`
+// (forward: the r, z and n columns of its 16 hidden units; backward: the 16 hidden units themselves).  Accumulator
+// register q of lane l belongs to row 4 * (l / 16) + q and column l % 16 in every tile, so the gate stage finds all
+// its operands in the lane's own registers.  Operands are staged through LDS in chunks of KC contraction steps; the
+// next chunk's global loads are in flight while the current one is multiplied.  One step moves little data per
+// workgroup and every chunk costs a full memory latency, so the chunks are long rather than many, and two
+// wavefronts share each SIMD so that one's LDS reads overlap the other's matrix instructions.
+constexpr int GS_JB = 32;          // hidden units per workgroup
+constexpr int GS_ROWS = 32;        // rows per workgroup
+constexpr int GS_THREADS = 256;
+
+template <int NTW, int KC>
+struct GruTile {
+  static constexpr int NT = 2 * NTW;            // tiles per workgroup: wavefront column wj owns tiles wj * NTW ...
+  static constexpr int APITCH = KC + 4;         // floats per staged A row (16-byte aligned, spreads the banks)
+  static constexpr int COLS = 16 * NT, BPITCH = COLS + 8;
+  static constexpr int A_VECS = GS_ROWS * KC / 4, B_VECS = KC * COLS / 4;
+  static constexpr int A_PER = (A_VECS + GS_THREADS - 1) / GS_THREADS, B_PER = (B_VECS + GS_THREADS - 1) / GS_THREADS;
+  static constexpr int LDS_FLOATS = GS_ROWS * APITCH + KC * BPITCH;
+
+  // acc[u] += A[row0 + 16 wr .., 0 .. K) * B[0 .. K, col0[wj * NTW + u] .. + 16).  Rows >= n_rows read as zero and so
+  // do the columns of tile t from col_end[t] on.  K, lda, ldb, col0[], col_end[] are multiples of 4 and A, B are
+  // 16-byte aligned, so every 16-byte fetch is entirely inside or entirely outside.
+  static __device__ __forceinline__ void mma(const float* __restrict__ A, int lda, int row0, int n_rows,
+                                             const float* __restrict__ B, int ldb, const int (&col0)[NT],
+                                             const int (&col_end)[NT], int K, float* smem, f4 (&acc)[NTW]) {
+    float* As = smem;
+    float* Bs = smem + GS_ROWS * APITCH;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave & 1, wj = wave >> 1;
+    const int m = lane & 15, kq = lane >> 4;
+    // what this lane fetches of every chunk: fixed (row, k offset) pairs of A and (k, column) pairs of B
+    int a_off[A_PER], a_kc[A_PER], b_col[B_PER], b_k[B_PER];
+    bool a_ok[A_PER], b_ok[B_PER];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const float r = sigmoidf_(gir[c] + ghr[c]);
-    const float z = sigmoidf_(giz[c] + ghz[c]);
-    const float nn = tanhf_(gin[c] + r * ghn[c]);
-    h[c] = (1.0f - z) * nn + z * hin[c];
+    for (int i = 0; i < A_PER; ++i) {
+      const int v = tid + i * GS_THREADS;
+      const int r = v / (KC / 4);
+      a_kc[i] = (v % (KC / 4)) * 4;
+      a_ok[i] = v < A_VECS && row0 + r < n_rows;
+      a_off[i] = min(row0 + r, n_rows - 1) * lda;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i) {
+      const int v = tid + i * GS_THREADS;
+      const int c4 = v % (COLS / 4), t = c4 / 4;
+      b_k[i] = v / (COLS / 4);
+      int c0 = col0[0], ce = col_end[0];
+#pragma unroll
+      for (int u = 1; u < NT; ++u) { c0 = t == u ? col0[u] : c0; ce = t == u ? col_end[u] : ce; }
+      const int col = c0 + (c4 % 4) * 4;
+      b_ok[i] = v < B_VECS && col < ce;
+      b_col[i] = b_ok[i] ? col : 0;
+    }
+    // Loads are issued unconditionally from clamped (always valid) addresses and the out-of-range parts are zeroed
+    // only when the chunk is written to LDS, so nothing waits on a load before the chunk is needed.
+    f4 ra[A_PER], rb[B_PER];
+    auto fetch = [&](int k0) {
+#pragma unroll
+      for (int i = 0; i < A_PER; ++i) ra[i] = ld4(A + (long)a_off[i] + min(k0 + a_kc[i], K - 4));
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) rb[i] = ld4(B + (long)min(k0 + b_k[i], K - 1) * ldb + b_col[i]);
+    };
+    auto stage = [&](int k0) {
+#pragma unroll
+      for (int i = 0; i < A_PER; ++i) {
+        const int v = tid + i * GS_THREADS;
+        const f4 x = (a_ok[i] && k0 + a_kc[i] < K) ? ra[i] : f4{0.f, 0.f, 0.f, 0.f};
+        if (A_VECS % GS_THREADS == 0 || v < A_VECS) st4(As + (v / (KC / 4)) * APITCH + a_kc[i], x);
+      }
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) {
+        const int v = tid + i * GS_THREADS;
+        const f4 x = (b_ok[i] && k0 + b_k[i] < K) ? rb[i] : f4{0.f, 0.f, 0.f, 0.f};
+        if (B_VECS % GS_THREADS == 0 || v < B_VECS) st4(Bs + b_k[i] * BPITCH + (v % (COLS / 4)) * 4, x);
+      }
+    };
+    fetch(0);
+    const float* ap = As + (wr * 16 + m) * APITCH + kq;
+    const float* bp = Bs + kq * BPITCH + wj * NTW * 16 + m;
+    for (int k0 = 0; k0 < K; k0 += KC) {
+      __syncthreads();               // the previous chunk has been consumed
+      stage(k0);
+      __syncthreads();
+      fetch(k0 + KC);                // past the end this re-reads the last rows (clamped); never staged
+      __builtin_amdgcn_sched_barrier(0);
+      // operands of contraction step s + 1 are read from LDS while the matrix instructions of step s run
+      float a_cur = ap[0], b_cur[NTW];
+#pragma unroll
+      for (int u = 0; u < NTW; ++u) b_cur[u] = bp[16 * u];
+#pragma unroll
+      for (int s4 = 0; s4 < KC / 4; ++s4) {
+        float a_nxt = 0.f, b_nxt[NTW];
+        if (s4 + 1 < KC / 4) {
+          a_nxt = ap[4 * (s4 + 1)];
+#pragma unroll
+          for (int u = 0; u < NTW; ++u) b_nxt[u] = bp[4 * (s4 + 1) * BPITCH + 16 * u];
+        }
+#pragma unroll
+        for (int u = 0; u < NTW; ++u) acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur, b_cur[u], acc[u], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1 + NTW, 0);    // next step's LDS reads ...
+        __builtin_amdgcn_sched_group_barrier(0x008, NTW, 0);        // ... then this step's matrix instructions
+        if (s4 + 1 < KC / 4) {
+          a_cur = a_nxt;
+#pragma unroll
+          for (int u = 0; u < NTW; ++u) b_cur[u] = b_nxt[u];
+        }
+      }
+    }
   }
-  st4(n.h_out + (long)i * H + j, h);
-  if (n.hin_next != nullptr) st4(n.hin_next + (long)i * H + j, h * keep);
+};
+
+// Workgroup -> (row block, hidden-unit block).  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each
+// with an L2 of its own: all hidden-unit blocks of a row block go to one XCD, so a row block's operand rows are
+// fetched into one L2 only (the weights, shared by every row block, fit in each L2).
+constexpr int GS_XCDS = 8;
+__device__ __forceinline__ void step_block(int H, int& rb, int& jb) {
+  const int jblocks = (H + GS_JB - 1) / GS_JB;
+  const int xcd = (int)blockIdx.x % GS_XCDS, i = (int)blockIdx.x / GS_XCDS;
+  rb = (i / jblocks) * GS_XCDS + xcd;
+  jb = i % jblocks;
 }
 
-__global__ __launch_bounds__(256) void gru_gates_bwd_kernel(const GruBwdArgs a) {
-  const GruBwdNet& n = a.net[blockIdx.y];
-  const int H = n.H, q = H >> 2;
-  const long e = (long)blockIdx.x * 256 + threadIdx.x;
-  if (e >= (long)a.nb * q) return;
-  const int i = (int)(e / q), j = (int)(e - (long)i * q) * 4;
-  const long o = (long)i * H + j, o3 = (long)i * 3 * H + j;
-  f4 dh = ld4(n.dh_ext + o);
-  if (n.back != nullptr) {
-    float keep = 1.0f;
-    if (a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[i] : i] ? 0.0f : 1.0f;
-    dh += (ld4(n.back + o) + ld4(n.direct_in + o)) * keep;
-  }
-  const f4 gir = ld4(n.gi + o3), giz = ld4(n.gi + o3 + H), gin = ld4(n.gi + o3 + 2 * H);
-  const f4 ghr = ld4(n.gh + o3), ghz = ld4(n.gh + o3 + H), ghn = ld4(n.gh + o3 + 2 * H);
-  const f4 hin = ld4(n.hin + o);
-  f4 dr_pre, dz_pre, dn_pre, dn_r, direct;
+__global__ __launch_bounds__(GS_THREADS) void gru_step_fwd_kernel(const GruStepFwdArgs a) {
+  using Tile = GruTile<3, 128>;
+  __shared__ __attribute__((aligned(16))) float smem[Tile::LDS_FLOATS];
+  const int z = blockIdx.y;
+  const GruFwdNet& n = a.net[z];
+  const int H = n.H, nb = a.nb;
+  int rb, jb;
+  step_block(H, rb, jb);
+  const int row0 = rb * GS_ROWS, j0 = jb * GS_JB;
+  if (row0 >= nb) return;
+  int col0[6], col_end[6];      // tile wj * 3 + g: gate g of hidden units j0 + 16 wj ...
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const float r = sigmoidf_(gir[c] + ghr[c]);
-    const float z = sigmoidf_(giz[c] + ghz[c]);
-    const float nn = tanhf_(gin[c] + r * ghn[c]);
-    const float dn = dh[c] * (1.0f - z);
-    const float dz = dh[c] * (hin[c] - nn);
-    direct[c] = dh[c] * z;
-    dn_pre[c] = dn * (1.0f - nn * nn);
-    dr_pre[c] = dn_pre[c] * ghn[c] * r * (1.0f - r);
-    dz_pre[c] = dz * z * (1.0f - z);
-    dn_r[c] = dn_pre[c] * r;
+  for (int t = 0; t < 6; ++t) { col0[t] = (t % 3) * H + j0 + (t / 3) * 16; col_end[t] = (t % 3) * H + H; }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wr = wave & 1, wj = wave >> 1;
+  const int j = j0 + wj * 16 + (lane & 15), jc = min(j, H - 1);
+  const int rbase = row0 + wr * 16 + 4 * (lane >> 4);
+  // the gate stage's own operands do not depend on the contraction: fetch them first (clamped addresses, no
+  // branches) so their latency hides behind it
+  float pgi[4][3], phin[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = min(rbase + q, nb - 1);
+    const long o3 = (long)row * 3 * H + jc;
+    pgi[q][0] = n.gi[o3]; pgi[q][1] = n.gi[o3 + H]; pgi[q][2] = n.gi[o3 + 2 * H];
+    phin[q] = n.hin[(long)row * H + jc];
   }
-  st4(n.dgi + o3, dr_pre); st4(n.dgi + o3 + H, dz_pre); st4(n.dgi + o3 + 2 * H, dn_pre);
-  st4(n.dgh + o3, dr_pre); st4(n.dgh + o3 + H, dz_pre); st4(n.dgh + o3 + 2 * H, dn_r);
-  st4(n.direct_out + o, direct);
+  const float* bh = n.b_hh;
+  const float br = bh[jc], bz = bh[H + jc], bn = bh[2 * H + jc];
+  f4 acc[3];
+#pragma unroll
+  for (int t = 0; t < 3; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
+  Tile::mma(n.hin, H, row0, nb, n.w_hh, 3 * H, col0, col_end, H, smem, acc);
+  if (j >= H) return;
+  float* gh_out = n.gh_out;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = rbase + q;
+    if (row >= nb) continue;
+    const long o = (long)row * H + j, o3 = (long)row * 3 * H + j;
+    const float ghr = acc[0][q] + br, ghz = acc[1][q] + bz, ghn = acc[2][q] + bn;
+    const float r = sigmoidf_(pgi[q][0] + ghr);
+    const float zz = sigmoidf_(pgi[q][1] + ghz);
+    const float nn = tanhf_(pgi[q][2] + r * ghn);
+    const float h = (1.0f - zz) * nn + zz * phin[q];
+    n.h_out[o] = h;
+    if (n.hin_next != nullptr) {
+      float keep = 1.0f;
+      if (a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[row] : row] ? 0.0f : 1.0f;
+      n.hin_next[o] = h * keep;
+    }
+    if (gh_out != nullptr) { gh_out[o3] = ghr; gh_out[o3 + H] = ghz; gh_out[o3 + 2 * H] = ghn; }
+  }
+}
+
+__global__ __launch_bounds__(GS_THREADS) void gru_step_bwd_kernel(const GruStepBwdArgs a) {
+  using Tile = GruTile<1, 128>;
+  __shared__ __attribute__((aligned(16))) float smem[Tile::LDS_FLOATS];
+  const int z = blockIdx.y;
+  const GruBwdNet& n = a.net[z];
+  const int H = n.H, nb = a.nb;
+  int rb, jb;
+  step_block(H, rb, jb);
+  const int row0 = rb * GS_ROWS, j0 = jb * GS_JB;
+  if (row0 >= nb) return;
+  const bool has_next = n.dgh_next != nullptr;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wr = wave & 1, wj = wave >> 1;
+  const int j = j0 + wj * 16 + (lane & 15), jc = min(j, H - 1);
+  const int rbase = row0 + wr * 16 + 4 * (lane >> 4);
+  // the gate stage's own operands, fetched ahead of the contraction (clamped addresses, no branches)
+  float pgi[4][3], pgh[4][3], phin[4], pdh[4], pdir[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = min(rbase + q, nb - 1);
+    const long o = (long)row * H + jc, o3 = (long)row * 3 * H + jc;
+#pragma unroll
+    for (int g = 0; g < 3; ++g) { pgi[q][g] = n.gi[o3 + g * H]; pgh[q][g] = n.gh[o3 + g * H]; }
+    phin[q] = n.hin[o];
+    pdh[q] = n.dh_ext[o];
+    pdir[q] = has_next ? n.direct_in[o] : 0.f;
+  }
+  f4 acc[1] = {f4{0.f, 0.f, 0.f, 0.f}};
+  if (has_next) {
+    const int col0[2] = {j0, j0 + 16}, col_end[2] = {H, H};
+    Tile::mma(n.dgh_next, 3 * H, row0, nb, n.whh_t, H, col0, col_end, 3 * H, smem, acc);
+  }
+  if (j >= H) return;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = rbase + q;
+    if (row >= nb) continue;
+    const long o = (long)row * H + j, o3 = (long)row * 3 * H + j;
+    float dh = pdh[q];
+    if (has_next) {
+      float keep = 1.0f;
+      if (a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[row] : row] ? 0.0f : 1.0f;
+      dh += (acc[0][q] + pdir[q]) * keep;
+    }
+    const float ghn = pgh[q][2];
+    const float r = sigmoidf_(pgi[q][0] + pgh[q][0]);
+    const float zz = sigmoidf_(pgi[q][1] + pgh[q][1]);
+    const float nn = tanhf_(pgi[q][2] + r * ghn);
+    const float dn = dh * (1.0f - zz);
+    const float dz = dh * (phin[q] - nn);
+    const float dn_pre = dn * (1.0f - nn * nn);
+    const float dr_pre = dn_pre * ghn * r * (1.0f - r);
+    const float dz_pre = dz * zz * (1.0f - zz);
+    n.direct_out[o] = dh * zz;
+    n.dgi[o3] = dr_pre; n.dgi[o3 + H] = dz_pre; n.dgi[o3 + 2 * H] = dn_pre;
+    n.dgh[o3] = dr_pre; n.dgh[o3 + H] = dz_pre; n.dgh[o3 + 2 * H] = dn_pre * r;
+  }
 }
 
 __global__ __launch_bounds__(256) void row_gather_kernel(const RowGatherArgs a) {
@@ -107,25 +288,33 @@ __global__ __launch_bounds__(256) void column_rows_kernel(const int32_t* __restr
 
 }  // namespace
 
-hipError_t launch_gru_gates_fwd(const GruFwdArgs& a, hipStream_t stream) {
-  long work = 0;
-  for (int k = 0; k < a.n_nets; ++k) { const long w = (long)a.nb * (a.net[k].H >> 2); work = w > work ? w : work; }
-  if (work == 0) return hipSuccess;
-  double bytes = 0.0;
-  for (int k = 0; k < a.n_nets; ++k) bytes += 4.0 * a.nb * a.net[k].H * (6 + 1 + 1 + (a.net[k].hin_next ? 1 : 0));
-  TraceScope ts(stream, "gru_gates_fwd", 0.0, bytes);
-  hipLaunchKernelGGL(gru_gates_fwd_kernel, dim3((unsigned)((work + 255) / 256), a.n_nets), dim3(256), 0, stream, a);
+static dim3 step_grid(int nb, const int* H, int n_nets) {
+  int blocks = 0;
+  for (int k = 0; k < n_nets; ++k) {
+    const int rblocks = ((nb + GS_ROWS - 1) / GS_ROWS + GS_XCDS - 1) / GS_XCDS * GS_XCDS;   // see step_block
+    const int b = rblocks * ((H[k] + GS_JB - 1) / GS_JB);
+    blocks = b > blocks ? b : blocks;
+  }
+  return dim3(blocks, n_nets);
+}
+
+hipError_t launch_gru_step_fwd(const GruStepFwdArgs& a, hipStream_t stream) {
+  if (a.nb <= 0 || a.n_nets <= 0) return hipSuccess;
+  int H[2] = {a.net[0].H, a.net[1].H};
+  double flops = 0.0;
+  for (int k = 0; k < a.n_nets; ++k) flops += 2.0 * a.nb * H[k] * 3.0 * H[k];
+  TraceScope ts(stream, "gru_step_fwd", flops, 0.0);
+  hipLaunchKernelGGL(gru_step_fwd_kernel, step_grid(a.nb, H, a.n_nets), dim3(GS_THREADS), 0, stream, a);
   return hipGetLastError();
 }
 
-hipError_t launch_gru_gates_bwd(const GruBwdArgs& a, hipStream_t stream) {
-  long work = 0;
-  for (int k = 0; k < a.n_nets; ++k) { const long w = (long)a.nb * (a.net[k].H >> 2); work = w > work ? w : work; }
-  if (work == 0) return hipSuccess;
-  double bytes = 0.0;
-  for (int k = 0; k < a.n_nets; ++k) bytes += 4.0 * a.nb * a.net[k].H * (6 + 2 + (a.net[k].back ? 2 : 0) + 6 + 1);
-  TraceScope ts(stream, "gru_gates_bwd", 0.0, bytes);
-  hipLaunchKernelGGL(gru_gates_bwd_kernel, dim3((unsigned)((work + 255) / 256), a.n_nets), dim3(256), 0, stream, a);
+hipError_t launch_gru_step_bwd(const GruStepBwdArgs& a, hipStream_t stream) {
+  if (a.nb <= 0 || a.n_nets <= 0) return hipSuccess;
+  int H[2] = {a.net[0].H, a.net[1].H};
+  double flops = 0.0;
+  for (int k = 0; k < a.n_nets; ++k) flops += a.net[k].dgh_next ? 2.0 * a.nb * H[k] * 3.0 * H[k] : 0.0;
+  TraceScope ts(stream, "gru_step_bwd", flops, 0.0);
+  hipLaunchKernelGGL(gru_step_bwd_kernel, step_grid(a.nb, H, a.n_nets), dim3(GS_THREADS), 0, stream, a);
   return hipGetLastError();
 }
 
