@@ -31,4 +31,7 @@ tests/test_oracle_*.py):
   recurrent.act / minibatch_loss_and_grads / ppo_update
                                           pinned (act == sequence re-run, on-policy identities, finite
                                           differences of the scalar loss, column-wise minibatches)
+  recurrent.bc_collect_step / bc_minibatch_loss_and_grad / bc_update
+                                          pinned (zero loss on the student's own roll-out, finite
+                                          differences, memory-free special case == bc.bc_loss_and_grad)
 """

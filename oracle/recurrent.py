@@ -17,13 +17,18 @@ shuffled per epoch); each is re-run through the memory from its stored h0 with t
 into the hidden states and from there through time (truncated at the roll-out start, never across an episode
 boundary).  One gradient norm over all four parameter sets, one Adam step counter.
 
+Distillation with a recurrent student (Sec. 2.1 with Sec. 3): the student, a GRU memory in front of an MLP, is
+rolled out with its state carried and reset like the actor's; the expert's actions on the visited states are the
+targets; the update regresses the student's outputs on them over whole environment columns with the same
+back-propagation through time (bc_* functions below).
+
 A network's flat parameter vector is the GRU layout followed by the MLP layout (log_std last for the actor).
 
 Oracle code: test infrastructure only.
 """
 import numpy as np
 
-from . import gru, adam, rng
+from . import gru, mlp, adam, rng
 from . import ppo as _ppo
 
 
@@ -102,3 +107,54 @@ def ppo_update(actor, critic, D_a, D_c, H, dims_a, dims_c, rollout, cfg, opt, re
                           terms["clip_frac"], 0.0, 0.0])
     return dict(actor=actor, critic=critic, opt=opt, stats=np.array(stats), g_actor=g_a, g_critic=g_c,
                 perms=np.array(perms), trace=trace)
+
+
+def bc_collect_step(student, D, H, dims_s, obs_s, h, reset, alpha=1.0):
+    """One collection step of a recurrent student: (mean action, new state, state the step started from)."""
+    g, m = split(student, D, H)
+    hin = np.asarray(h, np.float64) * (1.0 - np.asarray(reset, np.float64))[:, None]
+    h_new, _ = gru.cell(gru.unpack(g, D, H), obs_s, hin)
+    a, _ = mlp.forward(mlp.unpack(m, dims_s), h_new, alpha)
+    return a, h_new, hin
+
+
+def bc_minibatch_loss_and_grad(student, D, H, dims_s, batch, alpha=1.0):
+    """batch: obs [T, nb, D], targets [T, nb, A], dones [T, nb], h0 [nb, H].
+    L = mean over the T * nb rows and the A action dims of (student - target)^2; returns (L, flat gradient)."""
+    g, m = split(student, D, H)
+    pg, layers = gru.unpack(g, D, H), mlp.unpack(m, dims_s)
+    dones = np.asarray(batch["dones"])
+    T, nb = dones.shape
+    Hs, cache_g = gru.sequence_forward(pg, batch["obs"], batch["h0"], dones)
+    y, cache_m = mlp.forward(layers, Hs.reshape(T * nb, H), alpha)
+    diff = y - np.asarray(batch["targets"], np.float64).reshape(T * nb, -1)
+    grads_m, dH = mlp.backward(layers, cache_m, 2.0 * diff / diff.size, alpha)
+    g_g, _ = gru.sequence_backward(pg, cache_g, dones, dH.reshape(T, nb, H))
+    return float(np.mean(diff ** 2)), np.concatenate([g_g, mlp.pack(grads_m)])
+
+
+def bc_update(student, D, H, dims_s, rollout, cfg, opt, record=False):
+    """E epochs x M minibatches of whole environment columns; cfg is an oracle.bc.BCConfig.
+    rollout: obs [T, N, D], targets [T, N, A], dones [T, N], h0 [N, H].  opt: m, v, step."""
+    student = np.asarray(student, np.float64).copy()
+    opt = {k: (np.asarray(v, np.float64).copy() if k != "step" else int(v)) for k, v in opt.items()}
+    N = np.asarray(rollout["dones"]).shape[1]
+    assert N % cfg.minibatches == 0
+    nb = N // cfg.minibatches
+    stats, trace = [], []
+    g = None
+    for e in range(cfg.epochs):
+        perm = rng.permutation(cfg.seed, cfg.call_index, e + cfg.epoch_offset, N)
+        for m in range(cfg.minibatches):
+            envs = perm[m * nb:(m + 1) * nb]
+            batch = {k: (np.asarray(v)[envs] if k == "h0" else np.asarray(v)[:, envs]) for k, v in rollout.items()}
+            before = dict(student=student.copy(), opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()}) if record else None
+            loss, g = bc_minibatch_loss_and_grad(student, D, H, dims_s, batch, cfg.elu_alpha)
+            norm = adam.global_norm([g])
+            s = adam.clip_scale(norm, cfg.max_grad_norm)
+            student, opt["m"], opt["v"], opt["step"] = adam.adam_step(student, s * g, opt["m"], opt["v"], opt["step"], cfg.lr,
+                                                                      cfg.beta1, cfg.beta2, cfg.adam_eps)
+            if record:
+                trace.append(dict(envs=envs, before=before, g=g, student=student.copy()))
+            stats.append([loss, norm])
+    return dict(student=student, opt=opt, stats=np.array(stats), g=g, trace=trace)

@@ -1341,15 +1341,15 @@ struct RnnPlan {
   size_t bytes = 0;
 };
 
-void carve_memory(Carver& c, const rslx_gru& g, int32_t rows, int32_t nb, RnnBufs& b) {
+void carve_memory(Carver& c, const rslx_gru& g, int32_t rows, int32_t nb, RnnBufs& b, int group = 2) {
   const size_t H = g.hidden;
   b.gi = c.take<float>(rows * 3 * H); b.gh = c.take<float>(rows * 3 * H);
   b.dgi = c.take<float>(rows * 3 * H); b.dgh = c.take<float>(rows * 3 * H);
   b.hin = c.take<float>(rows * H); b.hs = c.take<float>(rows * H); b.dh = c.take<float>(rows * H);
   b.direct = c.take<float>(nb * H);
   b.whh_t = c.take<float>(3 * H * H);
-  plan_layer(b.plan, 0, g.in_dim, 3 * g.hidden, rows, 2, false);
-  plan_layer(b.plan, 1, g.hidden, 3 * g.hidden, rows, 2, false);
+  plan_layer(b.plan, 0, g.in_dim, 3 * g.hidden, rows, group, false);
+  plan_layer(b.plan, 1, g.hidden, 3 * g.hidden, rows, group, false);
   b.partials = c.take<float>((size_t)b.plan.total);
 }
 
@@ -1416,6 +1416,81 @@ GemmProblem gate_dw_problem(const XView& x, int M, const float* dG, int H3, int3
   return p;
 }
 
+// Memories forward over one column-wise minibatch: the input-side gates of all T steps in one GEMM (rows gathered
+// from the roll-out through ridx), then one fused step launch per time step for all `count` memories.
+int32_t memories_forward(const rslx_gru* const* mem, RnnBufs* const* mb, int count, const float* const* obs,
+                         const float* const* h0, const int32_t* envs, const int32_t* ridx, const uint8_t* dones, int T,
+                         int nb, int N, hipStream_t s) {
+  const int rows = T * nb;
+  RowGatherArgs rg;
+  memset(&rg, 0, sizeof rg);
+  rg.n_jobs = count; rg.nb = nb; rg.idx = envs;
+  for (int k = 0; k < count; ++k) rg.job[k] = RowGatherJob{h0[k], mb[k]->hin, nullptr, mem[k]->hidden};
+  RSLX_HIP(launch_row_gather(rg, s));
+  GemmBatch bi;
+  bi.count = count;
+  for (int k = 0; k < count; ++k) {
+    XView x;
+    x.base = obs[k]; x.ld = mem[k]->in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * N;
+    bi.p[k] = gate_problem(x, mem[k]->in_dim, mem[k]->params, mem[k]->params + gru_off_bih(*mem[k]), mb[k]->gi, rows,
+                           3 * mem[k]->hidden);
+  }
+  RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
+  for (int t = 0; t < T; ++t) {
+    GruStepFwdArgs sa;
+    memset(&sa, 0, sizeof sa);
+    sa.n_nets = count; sa.nb = nb; sa.done = dones; sa.done_idx = ridx + (size_t)t * nb;
+    for (int k = 0; k < count; ++k) {
+      const rslx_gru& g = *mem[k];
+      const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
+      sa.net[k] = GruFwdNet{mb[k]->gi + o3, mb[k]->hin + o, mb[k]->hs + o,
+                            t + 1 < T ? mb[k]->hin + o + (size_t)nb * H : nullptr, g.params + gru_off_whh(g),
+                            g.params + gru_off_bhh(g), mb[k]->gh + o3, g.hidden};
+    }
+    RSLX_HIP(launch_gru_step_fwd(sa, s));
+  }
+  return RSLX_OK;
+}
+
+// Back-propagation through time from mb[k]->dh (the gradient w.r.t. every step's new state): one fused step launch
+// per time step, last to first, then the weight gradients of both sides of the gates over all steps at once
+// (split partials, to be summed by the caller's reduction).
+int32_t memories_backward(const rslx_gru* const* mem, RnnBufs* const* mb, int count, const float* const* obs,
+                          const int32_t* ridx, const uint8_t* dones, int T, int nb, int N, hipStream_t s) {
+  const int rows = T * nb;
+  TransposeBatch tb;
+  tb.count = count;
+  for (int k = 0; k < count; ++k)
+    tb.job[k] = TransposeJob{mem[k]->params + gru_off_whh(*mem[k]), mb[k]->whh_t, mem[k]->hidden, 3 * mem[k]->hidden};
+  RSLX_HIP(launch_transpose(tb, s));
+  for (int t = T - 1; t >= 0; --t) {
+    GruStepBwdArgs sb;
+    memset(&sb, 0, sizeof sb);
+    sb.n_nets = count; sb.nb = nb; sb.done = dones; sb.done_idx = ridx + (size_t)t * nb;
+    for (int k = 0; k < count; ++k) {
+      const rslx_gru& g = *mem[k];
+      const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
+      const bool last = t == T - 1;
+      sb.net[k] = GruBwdNet{mb[k]->dh + o, last ? nullptr : mb[k]->dgh + o3 + (size_t)nb * 3 * H, mb[k]->direct,
+                            mb[k]->whh_t, mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3,
+                            mb[k]->dgh + o3, mb[k]->direct, g.hidden};
+    }
+    RSLX_HIP(launch_gru_step_bwd(sb, s));
+  }
+  GemmBatch bwi, bwh;
+  bwi.count = bwh.count = count;
+  for (int k = 0; k < count; ++k) {
+    const rslx_gru& g = *mem[k];
+    XView x;
+    x.base = obs[k]; x.ld = g.in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * N;
+    bwi.p[k] = gate_dw_problem(x, g.in_dim, mb[k]->dgi, 3 * g.hidden, rows, *mb[k], 0);
+    bwh.p[k] = gate_dw_problem(plain_view(mb[k]->hin, g.hidden), g.hidden, mb[k]->dgh, 3 * g.hidden, rows, *mb[k], 1);
+  }
+  RSLX_HIP(launch_gemm(GEMM_DW, bwi, s));
+  RSLX_HIP(launch_gemm(GEMM_DW, bwh, s));
+  return RSLX_OK;
+}
+
 void reduce_add_memory(ReduceArgs& a, const rslx_gru& g, const RnnBufs& b) {
   for (int l = 0; l < 2; ++l) {
     ReduceSeg& sg = a.seg[a.n_seg++];
@@ -1476,36 +1551,7 @@ int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru
       const int32_t* ridx = p.rows_all + ((size_t)e * cfg->minibatches + m) * rows;
       float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
 
-      // ---- memories forward: input-side gates for all steps at once, then step by step ----
-      {
-        RowGatherArgs rg;
-        memset(&rg, 0, sizeof rg);
-        rg.n_jobs = 2; rg.nb = nb; rg.idx = envs;
-        for (int k = 0; k < 2; ++k) rg.job[k] = RowGatherJob{h0[k], mb[k]->hin, nullptr, mem[k]->hidden};
-        RSLX_HIP(launch_row_gather(rg, s));
-        GemmBatch bi;
-        bi.count = 2;
-        for (int k = 0; k < 2; ++k) {
-          XView x;
-          x.base = obs[k]; x.ld = mem[k]->in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * p.N;
-          bi.p[k] = gate_problem(x, mem[k]->in_dim, mem[k]->params, mem[k]->params + gru_off_bih(*mem[k]), mb[k]->gi, rows,
-                                 3 * mem[k]->hidden);
-        }
-        RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
-      }
-      for (int t = 0; t < T; ++t) {
-        GruStepFwdArgs sa;
-        memset(&sa, 0, sizeof sa);
-        sa.n_nets = 2; sa.nb = nb; sa.done = dones; sa.done_idx = ridx + (size_t)t * nb;
-        for (int k = 0; k < 2; ++k) {
-          const rslx_gru& g = *mem[k];
-          const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
-          sa.net[k] = GruFwdNet{mb[k]->gi + o3, mb[k]->hin + o, mb[k]->hs + o,
-                                t + 1 < T ? mb[k]->hin + o + (size_t)nb * H : nullptr, g.params + gru_off_whh(g),
-                                g.params + gru_off_bhh(g), mb[k]->gh + o3, g.hidden};
-        }
-        RSLX_HIP(launch_gru_step_fwd(sa, s));
-      }
+      RSLX_TRY(memories_forward(mem, mb, 2, obs, h0, envs, ridx, dones, T, nb, p.N, s));
 
       // ---- MLPs on the hidden states, loss head, MLP backward down to the hidden states ----
       XView xa = plain_view(p.ma.hs, gru_actor->hidden), xc = plain_view(p.mc.hs, gru_critic->hidden);
@@ -1540,41 +1586,7 @@ int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru
                       BwdJob{critic, xc, rows, &p.critic.act, p.critic.d_out, p.critic.wt, p.critic.partials, &p.critic.plan, p.mc.dh}};
       RSLX_TRY(backward_nets(bj, 2, s, p.fused_head));
 
-      // ---- back-propagation through time ----
-      {
-        TransposeBatch tb;
-        tb.count = 2;
-        for (int k = 0; k < 2; ++k)
-          tb.job[k] = TransposeJob{mem[k]->params + gru_off_whh(*mem[k]), mb[k]->whh_t, mem[k]->hidden, 3 * mem[k]->hidden};
-        RSLX_HIP(launch_transpose(tb, s));
-      }
-      for (int t = T - 1; t >= 0; --t) {
-        GruStepBwdArgs sb;
-        memset(&sb, 0, sizeof sb);
-        sb.n_nets = 2; sb.nb = nb; sb.done = dones; sb.done_idx = ridx + (size_t)t * nb;
-        for (int k = 0; k < 2; ++k) {
-          const rslx_gru& g = *mem[k];
-          const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
-          const bool last = t == T - 1;
-          sb.net[k] = GruBwdNet{mb[k]->dh + o, last ? nullptr : mb[k]->dgh + o3 + (size_t)nb * 3 * H, mb[k]->direct,
-                                mb[k]->whh_t, mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3,
-                                mb[k]->dgh + o3, mb[k]->direct, g.hidden};
-        }
-        RSLX_HIP(launch_gru_step_bwd(sb, s));
-      }
-      {   // weight gradients of both sides of the gates, all steps at once
-        GemmBatch bwi, bwh;
-        bwi.count = bwh.count = 2;
-        for (int k = 0; k < 2; ++k) {
-          const rslx_gru& g = *mem[k];
-          XView x;
-          x.base = obs[k]; x.ld = g.in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * p.N;
-          bwi.p[k] = gate_dw_problem(x, g.in_dim, mb[k]->dgi, 3 * g.hidden, rows, *mb[k], 0);
-          bwh.p[k] = gate_dw_problem(plain_view(mb[k]->hin, g.hidden), g.hidden, mb[k]->dgh, 3 * g.hidden, rows, *mb[k], 1);
-        }
-        RSLX_HIP(launch_gemm(GEMM_DW, bwi, s));
-        RSLX_HIP(launch_gemm(GEMM_DW, bwh, s));
-      }
+      RSLX_TRY(memories_backward(mem, mb, 2, obs, ridx, dones, T, nb, p.N, s));
       {   // one launch: every split sum and the loss head's sums
         ReduceArgs ra;
         memset(&ra, 0, sizeof ra);

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import gru, mlp, recurrent, ppo, rng
+from oracle import gru, mlp, recurrent, ppo, rng, bc
 
 
 def _rand_gru(g, D, H, scale=0.5):
@@ -246,3 +246,61 @@ def test_recurrent_update_minibatches_are_whole_environment_columns():
     g1 = res2["trace"][0]["g_actor"]
     big = np.abs(g1) > 1e-6
     np.testing.assert_allclose(step1[big], -1e-3 * np.sign(g1[big]), rtol=1e-3)
+
+
+def _tiny_distill(seed=8, T=6, N=8, D=4, H=6, A=3, hidden=(7,)):
+    g = np.random.default_rng(seed)
+    dims = (H,) + hidden + (A,)
+    student = np.concatenate([_rand_gru(g, D, H), 0.4 * g.standard_normal(mlp.n_params(dims))])
+    obs = g.standard_normal((T, N, D))
+    dones = (g.random((T, N)) < 0.25).astype(np.uint8)
+    return dict(student=student, D=D, H=H, dims=dims, T=T, N=N, A=A,
+                ro=dict(obs=obs, targets=g.standard_normal((T, N, A)), dones=dones, h0=0.3 * g.standard_normal((N, H))))
+
+
+def test_recurrent_bc_zero_loss_on_own_rollout_and_finite_differences():
+    P = _tiny_distill()
+    D, H, ro = P["D"], P["H"], P["ro"]
+    # targets = what the student itself outputs when stepped through the roll-out with resets: zero loss, zero gradient
+    h, reset, outs = ro["h0"], np.zeros(P["N"]), []
+    for t in range(P["T"]):
+        a, h, hin = recurrent.bc_collect_step(P["student"], D, H, P["dims"], ro["obs"][t], h, reset)
+        if t == 0:
+            assert np.array_equal(hin, ro["h0"])
+        outs.append(a); reset = ro["dones"][t]
+    own = dict(ro, targets=np.stack(outs))
+    loss, grad = recurrent.bc_minibatch_loss_and_grad(P["student"], D, H, P["dims"], own)
+    assert loss < 1e-28 and np.abs(grad).max() < 1e-13
+    # finite differences of the scalar loss on random targets
+    loss, grad = recurrent.bc_minibatch_loss_and_grad(P["student"], D, H, P["dims"], ro)
+    g = np.random.default_rng(0)
+    f = lambda s: recurrent.bc_minibatch_loss_and_grad(s, D, H, P["dims"], ro)[0]
+    for k in g.choice(P["student"].size, 40, replace=False):
+        d = np.zeros_like(P["student"]); d[k] = 1e-6
+        fd = (f(P["student"] + d) - f(P["student"] - d)) / 2e-6
+        assert abs(fd - grad[k]) <= 1e-6 * max(1e-2, abs(fd)), (k, fd, grad[k])
+    # without a memory effect (update gate shut: h' = n, reset gate shut: hidden side dropped) the loss is that of a
+    # feed-forward net tanh(x W_in + b_in) -> MLP, which oracle.bc covers
+    W_ih, b_ih, W_hh, b_hh = gru.unpack(P["student"][:gru.n_params(D, H)], D, H)
+    b_ih = b_ih.copy(); b_ih[:2 * H] = -60.0
+    frozen = np.concatenate([gru.pack(W_ih, b_ih, W_hh, b_hh), P["student"][gru.n_params(D, H):]])
+    loss_r, _ = recurrent.bc_minibatch_loss_and_grad(frozen, D, H, P["dims"], ro)
+    feat = np.tanh(ro["obs"].reshape(-1, D) @ W_ih[:, 2 * H:] + b_ih[2 * H:])
+    loss_f, _ = bc.bc_loss_and_grad(P["student"][gru.n_params(D, H):], P["dims"], feat, ro["targets"].reshape(-1, P["A"]))
+    assert abs(loss_r - loss_f) < 1e-12
+
+
+def test_recurrent_bc_update_columns_and_first_step():
+    P = _tiny_distill(seed=9)
+    n = P["student"].size
+    cfg = bc.BCConfig(epochs=2, minibatches=4, lr=1e-3, seed=4, call_index=1)
+    res = recurrent.bc_update(P["student"], P["D"], P["H"], P["dims"], P["ro"], cfg, dict(m=np.zeros(n), v=np.zeros(n), step=0), record=True)
+    assert res["opt"]["step"] == 8 and res["stats"].shape == (8, 2)
+    perm = rng.permutation(4, 1, 1, P["N"])
+    assert np.array_equal(res["trace"][6]["envs"], perm[4:6])
+    tr = res["trace"][0]
+    sub = {k: (v[tr["envs"]] if k == "h0" else v[:, tr["envs"]]) for k, v in P["ro"].items()}
+    loss, g = recurrent.bc_minibatch_loss_and_grad(P["student"], P["D"], P["H"], P["dims"], sub)
+    assert abs(loss - res["stats"][0, 0]) < 1e-14
+    big = np.abs(g) > 1e-4          # Adam's first step is lr * g / (|g| + eps): within 1e-3 of lr * sign(g) there
+    np.testing.assert_allclose((tr["student"] - P["student"])[big], -1e-3 * np.sign(g[big]), rtol=1e-3)
