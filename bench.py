@@ -217,12 +217,19 @@ def distill_iteration(args, rx, torch, np, w, inp):
     dev = lambda x: torch.as_tensor(np.ascontiguousarray(x)).cuda()
     student = rx.Mlp(w.dims_student, dev(inp["student"]), trainable=True)
     teacher = rx.Mlp(w.dims_actor, dev(inp["teacher"]))
+    rec = w.student_memory > 0          # recurrent student: a GRU memory in front of the MLP, column-wise minibatches
+    if rec:
+        H = w.student_memory
+        gru = rx.Gru(w.student_obs, H, dev(inp["gru_student"]), trainable=True)
+        h, h0, reset0, dones = dev(inp["h_student"]), torch.empty(N, H, device="cuda"), dev(inp["reset0"]), dev(inp["dones"])
+        sws = rx.workspace(rx.rslx_gru_step_workspace_bytes(gru, N))
     obs_s, obs_t = dev(inp["obs_student"]), dev(inp["obs"][:T])
     actions, targets = torch.empty(T, N, A, device="cuda"), torch.empty(T, N, A, device="cuda")
     cfg_kw = dict(lr=w.lr, epochs=w.epochs, minibatches=w.minibatches, seed=20250910)
     stats = torch.zeros(w.epochs * w.minibatches, rx.NSTATS, device="cuda")
     cws = rx.workspace(rx.rslx_bc_collect_workspace_bytes(student, teacher, N))
-    uws = rx.workspace(rx.rslx_bc_update_workspace_bytes(student, None, B, rx.BcCfg(**cfg_kw)))
+    uws = rx.workspace(rx.rslx_bc_update_recurrent_workspace_bytes(gru, student, T, N, rx.BcCfg(**cfg_kw)) if rec
+                       else rx.rslx_bc_update_workspace_bytes(student, None, B, rx.BcCfg(**cfg_kw)))
     adam_step = ctypes.c_int64(0)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
@@ -231,10 +238,18 @@ def distill_iteration(args, rx, torch, np, w, inp):
         if timed:
             e[0].record()
         for t in range(T):
-            rx.rslx_bc_collect(student, teacher, obs_s[t], obs_t[t], N, actions[t], targets[t], cws)
+            if rec:
+                reset = dones[t - 1] if t > 0 else (reset0 if it == 0 else dones[T - 1])
+                rx.rslx_gru_step(gru, obs_s[t], N, h, reset, h0 if t == 0 else None, sws)
+                rx.rslx_bc_collect(student, teacher, h, obs_t[t], N, actions[t], targets[t], cws)
+            else:
+                rx.rslx_bc_collect(student, teacher, obs_s[t], obs_t[t], N, actions[t], targets[t], cws)
         if timed:
             e[1].record()
-        if ctr is None:
+        if rec:
+            rx.rslx_bc_update_recurrent(gru, student, obs_s, targets, dones, h0, T, N, rx.BcCfg(call_index=it, **cfg_kw),
+                                        adam_step, stats, uws)
+        elif ctr is None:
             rx.rslx_bc_update(student, None, obs_s, None, targets, B, rx.BcCfg(call_index=it, **cfg_kw), adam_step, stats, uws)
         else:
             rx.rslx_bc_update_dc(student, None, obs_s, None, targets, B, rx.BcCfg(**cfg_kw), ctr, stats, uws)
@@ -261,7 +276,7 @@ def distill_iteration(args, rx, torch, np, w, inp):
         traced_ms = (time.perf_counter() - t2) * 1e3 / args.steps
         roofline, breakdown = summarize_trace(rx.rslx_trace_end(), w, args.steps)
     graph_ms = None
-    if not args.no_graph:
+    if not args.no_graph and not rec:
         ctr = rx.dev_counters(call_index=args.warmup + 2 * args.steps, adam_step=adam_step.value)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
@@ -278,14 +293,19 @@ def distill_iteration(args, rx, torch, np, w, inp):
     fwd = lambda dims: sum(2 * i * o for i, o in zip(dims[:-1], dims[1:]))
     upd_flops = (3 * fwd(w.dims_student) - 2 * w.dims_student[0] * w.dims_student[1]) * B * w.epochs
     col_flops = (fwd(w.dims_student) + fwd(w.dims_actor)) * B
+    if rec:
+        D = w.student_obs
+        upd_flops = (3 * fwd(w.dims_student) + 2 * (D + H) * 3 * H + 2 * D * 3 * H + 4 * H * 3 * H) * B * w.epochs
+        col_flops += 2 * (D + H) * 3 * H * B
     return {
         "metric": "BC (distillation) transitions/sec: collection (student acts, teacher relabels) + update, 1 GPU",
         "value": round(B / (ms_per_step * 1e-3), 1),
         "unit": "transitions/s (whole iteration: %d collect + %dx%d BC update)" % (T, w.epochs, w.minibatches),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: N=%d envs, T=%d, teacher %s, student %s ELU, %d epochs x %d minibatches"
-                   % (w.name, N, T, list(w.dims_actor), list(w.dims_student), w.epochs, w.minibatches)},
+        "config": {"workload": "%s: N=%d envs, T=%d, teacher %s, student %s%s ELU, %d epochs x %d minibatches"
+                   % (w.name, N, T, list(w.dims_actor), "GRU %d + MLP " % w.student_memory if rec else "", list(w.dims_student),
+                      w.epochs, w.minibatches)},
         "phase_ms": {k: round(v, 4) for k, v in med.items()},
         "collect_tflops": round(col_flops / (med["collect"] * 1e-3) / 1e12, 2),
         "update_tflops": round(upd_flops / (med["update"] * 1e-3) / 1e12, 2),

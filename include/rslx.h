@@ -324,6 +324,30 @@ int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru
                                   int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
                                   void* stream);
 
+/* One step of a single memory (the recurrent student of the distillation loop, paper Sec. 2.1 with
+ * Sec. 3): hin = reset[n] ? 0 : h[n];  h[n] <- GRU(obs[n], hin), in place; h0_out (optional)
+ * receives hin.  The student's action and the expert's label then come from
+ * rslx_bc_collect(student_mlp, teacher, h, obs_teacher, ...). */
+size_t rslx_gru_step_workspace_bytes(const rslx_gru* gru, int32_t N);
+int32_t rslx_gru_step(const rslx_gru* gru, const float* obs, int32_t N, float* h,
+                      const uint8_t* reset_or_null, float* h0_out, void* ws, size_t ws_bytes,
+                      void* stream);
+
+/* Behaviour cloning of a recurrent student (GRU memory + MLP, student->dims[0] == gru->hidden) on
+ * a roll-out: obs_student [T, N, Ds], targets [T, N, A] (the expert's actions on the visited
+ * states), dones uint8 [T, N], h0 [N, H] (the state the roll-out's first step started from); all
+ * device.  Minibatches are whole environment columns as in rslx_ppo_update_recurrent (cfg's
+ * permutation stream over N; N % minibatches != 0 is RSLX_ERR_SHAPE); per minibatch
+ * L = mean over the T * N / minibatches rows and the A action dims of (student - target)^2,
+ * back-propagated through the MLP and through time, optional clip, Adam (one step counter for
+ * memory and MLP).  stats as in rslx_bc_update. */
+size_t rslx_bc_update_recurrent_workspace_bytes(const rslx_gru* gru, const rslx_mlp* student, int32_t T,
+                                                int32_t N, const rslx_bc_cfg* cfg);
+int32_t rslx_bc_update_recurrent(rslx_gru* gru, rslx_mlp* student, const float* obs_student,
+                                 const float* targets, const uint8_t* dones, const float* h0, int32_t T,
+                                 int32_t N, const rslx_bc_cfg* cfg, int64_t* adam_step, float* stats,
+                                 void* ws, size_t ws_bytes, void* stream);
+
 /* ---- behaviour cloning update (paper Sec. 2.1) ---------------------------------------- */
 
 /* targets = teacher(obs_teacher) (once; or the caller's precomputed `targets_or_null` [B, A]);

@@ -13,7 +13,8 @@ __all__ = [
     "ACT_DETERMINISTIC", "ACT_VALUES_ONLY", "EXPORTS", "rslx_trace_begin", "rslx_trace_end",
     "dev_counters", "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes",
     "rslx_bc_collect", "Gru", "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent",
-    "rslx_ppo_update_recurrent_workspace_bytes", "rslx_ppo_update_recurrent",
+    "rslx_ppo_update_recurrent_workspace_bytes", "rslx_ppo_update_recurrent", "rslx_gru_step_workspace_bytes",
+    "rslx_gru_step", "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
 ]
 
 MAX_LAYERS = 8
@@ -28,7 +29,8 @@ EXPORTS = [
     "rslx_bc_update", "rslx_sym_augment", "rslx_rnd_workspace_bytes", "rslx_rnd", "rslx_trace_begin", "rslx_trace_end",
     "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes", "rslx_bc_collect",
     "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent", "rslx_ppo_update_recurrent_workspace_bytes",
-    "rslx_ppo_update_recurrent",
+    "rslx_ppo_update_recurrent", "rslx_gru_step_workspace_bytes", "rslx_gru_step",
+    "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
 ]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librslx.so")
@@ -136,6 +138,11 @@ _sig("rslx_ppo_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CGru), _P(_CM
                                                                _P(_CPpoCfg)])
 _sig("rslx_ppo_update_recurrent", C.c_int32, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), _P(_CRollout), _vp, _vp, _vp,
                                               _P(_CPpoCfg), _P(C.c_int64), _vp, _vp, C.c_size_t, _vp])
+_sig("rslx_gru_step_workspace_bytes", C.c_size_t, [_P(_CGru), C.c_int32])
+_sig("rslx_gru_step", C.c_int32, [_P(_CGru), _vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_size_t, _vp])
+_sig("rslx_bc_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CGru), _P(_CMlp), C.c_int32, C.c_int32, _P(_CBcCfg)])
+_sig("rslx_bc_update_recurrent", C.c_int32, [_P(_CGru), _P(_CMlp), _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, _P(_CBcCfg),
+                                             _P(C.c_int64), _vp, _vp, C.c_size_t, _vp])
 _sig("rslx_sym_augment", C.c_int32, [_P(_CSym), _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, _vp])
 _sig("rslx_rnd_workspace_bytes", C.c_size_t, [_P(_CMlp), C.c_int32])
 _sig("rslx_rnd", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, C.c_int32, C.c_int32, _vp, C.c_int32, _vp, C.c_float, C.c_int32,
@@ -437,6 +444,29 @@ def rslx_ppo_update_recurrent(gru_actor, actor, gru_critic, critic, rollout, don
                                          _ptr(dones), _ptr(h0_actor), _ptr(h0_critic), _ref(cfg.c), C.byref(adam_step),
                                          _ptr(stats), _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
            "rslx_ppo_update_recurrent")
+
+
+def rslx_gru_step_workspace_bytes(gru, N):
+    return lib.rslx_gru_step_workspace_bytes(_ref(gru.c), N)
+
+
+def rslx_gru_step(gru, obs, N, h, reset, h0_out, ws):
+    _check(lib.rslx_gru_step(_ref(gru.c), _ptr(obs), N, _ptr(h), _ptr(reset), _ptr(h0_out), _ptr(ws),
+                             ws.numel() if ws is not None else 0, _stream()), "rslx_gru_step")
+
+
+def rslx_bc_update_recurrent_workspace_bytes(gru, student, T, N, cfg):
+    n = lib.rslx_bc_update_recurrent_workspace_bytes(_ref(gru.c), _ref(student.c), T, N, _ref(cfg.c))
+    if n == 0:
+        raise RslxError("rslx_bc_update_recurrent_workspace_bytes: %s" % lib.rslx_last_error().decode())
+    return n
+
+
+def rslx_bc_update_recurrent(gru, student, obs_student, targets, dones, h0, T, N, cfg, adam_step, stats, ws):
+    """adam_step: ctypes.c_int64, updated in place."""
+    _check(lib.rslx_bc_update_recurrent(_ref(gru.c), _ref(student.c), _ptr(obs_student), _ptr(targets), _ptr(dones), _ptr(h0),
+                                        T, N, _ref(cfg.c), C.byref(adam_step), _ptr(stats), _ptr(ws),
+                                        ws.numel() if ws is not None else 0, _stream()), "rslx_bc_update_recurrent")
 
 
 def rslx_sym_augment(sym, obs_in, act_in, B, D, A, obs_out, act_out):

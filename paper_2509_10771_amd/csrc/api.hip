@@ -1624,3 +1624,158 @@ int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru
 }
 
 }  // extern "C"
+
+// ---- a single memory: one step, and behaviour cloning of a recurrent student ---------------------------------
+namespace {
+
+struct RnnBcPlan {
+  int32_t nb, rows;
+  int32_t* perms = nullptr;      // [E, N]
+  void* perm_ws = nullptr;
+  int32_t* rows_all = nullptr;   // [E, M, T, nb]
+  TrainBufs student;
+  RnnBufs mem;
+  double* sumsq_all = nullptr;
+  int32_t n_sumsq = 0;
+  double* mse_partials = nullptr;
+  size_t bytes = 0;
+};
+
+void rnn_bc_plan(Carver& c, const rslx_gru* g, const rslx_mlp* student, int32_t T, int32_t N, const rslx_bc_cfg* cfg, RnnBcPlan& p) {
+  p.nb = N / cfg->minibatches;
+  p.rows = T * p.nb;
+  p.perms = c.take<int32_t>((size_t)cfg->epochs * N);
+  p.perm_ws = c.take<char>(perm_workspace_bytes(N));
+  p.rows_all = c.take<int32_t>((size_t)cfg->epochs * T * N);
+  carve_train(c, *student, p.rows, 1, p.student, true);
+  carve_memory(c, *g, p.rows, p.nb, p.mem, 1);
+  p.n_sumsq = p.student.n_sumsq + p.mem.plan.blocks;
+  p.sumsq_all = c.take<double>((size_t)p.n_sumsq + 1);
+  p.mse_partials = c.take<double>(mse_num_blocks((int64_t)p.rows * student->dims[student->n_layers]));
+  p.bytes = c.off + 256;
+}
+
+int32_t rnn_bc_validate(const rslx_gru* g, const rslx_mlp* student, int32_t T, int32_t N, const rslx_bc_cfg* cfg, bool need_buffers) {
+  if (!cfg) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update_recurrent: null cfg");
+  RSLX_TRY(check_gru(g, "rslx_bc_update_recurrent memory", need_buffers));
+  RSLX_TRY(check_mlp(student, "rslx_bc_update_recurrent student", need_buffers));
+  if (student->dims[0] != g->hidden) return fail(RSLX_ERR_SHAPE, "rslx_bc_update_recurrent: student input width != memory width");
+  if (student->n_layers + 2 > 16) return fail(RSLX_ERR_UNSUPPORTED, "rslx_bc_update_recurrent: too many layers");
+  if (T < 1 || N < 1 || (int64_t)T * N > (1 << 30)) return fail(RSLX_ERR_SHAPE, "rslx_bc_update_recurrent: T = %d, N = %d", T, N);
+  if (cfg->minibatches < 1 || cfg->epochs < 0 || N % cfg->minibatches != 0)
+    return fail(RSLX_ERR_SHAPE, "rslx_bc_update_recurrent: N = %d is not a multiple of minibatches = %d", N, cfg->minibatches);
+  return RSLX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rslx_gru_step_workspace_bytes(const rslx_gru* gru, int32_t N) {
+  if (!gru || N <= 0) return 256;
+  Carver c(nullptr);
+  act_recurrent_carve(c, gru, nullptr, N, nullptr, nullptr);
+  return c.off + 256;
+}
+
+int32_t rslx_gru_step(const rslx_gru* gru, const float* obs, int32_t N, float* h, const uint8_t* reset_or_null,
+                      float* h0_out, void* ws, size_t ws_bytes, void* stream) {
+  if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_gru_step: N = %d", N);
+  RSLX_TRY(check_gru(gru, "rslx_gru_step memory", false));
+  if (!obs || !h) return fail(RSLX_ERR_INVALID_ARG, "rslx_gru_step: null input or state");
+  if (!aligned16(h) || (h0_out && !aligned16(h0_out))) return fail(RSLX_ERR_INVALID_ARG, "rslx_gru_step: state buffers not 16-byte aligned");
+  if (N == 0) return RSLX_OK;
+  if (!ws || ws_bytes < rslx_gru_step_workspace_bytes(gru, N)) return fail(RSLX_ERR_WORKSPACE, "rslx_gru_step: workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  StepBufs b;
+  act_recurrent_carve(c, gru, nullptr, N, &b, nullptr);
+  RowGatherArgs rg;
+  memset(&rg, 0, sizeof rg);
+  rg.n_jobs = 1; rg.nb = N; rg.reset = reset_or_null;
+  rg.job[0] = RowGatherJob{h, b.hin, h0_out, gru->hidden};
+  RSLX_HIP(launch_row_gather(rg, s));
+  const rslx_gru* g[1] = {gru};
+  const float* o[1] = {obs};
+  const StepBufs bb[1] = {b};
+  float* out[1] = {h};
+  return gru_step(g, o, bb, out, 1, N, s);
+}
+
+size_t rslx_bc_update_recurrent_workspace_bytes(const rslx_gru* gru, const rslx_mlp* student, int32_t T, int32_t N,
+                                                const rslx_bc_cfg* cfg) {
+  if (rnn_bc_validate(gru, student, T, N, cfg, false) != RSLX_OK) return 0;
+  Carver c(nullptr);
+  RnnBcPlan p;
+  rnn_bc_plan(c, gru, student, T, N, cfg, p);
+  return p.bytes;
+}
+
+int32_t rslx_bc_update_recurrent(rslx_gru* gru, rslx_mlp* student, const float* obs_student, const float* targets,
+                                 const uint8_t* dones, const float* h0, int32_t T, int32_t N, const rslx_bc_cfg* cfg,
+                                 int64_t* adam_step, float* stats, void* ws, size_t ws_bytes, void* stream) {
+  RSLX_TRY(rnn_bc_validate(gru, student, T, N, cfg, true));
+  if (!obs_student || !targets || !dones || !h0 || !adam_step || !stats)
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update_recurrent: null pointer");
+  if (!aligned16(h0)) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update_recurrent: h0 not 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(ws);
+  RnnBcPlan p;
+  rnn_bc_plan(c, gru, student, T, N, cfg, p);
+  if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_bc_update_recurrent: workspace %zu < %zu bytes", ws_bytes, p.bytes);
+  const int A = student->dims[student->n_layers], Ls = student->n_layers;
+  const int nb = p.nb, rows = p.rows;
+  const rslx_gru* mem[1] = {gru};
+  RnnBufs* mb[1] = {&p.mem};
+  const float* obs[1] = {obs_student};
+  const float* h0s[1] = {h0};
+  {
+    std::vector<uint64_t> bases(cfg->epochs);
+    for (int e = 0; e < cfg->epochs; ++e)
+      bases[e] = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
+    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, N, p.perms, p.perm_ws, s));
+    RSLX_HIP(launch_column_rows(p.perms, cfg->epochs, cfg->minibatches, T, N, p.rows_all, s));
+  }
+  const int nbm = mse_num_blocks((int64_t)rows * A);
+  for (int e = 0; e < cfg->epochs; ++e) {
+    for (int m = 0; m < cfg->minibatches; ++m) {
+      const int32_t* envs = p.perms + (size_t)e * N + (size_t)m * nb;
+      const int32_t* ridx = p.rows_all + ((size_t)e * cfg->minibatches + m) * rows;
+      float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
+      RSLX_HIP(launch_fill(stats_row, RSLX_NSTATS, 0.f, s));
+      RSLX_TRY(memories_forward(mem, mb, 1, obs, h0s, envs, ridx, dones, T, nb, N, s));
+      XView xs = plain_view(p.mem.hs, gru->hidden);
+      NetJob fj{student, xs, rows, &p.student.act};
+      RSLX_TRY(forward_nets(&fj, 1, s));
+      RSLX_HIP(launch_mse(p.student.act.out[Ls - 1], targets, ridx, rows, A, p.student.d_out, p.mse_partials, s));
+      RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)rows * A, stats_row, s));
+      BwdJob bj{student, xs, rows, &p.student.act, p.student.d_out, p.student.wt, p.student.partials, &p.student.plan, p.mem.dh};
+      RSLX_TRY(backward_nets(&bj, 1, s));
+      RSLX_TRY(memories_backward(mem, mb, 1, obs, ridx, dones, T, nb, N, s));
+      {
+        ReduceArgs ra;
+        memset(&ra, 0, sizeof ra);
+        ra.sumsq_blocks = p.sumsq_all;
+        reduce_add_net(ra, *student, p.student);
+        reduce_add_memory(ra, *gru, p.mem);
+        RSLX_HIP(launch_reduce_partials(ra, s));
+      }
+      const int64_t t1 = *adam_step + 1;
+      AdamArgs aa;
+      memset(&aa, 0, sizeof aa);
+      aa.seg[0] = AdamSegment{student->params, student->grads, student->adam_m, student->adam_v, weight_count(*student)};
+      aa.seg[1] = AdamSegment{gru->params, gru->grads, gru->adam_m, gru->adam_v, gru_count(*gru)};
+      aa.n_seg = 2;
+      aa.sumsq_blocks = p.sumsq_all; aa.n_sumsq = p.n_sumsq;
+      aa.max_grad_norm = cfg->max_grad_norm;
+      aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;
+      aa.bc1 = bias_correction(cfg->beta1, t1); aa.bc2 = bias_correction(cfg->beta2, t1);
+      aa.grad_norm_out = stats_row + RSLX_STAT_GRAD_NORM;
+      RSLX_HIP(launch_adam(aa, s));
+      *adam_step = t1;
+    }
+  }
+  return RSLX_OK;
+}
+
+}  // extern "C"

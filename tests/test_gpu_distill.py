@@ -158,3 +158,125 @@ def test_distillation_iteration_matches_oracle_and_graph_replays(rx):
         for i, (tr, te) in enumerate(zip(rec.outputs(), eager.outputs())):
             assert torch.equal(tr, te), (k, i)
         assert host(rec.ctr).tolist() == [0, k + 1, (k + 1) * n, 0]
+
+
+# ---- distillation into a recurrent student (GRU memory + MLP), paper Sec. 2.1 with Sec. 3 ----------------------
+import ctypes as C
+from oracle import recurrent as orec, gru as ogru
+
+
+def _rec_flat(inp):
+    return np.concatenate([inp["gru_student"], inp["student"]])
+
+
+def _rec_student(rx, w, flat, opt=None):
+    k = ogru.n_params(w.student_obs, w.student_memory)
+    p = dev(flat, torch.float32)
+    g = rx.Gru(w.student_obs, w.student_memory, p[:k], trainable=True)
+    m = rx.Mlp(w.dims_student, p[k:], trainable=True)
+    if opt is not None:
+        mm, vv = dev(opt["m"], torch.float32), dev(opt["v"], torch.float32)
+        g.adam_m, g.adam_v, m.adam_m, m.adam_v = mm[:k], vv[:k], mm[k:], vv[k:]
+    return g, m
+
+
+def _rec_rollout(w, inp):
+    """The oracle rolls the recurrent student over the T slabs; the teacher labels every visited state."""
+    T, N = w.T, w.N
+    flat = _rec_flat(inp)
+    h, reset = inp["h_student"].astype(np.float64), inp["reset0"]
+    acts, tgts, hs, h0 = [], [], [], None
+    for t in range(T):
+        a, h, hin = orec.bc_collect_step(flat, w.student_obs, w.student_memory, w.dims_student, inp["obs_student"][t], h, reset)
+        if t == 0:
+            h0 = hin
+        acts.append(a); hs.append(h)
+        tgts.append(obc.teacher_targets(inp["teacher"], w.dims_actor, inp["obs"][t]))
+        reset = inp["dones"][t]
+    c32 = lambda x: np.ascontiguousarray(np.asarray(x, np.float32))
+    return dict(actions=c32(np.stack(acts)), targets=c32(np.stack(tgts)), hs=c32(np.stack(hs)), h0=c32(h0))
+
+
+@pytest.mark.parametrize("N", [96, 1000])
+def test_recurrent_student_collection_matches_oracle(rx, N):
+    w = WORKLOADS["distill_recurrent"].scaled(N)
+    inp = make_inputs(w)
+    ref = _rec_rollout(w, inp)
+    T, A, H = w.T, w.A, w.student_memory
+    g, m = _rec_student(rx, w, _rec_flat(inp))
+    teacher = rx.Mlp(w.dims_actor, dev(inp["teacher"]))
+    h, h0 = dev(inp["h_student"]), torch.zeros(N, H, device="cuda")
+    obs_s, obs_t, dones, reset0 = dev(inp["obs_student"]), dev(inp["obs"]), dev(inp["dones"]), dev(inp["reset0"])
+    actions, targets = torch.empty(T, N, A, device="cuda"), torch.empty(T, N, A, device="cuda")
+    sws = rx.workspace(rx.rslx_gru_step_workspace_bytes(g, N))
+    cws = rx.workspace(rx.rslx_bc_collect_workspace_bytes(m, teacher, N))
+    for t in range(T):
+        rx.rslx_gru_step(g, obs_s[t], N, h, reset0 if t == 0 else dones[t - 1], h0 if t == 0 else None, sws)
+        rx.rslx_bc_collect(m, teacher, h, obs_t[t], N, actions[t], targets[t], cws)
+        torch.cuda.synchronize()
+        assert rel_l2(host(h), ref["hs"][t]) <= 2e-5, t
+    assert rel_l2(host(actions), ref["actions"]) <= 2e-5 and rel_l2(host(targets), ref["targets"]) <= 1e-5
+    assert rel_l2(host(h0), ref["h0"]) <= 1e-6
+
+
+class RecDistillCase:
+    def __init__(self, w, epochs, clip=0.0):
+        self.w, self.epochs, self.clip = w, epochs, clip
+        inp = self.inp = make_inputs(w)
+        ro = _rec_rollout(w, inp)
+        self.flat0 = _rec_flat(inp).astype(np.float32)
+        self.oro = dict(obs=inp["obs_student"], targets=ro["targets"], dones=inp["dones"], h0=ro["h0"])
+        self.ocfg = obc.BCConfig(lr=f32(w.lr), beta1=f32(0.9), beta2=f32(0.999), adam_eps=f32(1e-8), epochs=epochs,
+                                 minibatches=w.minibatches, max_grad_norm=f32(clip), seed=5, call_index=2)
+        n = self.flat0.size
+        self.ref = orec.bc_update(self.flat0, w.student_obs, w.student_memory, w.dims_student, self.oro, self.ocfg,
+                                  dict(m=np.zeros(n), v=np.zeros(n), step=0), record=True)
+
+    def run(self, rx, flat, opt, envs, epochs, minibatches, step0):
+        w = self.w
+        o = self.oro if envs is None else {k: (v[envs] if k == "h0" else v[:, envs]) for k, v in self.oro.items()}
+        N = o["dones"].shape[1]
+        g, m = _rec_student(rx, w, flat, opt)
+        cfg = rx.BcCfg(lr=w.lr, epochs=epochs, minibatches=minibatches, max_grad_norm=self.clip, seed=5, call_index=2)
+        stats = torch.zeros(epochs * minibatches, rx.NSTATS, device="cuda")
+        ws = rx.workspace(rx.rslx_bc_update_recurrent_workspace_bytes(g, m, w.T, N, cfg))
+        step = C.c_int64(step0)
+        rx.rslx_bc_update_recurrent(g, m, dev(o["obs"]), dev(o["targets"]), dev(o["dones"]), dev(o["h0"]), w.T, N, cfg, step,
+                                    stats, ws)
+        torch.cuda.synchronize()
+        params = np.concatenate([host(g.params), host(m.params)])
+        grads = np.concatenate([host(g.grads), host(m.grads)])
+        return host(stats), step.value, params, grads
+
+
+def _check_rec_student(name, w, got, ref, tol):
+    D, H = w.student_obs, w.student_memory
+    o = 0
+    for nm, n in (("W_ih", D * 3 * H), ("b_ih", 3 * H), ("W_hh", H * 3 * H), ("b_hh", 3 * H), ("mlp", got.size - ogru.n_params(D, H))):
+        r = np.asarray(ref[o:o + n], np.float64)
+        err = np.linalg.norm(np.asarray(got[o:o + n], np.float64) - r)
+        assert err <= tol * np.linalg.norm(r) + 1e-12, (name, nm, err, np.linalg.norm(r))
+        o += n
+
+
+@pytest.mark.parametrize("N,hidden,mem,clip", [(96, (64, 32), 32, 0.0), (140, (72, 40), 44, 0.5), (256, (256, 128), 256, 0.0)])
+def test_bc_update_recurrent_matches_oracle(rx, N, hidden, mem, clip):
+    w = replace(WORKLOADS["distill_recurrent"].scaled(N), student_hidden=hidden, student_memory=mem, done_p=0.04)
+    case = RecDistillCase(w, 1, clip)
+    ref = case.ref
+    assert case.inp["dones"][:-1].sum() > 10
+    # every optimiser step replayed from the oracle's state before it, on that minibatch's environment columns
+    for k, tr in enumerate(ref["trace"]):
+        b = tr["before"]
+        stats, step, params, grads = case.run(rx, b["student"], b["opt"], tr["envs"], 1, 1, b["opt"]["step"])
+        assert step == b["opt"]["step"] + 1
+        assert abs(stats[0, 0] - ref["stats"][k, 0]) <= TOL * ref["stats"][k, 0]
+        assert abs(stats[0, 4] - ref["stats"][k, 1]) <= TOL * ref["stats"][k, 1]
+        _check_rec_student("g step %d" % k, w, grads, tr["g"], TOL)
+        _check_rec_student("student step %d" % k, w, params, tr["student"], TOL)
+    # one free-running call
+    n = w.minibatches
+    stats, step, params, _ = case.run(rx, case.flat0, None, None, 1, n, 0)
+    assert step == n
+    assert np.all(np.abs(stats[:, 0] - ref["stats"][:, 0]) <= 2e-2 * np.maximum(ref["stats"][:, 0], 1e-3))
+    assert rel_l2(params, ref["student"]) <= 2 * TOL

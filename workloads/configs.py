@@ -47,6 +47,7 @@ class Workload:
     rnd_subset: int = 0             # > 0: the RND networks read this many of the Da observation columns
     timeout_p: float = 0.0          # per-step probability that an episode ends by time limit (also sets done)
     memory_hidden: int = 0          # > 0: actor and critic each have a GRU memory of this width in front of their MLP
+    student_memory: int = 0         # > 0: the distillation student has a GRU memory of this width in front of its MLP
 
     @property
     def B(self):
@@ -62,7 +63,7 @@ class Workload:
 
     @property
     def dims_student(self):
-        return (self.student_obs,) + tuple(self.student_hidden) + (self.A,)
+        return (self.student_memory or self.student_obs,) + tuple(self.student_hidden) + (self.A,)
 
     @property
     def dims_rnd(self):
@@ -95,6 +96,10 @@ WORKLOADS = {
     # holds resets
     "recurrent": Workload("recurrent", 8, N=4096, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128), heavy_tail=True,
                           done_p=0.01, memory_hidden=256),
+    # distillation into a recurrent student: the distill workload's teacher, a student with a 256-wide GRU memory
+    "distill_recurrent": Workload("distill_recurrent", 9, N=4096, T=24, Da=235, Dc=235, A=12, hidden=(512, 256, 128),
+                                  height_scan=187, bc=True, student_hidden=(256, 128), student_obs=48, epochs=2,
+                                  minibatches=4, done_p=0.01, student_memory=256),
 }
 
 
@@ -184,6 +189,10 @@ def make_inputs(w, seed=None):
         out["obs_student"] = np.ascontiguousarray(obs[:T, :, :w.student_obs] + noise)
         out["teacher"] = xavier_mlp(gen, w.dims_actor)
         out["student"] = xavier_mlp(gen, w.dims_student)
+        if w.student_memory:
+            out["gru_student"] = uniform_gru(gen, w.student_obs, w.student_memory)
+            out["h_student"] = (0.5 * gen.standard_normal((N, w.student_memory))).astype(np.float32)
+            out["reset0"] = (gen.random(N) < w.done_p).astype(np.uint8)
     if w.rnd:
         if w.rnd_subset:
             out["rnd_subset_idx"] = np.sort(gen.choice(w.Da, size=w.rnd_subset, replace=False)).astype(np.int32)
