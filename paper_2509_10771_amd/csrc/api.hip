@@ -1321,7 +1321,6 @@ struct RnnBufs {          // per memory, one column-wise minibatch (rows = T * n
   float* hs = nullptr;    // [rows, H] new states = input of the MLP
   float* dh = nullptr;    // [rows, H] gradient from the MLP
   float* direct = nullptr;  // [nb, H]
-  float* whh_t = nullptr;   // [3H, H]
   SplitPlan plan;           // layer 0: W_ih / b_ih, layer 1: W_hh / b_hh
   float* partials = nullptr;
 };
@@ -1347,7 +1346,6 @@ void carve_memory(Carver& c, const rslx_gru& g, int32_t rows, int32_t nb, RnnBuf
   b.dgi = c.take<float>(rows * 3 * H); b.dgh = c.take<float>(rows * 3 * H);
   b.hin = c.take<float>(rows * H); b.hs = c.take<float>(rows * H); b.dh = c.take<float>(rows * H);
   b.direct = c.take<float>(nb * H);
-  b.whh_t = c.take<float>(3 * H * H);
   plan_layer(b.plan, 0, g.in_dim, 3 * g.hidden, rows, group, false);
   plan_layer(b.plan, 1, g.hidden, 3 * g.hidden, rows, group, false);
   b.partials = c.take<float>((size_t)b.plan.total);
@@ -1458,11 +1456,6 @@ int32_t memories_forward(const rslx_gru* const* mem, RnnBufs* const* mb, int cou
 int32_t memories_backward(const rslx_gru* const* mem, RnnBufs* const* mb, int count, const float* const* obs,
                           const int32_t* ridx, const uint8_t* dones, int T, int nb, int N, hipStream_t s) {
   const int rows = T * nb;
-  TransposeBatch tb;
-  tb.count = count;
-  for (int k = 0; k < count; ++k)
-    tb.job[k] = TransposeJob{mem[k]->params + gru_off_whh(*mem[k]), mb[k]->whh_t, mem[k]->hidden, 3 * mem[k]->hidden};
-  RSLX_HIP(launch_transpose(tb, s));
   for (int t = T - 1; t >= 0; --t) {
     GruStepBwdArgs sb;
     memset(&sb, 0, sizeof sb);
@@ -1472,7 +1465,7 @@ int32_t memories_backward(const rslx_gru* const* mem, RnnBufs* const* mb, int co
       const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
       const bool last = t == T - 1;
       sb.net[k] = GruBwdNet{mb[k]->dh + o, last ? nullptr : mb[k]->dgh + o3 + (size_t)nb * 3 * H, mb[k]->direct,
-                            mb[k]->whh_t, mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3,
+                            g.params + gru_off_whh(g), mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3,
                             mb[k]->dgh + o3, mb[k]->direct, g.hidden};
     }
     RSLX_HIP(launch_gru_step_bwd(sb, s));

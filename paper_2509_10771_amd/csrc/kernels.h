@@ -268,7 +268,7 @@ struct GruBwdNet {
   const float* dh_ext;    // [nb, H] gradient arriving from the layers above
   const float* dgh_next;  // [nb, 3H] this network's dgh of step t + 1, null on the last step
   const float* direct_in; // [nb, H] direct_out of step t + 1 (may alias direct_out), unused on the last step
-  const float* whh_t;     // [3H, H] row-major (W_hh transposed)
+  const float* w_hh;      // [H, 3H] row-major: back[row, j] = sum_k dgh_next[row, k] W_hh[j, k]
   const float* gi; const float* gh; const float* hin;
   float* dgi; float* dgh; // [nb, 3H]
   float* direct_out;      // [nb, H]

@@ -134,6 +134,107 @@ struct GruTile {
   }
 };
 
+// The same accumulation for an operand pair that is contiguous along the contraction on BOTH sides: A[row, k] and
+// Bt[col, k] (D[row, col] += sum_k A[row, k] Bt[col, k]).  Both are staged row-major with the contraction index
+// innermost, so one 16-byte LDS read per operand feeds four matrix instructions: lane (m, kq) of group g reads
+// k = 16 g + 4 kq .. + 3 and uses component i in instruction i, which then contracts over {16 g + 4 kq' + i} - the
+// order of the sum inside a group of 16 is permuted, nothing else.  The backward step uses it (A = dgh of the next
+// step, Bt = the rows of W_hh itself), where one instruction per contraction step would leave the LDS latency bare.
+template <int NTW, int KC>
+struct GruTileKK {
+  static constexpr int NT = 2 * NTW;
+  static constexpr int PITCH = KC + 4;
+  static constexpr int BROWS = 16 * NT;
+  static constexpr int A_VECS = GS_ROWS * KC / 4, B_VECS = BROWS * KC / 4;
+  static constexpr int A_PER = (A_VECS + GS_THREADS - 1) / GS_THREADS, B_PER = (B_VECS + GS_THREADS - 1) / GS_THREADS;
+  static constexpr int LDS_FLOATS = (GS_ROWS + BROWS) * PITCH;
+  static_assert(KC % 16 == 0 && A_VECS % GS_THREADS == 0 && B_VECS % GS_THREADS == 0, "chunk shape");
+
+  // acc[u] += A[row0 + 16 wr .., 0 .. K) * Bt[col0[wj * NTW + u] .. + 16, 0 .. K)^T.  Rows >= n_rows and Bt rows from
+  // col_end[t] on read as zero; K, lda, ldbt multiples of 4, A and Bt 16-byte aligned.
+  static __device__ __forceinline__ void mma(const float* __restrict__ A, int lda, int row0, int n_rows,
+                                             const float* __restrict__ Bt, int ldbt, const int (&col0)[NT],
+                                             const int (&col_end)[NT], int K, float* smem, f4 (&acc)[NTW]) {
+    float* As = smem;
+    float* Bs = smem + GS_ROWS * PITCH;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave & 1, wj = wave >> 1;
+    const int m = lane & 15, kq = lane >> 4;
+    int a_off[A_PER], a_kc[A_PER], b_off[B_PER], b_kc[B_PER];
+    bool a_ok[A_PER], b_ok[B_PER];
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i) {
+      const int v = tid + i * GS_THREADS;
+      const int r = v / (KC / 4);
+      a_kc[i] = (v % (KC / 4)) * 4;
+      a_ok[i] = row0 + r < n_rows;
+      a_off[i] = min(row0 + r, n_rows - 1) * lda;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i) {
+      const int v = tid + i * GS_THREADS;
+      const int c = v / (KC / 4), t = c / 16;
+      b_kc[i] = (v % (KC / 4)) * 4;
+      int c0 = col0[0], ce = col_end[0];
+#pragma unroll
+      for (int u = 1; u < NT; ++u) { c0 = t == u ? col0[u] : c0; ce = t == u ? col_end[u] : ce; }
+      const int col = c0 + (c % 16);
+      b_ok[i] = col < ce;
+      b_off[i] = min(col, ce - 1) * ldbt;           // clamped: always a valid row
+    }
+    f4 ra[A_PER], rb[B_PER];
+    auto fetch = [&](int k0) {      // unconditional loads from clamped addresses; zeroing happens at staging time
+#pragma unroll
+      for (int i = 0; i < A_PER; ++i) ra[i] = ld4(A + (long)a_off[i] + min(k0 + a_kc[i], K - 4));
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) rb[i] = ld4(Bt + (long)b_off[i] + min(k0 + b_kc[i], K - 4));
+    };
+    auto stage = [&](int k0) {
+#pragma unroll
+      for (int i = 0; i < A_PER; ++i) {
+        const int v = tid + i * GS_THREADS;
+        st4(As + (v / (KC / 4)) * PITCH + a_kc[i], (a_ok[i] && k0 + a_kc[i] < K) ? ra[i] : f4{0.f, 0.f, 0.f, 0.f});
+      }
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) {
+        const int v = tid + i * GS_THREADS;
+        st4(Bs + (v / (KC / 4)) * PITCH + b_kc[i], (b_ok[i] && k0 + b_kc[i] < K) ? rb[i] : f4{0.f, 0.f, 0.f, 0.f});
+      }
+    };
+    const float* ap = As + (wr * 16 + m) * PITCH + 4 * kq;
+    const float* bp = Bs + (wj * NTW * 16 + m) * PITCH + 4 * kq;
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += KC) {
+      __syncthreads();               // the previous chunk has been consumed
+      stage(k0);
+      __syncthreads();
+      fetch(k0 + KC);                // past the end this re-reads clamped addresses; never staged
+      __builtin_amdgcn_sched_barrier(0);
+      f4 a_cur = ld4(ap), b_cur[NTW];
+#pragma unroll
+      for (int u = 0; u < NTW; ++u) b_cur[u] = ld4(bp + u * 16 * PITCH);
+#pragma unroll
+      for (int g = 0; g < KC / 16; ++g) {
+        f4 a_nxt = a_cur, b_nxt[NTW];
+#pragma unroll
+        for (int u = 0; u < NTW; ++u) b_nxt[u] = b_cur[u];
+        if (g + 1 < KC / 16) {
+          a_nxt = ld4(ap + 16 * (g + 1));
+#pragma unroll
+          for (int u = 0; u < NTW; ++u) b_nxt[u] = ld4(bp + u * 16 * PITCH + 16 * (g + 1));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int u = 0; u < NTW; ++u) acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[i], b_cur[u][i], acc[u], 0, 0, 0);
+        a_cur = a_nxt;
+#pragma unroll
+        for (int u = 0; u < NTW; ++u) b_cur[u] = b_nxt[u];
+      }
+    }
+  }
+};
+
 // Workgroup -> (row block, hidden-unit block).  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each
 // with an L2 of its own: all hidden-unit blocks of a row block go to one XCD, so a row block's operand rows are
 // fetched into one L2 only (the weights, shared by every row block, fit in each L2).
@@ -201,7 +302,7 @@ __global__ __launch_bounds__(GS_THREADS) void gru_step_fwd_kernel(const GruStepF
 }
 
 __global__ __launch_bounds__(GS_THREADS) void gru_step_bwd_kernel(const GruStepBwdArgs a) {
-  using Tile = GruTile<1, 128>;
+  using Tile = GruTileKK<1, 128>;
   __shared__ __attribute__((aligned(16))) float smem[Tile::LDS_FLOATS];
   const int z = blockIdx.y;
   const GruBwdNet& n = a.net[z];
@@ -229,8 +330,8 @@ __global__ __launch_bounds__(GS_THREADS) void gru_step_bwd_kernel(const GruStepB
   }
   f4 acc[1] = {f4{0.f, 0.f, 0.f, 0.f}};
   if (has_next) {
-    const int col0[2] = {j0, j0 + 16}, col_end[2] = {H, H};
-    Tile::mma(n.dgh_next, 3 * H, row0, nb, n.whh_t, H, col0, col_end, 3 * H, smem, acc);
+    const int col0[2] = {j0, j0 + 16}, col_end[2] = {H, H};      // rows of W_hh = hidden units
+    Tile::mma(n.dgh_next, 3 * H, row0, nb, n.w_hh, 3 * H, col0, col_end, 3 * H, smem, acc);
   }
   if (j >= H) return;
 #pragma unroll
