@@ -183,7 +183,7 @@ def _check_net(name, w, which, got, ref, tol):
     _check_vec(name, dims, which == "actor", got[k:], ref[k:], tol)
 
 
-def check_forced_steps(rx, case, steps=None):
+def check_forced_steps(rx, case, steps=None, floor=1e-3):
     w, ref = case.w, case.ref
     for k, tr in enumerate(ref["trace"]):
         if steps is not None and k not in steps:
@@ -192,21 +192,21 @@ def check_forced_steps(rx, case, steps=None):
         nets = _nets(rx, w, b["actor"], b["critic"], b["opt"])
         stats, step = _call(rx, nets, case.gpu_rollout(rx, tr["envs"]), case.gpu_cfg(rx, 1, 1), 1, b["opt"]["step"])
         assert step == b["opt"]["step"] + 1
-        _check_stats(stats[0], ref["stats"][k], TOL)
+        _check_stats(stats[0], ref["stats"][k], TOL, floor=floor)
         _check_net("g_actor step %d" % k, w, "actor", _grads(nets[0], nets[1]), tr["g_actor"], TOL)
         _check_net("g_critic step %d" % k, w, "critic", _grads(nets[2], nets[3]), tr["g_critic"], TOL)
         _check_net("actor step %d" % k, w, "actor", _params(nets[0], nets[1]), tr["actor"], TOL)
         _check_net("critic step %d" % k, w, "critic", _params(nets[2], nets[3]), tr["critic"], TOL)
 
 
-def check_free_running(rx, case, later_tol=2e-2, param_tol=None):
+def check_free_running(rx, case, later_tol=2e-2, param_tol=None, floor=1e-3):
     w, ref = case.w, case.ref
     nets = _nets(rx, w, case.actor0, case.critic0)
     n = case.epochs * w.minibatches
     stats, step = _call(rx, nets, case.gpu_rollout(rx), case.gpu_cfg(rx, case.epochs, w.minibatches), n, 0)
     assert step == n == ref["opt"]["step"]
-    _check_stats(stats[0], ref["stats"][0], TOL)
-    _check_stats(stats, ref["stats"], later_tol, floor=1e-2)
+    _check_stats(stats[0], ref["stats"][0], TOL, floor=floor)
+    _check_stats(stats, ref["stats"], later_tol, floor=max(floor, 1e-2))
     param_tol = TOL * max(1, case.epochs) if param_tol is None else param_tol
     assert rel_l2(_params(nets[0], nets[1]), ref["actor"]) <= param_tol
     assert rel_l2(_params(nets[2], nets[3]), ref["critic"]) <= param_tol
@@ -256,3 +256,45 @@ def test_recurrent_update_rejects_bad_shapes(rx):
     bad.hidden = 18
     with pytest.raises(rx.RslxError):      # memory width must be a multiple of 4 (and match the MLP input)
         rx.rslx_ppo_update_recurrent_workspace_bytes(bad, nets[1], nets[2], nets[3], ro, rx.PpoCfg(epochs=1, minibatches=3))
+
+
+@pytest.mark.parametrize("T,N,M,done_p", [(1, 32, 4, 0.1), (5, 4, 4, 0.3), (6, 48, 2, 1.0), (6, 48, 2, 0.0)])
+def test_recurrent_update_degenerate_shapes(rx, T, N, M, done_p):
+    """One-step roll-outs, one environment per minibatch, an episode end on every step (no state is ever carried:
+    the memory acts as a feed-forward layer) and none at all."""
+    w = replace(WORKLOADS["recurrent"].scaled(N), T=T, minibatches=M, hidden=(64, 32), memory_hidden=32, done_p=done_p)
+    case = RCase(w, 1, perturb=0.1)
+    if done_p == 1.0:
+        assert case.inp["dones"].all()
+    # with 5 to 96 samples per minibatch the surrogate is a mean of a few O(1) terms of both signs and can come out
+    # near zero; its fp32 rounding is relative to the terms, so the statistics are compared with a floor of 0.05
+    check_forced_steps(rx, case, floor=5e-2)
+    check_free_running(rx, case, floor=5e-2)
+
+
+def test_recurrent_empty_calls_are_no_ops(rx):
+    w = replace(WORKLOADS["recurrent"].scaled(16), hidden=(32, 32), memory_hidden=16)
+    inp = make_inputs(w)
+    ro = oracle_collect(w, inp)
+    nets = _nets(rx, w, _flat(inp, "actor"), _flat(inp, "critic"))
+    before = [host(n.params).copy() for n in nets]
+    # zero environments in act
+    rx.rslx_act_recurrent(nets[0], nets[1], nets[2], nets[3], dev(inp["obs"][0]), dev(inp["obs"][0]), 0, dev(inp["h_actor"]),
+                          dev(inp["h_critic"]), None, None, None, SEED, 0, None, torch.zeros(1, device="cuda"),
+                          torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda"),
+                          torch.zeros(1, device="cuda"), 0, rx.workspace(256))
+    # zero epochs in the update
+    case_ro = dict(obs_a=inp["obs"][:w.T], dones=inp["dones"], h0_a=ro["h0_a"], h0_c=ro["h0_c"],
+                   **{k: ro[k] for k in ("actions", "logp", "values", "mu", "sigma", "adv", "returns")})
+    d_obs = dev(case_ro["obs_a"])
+    g_ro = rx.Rollout(w.T, w.N, d_obs, d_obs, dev(case_ro["actions"]), dev(case_ro["logp"]), dev(case_ro["values"]),
+                      dev(case_ro["mu"]), dev(case_ro["sigma"]), dev(case_ro["adv"]), dev(case_ro["returns"]))
+    cfg = rx.PpoCfg(epochs=0, minibatches=4)
+    stats = torch.zeros(1, rx.NSTATS, device="cuda")
+    step = C.c_int64(3)
+    ws = rx.workspace(rx.rslx_ppo_update_recurrent_workspace_bytes(*nets, g_ro, cfg))
+    rx.rslx_ppo_update_recurrent(*nets, g_ro, dev(inp["dones"]), dev(ro["h0_a"]), dev(ro["h0_c"]), cfg, step, stats, ws)
+    torch.cuda.synchronize()
+    assert step.value == 3
+    for n, b in zip(nets, before):
+        assert np.array_equal(host(n.params), b)
