@@ -28,6 +28,10 @@ tests/test_oracle_*.py):
                                           separately run episodes for the resets)
   gru.cell_backward / sequence_backward . pinned (finite differences, library autodiff, per-episode
                                           brute force)
+  lstm.cell / sequence_forward / cell_backward / sequence_backward
+                                          pinned (library LSTM cell and LSTM in fp64, closed forms,
+                                          per-episode brute force, finite differences, library autodiff)
+  recurrent.* with cell="lstm" .......... pinned (on-policy identities, finite differences of both losses)
   recurrent.act / minibatch_loss_and_grads / ppo_update
                                           pinned (act == sequence re-run, on-policy identities, finite
                                           differences of the scalar loss, column-wise minibatches)

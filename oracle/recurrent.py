@@ -3,7 +3,8 @@ time (fp64).
 
 Sec. 3 of the paper: recurrent networks are supported for the RL and the distillation setting by managing the
 hidden states across roll-outs and back-propagating through time.  The model here: actor and critic each own a
-GRU memory (oracle.gru) whose state feeds their MLP (oracle.mlp),
+memory, a GRU (oracle.gru) or an LSTM (oracle.lstm, `cell="lstm"`; its state is the packed pair [h | c] and the
+MLP sees h), whose hidden state feeds their MLP (oracle.mlp),
 
     h^a_t = GRU_a(obs^a_t, hin^a_t),  mu_t = actor_mlp(h^a_t);    h^c_t = GRU_c(obs^c_t, hin^c_t),  V_t = critic_mlp(h^c_t)
 
@@ -28,52 +29,57 @@ Oracle code: test infrastructure only.
 """
 import numpy as np
 
-from . import gru, mlp, adam, rng
+from . import gru, lstm, mlp, adam, rng
 from . import ppo as _ppo
 
 
-def split(flat, D, H):
-    """(gru part, mlp part) of a recurrent network's flat parameter vector."""
-    k = gru.n_params(D, H)
+CELLS = {"gru": gru, "lstm": lstm}     # same interface; the state is packed per row (GRU: h, LSTM: [h | c])
+
+
+def split(flat, D, H, cell="gru"):
+    """(memory part, mlp part) of a recurrent network's flat parameter vector."""
+    k = CELLS[cell].n_params(D, H)
     flat = np.asarray(flat, np.float64)
     return flat[:k], flat[k:]
 
 
-def act(actor, critic, D_a, D_c, H, dims_a, dims_c, obs_a, obs_c, h_a, h_c, reset, eps, alpha=1.0):
+def act(actor, critic, D_a, D_c, H, dims_a, dims_c, obs_a, obs_c, h_a, h_c, reset, eps, alpha=1.0, cell="gru"):
     """One roll-out step.  reset [N] (0/1): environments whose episode ended on the previous step start from a
     zero state.  Returns the outputs of ppo.act plus the new states h_a, h_c and the states the step started
-    from (hin_a, hin_c)."""
-    ga, ma = split(actor, D_a, H)
-    gc, mc = split(critic, D_c, H)
+    from (hin_a, hin_c).  States are packed per row as the cell defines (GRU: h; LSTM: [h | c])."""
+    C = CELLS[cell]
+    ga, ma = split(actor, D_a, H, cell)
+    gc, mc = split(critic, D_c, H, cell)
     keep = (1.0 - np.asarray(reset, np.float64))[:, None]
     hin_a, hin_c = np.asarray(h_a, np.float64) * keep, np.asarray(h_c, np.float64) * keep
-    ha, _ = gru.cell(gru.unpack(ga, D_a, H), obs_a, hin_a)
-    hc, _ = gru.cell(gru.unpack(gc, D_c, H), obs_c, hin_c)
-    out = _ppo.act(ma, mc, dims_a, dims_c, ha, hc, eps, alpha)
+    ha, _ = C.cell(C.unpack(ga, D_a, H), obs_a, hin_a)
+    hc, _ = C.cell(C.unpack(gc, D_c, H), obs_c, hin_c)
+    out = _ppo.act(ma, mc, dims_a, dims_c, C.hidden(ha, H), C.hidden(hc, H), eps, alpha)
     out.update(h_a=ha, h_c=hc, hin_a=hin_a, hin_c=hin_c)
     return out
 
 
-def minibatch_loss_and_grads(actor, critic, D_a, D_c, H, dims_a, dims_c, batch, cfg):
+def minibatch_loss_and_grads(actor, critic, D_a, D_c, H, dims_a, dims_c, batch, cfg, cell="gru"):
     """batch: arrays with leading [T, nb]: obs_a, obs_c, actions, logp, adv, returns, values, mu, sigma, dones,
     and h0_a, h0_c [nb, H].  Returns (terms, g_actor, g_critic) in the flat layouts."""
-    ga, ma = split(actor, D_a, H)
-    gc, mc = split(critic, D_c, H)
-    pa, pc = gru.unpack(ga, D_a, H), gru.unpack(gc, D_c, H)
+    C = CELLS[cell]
+    ga, ma = split(actor, D_a, H, cell)
+    gc, mc = split(critic, D_c, H, cell)
+    pa, pc = C.unpack(ga, D_a, H), C.unpack(gc, D_c, H)
     dones = np.asarray(batch["dones"])
     T, nb = dones.shape
-    Ha, cache_a = gru.sequence_forward(pa, batch["obs_a"], batch["h0_a"], dones)
-    Hc, cache_c = gru.sequence_forward(pc, batch["obs_c"], batch["h0_c"], dones)
+    Ha, cache_a = C.sequence_forward(pa, batch["obs_a"], batch["h0_a"], dones)
+    Hc, cache_c = C.sequence_forward(pc, batch["obs_c"], batch["h0_c"], dones)
     rows = {k: np.asarray(batch[k]).reshape((T * nb,) + np.asarray(batch[k]).shape[2:])
             for k in ("actions", "logp", "adv", "returns", "values", "mu", "sigma")}
     rows["obs_a"], rows["obs_c"] = Ha.reshape(T * nb, H), Hc.reshape(T * nb, H)
     terms, g_ma, g_mc, dHa, dHc = _ppo.minibatch_loss_and_grads(ma, mc, dims_a, dims_c, rows, cfg, None, input_grads=True)
-    g_ga, _ = gru.sequence_backward(pa, cache_a, dones, dHa.reshape(T, nb, H))
-    g_gc, _ = gru.sequence_backward(pc, cache_c, dones, dHc.reshape(T, nb, H))
+    g_ga, _ = C.sequence_backward(pa, cache_a, dones, dHa.reshape(T, nb, H))
+    g_gc, _ = C.sequence_backward(pc, cache_c, dones, dHc.reshape(T, nb, H))
     return terms, np.concatenate([g_ga, g_ma]), np.concatenate([g_gc, g_mc])
 
 
-def ppo_update(actor, critic, D_a, D_c, H, dims_a, dims_c, rollout, cfg, opt, record=False):
+def ppo_update(actor, critic, D_a, D_c, H, dims_a, dims_c, rollout, cfg, opt, record=False, cell="gru"):
     """E epochs x M minibatches of whole environment columns.
 
     rollout: arrays [T, N, ...] obs_a, obs_c, actions, logp, adv, returns, values, mu, sigma, dones and
@@ -95,7 +101,7 @@ def ppo_update(actor, critic, D_a, D_c, H, dims_a, dims_c, rollout, cfg, opt, re
             batch = {k: (np.asarray(v)[envs] if k in ("h0_a", "h0_c") else np.asarray(v)[:, envs]) for k, v in rollout.items()}
             before = dict(actor=actor.copy(), critic=critic.copy(),
                           opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()}) if record else None
-            terms, g_a, g_c = minibatch_loss_and_grads(actor, critic, D_a, D_c, H, dims_a, dims_c, batch, cfg)
+            terms, g_a, g_c = minibatch_loss_and_grads(actor, critic, D_a, D_c, H, dims_a, dims_c, batch, cfg, cell)
             norm = adam.global_norm([g_a, g_c])
             s = adam.clip_scale(norm, cfg.max_grad_norm)
             t0 = opt["step"]
@@ -109,31 +115,33 @@ def ppo_update(actor, critic, D_a, D_c, H, dims_a, dims_c, rollout, cfg, opt, re
                 perms=np.array(perms), trace=trace)
 
 
-def bc_collect_step(student, D, H, dims_s, obs_s, h, reset, alpha=1.0):
+def bc_collect_step(student, D, H, dims_s, obs_s, h, reset, alpha=1.0, cell="gru"):
     """One collection step of a recurrent student: (mean action, new state, state the step started from)."""
-    g, m = split(student, D, H)
+    C = CELLS[cell]
+    g, m = split(student, D, H, cell)
     hin = np.asarray(h, np.float64) * (1.0 - np.asarray(reset, np.float64))[:, None]
-    h_new, _ = gru.cell(gru.unpack(g, D, H), obs_s, hin)
-    a, _ = mlp.forward(mlp.unpack(m, dims_s), h_new, alpha)
+    h_new, _ = C.cell(C.unpack(g, D, H), obs_s, hin)
+    a, _ = mlp.forward(mlp.unpack(m, dims_s), C.hidden(h_new, H), alpha)
     return a, h_new, hin
 
 
-def bc_minibatch_loss_and_grad(student, D, H, dims_s, batch, alpha=1.0):
+def bc_minibatch_loss_and_grad(student, D, H, dims_s, batch, alpha=1.0, cell="gru"):
     """batch: obs [T, nb, D], targets [T, nb, A], dones [T, nb], h0 [nb, H].
     L = mean over the T * nb rows and the A action dims of (student - target)^2; returns (L, flat gradient)."""
-    g, m = split(student, D, H)
-    pg, layers = gru.unpack(g, D, H), mlp.unpack(m, dims_s)
+    C = CELLS[cell]
+    g, m = split(student, D, H, cell)
+    pg, layers = C.unpack(g, D, H), mlp.unpack(m, dims_s)
     dones = np.asarray(batch["dones"])
     T, nb = dones.shape
-    Hs, cache_g = gru.sequence_forward(pg, batch["obs"], batch["h0"], dones)
+    Hs, cache_g = C.sequence_forward(pg, batch["obs"], batch["h0"], dones)
     y, cache_m = mlp.forward(layers, Hs.reshape(T * nb, H), alpha)
     diff = y - np.asarray(batch["targets"], np.float64).reshape(T * nb, -1)
     grads_m, dH = mlp.backward(layers, cache_m, 2.0 * diff / diff.size, alpha)
-    g_g, _ = gru.sequence_backward(pg, cache_g, dones, dH.reshape(T, nb, H))
+    g_g, _ = C.sequence_backward(pg, cache_g, dones, dH.reshape(T, nb, H))
     return float(np.mean(diff ** 2)), np.concatenate([g_g, mlp.pack(grads_m)])
 
 
-def bc_update(student, D, H, dims_s, rollout, cfg, opt, record=False):
+def bc_update(student, D, H, dims_s, rollout, cfg, opt, record=False, cell="gru"):
     """E epochs x M minibatches of whole environment columns; cfg is an oracle.bc.BCConfig.
     rollout: obs [T, N, D], targets [T, N, A], dones [T, N], h0 [N, H].  opt: m, v, step."""
     student = np.asarray(student, np.float64).copy()
@@ -149,7 +157,7 @@ def bc_update(student, D, H, dims_s, rollout, cfg, opt, record=False):
             envs = perm[m * nb:(m + 1) * nb]
             batch = {k: (np.asarray(v)[envs] if k == "h0" else np.asarray(v)[:, envs]) for k, v in rollout.items()}
             before = dict(student=student.copy(), opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()}) if record else None
-            loss, g = bc_minibatch_loss_and_grad(student, D, H, dims_s, batch, cfg.elu_alpha)
+            loss, g = bc_minibatch_loss_and_grad(student, D, H, dims_s, batch, cfg.elu_alpha, cell)
             norm = adam.global_norm([g])
             s = adam.clip_scale(norm, cfg.max_grad_norm)
             student, opt["m"], opt["v"], opt["step"] = adam.adam_step(student, s * g, opt["m"], opt["v"], opt["step"], cfg.lr,
