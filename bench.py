@@ -220,9 +220,9 @@ def distill_iteration(args, rx, torch, np, w, inp):
     rec = w.student_memory > 0          # recurrent student: a GRU memory in front of the MLP, column-wise minibatches
     if rec:
         H = w.student_memory
-        gru = rx.Gru(w.student_obs, H, dev(inp["gru_student"]), trainable=True)
+        gru = rx.Gru(w.student_obs, H, dev(inp["mem_student"]), trainable=True)
         h, h0, reset0, dones = dev(inp["h_student"]), torch.empty(N, H, device="cuda"), dev(inp["reset0"]), dev(inp["dones"])
-        sws = rx.workspace(rx.rslx_gru_step_workspace_bytes(gru, N))
+        sws = rx.workspace(rx.rslx_memory_step_workspace_bytes(gru, N))
     obs_s, obs_t = dev(inp["obs_student"]), dev(inp["obs"][:T])
     actions, targets = torch.empty(T, N, A, device="cuda"), torch.empty(T, N, A, device="cuda")
     cfg_kw = dict(lr=w.lr, epochs=w.epochs, minibatches=w.minibatches, seed=20250910)
@@ -240,7 +240,7 @@ def distill_iteration(args, rx, torch, np, w, inp):
         for t in range(T):
             if rec:
                 reset = dones[t - 1] if t > 0 else (reset0 if it == 0 else dones[T - 1])
-                rx.rslx_gru_step(gru, obs_s[t], N, h, reset, h0 if t == 0 else None, sws)
+                rx.rslx_memory_step(gru, obs_s[t], N, h, reset, h0 if t == 0 else None, None, sws)
                 rx.rslx_bc_collect(student, teacher, h, obs_t[t], N, actions[t], targets[t], cws)
             else:
                 rx.rslx_bc_collect(student, teacher, obs_s[t], obs_t[t], N, actions[t], targets[t], cws)
@@ -323,7 +323,7 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
     dev = lambda x: torch.as_tensor(np.ascontiguousarray(x)).cuda()
     nets = []
     for which, D, dims, log_std in (("actor", w.Da, w.dims_actor, True), ("critic", w.Dc, w.dims_critic, False)):
-        nets.append(rx.Gru(D, H, dev(inp["gru_" + which]), trainable=True))
+        nets.append(rx.Gru(D, H, dev(inp["mem_" + which]), trainable=True))
         nets.append(rx.Mlp(dims, dev(inp[which]), trainable=True, has_log_std=log_std))
     ga, ma, gc, mc = nets
     obs, rewards, dones = dev(inp["obs"]), dev(inp["rewards"]), dev(inp["dones"])

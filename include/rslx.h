@@ -271,32 +271,40 @@ int32_t rslx_ppo_update_dc(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout
 
 /* ---- recurrent actor-critic (paper Sec. 3: hidden states managed across roll-outs, BPTT) ---- */
 
-/* A gated recurrent unit in front of an MLP (Cho et al. 2014; the reset gate multiplies the
- * hidden-side candidate term, bias included):
- *   gi = x W_ih + b_ih,  gh = h W_hh + b_hh        (3H wide, gate order r, z, n)
+/* A recurrent memory in front of an MLP, one of two cells over one flat device buffer
+ *   W_ih [in_dim, G*H] row-major, b_ih [G*H], W_hh [H, G*H] row-major, b_hh [G*H]      (H = hidden)
+ * RSLX_CELL_GRU (G = 3, gate order r, z, n; Cho et al. 2014 with the reset gate on the hidden-side
+ * candidate term, bias included), state per row: h [H]
+ *   gi = x W_ih + b_ih,  gh = h W_hh + b_hh
  *   r = sigmoid(gi_r + gh_r), z = sigmoid(gi_z + gh_z), n = tanh(gi_n + r gh_n), h' = (1-z) n + z h
- * Flat device layout: W_ih [in_dim, 3H] row-major, b_ih [3H], W_hh [H, 3H] row-major, b_hh [3H].
+ * RSLX_CELL_LSTM (G = 4, gate order i, f, g, o; forget gate, no peepholes), state per row: [h | c] [2H]
+ *   a = x W_ih + b_ih + h W_hh + b_hh
+ *   i = sigmoid(a_i), f = sigmoid(a_f), g = tanh(a_g), o = sigmoid(a_o), c' = f c + i g, h' = o tanh(c')
+ * "State" below always means the packed row of width S = H (GRU) or 2H (LSTM); the MLP reads h.
  * hidden must be a multiple of 4; buffers 16-byte aligned; grads/adam_* NULL for inference. */
-typedef struct rslx_gru {
+#define RSLX_CELL_GRU 0
+#define RSLX_CELL_LSTM 1
+typedef struct rslx_memory {
+  int32_t cell;
   int32_t in_dim, hidden;
   float* params;
   float* grads;
   float* adam_m;
   float* adam_v;
-} rslx_gru;
+} rslx_memory;
 
-/* One roll-out step of a recurrent actor-critic: each network is a GRU whose new state feeds its
- * MLP (mlp.dims[0] == gru.hidden).  For every environment n:
- *   hin = reset[n] ? 0 : h[n];   h[n] <- GRU(obs[n], hin);   mu, V = MLPs(h[n]);  then as rslx_act.
+/* One roll-out step of a recurrent actor-critic: each network is a memory whose new hidden state
+ * feeds its MLP (mlp.dims[0] == memory.hidden).  For every environment n:
+ *   sin = reset[n] ? 0 : s[n];   s[n] <- cell(obs[n], sin);   mu, V = MLPs(h of s[n]);  then as rslx_act.
  * reset_or_null (device uint8 [N]) carries the previous step's episode-end flags.  h_actor
- * [N, H_a] and h_critic [N, H_c] (device) are updated in place; when h0_actor_out / h0_critic_out
- * are not NULL they receive hin, the state the step started from - the roll-out's first step
+ * [N, S_a] and h_critic [N, S_c] (device, packed states) are updated in place; when h0_actor_out / h0_critic_out
+ * are not NULL they receive sin, the state the step started from - the roll-out's first step
  * stores it for rslx_ppo_update_recurrent.  With RSLX_ACT_VALUES_ONLY only the critic runs and
  * NO state is written (the bootstrap value of the observation that opens the next roll-out).
  * Everything else (noise, outputs, flags, errors) is as in rslx_act. */
-size_t rslx_act_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor,
-                                          const rslx_gru* gru_critic, const rslx_mlp* critic, int32_t N);
-int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+size_t rslx_act_recurrent_workspace_bytes(const rslx_memory* mem_actor, const rslx_mlp* actor,
+                                          const rslx_memory* mem_critic, const rslx_mlp* critic, int32_t N);
+int32_t rslx_act_recurrent(const rslx_memory* mem_actor, const rslx_mlp* actor, const rslx_memory* mem_critic,
                            const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
                            int32_t N, float* h_actor, float* h_critic, const uint8_t* reset_or_null,
                            float* h0_actor_out, float* h0_critic_out, uint64_t seed, uint64_t step,
@@ -308,42 +316,44 @@ int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, con
  * whole environment columns: per epoch the N environments are shuffled (the permutation stream of
  * rslx_ppo_update, over N instead of T*N) and minibatch m takes the m-th slice of N / minibatches
  * environments with all T steps, rows ordered step-major.  Each minibatch is re-run through both
- * memories from h0 (the states the roll-out's first step started from, [N, H]) with the state
+ * memories from h0 (the packed states the roll-out's first step started from, [N, S]) with the state
  * zeroed after every step whose `dones` flag is set; the loss of rslx_ppo_update (means over the
  * T * N / minibatches samples) is back-propagated through the MLPs into the hidden states and
  * through time, truncated at the roll-out start and never across an episode end.  One gradient
- * norm over the four parameter sets, one Adam step counter.  ro->Da / ro->Dc are the GRU input
- * widths.  dones: device uint8 [T, N].  N % minibatches != 0 is RSLX_ERR_SHAPE.  Symmetry and RND
+ * norm over the four parameter sets, one Adam step counter.  ro->Da / ro->Dc are the memories' input
+ * widths; both memories use the same cell.  dones: device uint8 [T, N].  N % minibatches != 0 is RSLX_ERR_SHAPE.  Symmetry and RND
  * are not available here.  grads of all four hold the last minibatch's gradient on return. */
-size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor,
-                                                 const rslx_gru* gru_critic, const rslx_mlp* critic,
+size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_memory* mem_actor, const rslx_mlp* actor,
+                                                 const rslx_memory* mem_critic, const rslx_mlp* critic,
                                                  const rslx_rollout* ro, const rslx_ppo_cfg* cfg);
-int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru* gru_critic,
+int32_t rslx_ppo_update_recurrent(rslx_memory* mem_actor, rslx_mlp* actor, rslx_memory* mem_critic,
                                   rslx_mlp* critic, const rslx_rollout* ro, const uint8_t* dones,
                                   const float* h0_actor, const float* h0_critic, const rslx_ppo_cfg* cfg,
                                   int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
                                   void* stream);
 
 /* One step of a single memory (the recurrent student of the distillation loop, paper Sec. 2.1 with
- * Sec. 3): hin = reset[n] ? 0 : h[n];  h[n] <- GRU(obs[n], hin), in place; h0_out (optional)
- * receives hin.  The student's action and the expert's label then come from
- * rslx_bc_collect(student_mlp, teacher, h, obs_teacher, ...). */
-size_t rslx_gru_step_workspace_bytes(const rslx_gru* gru, int32_t N);
-int32_t rslx_gru_step(const rslx_gru* gru, const float* obs, int32_t N, float* h,
-                      const uint8_t* reset_or_null, float* h0_out, void* ws, size_t ws_bytes,
-                      void* stream);
+ * Sec. 3): sin = reset[n] ? 0 : s[n];  s[n] <- cell(obs[n], sin), in place on the packed state
+ * s [N, S]; s0_out (optional, [N, S]) receives sin; h_dense_out (optional, [N, H]) receives the
+ * new hidden state as a dense matrix (for a GRU the state itself is that matrix).  The student's
+ * action and the expert's label then come from
+ * rslx_bc_collect(student_mlp, teacher, hidden state, obs_teacher, ...). */
+size_t rslx_memory_step_workspace_bytes(const rslx_memory* mem, int32_t N);
+int32_t rslx_memory_step(const rslx_memory* mem, const float* obs, int32_t N, float* s,
+                         const uint8_t* reset_or_null, float* s0_out, float* h_dense_out, void* ws,
+                         size_t ws_bytes, void* stream);
 
-/* Behaviour cloning of a recurrent student (GRU memory + MLP, student->dims[0] == gru->hidden) on
+/* Behaviour cloning of a recurrent student (memory + MLP, student->dims[0] == mem->hidden) on
  * a roll-out: obs_student [T, N, Ds], targets [T, N, A] (the expert's actions on the visited
- * states), dones uint8 [T, N], h0 [N, H] (the state the roll-out's first step started from); all
+ * states), dones uint8 [T, N], h0 [N, S] (the packed state the roll-out's first step started from); all
  * device.  Minibatches are whole environment columns as in rslx_ppo_update_recurrent (cfg's
  * permutation stream over N; N % minibatches != 0 is RSLX_ERR_SHAPE); per minibatch
  * L = mean over the T * N / minibatches rows and the A action dims of (student - target)^2,
  * back-propagated through the MLP and through time, optional clip, Adam (one step counter for
  * memory and MLP).  stats as in rslx_bc_update. */
-size_t rslx_bc_update_recurrent_workspace_bytes(const rslx_gru* gru, const rslx_mlp* student, int32_t T,
+size_t rslx_bc_update_recurrent_workspace_bytes(const rslx_memory* mem, const rslx_mlp* student, int32_t T,
                                                 int32_t N, const rslx_bc_cfg* cfg);
-int32_t rslx_bc_update_recurrent(rslx_gru* gru, rslx_mlp* student, const float* obs_student,
+int32_t rslx_bc_update_recurrent(rslx_memory* mem, rslx_mlp* student, const float* obs_student,
                                  const float* targets, const uint8_t* dones, const float* h0, int32_t T,
                                  int32_t N, const rslx_bc_cfg* cfg, int64_t* adam_step, float* stats,
                                  void* ws, size_t ws_bytes, void* stream);

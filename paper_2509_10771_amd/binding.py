@@ -12,9 +12,9 @@ __all__ = [
     "rslx_bc_update", "rslx_bc_update_workspace_bytes", "rslx_sym_augment", "rslx_rnd", "rslx_rnd_workspace_bytes",
     "ACT_DETERMINISTIC", "ACT_VALUES_ONLY", "EXPORTS", "rslx_trace_begin", "rslx_trace_end",
     "dev_counters", "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes",
-    "rslx_bc_collect", "Gru", "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent",
-    "rslx_ppo_update_recurrent_workspace_bytes", "rslx_ppo_update_recurrent", "rslx_gru_step_workspace_bytes",
-    "rslx_gru_step", "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
+    "rslx_bc_collect", "Memory", "Gru", "Lstm", "CELL_GRU", "CELL_LSTM", "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent",
+    "rslx_ppo_update_recurrent_workspace_bytes", "rslx_ppo_update_recurrent", "rslx_memory_step_workspace_bytes",
+    "rslx_memory_step", "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
 ]
 
 MAX_LAYERS = 8
@@ -29,7 +29,7 @@ EXPORTS = [
     "rslx_bc_update", "rslx_sym_augment", "rslx_rnd_workspace_bytes", "rslx_rnd", "rslx_trace_begin", "rslx_trace_end",
     "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes", "rslx_bc_collect",
     "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent", "rslx_ppo_update_recurrent_workspace_bytes",
-    "rslx_ppo_update_recurrent", "rslx_gru_step_workspace_bytes", "rslx_gru_step",
+    "rslx_ppo_update_recurrent", "rslx_memory_step_workspace_bytes", "rslx_memory_step",
     "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
 ]
 
@@ -54,9 +54,9 @@ class _CMlp(C.Structure):
                 ("has_log_std", C.c_int32), ("params", _vp), ("grads", _vp), ("adam_m", _vp), ("adam_v", _vp)]
 
 
-class _CGru(C.Structure):
-    _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("params", _vp), ("grads", _vp), ("adam_m", _vp),
-                ("adam_v", _vp)]
+class _CMemory(C.Structure):
+    _fields_ = [("cell", C.c_int32), ("in_dim", C.c_int32), ("hidden", C.c_int32), ("params", _vp), ("grads", _vp),
+                ("adam_m", _vp), ("adam_v", _vp)]
 
 
 class _CRollout(C.Structure):
@@ -130,18 +130,18 @@ _sig("rslx_bc_update_dc", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, _vp, C.c_i
                                       C.c_size_t, _vp])
 _sig("rslx_bc_collect_workspace_bytes", C.c_size_t, [_P(_CMlp), _P(_CMlp), C.c_int32])
 _sig("rslx_bc_collect", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp, C.c_size_t, _vp])
-_sig("rslx_act_recurrent_workspace_bytes", C.c_size_t, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), C.c_int32])
-_sig("rslx_act_recurrent", C.c_int32, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp,
+_sig("rslx_act_recurrent_workspace_bytes", C.c_size_t, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), C.c_int32])
+_sig("rslx_act_recurrent", C.c_int32, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp,
                                        _vp, C.c_uint64, C.c_uint64, _vp, _vp, _vp, _vp, _vp, _vp, C.c_uint32, _vp,
                                        C.c_size_t, _vp])
-_sig("rslx_ppo_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), _P(_CRollout),
+_sig("rslx_ppo_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _P(_CRollout),
                                                                _P(_CPpoCfg)])
-_sig("rslx_ppo_update_recurrent", C.c_int32, [_P(_CGru), _P(_CMlp), _P(_CGru), _P(_CMlp), _P(_CRollout), _vp, _vp, _vp,
+_sig("rslx_ppo_update_recurrent", C.c_int32, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _P(_CRollout), _vp, _vp, _vp,
                                               _P(_CPpoCfg), _P(C.c_int64), _vp, _vp, C.c_size_t, _vp])
-_sig("rslx_gru_step_workspace_bytes", C.c_size_t, [_P(_CGru), C.c_int32])
-_sig("rslx_gru_step", C.c_int32, [_P(_CGru), _vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_size_t, _vp])
-_sig("rslx_bc_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CGru), _P(_CMlp), C.c_int32, C.c_int32, _P(_CBcCfg)])
-_sig("rslx_bc_update_recurrent", C.c_int32, [_P(_CGru), _P(_CMlp), _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, _P(_CBcCfg),
+_sig("rslx_memory_step_workspace_bytes", C.c_size_t, [_P(_CMemory), C.c_int32])
+_sig("rslx_memory_step", C.c_int32, [_P(_CMemory), _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp])
+_sig("rslx_bc_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CMemory), _P(_CMlp), C.c_int32, C.c_int32, _P(_CBcCfg)])
+_sig("rslx_bc_update_recurrent", C.c_int32, [_P(_CMemory), _P(_CMlp), _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, _P(_CBcCfg),
                                              _P(C.c_int64), _vp, _vp, C.c_size_t, _vp])
 _sig("rslx_sym_augment", C.c_int32, [_P(_CSym), _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, _vp])
 _sig("rslx_rnd_workspace_bytes", C.c_size_t, [_P(_CMlp), C.c_int32])
@@ -205,12 +205,18 @@ class Mlp:
         return s
 
 
-class Gru:
-    """GRU memory over a flat device buffer: W_ih [in, 3H], b_ih [3H], W_hh [H, 3H], b_hh [3H]."""
+CELL_GRU, CELL_LSTM = 0, 1
 
-    def __init__(self, in_dim, hidden, params, trainable=False):
-        self.in_dim, self.hidden = int(in_dim), int(hidden)
-        assert params.numel() == 3 * self.hidden * (self.in_dim + self.hidden + 2)
+
+class Memory:
+    """Recurrent memory over a flat device buffer: W_ih [in, G H], b_ih [G H], W_hh [H, G H], b_hh [G H]
+    (GRU: G = 3, state width H; LSTM: G = 4, packed state [h | c] of width 2 H)."""
+
+    def __init__(self, cell, in_dim, hidden, params, trainable=False):
+        self.cell, self.in_dim, self.hidden = int(cell), int(in_dim), int(hidden)
+        self.gates = 4 if self.cell == CELL_LSTM else 3
+        self.state_width = 2 * self.hidden if self.cell == CELL_LSTM else self.hidden
+        assert params.numel() == self.gates * self.hidden * (self.in_dim + self.hidden + 2)
         self.params = params
         self.grads = torch.zeros_like(params) if trainable else None
         self.adam_m = torch.zeros_like(params) if trainable else None
@@ -218,7 +224,16 @@ class Gru:
 
     @property
     def c(self):
-        return _CGru(self.in_dim, self.hidden, _ptr(self.params), _ptr(self.grads), _ptr(self.adam_m), _ptr(self.adam_v))
+        return _CMemory(self.cell, self.in_dim, self.hidden, _ptr(self.params), _ptr(self.grads), _ptr(self.adam_m),
+                        _ptr(self.adam_v))
+
+
+def Gru(in_dim, hidden, params, trainable=False):
+    return Memory(CELL_GRU, in_dim, hidden, params, trainable)
+
+
+def Lstm(in_dim, hidden, params, trainable=False):
+    return Memory(CELL_LSTM, in_dim, hidden, params, trainable)
 
 
 class Rollout:
@@ -446,13 +461,13 @@ def rslx_ppo_update_recurrent(gru_actor, actor, gru_critic, critic, rollout, don
            "rslx_ppo_update_recurrent")
 
 
-def rslx_gru_step_workspace_bytes(gru, N):
-    return lib.rslx_gru_step_workspace_bytes(_ref(gru.c), N)
+def rslx_memory_step_workspace_bytes(mem, N):
+    return lib.rslx_memory_step_workspace_bytes(_ref(mem.c), N)
 
 
-def rslx_gru_step(gru, obs, N, h, reset, h0_out, ws):
-    _check(lib.rslx_gru_step(_ref(gru.c), _ptr(obs), N, _ptr(h), _ptr(reset), _ptr(h0_out), _ptr(ws),
-                             ws.numel() if ws is not None else 0, _stream()), "rslx_gru_step")
+def rslx_memory_step(mem, obs, N, state, reset, s0_out, h_dense_out, ws):
+    _check(lib.rslx_memory_step(_ref(mem.c), _ptr(obs), N, _ptr(state), _ptr(reset), _ptr(s0_out), _ptr(h_dense_out), _ptr(ws),
+                                ws.numel() if ws is not None else 0, _stream()), "rslx_memory_step")
 
 
 def rslx_bc_update_recurrent_workspace_bytes(gru, student, T, N, cfg):

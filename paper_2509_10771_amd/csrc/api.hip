@@ -450,7 +450,9 @@ hipError_t advance_counters(rslx_dev_counters* c, int64_t act, int64_t call, int
 int32_t act_impl(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
                  int32_t N, uint64_t seed, uint64_t step, rslx_dev_counters* counters, const float* eps_or_null,
                  float* actions, float* logp, float* values, float* mu, float* sigma, uint32_t flags, void* ws,
-                 size_t ws_bytes, void* stream) {
+                 size_t ws_bytes, void* stream, int32_t ld_actor = 0, int32_t ld_critic = 0) {
+  // ld_actor / ld_critic: row strides of the input matrices when they are wider than the networks' inputs (the
+  // hidden part of a packed recurrent state); 0 = dense.
   const bool values_only = (flags & RSLX_ACT_VALUES_ONLY) != 0;
   const int64_t* step_dev = counters ? &counters->act_step : nullptr;
   const uint64_t noise_pre = mix64_host(seed ^ 0xAC7ull);
@@ -475,10 +477,10 @@ int32_t act_impl(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs
     fa.n_rows = N;
     fa.max_dim = max_dim_of(*critic);
     if (a) {
-      fa.net[fa.n_nets++] = fused_net(*a, obs_actor, a->dims[0], nullptr, mu, true);
+      fa.net[fa.n_nets++] = fused_net(*a, obs_actor, ld_actor ? ld_actor : a->dims[0], nullptr, mu, true);
       fa.max_dim = max_dim_of(*a) > fa.max_dim ? max_dim_of(*a) : fa.max_dim;
     }
-    fa.net[fa.n_nets++] = fused_net(*critic, obs_critic, critic->dims[0], nullptr, values, false);
+    fa.net[fa.n_nets++] = fused_net(*critic, obs_critic, ld_critic ? ld_critic : critic->dims[0], nullptr, values, false);
     fa.deterministic = (flags & RSLX_ACT_DETERMINISTIC) ? 1 : 0;
     fa.eps = eps_or_null;
     fa.noise_base = mix64_host(noise_pre ^ step);
@@ -499,10 +501,10 @@ int32_t act_impl(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs
   int nj = 0;
   if (a) {
     ba.out[a->n_layers - 1] = mu;
-    XView xa; xa.base = obs_actor; xa.ld = a->dims[0];
+    XView xa; xa.base = obs_actor; xa.ld = ld_actor ? ld_actor : a->dims[0];
     jobs[nj++] = NetJob{a, xa, N, &ba};
   }
-  XView xc; xc.base = obs_critic; xc.ld = critic->dims[0];
+  XView xc; xc.base = obs_critic; xc.ld = ld_critic ? ld_critic : critic->dims[0];
   jobs[nj++] = NetJob{critic, xc, N, &bc};
   RSLX_TRY(forward_nets(jobs, nj, s));
   if (a) {
@@ -1155,17 +1157,21 @@ int32_t rslx_rnd(const rslx_mlp* target, const rslx_mlp* predictor, const float*
 }  // extern "C"
 
 // ======================================================================================================
-// Recurrent actor-critic: GRU memories in front of the MLPs, back-propagation through time.
+// Recurrent actor-critic: GRU or LSTM memories in front of the MLPs, back-propagation through time.
 // ======================================================================================================
 namespace {
 
-int64_t gru_off_bih(const rslx_gru& g) { return (int64_t)g.in_dim * 3 * g.hidden; }
-int64_t gru_off_whh(const rslx_gru& g) { return gru_off_bih(g) + 3 * g.hidden; }
-int64_t gru_off_bhh(const rslx_gru& g) { return gru_off_whh(g) + (int64_t)g.hidden * 3 * g.hidden; }
-int64_t gru_count(const rslx_gru& g) { return gru_off_bhh(g) + 3 * g.hidden; }
+int gates(const rslx_memory& g) { return g.cell == RSLX_CELL_LSTM ? 4 : 3; }
+int gate_width(const rslx_memory& g) { return gates(g) * g.hidden; }                              // G H
+int state_width(const rslx_memory& g) { return g.cell == RSLX_CELL_LSTM ? 2 * g.hidden : g.hidden; }   // S
+int64_t gru_off_bih(const rslx_memory& g) { return (int64_t)g.in_dim * gate_width(g); }
+int64_t gru_off_whh(const rslx_memory& g) { return gru_off_bih(g) + gate_width(g); }
+int64_t gru_off_bhh(const rslx_memory& g) { return gru_off_whh(g) + (int64_t)g.hidden * gate_width(g); }
+int64_t gru_count(const rslx_memory& g) { return gru_off_bhh(g) + gate_width(g); }
 
-int32_t check_gru(const rslx_gru* g, const char* name, bool trainable) {
+int32_t check_gru(const rslx_memory* g, const char* name, bool trainable) {
   if (!g) return fail(RSLX_ERR_INVALID_ARG, "%s: null memory", name);
+  if (g->cell != RSLX_CELL_GRU && g->cell != RSLX_CELL_LSTM) return fail(RSLX_ERR_INVALID_ARG, "%s: unknown cell %d", name, g->cell);
   if (g->in_dim < 1 || g->in_dim > (1 << 20) || g->hidden < 4 || g->hidden > (1 << 16) || g->hidden % 4 != 0)
     return fail(RSLX_ERR_SHAPE, "%s: in_dim = %d, hidden = %d (hidden must be a multiple of 4)", name, g->in_dim, g->hidden);
   if (!g->params || !aligned16(g->params)) return fail(RSLX_ERR_INVALID_ARG, "%s: params null or not 16-byte aligned", name);
@@ -1177,7 +1183,7 @@ int32_t check_gru(const rslx_gru* g, const char* name, bool trainable) {
   return RSLX_OK;
 }
 
-// C[M, 3H] = X W + b for one side of a memory's gates (X given as a view or as a plain matrix).
+// C[M, G H] = X W + b for one side of a memory's gates (X given as a view or as a plain matrix).
 GemmProblem gate_problem(const XView& x, int K, const float* W, const float* b, float* C, int M, int H3) {
   GemmProblem p = blank_problem();
   set_x(p, x);
@@ -1197,45 +1203,46 @@ XView plain_view(const float* base, int ld) {
 }
 
 struct StepBufs {     // one memory's buffers of a single act step
-  float* hin = nullptr;
-  float* gi = nullptr;
-  float* hnew = nullptr;    // values-only: the state is not written back
+  float* hin = nullptr;     // [N, S] state the step starts from (after reset)
+  float* gi = nullptr;      // [N, G H]
+  float* hnew = nullptr;    // [N, S] values-only: the state is not written back
 };
 
-size_t act_recurrent_carve(Carver& c, const rslx_gru* ga, const rslx_gru* gc, int32_t N, StepBufs* ba, StepBufs* bc) {
-  const rslx_gru* g[2] = {ga, gc};
+size_t act_recurrent_carve(Carver& c, const rslx_memory* ga, const rslx_memory* gc, int32_t N, StepBufs* ba, StepBufs* bc) {
+  const rslx_memory* g[2] = {ga, gc};
   StepBufs* b[2] = {ba, bc};
   for (int k = 0; k < 2; ++k) {
     if (!g[k]) continue;
     StepBufs t;
-    t.hin = c.take<float>((size_t)N * g[k]->hidden);
-    t.gi = c.take<float>((size_t)N * 3 * g[k]->hidden);
-    t.hnew = c.take<float>((size_t)N * g[k]->hidden);
+    t.hin = c.take<float>((size_t)N * state_width(*g[k]));
+    t.gi = c.take<float>((size_t)N * gate_width(*g[k]));
+    t.hnew = c.take<float>((size_t)N * state_width(*g[k]));
     if (b[k]) *b[k] = t;
   }
   return c.off;
 }
 
 // hin -> gi -> new state (hidden-side contraction fused with the gates), for the memories listed (1 or 2), each with its own input matrix.
-int32_t gru_step(const rslx_gru* const* g, const float* const* obs, const StepBufs* b, float* const* h_out, int count,
+int32_t gru_step(const rslx_memory* const* g, const float* const* obs, const StepBufs* b, float* const* h_out, int count,
                  int32_t N, hipStream_t s) {
   GemmBatch bi;
   bi.count = count;
-  GruStepFwdArgs sa;
+  StepFwdArgs sa;
   memset(&sa, 0, sizeof sa);
-  sa.n_nets = count; sa.nb = N;
+  sa.n_nets = count; sa.nb = N; sa.cell = g[0]->cell;
   for (int k = 0; k < count; ++k) {
-    const rslx_gru& m = *g[k];
-    bi.p[k] = gate_problem(plain_view(obs[k], m.in_dim), m.in_dim, m.params, m.params + gru_off_bih(m), b[k].gi, N, 3 * m.hidden);
-    sa.net[k] = GruFwdNet{b[k].gi, b[k].hin, h_out[k], nullptr, m.params + gru_off_whh(m), m.params + gru_off_bhh(m),
-                          nullptr, m.hidden};
+    const rslx_memory& m = *g[k];
+    bi.p[k] = gate_problem(plain_view(obs[k], m.in_dim), m.in_dim, m.params, m.params + gru_off_bih(m), b[k].gi, N, gate_width(m));
+    // the new packed state goes to h_out[k] ([N, S]): h in its first H columns, an LSTM's c behind it
+    sa.net[k] = StepFwdNet{b[k].gi, b[k].hin, h_out[k], m.cell == RSLX_CELL_LSTM ? h_out[k] + m.hidden : nullptr, nullptr,
+                           m.params + gru_off_whh(m), m.params + gru_off_bhh(m), nullptr, m.hidden, state_width(m)};
   }
   RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
-  RSLX_HIP(launch_gru_step_fwd(sa, s));
+  RSLX_HIP(launch_step_fwd(sa, s));
   return RSLX_OK;
 }
 
-int32_t act_recurrent_validate(const rslx_gru* ga, const rslx_mlp* actor, const rslx_gru* gc, const rslx_mlp* critic,
+int32_t act_recurrent_validate(const rslx_memory* ga, const rslx_mlp* actor, const rslx_memory* gc, const rslx_mlp* critic,
                                bool values_only) {
   RSLX_TRY(check_gru(gc, "rslx_act_recurrent critic memory", false));
   RSLX_TRY(check_mlp(critic, "rslx_act_recurrent critic", false));
@@ -1244,6 +1251,7 @@ int32_t act_recurrent_validate(const rslx_gru* ga, const rslx_mlp* actor, const 
     RSLX_TRY(check_gru(ga, "rslx_act_recurrent actor memory", false));
     RSLX_TRY(check_mlp(actor, "rslx_act_recurrent actor", false));
     if (actor->dims[0] != ga->hidden) return fail(RSLX_ERR_SHAPE, "rslx_act_recurrent: actor input width != memory width");
+    if (ga->cell != gc->cell) return fail(RSLX_ERR_UNSUPPORTED, "rslx_act_recurrent: the two memories use different cells");
   }
   return RSLX_OK;
 }
@@ -1252,7 +1260,7 @@ int32_t act_recurrent_validate(const rslx_gru* ga, const rslx_mlp* actor, const 
 
 extern "C" {
 
-size_t rslx_act_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+size_t rslx_act_recurrent_workspace_bytes(const rslx_memory* gru_actor, const rslx_mlp* actor, const rslx_memory* gru_critic,
                                           const rslx_mlp* critic, int32_t N) {
   if (N <= 0 || !gru_critic || !critic) return 256;
   Carver c(nullptr);
@@ -1260,7 +1268,7 @@ size_t rslx_act_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_
   return (c.off + 255) / 256 * 256 + rslx_act_workspace_bytes(actor, critic, N);
 }
 
-int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+int32_t rslx_act_recurrent(const rslx_memory* gru_actor, const rslx_mlp* actor, const rslx_memory* gru_critic,
                            const rslx_mlp* critic, const float* obs_actor, const float* obs_critic, int32_t N,
                            float* h_actor, float* h_critic, const uint8_t* reset_or_null, float* h0_actor_out,
                            float* h0_critic_out, uint64_t seed, uint64_t step, const float* eps_or_null, float* actions,
@@ -1275,7 +1283,7 @@ int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, con
       (h0_critic_out && !aligned16(h0_critic_out)))
     return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: state buffers not 16-byte aligned");
   if (N == 0) return RSLX_OK;
-  const rslx_gru* ga = values_only ? nullptr : gru_actor;
+  const rslx_memory* ga = values_only ? nullptr : gru_actor;
   const rslx_mlp* a = values_only ? nullptr : actor;
   if (!ws || ws_bytes < rslx_act_recurrent_workspace_bytes(ga, a, gru_critic, critic, N))
     return fail(RSLX_ERR_WORKSPACE, "rslx_act_recurrent: workspace too small");
@@ -1288,27 +1296,28 @@ int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, con
   RowGatherArgs rg;
   memset(&rg, 0, sizeof rg);
   rg.nb = N; rg.reset = reset_or_null;
-  if (ga) rg.job[rg.n_jobs++] = RowGatherJob{h_actor, ba.hin, values_only ? nullptr : h0_actor_out, ga->hidden};
-  rg.job[rg.n_jobs++] = RowGatherJob{h_critic, bc.hin, values_only ? nullptr : h0_critic_out, gru_critic->hidden};
+  if (ga) rg.job[rg.n_jobs++] = RowGatherJob{h_actor, ba.hin, values_only ? nullptr : h0_actor_out, state_width(*ga)};
+  rg.job[rg.n_jobs++] = RowGatherJob{h_critic, bc.hin, values_only ? nullptr : h0_critic_out, state_width(*gru_critic)};
   RSLX_HIP(launch_row_gather(rg, s));
 
   const float* h_in_actor_mlp = h_actor;
   const float* h_in_critic_mlp = values_only ? bc.hnew : h_critic;
   if (ga) {
-    const rslx_gru* g[2] = {ga, gru_critic};
+    const rslx_memory* g[2] = {ga, gru_critic};
     const float* obs[2] = {obs_actor, obs_critic};
     const StepBufs b[2] = {ba, bc};
     float* out[2] = {h_actor, h_critic};
     RSLX_TRY(gru_step(g, obs, b, out, 2, N, s));
   } else {
-    const rslx_gru* g[1] = {gru_critic};
+    const rslx_memory* g[1] = {gru_critic};
     const float* obs[1] = {obs_critic};
     const StepBufs b[1] = {bc};
     float* out[1] = {bc.hnew};
     RSLX_TRY(gru_step(g, obs, b, out, 1, N, s));
   }
   return act_impl(a, critic, h_in_actor_mlp, h_in_critic_mlp, N, seed, step, nullptr, eps_or_null, actions, logp, values,
-                  mu, sigma, flags, static_cast<char*>(ws) + used, ws_bytes - used, stream);
+                  mu, sigma, flags, static_cast<char*>(ws) + used, ws_bytes - used, stream, ga ? state_width(*ga) : 0,
+                  state_width(*gru_critic));
 }
 
 }  // extern "C"
@@ -1316,11 +1325,14 @@ int32_t rslx_act_recurrent(const rslx_gru* gru_actor, const rslx_mlp* actor, con
 namespace {
 
 struct RnnBufs {          // per memory, one column-wise minibatch (rows = T * nb)
-  float* gi = nullptr; float* gh = nullptr; float* dgi = nullptr; float* dgh = nullptr;   // [rows, 3H]
-  float* hin = nullptr;   // [rows, H] state every step starts from
-  float* hs = nullptr;    // [rows, H] new states = input of the MLP
+  float* gi = nullptr;    // [rows, G H] input-side gate terms
+  float* gh = nullptr;    // [rows, G H] what the forward steps store for the backward pass (GRU: gh, LSTM: a)
+  float* dgi = nullptr;   // [rows, G H] GRU only: gradient w.r.t. gi
+  float* dgh = nullptr;   // [rows, G H] gradient w.r.t. the hidden-side terms (LSTM: w.r.t. a, serves both sides)
+  float* hin = nullptr;   // [rows, S] packed state every step starts from
+  float* hs = nullptr;    // [rows, H] new hidden states = input of the MLP
   float* dh = nullptr;    // [rows, H] gradient from the MLP
-  float* direct = nullptr;  // [nb, H]
+  float* direct = nullptr;  // [nb, H] carried between backward steps (GRU: dh z, LSTM: gradient w.r.t. c)
   SplitPlan plan;           // layer 0: W_ih / b_ih, layer 1: W_hh / b_hh
   float* partials = nullptr;
 };
@@ -1340,18 +1352,19 @@ struct RnnPlan {
   size_t bytes = 0;
 };
 
-void carve_memory(Carver& c, const rslx_gru& g, int32_t rows, int32_t nb, RnnBufs& b, int group = 2) {
-  const size_t H = g.hidden;
-  b.gi = c.take<float>(rows * 3 * H); b.gh = c.take<float>(rows * 3 * H);
-  b.dgi = c.take<float>(rows * 3 * H); b.dgh = c.take<float>(rows * 3 * H);
-  b.hin = c.take<float>(rows * H); b.hs = c.take<float>(rows * H); b.dh = c.take<float>(rows * H);
+void carve_memory(Carver& c, const rslx_memory& g, int32_t rows, int32_t nb, RnnBufs& b, int group = 2) {
+  const size_t H = g.hidden, GH = gate_width(g), S = state_width(g);
+  b.gi = c.take<float>(rows * GH); b.gh = c.take<float>(rows * GH);
+  b.dgi = g.cell == RSLX_CELL_GRU ? c.take<float>(rows * GH) : nullptr;
+  b.dgh = c.take<float>(rows * GH);
+  b.hin = c.take<float>(rows * S); b.hs = c.take<float>(rows * H); b.dh = c.take<float>(rows * H);
   b.direct = c.take<float>(nb * H);
-  plan_layer(b.plan, 0, g.in_dim, 3 * g.hidden, rows, group, false);
-  plan_layer(b.plan, 1, g.hidden, 3 * g.hidden, rows, group, false);
+  plan_layer(b.plan, 0, g.in_dim, (int)GH, rows, group, false);
+  plan_layer(b.plan, 1, g.hidden, (int)GH, rows, group, false);
   b.partials = c.take<float>((size_t)b.plan.total);
 }
 
-void rnn_plan(Carver& c, const rslx_gru* ga, const rslx_mlp* actor, const rslx_gru* gc, const rslx_mlp* critic,
+void rnn_plan(Carver& c, const rslx_memory* ga, const rslx_mlp* actor, const rslx_memory* gc, const rslx_mlp* critic,
               const rslx_rollout* ro, const rslx_ppo_cfg* cfg, RnnPlan& p) {
   p.T = ro->T; p.N = ro->N;
   p.nb = ro->N / cfg->minibatches;
@@ -1372,7 +1385,7 @@ void rnn_plan(Carver& c, const rslx_gru* ga, const rslx_mlp* actor, const rslx_g
   p.bytes = c.off + 256;
 }
 
-int32_t rnn_validate(const rslx_gru* ga, const rslx_mlp* actor, const rslx_gru* gc, const rslx_mlp* critic,
+int32_t rnn_validate(const rslx_memory* ga, const rslx_mlp* actor, const rslx_memory* gc, const rslx_mlp* critic,
                      const rslx_rollout* ro, const rslx_ppo_cfg* cfg, bool need_buffers) {
   if (!ro || !cfg) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: null rollout or cfg");
   RSLX_TRY(check_gru(ga, "rslx_ppo_update_recurrent actor memory", need_buffers));
@@ -1385,6 +1398,7 @@ int32_t rnn_validate(const rslx_gru* ga, const rslx_mlp* actor, const rslx_gru* 
   if (ro->Da != ga->in_dim || ro->Dc != gc->in_dim || actor->dims[0] != ga->hidden || critic->dims[0] != gc->hidden ||
       ro->A != actor->dims[actor->n_layers] || critic->dims[critic->n_layers] != 1)
     return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: rollout, memory and network widths do not match");
+  if (ga->cell != gc->cell) return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: the two memories use different cells");
   if (ro->A > 32) return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: action width %d > 32", ro->A);
   if (actor->n_layers + critic->n_layers + 4 > 16)
     return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: more than 12 MLP layers in total");
@@ -1416,14 +1430,14 @@ GemmProblem gate_dw_problem(const XView& x, int M, const float* dG, int H3, int3
 
 // Memories forward over one column-wise minibatch: the input-side gates of all T steps in one GEMM (rows gathered
 // from the roll-out through ridx), then one fused step launch per time step for all `count` memories.
-int32_t memories_forward(const rslx_gru* const* mem, RnnBufs* const* mb, int count, const float* const* obs,
+int32_t memories_forward(const rslx_memory* const* mem, RnnBufs* const* mb, int count, const float* const* obs,
                          const float* const* h0, const int32_t* envs, const int32_t* ridx, const uint8_t* dones, int T,
                          int nb, int N, hipStream_t s) {
   const int rows = T * nb;
   RowGatherArgs rg;
   memset(&rg, 0, sizeof rg);
   rg.n_jobs = count; rg.nb = nb; rg.idx = envs;
-  for (int k = 0; k < count; ++k) rg.job[k] = RowGatherJob{h0[k], mb[k]->hin, nullptr, mem[k]->hidden};
+  for (int k = 0; k < count; ++k) rg.job[k] = RowGatherJob{h0[k], mb[k]->hin, nullptr, state_width(*mem[k])};
   RSLX_HIP(launch_row_gather(rg, s));
   GemmBatch bi;
   bi.count = count;
@@ -1431,60 +1445,61 @@ int32_t memories_forward(const rslx_gru* const* mem, RnnBufs* const* mb, int cou
     XView x;
     x.base = obs[k]; x.ld = mem[k]->in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * N;
     bi.p[k] = gate_problem(x, mem[k]->in_dim, mem[k]->params, mem[k]->params + gru_off_bih(*mem[k]), mb[k]->gi, rows,
-                           3 * mem[k]->hidden);
+                           gate_width(*mem[k]));
   }
   RSLX_HIP(launch_gemm(GEMM_FWD, bi, s));
   for (int t = 0; t < T; ++t) {
-    GruStepFwdArgs sa;
+    StepFwdArgs sa;
     memset(&sa, 0, sizeof sa);
-    sa.n_nets = count; sa.nb = nb; sa.done = dones; sa.done_idx = ridx + (size_t)t * nb;
+    sa.n_nets = count; sa.nb = nb; sa.cell = mem[0]->cell; sa.done = dones; sa.done_idx = ridx + (size_t)t * nb;
     for (int k = 0; k < count; ++k) {
-      const rslx_gru& g = *mem[k];
-      const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
-      sa.net[k] = GruFwdNet{mb[k]->gi + o3, mb[k]->hin + o, mb[k]->hs + o,
-                            t + 1 < T ? mb[k]->hin + o + (size_t)nb * H : nullptr, g.params + gru_off_whh(g),
-                            g.params + gru_off_bhh(g), mb[k]->gh + o3, g.hidden};
+      const rslx_memory& g = *mem[k];
+      const size_t H = g.hidden, GH = gate_width(g), S = state_width(g), r0 = (size_t)t * nb;
+      sa.net[k] = StepFwdNet{mb[k]->gi + r0 * GH, mb[k]->hin + r0 * S, mb[k]->hs + r0 * H, nullptr,
+                             t + 1 < T ? mb[k]->hin + (r0 + nb) * S : nullptr, g.params + gru_off_whh(g),
+                             g.params + gru_off_bhh(g), mb[k]->gh + r0 * GH, g.hidden, g.hidden};
     }
-    RSLX_HIP(launch_gru_step_fwd(sa, s));
+    RSLX_HIP(launch_step_fwd(sa, s));
   }
   return RSLX_OK;
 }
 
-// Back-propagation through time from mb[k]->dh (the gradient w.r.t. every step's new state): one fused step launch
-// per time step, last to first, then the weight gradients of both sides of the gates over all steps at once
+// Back-propagation through time from mb[k]->dh (the gradient w.r.t. every step's new hidden state): one fused step
+// launch per time step, last to first, then the weight gradients of both sides of the gates over all steps at once
 // (split partials, to be summed by the caller's reduction).
-int32_t memories_backward(const rslx_gru* const* mem, RnnBufs* const* mb, int count, const float* const* obs,
+int32_t memories_backward(const rslx_memory* const* mem, RnnBufs* const* mb, int count, const float* const* obs,
                           const int32_t* ridx, const uint8_t* dones, int T, int nb, int N, hipStream_t s) {
   const int rows = T * nb;
   for (int t = T - 1; t >= 0; --t) {
-    GruStepBwdArgs sb;
+    StepBwdArgs sb;
     memset(&sb, 0, sizeof sb);
-    sb.n_nets = count; sb.nb = nb; sb.done = dones; sb.done_idx = ridx + (size_t)t * nb;
+    sb.n_nets = count; sb.nb = nb; sb.cell = mem[0]->cell; sb.done = dones; sb.done_idx = ridx + (size_t)t * nb;
     for (int k = 0; k < count; ++k) {
-      const rslx_gru& g = *mem[k];
-      const size_t H = g.hidden, o = (size_t)t * nb * H, o3 = 3 * o;
+      const rslx_memory& g = *mem[k];
+      const size_t H = g.hidden, GH = gate_width(g), S = state_width(g), r0 = (size_t)t * nb;
       const bool last = t == T - 1;
-      sb.net[k] = GruBwdNet{mb[k]->dh + o, last ? nullptr : mb[k]->dgh + o3 + (size_t)nb * 3 * H, mb[k]->direct,
-                            g.params + gru_off_whh(g), mb[k]->gi + o3, mb[k]->gh + o3, mb[k]->hin + o, mb[k]->dgi + o3,
-                            mb[k]->dgh + o3, mb[k]->direct, g.hidden};
+      sb.net[k] = StepBwdNet{mb[k]->dh + r0 * H, last ? nullptr : mb[k]->dgh + (r0 + nb) * GH, mb[k]->direct,
+                             g.params + gru_off_whh(g), mb[k]->gi + r0 * GH, mb[k]->gh + r0 * GH, mb[k]->hin + r0 * S,
+                             mb[k]->dgi ? mb[k]->dgi + r0 * GH : nullptr, mb[k]->dgh + r0 * GH, g.hidden};
     }
-    RSLX_HIP(launch_gru_step_bwd(sb, s));
+    RSLX_HIP(launch_step_bwd(sb, s));
   }
   GemmBatch bwi, bwh;
   bwi.count = bwh.count = count;
   for (int k = 0; k < count; ++k) {
-    const rslx_gru& g = *mem[k];
+    const rslx_memory& g = *mem[k];
     XView x;
     x.base = obs[k]; x.ld = g.in_dim; x.row_idx = ridx; x.src_rows = (int64_t)T * N;
-    bwi.p[k] = gate_dw_problem(x, g.in_dim, mb[k]->dgi, 3 * g.hidden, rows, *mb[k], 0);
-    bwh.p[k] = gate_dw_problem(plain_view(mb[k]->hin, g.hidden), g.hidden, mb[k]->dgh, 3 * g.hidden, rows, *mb[k], 1);
+    // an LSTM's two sides of the gates share one gradient
+    bwi.p[k] = gate_dw_problem(x, g.in_dim, mb[k]->dgi ? mb[k]->dgi : mb[k]->dgh, gate_width(g), rows, *mb[k], 0);
+    bwh.p[k] = gate_dw_problem(plain_view(mb[k]->hin, state_width(g)), g.hidden, mb[k]->dgh, gate_width(g), rows, *mb[k], 1);
   }
   RSLX_HIP(launch_gemm(GEMM_DW, bwi, s));
   RSLX_HIP(launch_gemm(GEMM_DW, bwh, s));
   return RSLX_OK;
 }
 
-void reduce_add_memory(ReduceArgs& a, const rslx_gru& g, const RnnBufs& b) {
+void reduce_add_memory(ReduceArgs& a, const rslx_memory& g, const RnnBufs& b) {
   for (int l = 0; l < 2; ++l) {
     ReduceSeg& sg = a.seg[a.n_seg++];
     sg.partials = b.partials + b.plan.part_off[l];
@@ -1501,7 +1516,7 @@ void reduce_add_memory(ReduceArgs& a, const rslx_gru& g, const RnnBufs& b) {
 
 extern "C" {
 
-size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_gru* gru_actor, const rslx_mlp* actor, const rslx_gru* gru_critic,
+size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_memory* gru_actor, const rslx_mlp* actor, const rslx_memory* gru_critic,
                                                  const rslx_mlp* critic, const rslx_rollout* ro, const rslx_ppo_cfg* cfg) {
   if (rnn_validate(gru_actor, actor, gru_critic, critic, ro, cfg, false) != RSLX_OK) return 0;
   Carver c(nullptr);
@@ -1510,7 +1525,7 @@ size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_gru* gru_actor, cons
   return p.bytes;
 }
 
-int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru* gru_critic, rslx_mlp* critic,
+int32_t rslx_ppo_update_recurrent(rslx_memory* gru_actor, rslx_mlp* actor, rslx_memory* gru_critic, rslx_mlp* critic,
                                   const rslx_rollout* ro, const uint8_t* dones, const float* h0_actor, const float* h0_critic,
                                   const rslx_ppo_cfg* cfg, int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
                                   void* stream) {
@@ -1525,7 +1540,7 @@ int32_t rslx_ppo_update_recurrent(rslx_gru* gru_actor, rslx_mlp* actor, rslx_gru
   if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_ppo_update_recurrent: workspace %zu < %zu bytes", ws_bytes, p.bytes);
   const int A = ro->A, L_a = actor->n_layers, L_c = critic->n_layers;
   const int T = p.T, nb = p.nb, rows = p.rows;
-  const rslx_gru* mem[2] = {gru_actor, gru_critic};
+  const rslx_memory* mem[2] = {gru_actor, gru_critic};
   RnnBufs* mb[2] = {&p.ma, &p.mc};
   const float* obs[2] = {ro->obs_actor, ro->obs_critic};
   const float* h0[2] = {h0_actor, h0_critic};
@@ -1634,7 +1649,7 @@ struct RnnBcPlan {
   size_t bytes = 0;
 };
 
-void rnn_bc_plan(Carver& c, const rslx_gru* g, const rslx_mlp* student, int32_t T, int32_t N, const rslx_bc_cfg* cfg, RnnBcPlan& p) {
+void rnn_bc_plan(Carver& c, const rslx_memory* g, const rslx_mlp* student, int32_t T, int32_t N, const rslx_bc_cfg* cfg, RnnBcPlan& p) {
   p.nb = N / cfg->minibatches;
   p.rows = T * p.nb;
   p.perms = c.take<int32_t>((size_t)cfg->epochs * N);
@@ -1648,7 +1663,7 @@ void rnn_bc_plan(Carver& c, const rslx_gru* g, const rslx_mlp* student, int32_t 
   p.bytes = c.off + 256;
 }
 
-int32_t rnn_bc_validate(const rslx_gru* g, const rslx_mlp* student, int32_t T, int32_t N, const rslx_bc_cfg* cfg, bool need_buffers) {
+int32_t rnn_bc_validate(const rslx_memory* g, const rslx_mlp* student, int32_t T, int32_t N, const rslx_bc_cfg* cfg, bool need_buffers) {
   if (!cfg) return fail(RSLX_ERR_INVALID_ARG, "rslx_bc_update_recurrent: null cfg");
   RSLX_TRY(check_gru(g, "rslx_bc_update_recurrent memory", need_buffers));
   RSLX_TRY(check_mlp(student, "rslx_bc_update_recurrent student", need_buffers));
@@ -1664,38 +1679,41 @@ int32_t rnn_bc_validate(const rslx_gru* g, const rslx_mlp* student, int32_t T, i
 
 extern "C" {
 
-size_t rslx_gru_step_workspace_bytes(const rslx_gru* gru, int32_t N) {
-  if (!gru || N <= 0) return 256;
+size_t rslx_memory_step_workspace_bytes(const rslx_memory* mem, int32_t N) {
+  if (!mem || N <= 0) return 256;
   Carver c(nullptr);
-  act_recurrent_carve(c, gru, nullptr, N, nullptr, nullptr);
+  act_recurrent_carve(c, mem, nullptr, N, nullptr, nullptr);
   return c.off + 256;
 }
 
-int32_t rslx_gru_step(const rslx_gru* gru, const float* obs, int32_t N, float* h, const uint8_t* reset_or_null,
-                      float* h0_out, void* ws, size_t ws_bytes, void* stream) {
-  if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_gru_step: N = %d", N);
-  RSLX_TRY(check_gru(gru, "rslx_gru_step memory", false));
-  if (!obs || !h) return fail(RSLX_ERR_INVALID_ARG, "rslx_gru_step: null input or state");
-  if (!aligned16(h) || (h0_out && !aligned16(h0_out))) return fail(RSLX_ERR_INVALID_ARG, "rslx_gru_step: state buffers not 16-byte aligned");
+int32_t rslx_memory_step(const rslx_memory* mem, const float* obs, int32_t N, float* state, const uint8_t* reset_or_null,
+                         float* s0_out, float* h_dense_out, void* ws, size_t ws_bytes, void* stream) {
+  if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_memory_step: N = %d", N);
+  RSLX_TRY(check_gru(mem, "rslx_memory_step memory", false));
+  if (!obs || !state) return fail(RSLX_ERR_INVALID_ARG, "rslx_memory_step: null input or state");
+  if (!aligned16(state) || (s0_out && !aligned16(s0_out)) || (h_dense_out && !aligned16(h_dense_out)))
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_memory_step: state buffers not 16-byte aligned");
   if (N == 0) return RSLX_OK;
-  if (!ws || ws_bytes < rslx_gru_step_workspace_bytes(gru, N)) return fail(RSLX_ERR_WORKSPACE, "rslx_gru_step: workspace too small");
+  if (!ws || ws_bytes < rslx_memory_step_workspace_bytes(mem, N)) return fail(RSLX_ERR_WORKSPACE, "rslx_memory_step: workspace too small");
   hipStream_t s = (hipStream_t)stream;
   Carver c(ws);
   StepBufs b;
-  act_recurrent_carve(c, gru, nullptr, N, &b, nullptr);
+  act_recurrent_carve(c, mem, nullptr, N, &b, nullptr);
   RowGatherArgs rg;
   memset(&rg, 0, sizeof rg);
   rg.n_jobs = 1; rg.nb = N; rg.reset = reset_or_null;
-  rg.job[0] = RowGatherJob{h, b.hin, h0_out, gru->hidden};
+  rg.job[0] = RowGatherJob{state, b.hin, s0_out, state_width(*mem)};
   RSLX_HIP(launch_row_gather(rg, s));
-  const rslx_gru* g[1] = {gru};
+  const rslx_memory* g[1] = {mem};
   const float* o[1] = {obs};
   const StepBufs bb[1] = {b};
-  float* out[1] = {h};
-  return gru_step(g, o, bb, out, 1, N, s);
+  float* out[1] = {state};
+  RSLX_TRY(gru_step(g, o, bb, out, 1, N, s));
+  if (h_dense_out) RSLX_HIP(launch_copy_matrix(state, state_width(*mem), N, mem->hidden, h_dense_out, s));
+  return RSLX_OK;
 }
 
-size_t rslx_bc_update_recurrent_workspace_bytes(const rslx_gru* gru, const rslx_mlp* student, int32_t T, int32_t N,
+size_t rslx_bc_update_recurrent_workspace_bytes(const rslx_memory* gru, const rslx_mlp* student, int32_t T, int32_t N,
                                                 const rslx_bc_cfg* cfg) {
   if (rnn_bc_validate(gru, student, T, N, cfg, false) != RSLX_OK) return 0;
   Carver c(nullptr);
@@ -1704,7 +1722,7 @@ size_t rslx_bc_update_recurrent_workspace_bytes(const rslx_gru* gru, const rslx_
   return p.bytes;
 }
 
-int32_t rslx_bc_update_recurrent(rslx_gru* gru, rslx_mlp* student, const float* obs_student, const float* targets,
+int32_t rslx_bc_update_recurrent(rslx_memory* gru, rslx_mlp* student, const float* obs_student, const float* targets,
                                  const uint8_t* dones, const float* h0, int32_t T, int32_t N, const rslx_bc_cfg* cfg,
                                  int64_t* adam_step, float* stats, void* ws, size_t ws_bytes, void* stream) {
   RSLX_TRY(rnn_bc_validate(gru, student, T, N, cfg, true));
@@ -1718,7 +1736,7 @@ int32_t rslx_bc_update_recurrent(rslx_gru* gru, rslx_mlp* student, const float* 
   if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_bc_update_recurrent: workspace %zu < %zu bytes", ws_bytes, p.bytes);
   const int A = student->dims[student->n_layers], Ls = student->n_layers;
   const int nb = p.nb, rows = p.rows;
-  const rslx_gru* mem[1] = {gru};
+  const rslx_memory* mem[1] = {gru};
   RnnBufs* mb[1] = {&p.mem};
   const float* obs[1] = {obs_student};
   const float* h0s[1] = {h0};

@@ -235,52 +235,60 @@ hipError_t launch_rnd_reward(const float* yp, const float* yt, int32_t N, int32_
 hipError_t launch_fill(float* p, int64_t n, float value, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
-// Gated recurrent unit (recurrent.hip), one time step per launch for up to two networks (the actor's and the
-// critic's memory); H % 4 == 0.
-//   gi = x W_ih + b_ih (from the GEMM kernel),  gh = hin W_hh + b_hh   ([*, 3H], gate order r, z, n)
-//   r = sigmoid(gi_r + gh_r), z = sigmoid(gi_z + gh_z), n = tanh(gi_n + r gh_n), h = (1 - z) n + z hin
-// Forward: gh is formed tile by tile on the matrix cores (and stored when gh_out is set: the backward pass reads
-// it), the gates are the epilogue.
+// Recurrent memory cells (recurrent.hip), one time step per launch for up to two networks (the actor's and the
+// critic's memory, same cell type); H % 4 == 0.  G gates, packed state rows of width S:
+//   GRU  (G = 3: r, z, n; S = H, state h):   gi = x W_ih + b_ih (from the GEMM kernel),  gh = h W_hh + b_hh
+//        r = sigmoid(gi_r + gh_r), z = sigmoid(gi_z + gh_z), n = tanh(gi_n + r gh_n), h' = (1 - z) n + z h
+//   LSTM (G = 4: i, f, g, o; S = 2H, state [h | c]):   a = gi + h W_hh + b_hh
+//        i, f, o = sigmoid(a_i, a_f, a_o), g = tanh(a_g), c' = f c + i g, h' = o tanh(c')
+// Forward: h W_hh is formed tile by tile on the matrix cores, the gates are the epilogue.  pre_out (when set;
+// the backward pass reads it) receives gh for the GRU and the whole pre-activation a for the LSTM.
 // ---------------------------------------------------------------------------------------------
-struct GruFwdNet {
-  const float* gi;        // [nb, 3H] this step's rows
-  const float* hin;       // [nb, H]
-  float* h_out;           // [nb, H]
-  float* hin_next;        // [nb, H] or null: h_out * (1 - done), the state the next step starts from
-  const float* w_hh;      // [H, 3H] row-major
-  const float* b_hh;      // [3H]
-  float* gh_out;          // [nb, 3H] or null
-  int32_t H;
+enum CellKind : int { CELL_GRU = 0, CELL_LSTM = 1 };
+struct StepFwdNet {
+  const float* gi;        // [nb, G H] this step's rows
+  const float* sin;       // [nb, S] packed state the step starts from
+  float* h_out;           // new hidden state, row stride ld_out
+  float* c_out;           // LSTM: new cell state, row stride ld_out; null = not stored
+  float* sin_next;        // [nb, S] or null: new state * (1 - done), what the next step starts from
+  const float* w_hh;      // [H, G H] row-major
+  const float* b_hh;      // [G H]
+  float* pre_out;         // [nb, G H] or null
+  int32_t H, ld_out;
 };
-struct GruStepFwdArgs {
-  GruFwdNet net[2];
-  int32_t n_nets, nb;
+struct StepFwdArgs {
+  StepFwdNet net[2];
+  int32_t n_nets, nb, cell;
   const uint8_t* done;      // episode-end flags (null = none); row i reads done[done_idx ? done_idx[i] : i]
   const int32_t* done_idx;
 };
-hipError_t launch_gru_step_fwd(const GruStepFwdArgs& a, hipStream_t stream);
+hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream);
 
-// One step of back-propagation through time.  back = dgh_next W_hh^T (what step t + 1 sends to its input state
-// through the hidden-side contraction) is formed tile by tile and never stored; with
-//   dh = dh_ext + (1 - done) (back + direct_in)
-// the epilogue writes dgi = [dr_pre, dz_pre, dn_pre], dgh = [dr_pre, dz_pre, dn_pre r] and direct_out = dh z.
-struct GruBwdNet {
+// One step of back-propagation through time.  back = dg_next W_hh^T (what step t + 1 sends to its input hidden
+// state through the hidden-side contraction) is formed tile by tile and never stored.  With keep = 1 - done:
+//   GRU:  dh = dh_ext + keep (back + carry);  writes dgi = [dr_pre, dz_pre, dn_pre], dg = [dr_pre, dz_pre, dn_pre r],
+//         carry <- dh z  (the direct path into the input state)
+//   LSTM: dh = dh_ext + keep back, dc' = keep carry;  writes dg = d loss / d a (the same for both sides of the
+//         gates; dgi is not used), carry <- (dc' + dh o (1 - tanh^2 c')) f
+struct StepBwdNet {
   const float* dh_ext;    // [nb, H] gradient arriving from the layers above
-  const float* dgh_next;  // [nb, 3H] this network's dgh of step t + 1, null on the last step
-  const float* direct_in; // [nb, H] direct_out of step t + 1 (may alias direct_out), unused on the last step
-  const float* w_hh;      // [H, 3H] row-major: back[row, j] = sum_k dgh_next[row, k] W_hh[j, k]
-  const float* gi; const float* gh; const float* hin;
-  float* dgi; float* dgh; // [nb, 3H]
-  float* direct_out;      // [nb, H]
+  const float* dg_next;   // [nb, G H] this network's dg of step t + 1, null on the last step
+  float* carry;           // [nb, H] in / out (not read on the last step)
+  const float* w_hh;      // [H, G H] row-major: back[row, j] = sum_k dg_next[row, k] W_hh[j, k]
+  const float* gi;        // [nb, G H] (GRU only)
+  const float* pre;       // [nb, G H] what the forward step stored in pre_out
+  const float* sin;       // [nb, S]
+  float* dgi;             // [nb, G H] (GRU only)
+  float* dg;              // [nb, G H]
   int32_t H;
 };
-struct GruStepBwdArgs {
-  GruBwdNet net[2];
-  int32_t n_nets, nb;
+struct StepBwdArgs {
+  StepBwdNet net[2];
+  int32_t n_nets, nb, cell;
   const uint8_t* done;      // flags of THIS step (they gate what step t + 1 sends back); null = none
   const int32_t* done_idx;
 };
-hipError_t launch_gru_step_bwd(const GruStepBwdArgs& a, hipStream_t stream);
+hipError_t launch_step_bwd(const StepBwdArgs& a, hipStream_t stream);
 
 // dst[i, :] = src[idx ? idx[i] : i, :] * (reset && reset[i] ? 0 : 1) for up to two [*, H] matrices; a second
 // copy of the result goes to dst2 when it is not null.
@@ -292,6 +300,10 @@ struct RowGatherArgs {
   const uint8_t* reset;
 };
 hipError_t launch_row_gather(const RowGatherArgs& a, hipStream_t stream);
+
+// dst[r, 0 .. cols) = src[r * ld_src + 0 .. cols) for r < rows (cols % 4 == 0): the hidden part of packed states as a
+// dense matrix.
+hipError_t launch_copy_matrix(const float* src, int32_t ld_src, int32_t rows, int32_t cols, float* dst, hipStream_t stream);
 
 // rows_out[((e * M + m) * T + t) * nb + i] = t * N + perm[e * N + m * nb + i]: the roll-out rows of every
 // column-wise minibatch, step-major.

@@ -1,6 +1,6 @@
-// Gated recurrent unit, one time step per launch: the hidden-side contraction on the matrix cores with the gate
-// stage (forward) or the gate derivatives (back-propagation through time) as its epilogue, and the index plumbing
-// of column-wise minibatches.  The input-side contractions and the weight gradients run in the GEMM kernel.
+// Recurrent memory cells (GRU, LSTM), one time step per launch: the hidden-side contraction on the matrix cores with
+// the gate stage (forward) or the gate derivatives (back-propagation through time) as its epilogue, and the index
+// plumbing of column-wise minibatches.  The input-side contractions and the weight gradients run in the GEMM kernel.
 #include "kernels.h"
 
 namespace rslx {
@@ -34,7 +34,7 @@ constexpr int GS_ROWS = 32;        // rows per workgroup
 constexpr int GS_THREADS = 256;
 
 template <int NTW, int KC>
-struct GruTile {
+struct StepTile {
   static constexpr int NT = 2 * NTW;            // tiles per workgroup: wavefront column wj owns tiles wj * NTW ...
   static constexpr int APITCH = KC + 4;         // floats per staged A row (16-byte aligned, spreads the banks)
   static constexpr int COLS = 16 * NT, BPITCH = COLS + 8;
@@ -141,7 +141,7 @@ struct GruTile {
 // order of the sum inside a group of 16 is permuted, nothing else.  The backward step uses it (A = dgh of the next
 // step, Bt = the rows of W_hh itself), where one instruction per contraction step would leave the LDS latency bare.
 template <int NTW, int KC>
-struct GruTileKK {
+struct StepTileKK {
   static constexpr int NT = 2 * NTW;
   static constexpr int PITCH = KC + 4;
   static constexpr int BROWS = 16 * NT;
@@ -246,117 +246,155 @@ __device__ __forceinline__ void step_block(int H, int& rb, int& jb) {
   jb = i % jblocks;
 }
 
-__global__ __launch_bounds__(GS_THREADS) void gru_step_fwd_kernel(const GruStepFwdArgs a) {
-  using Tile = GruTile<3, 128>;
+template <int CELL> struct CellShape;
+template <> struct CellShape<CELL_GRU> { static constexpr int G = 3, KC = 128; };
+template <> struct CellShape<CELL_LSTM> { static constexpr int G = 4, KC = 64; };   // shorter chunks: 8 tiles of weights in LDS
+
+template <int CELL>
+__global__ __launch_bounds__(GS_THREADS) void step_fwd_kernel(const StepFwdArgs a) {
+  constexpr int G = CellShape<CELL>::G;
+  using Tile = StepTile<G, CellShape<CELL>::KC>;
   __shared__ __attribute__((aligned(16))) float smem[Tile::LDS_FLOATS];
   const int z = blockIdx.y;
-  const GruFwdNet& n = a.net[z];
-  const int H = n.H, nb = a.nb;
+  const StepFwdNet& n = a.net[z];
+  const int H = n.H, nb = a.nb, S = CELL == CELL_LSTM ? 2 * H : H;
   int rb, jb;
   step_block(H, rb, jb);
   const int row0 = rb * GS_ROWS, j0 = jb * GS_JB;
   if (row0 >= nb) return;
-  int col0[6], col_end[6];      // tile wj * 3 + g: gate g of hidden units j0 + 16 wj ...
+  int col0[2 * G], col_end[2 * G];      // tile wj * G + g: gate g of hidden units j0 + 16 wj ...
 #pragma unroll
-  for (int t = 0; t < 6; ++t) { col0[t] = (t % 3) * H + j0 + (t / 3) * 16; col_end[t] = (t % 3) * H + H; }
+  for (int t = 0; t < 2 * G; ++t) { col0[t] = (t % G) * H + j0 + (t / G) * 16; col_end[t] = (t % G) * H + H; }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wr = wave & 1, wj = wave >> 1;
   const int j = j0 + wj * 16 + (lane & 15), jc = min(j, H - 1);
   const int rbase = row0 + wr * 16 + 4 * (lane >> 4);
   // the gate stage's own operands do not depend on the contraction: fetch them first (clamped addresses, no
   // branches) so their latency hides behind it
-  float pgi[4][3], phin[4];
+  float pgi[4][G], pst[4];      // pst: the state entry the gates blend with (GRU: h, LSTM: c)
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = min(rbase + q, nb - 1);
-    const long o3 = (long)row * 3 * H + jc;
-    pgi[q][0] = n.gi[o3]; pgi[q][1] = n.gi[o3 + H]; pgi[q][2] = n.gi[o3 + 2 * H];
-    phin[q] = n.hin[(long)row * H + jc];
-  }
-  const float* bh = n.b_hh;
-  const float br = bh[jc], bz = bh[H + jc], bn = bh[2 * H + jc];
-  f4 acc[3];
+    const long og = (long)row * G * H + jc;
 #pragma unroll
-  for (int t = 0; t < 3; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
-  Tile::mma(n.hin, H, row0, nb, n.w_hh, 3 * H, col0, col_end, H, smem, acc);
+    for (int g = 0; g < G; ++g) pgi[q][g] = n.gi[og + g * H];
+    pst[q] = n.sin[(long)row * S + (CELL == CELL_LSTM ? H : 0) + jc];
+  }
+  float bias[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) bias[g] = n.b_hh[g * H + jc];
+  f4 acc[G];
+#pragma unroll
+  for (int t = 0; t < G; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
+  Tile::mma(n.sin, S, row0, nb, n.w_hh, G * H, col0, col_end, H, smem, acc);
   if (j >= H) return;
-  float* gh_out = n.gh_out;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = rbase + q;
     if (row >= nb) continue;
-    const long o = (long)row * H + j, o3 = (long)row * 3 * H + j;
-    const float ghr = acc[0][q] + br, ghz = acc[1][q] + bz, ghn = acc[2][q] + bn;
-    const float r = sigmoidf_(pgi[q][0] + ghr);
-    const float zz = sigmoidf_(pgi[q][1] + ghz);
-    const float nn = tanhf_(pgi[q][2] + r * ghn);
-    const float h = (1.0f - zz) * nn + zz * phin[q];
-    n.h_out[o] = h;
-    if (n.hin_next != nullptr) {
-      float keep = 1.0f;
-      if (a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[row] : row] ? 0.0f : 1.0f;
-      n.hin_next[o] = h * keep;
+    const long og = (long)row * G * H + j;
+    float keep = 1.0f;
+    if (n.sin_next != nullptr && a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[row] : row] ? 0.0f : 1.0f;
+    if (CELL == CELL_GRU) {
+      const float ghr = acc[0][q] + bias[0], ghz = acc[1][q] + bias[1], ghn = acc[2][q] + bias[2];
+      const float r = sigmoidf_(pgi[q][0] + ghr);
+      const float zz = sigmoidf_(pgi[q][1] + ghz);
+      const float nn = tanhf_(pgi[q][2] + r * ghn);
+      const float h = (1.0f - zz) * nn + zz * pst[q];
+      n.h_out[(long)row * n.ld_out + j] = h;
+      if (n.sin_next != nullptr) n.sin_next[(long)row * S + j] = h * keep;
+      if (n.pre_out != nullptr) { n.pre_out[og] = ghr; n.pre_out[og + H] = ghz; n.pre_out[og + 2 * H] = ghn; }
+    } else {
+      float pre[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) pre[g] = pgi[q][g] + acc[g][q] + bias[g];
+      const float ii = sigmoidf_(pre[0]), ff = sigmoidf_(pre[1]), gg = tanhf_(pre[2]), oo = sigmoidf_(pre[3]);
+      const float c = ff * pst[q] + ii * gg;
+      const float h = oo * tanhf_(c);
+      n.h_out[(long)row * n.ld_out + j] = h;
+      if (n.c_out != nullptr) n.c_out[(long)row * n.ld_out + j] = c;
+      if (n.sin_next != nullptr) { n.sin_next[(long)row * S + j] = h * keep; n.sin_next[(long)row * S + H + j] = c * keep; }
+      if (n.pre_out != nullptr) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) n.pre_out[og + g * H] = pre[g];
+      }
     }
-    if (gh_out != nullptr) { gh_out[o3] = ghr; gh_out[o3 + H] = ghz; gh_out[o3 + 2 * H] = ghn; }
   }
 }
 
-__global__ __launch_bounds__(GS_THREADS) void gru_step_bwd_kernel(const GruStepBwdArgs a) {
-  using Tile = GruTileKK<1, 128>;
+template <int CELL>
+__global__ __launch_bounds__(GS_THREADS) void step_bwd_kernel(const StepBwdArgs a) {
+  constexpr int G = CellShape<CELL>::G;
+  using Tile = StepTileKK<1, 128>;
   __shared__ __attribute__((aligned(16))) float smem[Tile::LDS_FLOATS];
   const int z = blockIdx.y;
-  const GruBwdNet& n = a.net[z];
-  const int H = n.H, nb = a.nb;
+  const StepBwdNet& n = a.net[z];
+  const int H = n.H, nb = a.nb, S = CELL == CELL_LSTM ? 2 * H : H;
   int rb, jb;
   step_block(H, rb, jb);
   const int row0 = rb * GS_ROWS, j0 = jb * GS_JB;
   if (row0 >= nb) return;
-  const bool has_next = n.dgh_next != nullptr;
+  const bool has_next = n.dg_next != nullptr;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wr = wave & 1, wj = wave >> 1;
   const int j = j0 + wj * 16 + (lane & 15), jc = min(j, H - 1);
   const int rbase = row0 + wr * 16 + 4 * (lane >> 4);
   // the gate stage's own operands, fetched ahead of the contraction (clamped addresses, no branches)
-  float pgi[4][3], pgh[4][3], phin[4], pdh[4], pdir[4];
+  float pgi[4][G], ppre[4][G], pst[4], pdh[4], pcarry[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = min(rbase + q, nb - 1);
-    const long o = (long)row * H + jc, o3 = (long)row * 3 * H + jc;
+    const long o = (long)row * H + jc, og = (long)row * G * H + jc;
 #pragma unroll
-    for (int g = 0; g < 3; ++g) { pgi[q][g] = n.gi[o3 + g * H]; pgh[q][g] = n.gh[o3 + g * H]; }
-    phin[q] = n.hin[o];
+    for (int g = 0; g < G; ++g) {
+      ppre[q][g] = n.pre[og + g * H];
+      pgi[q][g] = CELL == CELL_GRU ? n.gi[og + g * H] : 0.f;
+    }
+    pst[q] = n.sin[(long)row * S + (CELL == CELL_LSTM ? H : 0) + jc];
     pdh[q] = n.dh_ext[o];
-    pdir[q] = has_next ? n.direct_in[o] : 0.f;
+    pcarry[q] = has_next ? n.carry[o] : 0.f;
   }
   f4 acc[1] = {f4{0.f, 0.f, 0.f, 0.f}};
   if (has_next) {
     const int col0[2] = {j0, j0 + 16}, col_end[2] = {H, H};      // rows of W_hh = hidden units
-    Tile::mma(n.dgh_next, 3 * H, row0, nb, n.w_hh, 3 * H, col0, col_end, 3 * H, smem, acc);
+    Tile::mma(n.dg_next, G * H, row0, nb, n.w_hh, G * H, col0, col_end, G * H, smem, acc);
   }
   if (j >= H) return;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = rbase + q;
     if (row >= nb) continue;
-    const long o = (long)row * H + j, o3 = (long)row * 3 * H + j;
-    float dh = pdh[q];
-    if (has_next) {
-      float keep = 1.0f;
-      if (a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[row] : row] ? 0.0f : 1.0f;
-      dh += (acc[0][q] + pdir[q]) * keep;
+    const long o = (long)row * H + j, og = (long)row * G * H + j;
+    float keep = 1.0f;
+    if (has_next && a.done != nullptr) keep = a.done[a.done_idx ? a.done_idx[row] : row] ? 0.0f : 1.0f;
+    if (CELL == CELL_GRU) {
+      float dh = pdh[q];
+      if (has_next) dh += (acc[0][q] + pcarry[q]) * keep;
+      const float ghn = ppre[q][2];
+      const float r = sigmoidf_(pgi[q][0] + ppre[q][0]);
+      const float zz = sigmoidf_(pgi[q][1] + ppre[q][1]);
+      const float nn = tanhf_(pgi[q][2] + r * ghn);
+      const float dn = dh * (1.0f - zz);
+      const float dz = dh * (pst[q] - nn);
+      const float dn_pre = dn * (1.0f - nn * nn);
+      const float dr_pre = dn_pre * ghn * r * (1.0f - r);
+      const float dz_pre = dz * zz * (1.0f - zz);
+      n.carry[o] = dh * zz;
+      n.dgi[og] = dr_pre; n.dgi[og + H] = dz_pre; n.dgi[og + 2 * H] = dn_pre;
+      n.dg[og] = dr_pre; n.dg[og + H] = dz_pre; n.dg[og + 2 * H] = dn_pre * r;
+    } else {
+      float dh = pdh[q], dc = 0.f;
+      if (has_next) { dh += acc[0][q] * keep; dc = pcarry[q] * keep; }
+      const float ii = sigmoidf_(ppre[q][0]), ff = sigmoidf_(ppre[q][1]), gg = tanhf_(ppre[q][2]), oo = sigmoidf_(ppre[q][3]);
+      const float tc = tanhf_(ff * pst[q] + ii * gg);
+      const float d_o = dh * tc;
+      const float dct = dc + dh * oo * (1.0f - tc * tc);
+      n.carry[o] = dct * ff;
+      n.dg[og] = dct * gg * ii * (1.0f - ii);
+      n.dg[og + H] = dct * pst[q] * ff * (1.0f - ff);
+      n.dg[og + 2 * H] = dct * ii * (1.0f - gg * gg);
+      n.dg[og + 3 * H] = d_o * oo * (1.0f - oo);
     }
-    const float ghn = pgh[q][2];
-    const float r = sigmoidf_(pgi[q][0] + pgh[q][0]);
-    const float zz = sigmoidf_(pgi[q][1] + pgh[q][1]);
-    const float nn = tanhf_(pgi[q][2] + r * ghn);
-    const float dn = dh * (1.0f - zz);
-    const float dz = dh * (phin[q] - nn);
-    const float dn_pre = dn * (1.0f - nn * nn);
-    const float dr_pre = dn_pre * ghn * r * (1.0f - r);
-    const float dz_pre = dz * zz * (1.0f - zz);
-    n.direct_out[o] = dh * zz;
-    n.dgi[o3] = dr_pre; n.dgi[o3 + H] = dz_pre; n.dgi[o3 + 2 * H] = dn_pre;
-    n.dgh[o3] = dr_pre; n.dgh[o3 + H] = dz_pre; n.dgh[o3 + 2 * H] = dn_pre * r;
   }
 }
 
@@ -371,6 +409,15 @@ __global__ __launch_bounds__(256) void row_gather_kernel(const RowGatherArgs a) 
   if (a.reset != nullptr && a.reset[i]) v = f4{0.f, 0.f, 0.f, 0.f};
   st4(J.dst + (long)i * J.H + j, v);
   if (J.dst2 != nullptr) st4(J.dst2 + (long)i * J.H + j, v);
+}
+
+__global__ __launch_bounds__(256) void copy_matrix_kernel(const float* __restrict__ src, int ld_src, int rows, int cols,
+                                                          float* __restrict__ dst) {
+  const int q = cols >> 2;
+  const long e = (long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long)rows * q) return;
+  const int r = (int)(e / q), c = (int)(e - (long)r * q) * 4;
+  st4(dst + (long)r * cols + c, ld4(src + (long)r * ld_src + c));
 }
 
 __global__ __launch_bounds__(256) void column_rows_kernel(const int32_t* __restrict__ perm, int E, int M, int T, int N,
@@ -399,23 +446,29 @@ static dim3 step_grid(int nb, const int* H, int n_nets) {
   return dim3(blocks, n_nets);
 }
 
-hipError_t launch_gru_step_fwd(const GruStepFwdArgs& a, hipStream_t stream) {
+hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream) {
   if (a.nb <= 0 || a.n_nets <= 0) return hipSuccess;
+  const int G = a.cell == CELL_LSTM ? 4 : 3;
   int H[2] = {a.net[0].H, a.net[1].H};
   double flops = 0.0;
-  for (int k = 0; k < a.n_nets; ++k) flops += 2.0 * a.nb * H[k] * 3.0 * H[k];
-  TraceScope ts(stream, "gru_step_fwd", flops, 0.0);
-  hipLaunchKernelGGL(gru_step_fwd_kernel, step_grid(a.nb, H, a.n_nets), dim3(GS_THREADS), 0, stream, a);
+  for (int k = 0; k < a.n_nets; ++k) flops += 2.0 * a.nb * H[k] * (double)G * H[k];
+  TraceScope ts(stream, a.cell == CELL_LSTM ? "lstm_step_fwd" : "gru_step_fwd", flops, 0.0);
+  const dim3 grid = step_grid(a.nb, H, a.n_nets);
+  if (a.cell == CELL_LSTM) hipLaunchKernelGGL(step_fwd_kernel<CELL_LSTM>, grid, dim3(GS_THREADS), 0, stream, a);
+  else hipLaunchKernelGGL(step_fwd_kernel<CELL_GRU>, grid, dim3(GS_THREADS), 0, stream, a);
   return hipGetLastError();
 }
 
-hipError_t launch_gru_step_bwd(const GruStepBwdArgs& a, hipStream_t stream) {
+hipError_t launch_step_bwd(const StepBwdArgs& a, hipStream_t stream) {
   if (a.nb <= 0 || a.n_nets <= 0) return hipSuccess;
+  const int G = a.cell == CELL_LSTM ? 4 : 3;
   int H[2] = {a.net[0].H, a.net[1].H};
   double flops = 0.0;
-  for (int k = 0; k < a.n_nets; ++k) flops += a.net[k].dgh_next ? 2.0 * a.nb * H[k] * 3.0 * H[k] : 0.0;
-  TraceScope ts(stream, "gru_step_bwd", flops, 0.0);
-  hipLaunchKernelGGL(gru_step_bwd_kernel, step_grid(a.nb, H, a.n_nets), dim3(GS_THREADS), 0, stream, a);
+  for (int k = 0; k < a.n_nets; ++k) flops += a.net[k].dg_next ? 2.0 * a.nb * H[k] * (double)G * H[k] : 0.0;
+  TraceScope ts(stream, a.cell == CELL_LSTM ? "lstm_step_bwd" : "gru_step_bwd", flops, 0.0);
+  const dim3 grid = step_grid(a.nb, H, a.n_nets);
+  if (a.cell == CELL_LSTM) hipLaunchKernelGGL(step_bwd_kernel<CELL_LSTM>, grid, dim3(GS_THREADS), 0, stream, a);
+  else hipLaunchKernelGGL(step_bwd_kernel<CELL_GRU>, grid, dim3(GS_THREADS), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -424,6 +477,13 @@ hipError_t launch_row_gather(const RowGatherArgs& a, hipStream_t stream) {
   for (int k = 0; k < a.n_jobs; ++k) { const long w = (long)a.nb * (a.job[k].H >> 2); work = w > work ? w : work; }
   if (work == 0) return hipSuccess;
   hipLaunchKernelGGL(row_gather_kernel, dim3((unsigned)((work + 255) / 256), a.n_jobs), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_matrix(const float* src, int32_t ld_src, int32_t rows, int32_t cols, float* dst, hipStream_t stream) {
+  const long total = (long)rows * (cols >> 2);
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_matrix_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, src, ld_src, rows, cols, dst);
   return hipGetLastError();
 }
 

@@ -24,6 +24,38 @@ def test_header_symbols_are_exported():
     assert rx.rslx_version() == 100
 
 
+def test_binding_signatures_have_the_declared_arity():
+    """Every prototype in the header and its ctypes signature in the binding take the same number of arguments."""
+    text = open(os.path.join(ROOT, "include", "rslx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    protos = re.findall(r"\b(rslx_[a-z_0-9]+)\s*\(([^()]*)\)\s*;", text)
+    assert len(protos) == len(B.EXPORTS)
+    for name, args in protos:
+        n = 0 if args.strip() in ("", "void") else len(args.split(","))
+        fn = getattr(rx.lib, name)
+        assert fn.argtypes is not None and len(fn.argtypes) == n, (name, n, fn.argtypes)
+
+
+def test_recurrent_argument_errors():
+    mlp_a, mlp_c = _cpu_mlp((8, 8, 2), True), _cpu_mlp((8, 8, 1))
+    gru = rx.Gru(4, 8, torch.zeros(3 * 8 * (4 + 8 + 2)), trainable=True)
+    lstm = rx.Lstm(4, 8, torch.zeros(4 * 8 * (4 + 8 + 2)), trainable=True)
+    assert (gru.state_width, lstm.state_width) == (8, 16)
+    z = lambda *s: torch.zeros(*s)
+    ro = rx.Rollout(3, 4, z(12, 4), z(12, 4), z(12, 2), z(12), z(12), z(12, 2), z(12, 2), z(12), z(12))
+    assert rx.rslx_ppo_update_recurrent_workspace_bytes(gru, mlp_a, gru, mlp_c, ro, rx.PpoCfg(minibatches=2)) > 0
+    assert rx.rslx_ppo_update_recurrent_workspace_bytes(lstm, mlp_a, lstm, mlp_c, ro, rx.PpoCfg(minibatches=2)) > 0
+    with pytest.raises(rx.RslxError, match="different cells"):
+        rx.rslx_ppo_update_recurrent_workspace_bytes(gru, mlp_a, lstm, mlp_c, ro, rx.PpoCfg(minibatches=2))
+    with pytest.raises(rx.RslxError, match="multiple of minibatches"):
+        rx.rslx_ppo_update_recurrent_workspace_bytes(gru, mlp_a, gru, mlp_c, ro, rx.PpoCfg(minibatches=3))
+    bad = rx.Memory(7, 4, 8, torch.zeros(3 * 8 * (4 + 8 + 2)), trainable=True)
+    with pytest.raises(rx.RslxError, match="unknown cell"):
+        rx.rslx_ppo_update_recurrent_workspace_bytes(bad, mlp_a, bad, mlp_c, ro, rx.PpoCfg(minibatches=2))
+    with pytest.raises(rx.RslxError, match="memory width"):
+        rx.rslx_bc_update_recurrent_workspace_bytes(gru, _cpu_mlp((6, 8, 2)), 3, 4, rx.BcCfg(minibatches=2))
+
+
 def _cpu_mlp(dims, log_std=False, trainable=True):
     n = sum(i * o + o for i, o in zip(dims[:-1], dims[1:])) + (dims[-1] if log_std else 0)
     return rx.Mlp(dims, torch.zeros(n), trainable=trainable, has_log_std=log_std)

@@ -166,13 +166,13 @@ from oracle import recurrent as orec, gru as ogru
 
 
 def _rec_flat(inp):
-    return np.concatenate([inp["gru_student"], inp["student"]])
+    return np.concatenate([inp["mem_student"], inp["student"]])
 
 
 def _rec_student(rx, w, flat, opt=None):
-    k = ogru.n_params(w.student_obs, w.student_memory)
+    k = orec.CELLS[w.memory_cell].n_params(w.student_obs, w.student_memory)
     p = dev(flat, torch.float32)
-    g = rx.Gru(w.student_obs, w.student_memory, p[:k], trainable=True)
+    g = rx.Memory(rx.CELL_LSTM if w.memory_cell == "lstm" else rx.CELL_GRU, w.student_obs, w.student_memory, p[:k], trainable=True)
     m = rx.Mlp(w.dims_student, p[k:], trainable=True)
     if opt is not None:
         mm, vv = dev(opt["m"], torch.float32), dev(opt["v"], torch.float32)
@@ -187,7 +187,8 @@ def _rec_rollout(w, inp):
     h, reset = inp["h_student"].astype(np.float64), inp["reset0"]
     acts, tgts, hs, h0 = [], [], [], None
     for t in range(T):
-        a, h, hin = orec.bc_collect_step(flat, w.student_obs, w.student_memory, w.dims_student, inp["obs_student"][t], h, reset)
+        a, h, hin = orec.bc_collect_step(flat, w.student_obs, w.student_memory, w.dims_student, inp["obs_student"][t], h, reset,
+                                         cell=w.memory_cell)
         if t == 0:
             h0 = hin
         acts.append(a); hs.append(h)
@@ -197,22 +198,24 @@ def _rec_rollout(w, inp):
     return dict(actions=c32(np.stack(acts)), targets=c32(np.stack(tgts)), hs=c32(np.stack(hs)), h0=c32(h0))
 
 
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
 @pytest.mark.parametrize("N", [96, 1000])
-def test_recurrent_student_collection_matches_oracle(rx, N):
-    w = WORKLOADS["distill_recurrent"].scaled(N)
+def test_recurrent_student_collection_matches_oracle(rx, N, cell):
+    w = replace(WORKLOADS["distill_recurrent"].scaled(N), memory_cell=cell)
     inp = make_inputs(w)
     ref = _rec_rollout(w, inp)
     T, A, H = w.T, w.A, w.student_memory
     g, m = _rec_student(rx, w, _rec_flat(inp))
     teacher = rx.Mlp(w.dims_actor, dev(inp["teacher"]))
-    h, h0 = dev(inp["h_student"]), torch.zeros(N, H, device="cuda")
+    S = inp["h_student"].shape[1]
+    h, h0, h_dense = dev(inp["h_student"]), torch.zeros(N, S, device="cuda"), torch.zeros(N, H, device="cuda")
     obs_s, obs_t, dones, reset0 = dev(inp["obs_student"]), dev(inp["obs"]), dev(inp["dones"]), dev(inp["reset0"])
     actions, targets = torch.empty(T, N, A, device="cuda"), torch.empty(T, N, A, device="cuda")
-    sws = rx.workspace(rx.rslx_gru_step_workspace_bytes(g, N))
+    sws = rx.workspace(rx.rslx_memory_step_workspace_bytes(g, N))
     cws = rx.workspace(rx.rslx_bc_collect_workspace_bytes(m, teacher, N))
     for t in range(T):
-        rx.rslx_gru_step(g, obs_s[t], N, h, reset0 if t == 0 else dones[t - 1], h0 if t == 0 else None, sws)
-        rx.rslx_bc_collect(m, teacher, h, obs_t[t], N, actions[t], targets[t], cws)
+        rx.rslx_memory_step(g, obs_s[t], N, h, reset0 if t == 0 else dones[t - 1], h0 if t == 0 else None, h_dense, sws)
+        rx.rslx_bc_collect(m, teacher, h_dense, obs_t[t], N, actions[t], targets[t], cws)
         torch.cuda.synchronize()
         assert rel_l2(host(h), ref["hs"][t]) <= 2e-5, t
     assert rel_l2(host(actions), ref["actions"]) <= 2e-5 and rel_l2(host(targets), ref["targets"]) <= 1e-5
@@ -230,7 +233,7 @@ class RecDistillCase:
                                  minibatches=w.minibatches, max_grad_norm=f32(clip), seed=5, call_index=2)
         n = self.flat0.size
         self.ref = orec.bc_update(self.flat0, w.student_obs, w.student_memory, w.dims_student, self.oro, self.ocfg,
-                                  dict(m=np.zeros(n), v=np.zeros(n), step=0), record=True)
+                                  dict(m=np.zeros(n), v=np.zeros(n), step=0), record=True, cell=w.memory_cell)
 
     def run(self, rx, flat, opt, envs, epochs, minibatches, step0):
         w = self.w
@@ -251,17 +254,20 @@ class RecDistillCase:
 
 def _check_rec_student(name, w, got, ref, tol):
     D, H = w.student_obs, w.student_memory
+    C = orec.CELLS[w.memory_cell]
+    G = C.GATES
     o = 0
-    for nm, n in (("W_ih", D * 3 * H), ("b_ih", 3 * H), ("W_hh", H * 3 * H), ("b_hh", 3 * H), ("mlp", got.size - ogru.n_params(D, H))):
+    for nm, n in (("W_ih", D * G * H), ("b_ih", G * H), ("W_hh", H * G * H), ("b_hh", G * H), ("mlp", got.size - C.n_params(D, H))):
         r = np.asarray(ref[o:o + n], np.float64)
         err = np.linalg.norm(np.asarray(got[o:o + n], np.float64) - r)
         assert err <= tol * np.linalg.norm(r) + 1e-12, (name, nm, err, np.linalg.norm(r))
         o += n
 
 
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
 @pytest.mark.parametrize("N,hidden,mem,clip", [(96, (64, 32), 32, 0.0), (140, (72, 40), 44, 0.5), (256, (256, 128), 256, 0.0)])
-def test_bc_update_recurrent_matches_oracle(rx, N, hidden, mem, clip):
-    w = replace(WORKLOADS["distill_recurrent"].scaled(N), student_hidden=hidden, student_memory=mem, done_p=0.04)
+def test_bc_update_recurrent_matches_oracle(rx, N, hidden, mem, clip, cell):
+    w = replace(WORKLOADS["distill_recurrent"].scaled(N), student_hidden=hidden, student_memory=mem, done_p=0.04, memory_cell=cell)
     case = RecDistillCase(w, 1, clip)
     ref = case.ref
     assert case.inp["dones"][:-1].sum() > 10

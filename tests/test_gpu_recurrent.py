@@ -26,7 +26,13 @@ def rx():
 
 
 def _flat(inp, which):
-    return np.concatenate([inp["gru_" + which], inp[which]])
+    return np.concatenate([inp["mem_" + which], inp[which]])
+
+
+def _cell(w):
+    """(oracle module of the workload's cell, number of gates, packed state width)."""
+    C = orec.CELLS[w.memory_cell]
+    return C, C.GATES, C.state_width(w.memory_hidden)
 
 
 def oracle_collect(w, inp):
@@ -38,14 +44,14 @@ def oracle_collect(w, inp):
     h0 = None
     for t in range(T):
         o = orec.act(actor, critic, w.Da, w.Dc, H, w.dims_actor, w.dims_critic, inp["obs"][t], inp["obs"][t], h_a, h_c, reset,
-                     orng.act_noise(SEED, t, N, A))
+                     orng.act_noise(SEED, t, N, A), cell=w.memory_cell)
         if t == 0:
             h0 = (o["hin_a"], o["hin_c"])
         for k in acc:
             acc[k].append(o[k])
         h_a, h_c, reset = o["h_a"], o["h_c"], inp["dones"][t]
     last = orec.act(actor, critic, w.Da, w.Dc, H, w.dims_actor, w.dims_critic, inp["obs"][T], inp["obs"][T], h_a, h_c, reset,
-                    np.zeros((N, A)))["values"]
+                    np.zeros((N, A)), cell=w.memory_cell)["values"]
     c32 = lambda x: np.ascontiguousarray(np.asarray(x, np.float32))
     ro = {k: c32(np.stack(v)) for k, v in acc.items()}
     ro["h0_a"], ro["h0_c"], ro["last"] = c32(h0[0]), c32(h0[1]), c32(last)
@@ -57,12 +63,14 @@ def oracle_collect(w, inp):
 def _nets(rx, w, actor_flat, critic_flat, opt=None):
     """(gru_a, mlp_a, gru_c, mlp_c) on slices of one flat device buffer per network and optimiser moment."""
     H = w.memory_hidden
+    C, _, _ = _cell(w)
+    cell_id = rx.CELL_LSTM if w.memory_cell == "lstm" else rx.CELL_GRU
     out = []
     for flat, D, dims, log_std, mk, vk in ((actor_flat, w.Da, w.dims_actor, True, "m_a", "v_a"),
                                            (critic_flat, w.Dc, w.dims_critic, False, "m_c", "v_c")):
-        k = ogru.n_params(D, H)
+        k = C.n_params(D, H)
         p = dev(flat, torch.float32)
-        g = rx.Gru(D, H, p[:k], trainable=True)
+        g = rx.Memory(cell_id, D, H, p[:k], trainable=True)
         m = rx.Mlp(dims, p[k:], trainable=True, has_log_std=log_std)
         if opt is not None:
             mm, vv = dev(opt[mk], torch.float32), dev(opt[vk], torch.float32)
@@ -79,15 +87,17 @@ def _grads(g, m):
     return np.concatenate([host(g.grads), host(m.grads)])
 
 
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
 @pytest.mark.parametrize("N", [64, 300])
-def test_act_recurrent_matches_oracle(rx, N):
-    w = WORKLOADS["recurrent"].scaled(N)
+def test_act_recurrent_matches_oracle(rx, N, cell):
+    w = replace(WORKLOADS["recurrent"].scaled(N), memory_cell=cell)
     inp = make_inputs(w)
     ref = oracle_collect(w, inp)
     T, A, H = w.T, w.A, w.memory_hidden
     ga, ma, gc, mc = _nets(rx, w, _flat(inp, "actor"), _flat(inp, "critic"))
     h_a, h_c = dev(inp["h_actor"]), dev(inp["h_critic"])
-    h0_a, h0_c = torch.zeros(N, H, device="cuda"), torch.zeros(N, H, device="cuda")
+    S = _cell(w)[2]
+    h0_a, h0_c = torch.zeros(N, S, device="cuda"), torch.zeros(N, S, device="cuda")
     obs, dones = dev(inp["obs"]), dev(inp["dones"])
     reset = dev(inp["reset0"])
     assert inp["reset0"].sum() > 0 or N < 100
@@ -139,7 +149,7 @@ class RCase:
         na, nc = self.actor0.size, self.critic0.size
         opt0 = dict(m_a=np.zeros(na), v_a=np.zeros(na), m_c=np.zeros(nc), v_c=np.zeros(nc), step=0)
         self.ref = orec.ppo_update(self.actor0, self.critic0, w.Da, w.Dc, w.memory_hidden, w.dims_actor, w.dims_critic, self.oro,
-                                   self.ocfg, opt0, record=True)
+                                   self.ocfg, opt0, record=True, cell=w.memory_cell)
 
     def gpu_rollout(self, rx, envs=None):
         o = self.oro if envs is None else {k: (v[envs] if k in ("h0_a", "h0_c") else v[:, envs]) for k, v in self.oro.items()}
@@ -166,15 +176,16 @@ def _call(rx, nets, ro_pack, cfg, n_rows, step0):
 
 
 def _layer_names(w, which):
-    """(dims-like description for error messages) GRU part first, then the MLP."""
-    return ogru.n_params(w.Da if which == "actor" else w.Dc, w.memory_hidden)
+    """Size of the memory part, which comes first in a network's flat vector."""
+    return _cell(w)[0].n_params(w.Da if which == "actor" else w.Dc, w.memory_hidden)
 
 
 def _check_net(name, w, which, got, ref, tol):
     k = _layer_names(w, which)
     D, H = (w.Da if which == "actor" else w.Dc), w.memory_hidden
     o = 0
-    for nm, n in (("W_ih", D * 3 * H), ("b_ih", 3 * H), ("W_hh", H * 3 * H), ("b_hh", 3 * H)):
+    G = _cell(w)[1]
+    for nm, n in (("W_ih", D * G * H), ("b_ih", G * H), ("W_hh", H * G * H), ("b_hh", G * H)):
         r = np.asarray(ref[o:o + n], np.float64)
         err = np.linalg.norm(np.asarray(got[o:o + n], np.float64) - r)
         assert err <= tol * np.linalg.norm(r) + 1e-12, (name, nm, err, np.linalg.norm(r))
@@ -213,32 +224,37 @@ def check_free_running(rx, case, later_tol=2e-2, param_tol=None, floor=1e-3):
     return nets, stats
 
 
-def test_recurrent_update_small(rx):
-    w = replace(WORKLOADS["recurrent"].scaled(64), hidden=(128, 128), memory_hidden=64, done_p=0.05)
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
+def test_recurrent_update_small(rx, cell):
+    w = replace(WORKLOADS["recurrent"].scaled(64), hidden=(128, 128), memory_hidden=64, done_p=0.05, memory_cell=cell)
     case = RCase(w, 1)
     assert case.inp["dones"][:-1].sum() > 10
     check_forced_steps(rx, case)
     check_free_running(rx, case)
 
 
-def test_recurrent_update_off_policy_start_odd_shapes(rx):
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
+def test_recurrent_update_off_policy_start_odd_shapes(rx, cell):
     """Ragged everything: 35 environments per minibatch, widths that are no multiple of the tiles, the unfused loss path."""
-    w = replace(WORKLOADS["recurrent"].scaled(140), T=9, Da=21, Dc=21, A=5, hidden=(72, 40), memory_hidden=44, done_p=0.08)
+    w = replace(WORKLOADS["recurrent"].scaled(140), T=9, Da=21, Dc=21, A=5, hidden=(72, 40), memory_hidden=44, done_p=0.08,
+                memory_cell=cell)
     case = RCase(w, 1, perturb=0.2)
     assert case.ref["stats"][0, 5] > 0.01
     check_forced_steps(rx, case)
     check_free_running(rx, case)
 
 
-def test_recurrent_update_two_epochs(rx):
-    w = replace(WORKLOADS["recurrent"].scaled(128), hidden=(256, 128), memory_hidden=128, done_p=0.03)
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
+def test_recurrent_update_two_epochs(rx, cell):
+    w = replace(WORKLOADS["recurrent"].scaled(128), hidden=(256, 128), memory_hidden=128, done_p=0.03, memory_cell=cell)
     case = RCase(w, 2)
     check_free_running(rx, case, later_tol=5e-2)
 
 
-def test_recurrent_update_full_width(rx):
+@pytest.mark.parametrize("name", ["recurrent", "recurrent_lstm"])
+def test_recurrent_update_full_width(rx, name):
     """The benchmark's network shapes (256-wide memories, [512, 256, 128] MLPs) at 512 environments."""
-    case = RCase(WORKLOADS["recurrent"].scaled(512), 1)
+    case = RCase(WORKLOADS[name].scaled(512), 1)
     check_forced_steps(rx, case, steps={0, 3})
     check_free_running(rx, case)
 
@@ -258,11 +274,13 @@ def test_recurrent_update_rejects_bad_shapes(rx):
         rx.rslx_ppo_update_recurrent_workspace_bytes(bad, nets[1], nets[2], nets[3], ro, rx.PpoCfg(epochs=1, minibatches=3))
 
 
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
 @pytest.mark.parametrize("T,N,M,done_p", [(1, 32, 4, 0.1), (5, 4, 4, 0.3), (6, 48, 2, 1.0), (6, 48, 2, 0.0)])
-def test_recurrent_update_degenerate_shapes(rx, T, N, M, done_p):
+def test_recurrent_update_degenerate_shapes(rx, T, N, M, done_p, cell):
     """One-step roll-outs, one environment per minibatch, an episode end on every step (no state is ever carried:
     the memory acts as a feed-forward layer) and none at all."""
-    w = replace(WORKLOADS["recurrent"].scaled(N), T=T, minibatches=M, hidden=(64, 32), memory_hidden=32, done_p=done_p)
+    w = replace(WORKLOADS["recurrent"].scaled(N), T=T, minibatches=M, hidden=(64, 32), memory_hidden=32, done_p=done_p,
+                memory_cell=cell)
     case = RCase(w, 1, perturb=0.1)
     if done_p == 1.0:
         assert case.inp["dones"].all()

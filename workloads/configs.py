@@ -47,7 +47,8 @@ class Workload:
     rnd_subset: int = 0             # > 0: the RND networks read this many of the Da observation columns
     timeout_p: float = 0.0          # per-step probability that an episode ends by time limit (also sets done)
     memory_hidden: int = 0          # > 0: actor and critic each have a GRU memory of this width in front of their MLP
-    student_memory: int = 0         # > 0: the distillation student has a GRU memory of this width in front of its MLP
+    student_memory: int = 0         # > 0: the distillation student has a memory of this width in front of its MLP
+    memory_cell: str = "gru"        # "gru" or "lstm": the cell of every memory of the workload
 
     @property
     def B(self):
@@ -92,10 +93,12 @@ WORKLOADS = {
     "curiosity_subset": Workload("curiosity_subset", 7, N=16384, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128),
                                  heavy_tail=True, rnd=True, rnd_hidden=(256, 256), rnd_out=64, minibatches=8,
                                  rnd_subset=24),
-    # recurrent actor-critic: a 256-wide GRU memory per network, episodes end often enough that every roll-out
-    # holds resets
+    # recurrent actor-critic: a 256-wide GRU (or, with memory_cell="lstm", LSTM) memory per network, episodes end
+    # often enough that every roll-out holds resets
     "recurrent": Workload("recurrent", 8, N=4096, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128), heavy_tail=True,
                           done_p=0.01, memory_hidden=256),
+    "recurrent_lstm": Workload("recurrent_lstm", 10, N=4096, T=24, Da=48, Dc=48, A=12, hidden=(512, 256, 128),
+                               heavy_tail=True, done_p=0.01, memory_hidden=256, memory_cell="lstm"),
     # distillation into a recurrent student: the distill workload's teacher, a student with a 256-wide GRU memory
     "distill_recurrent": Workload("distill_recurrent", 9, N=4096, T=24, Da=235, Dc=235, A=12, hidden=(512, 256, 128),
                                   height_scan=187, bc=True, student_hidden=(256, 128), student_obs=48, epochs=2,
@@ -116,10 +119,11 @@ def xavier_mlp(gen, dims, log_std=False):
     return np.concatenate(parts)
 
 
-def uniform_gru(gen, D, H):
-    """Flat float32 GRU parameters W_ih [D, 3H], b_ih [3H], W_hh [H, 3H], b_hh [3H], all ~ U(-1/sqrt(H), 1/sqrt(H))."""
+def uniform_memory(gen, D, H, gates=3):
+    """Flat float32 parameters of a recurrent cell with `gates` gates (GRU 3, LSTM 4): W_ih [D, G H], b_ih [G H],
+    W_hh [H, G H], b_hh [G H], all ~ U(-1/sqrt(H), 1/sqrt(H))."""
     a = 1.0 / np.sqrt(H)
-    return gen.uniform(-a, a, size=3 * H * (D + H + 2)).astype(np.float32)
+    return gen.uniform(-a, a, size=gates * H * (D + H + 2)).astype(np.float32)
 
 
 def random_involution(gen, n, p_fixed=0.2):
@@ -190,8 +194,9 @@ def make_inputs(w, seed=None):
         out["teacher"] = xavier_mlp(gen, w.dims_actor)
         out["student"] = xavier_mlp(gen, w.dims_student)
         if w.student_memory:
-            out["gru_student"] = uniform_gru(gen, w.student_obs, w.student_memory)
-            out["h_student"] = (0.5 * gen.standard_normal((N, w.student_memory))).astype(np.float32)
+            lstm = w.memory_cell == "lstm"
+            out["mem_student"] = uniform_memory(gen, w.student_obs, w.student_memory, 4 if lstm else 3)
+            out["h_student"] = (0.5 * gen.standard_normal((N, (2 if lstm else 1) * w.student_memory))).astype(np.float32)
             out["reset0"] = (gen.random(N) < w.done_p).astype(np.uint8)
     if w.rnd:
         if w.rnd_subset:
@@ -199,10 +204,11 @@ def make_inputs(w, seed=None):
         out["rnd_target"] = xavier_mlp(gen, w.dims_rnd)
         out["rnd_predictor"] = xavier_mlp(gen, w.dims_rnd)
     if w.memory_hidden:
-        H = w.memory_hidden
-        out["gru_actor"], out["gru_critic"] = uniform_gru(gen, w.Da, H), uniform_gru(gen, w.Dc, H)
-        out["h_actor"] = (0.5 * gen.standard_normal((N, H))).astype(np.float32)     # states carried in from before
-        out["h_critic"] = (0.5 * gen.standard_normal((N, H))).astype(np.float32)
+        H, lstm = w.memory_hidden, w.memory_cell == "lstm"
+        G, S = (4, 2 * H) if lstm else (3, H)                      # gates, packed state width ([h | c] for the LSTM)
+        out["mem_actor"], out["mem_critic"] = uniform_memory(gen, w.Da, H, G), uniform_memory(gen, w.Dc, H, G)
+        out["h_actor"] = (0.5 * gen.standard_normal((N, S))).astype(np.float32)     # states carried in from before
+        out["h_critic"] = (0.5 * gen.standard_normal((N, S))).astype(np.float32)
         out["reset0"] = (gen.random(N) < w.done_p).astype(np.uint8)                  # episode ends of the step before
     if w.timeout_p > 0.0:
         out["timeouts"] = (gen.random((T, N)) < w.timeout_p).astype(np.uint8)
