@@ -220,8 +220,10 @@ def distill_iteration(args, rx, torch, np, w, inp):
     rec = w.student_memory > 0          # recurrent student: a GRU memory in front of the MLP, column-wise minibatches
     if rec:
         H = w.student_memory
-        gru = rx.Gru(w.student_obs, H, dev(inp["mem_student"]), trainable=True)
-        h, h0, reset0, dones = dev(inp["h_student"]), torch.empty(N, H, device="cuda"), dev(inp["reset0"]), dev(inp["dones"])
+        lstm = w.memory_cell == "lstm"
+        gru = rx.Memory(rx.CELL_LSTM if lstm else rx.CELL_GRU, w.student_obs, H, dev(inp["mem_student"]), trainable=True)
+        h, reset0, dones = dev(inp["h_student"]), dev(inp["reset0"]), dev(inp["dones"])
+        h0, h_dense = torch.empty_like(h), torch.empty(N, H, device="cuda")
         sws = rx.workspace(rx.rslx_memory_step_workspace_bytes(gru, N))
     obs_s, obs_t = dev(inp["obs_student"]), dev(inp["obs"][:T])
     actions, targets = torch.empty(T, N, A, device="cuda"), torch.empty(T, N, A, device="cuda")
@@ -240,8 +242,8 @@ def distill_iteration(args, rx, torch, np, w, inp):
         for t in range(T):
             if rec:
                 reset = dones[t - 1] if t > 0 else (reset0 if it == 0 else dones[T - 1])
-                rx.rslx_memory_step(gru, obs_s[t], N, h, reset, h0 if t == 0 else None, None, sws)
-                rx.rslx_bc_collect(student, teacher, h, obs_t[t], N, actions[t], targets[t], cws)
+                rx.rslx_memory_step(gru, obs_s[t], N, h, reset, h0 if t == 0 else None, h_dense if lstm else None, sws)
+                rx.rslx_bc_collect(student, teacher, h_dense if lstm else h, obs_t[t], N, actions[t], targets[t], cws)
             else:
                 rx.rslx_bc_collect(student, teacher, obs_s[t], obs_t[t], N, actions[t], targets[t], cws)
         if timed:
@@ -295,8 +297,9 @@ def distill_iteration(args, rx, torch, np, w, inp):
     col_flops = (fwd(w.dims_student) + fwd(w.dims_actor)) * B
     if rec:
         D = w.student_obs
-        upd_flops = (3 * fwd(w.dims_student) + 2 * (D + H) * 3 * H + 2 * D * 3 * H + 4 * H * 3 * H) * B * w.epochs
-        col_flops += 2 * (D + H) * 3 * H * B
+        G = 4 if lstm else 3
+        upd_flops = (3 * fwd(w.dims_student) + 2 * (D + H) * G * H + 2 * D * G * H + 4 * H * G * H) * B * w.epochs
+        col_flops += 2 * (D + H) * G * H * B
     return {
         "metric": "BC (distillation) transitions/sec: collection (student acts, teacher relabels) + update, 1 GPU",
         "value": round(B / (ms_per_step * 1e-3), 1),
@@ -304,7 +307,7 @@ def distill_iteration(args, rx, torch, np, w, inp):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: N=%d envs, T=%d, teacher %s, student %s%s ELU, %d epochs x %d minibatches"
-                   % (w.name, N, T, list(w.dims_actor), "GRU %d + MLP " % w.student_memory if rec else "", list(w.dims_student),
+                   % (w.name, N, T, list(w.dims_actor), "%s %d + MLP " % (w.memory_cell.upper(), w.student_memory) if rec else "", list(w.dims_student),
                       w.epochs, w.minibatches)},
         "phase_ms": {k: round(v, 4) for k, v in med.items()},
         "collect_tflops": round(col_flops / (med["collect"] * 1e-3) / 1e12, 2),
@@ -320,15 +323,17 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
     """One iteration with GRU memories: T recurrent act steps (states carried across iterations, reset at episode
     ends), bootstrap value, GAE, and the column-wise PPO update with back-propagation through time."""
     T, N, A, B, H = w.T, w.N, w.A, w.B, w.memory_hidden
+    lstm = w.memory_cell == "lstm"
+    G, S = (4, 2 * H) if lstm else (3, H)          # gates, packed state width
     dev = lambda x: torch.as_tensor(np.ascontiguousarray(x)).cuda()
     nets = []
     for which, D, dims, log_std in (("actor", w.Da, w.dims_actor, True), ("critic", w.Dc, w.dims_critic, False)):
-        nets.append(rx.Gru(D, H, dev(inp["mem_" + which]), trainable=True))
+        nets.append(rx.Memory(rx.CELL_LSTM if lstm else rx.CELL_GRU, D, H, dev(inp["mem_" + which]), trainable=True))
         nets.append(rx.Mlp(dims, dev(inp[which]), trainable=True, has_log_std=log_std))
     ga, ma, gc, mc = nets
     obs, rewards, dones = dev(inp["obs"]), dev(inp["rewards"]), dev(inp["dones"])
     h_a, h_c, reset0 = dev(inp["h_actor"]), dev(inp["h_critic"]), dev(inp["reset0"])
-    h0_a, h0_c = torch.empty(N, H, device="cuda"), torch.empty(N, H, device="cuda")
+    h0_a, h0_c = torch.empty(N, S, device="cuda"), torch.empty(N, S, device="cuda")
     actions, mu, sigma = (torch.empty(T, N, A, device="cuda") for _ in range(3))
     logp, values, adv, ret = (torch.empty(T, N, device="cuda") for _ in range(4))
     last = torch.empty(N, device="cuda")
@@ -383,19 +388,19 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
         roofline, breakdown = summarize_trace(rx.rslx_trace_end(), w, args.steps)
     assert torch.isfinite(ma.params).all() and torch.isfinite(ga.params).all() and torch.isfinite(stats).all()
     fwd = lambda dims: sum(2 * i * o for i, o in zip(dims[:-1], dims[1:]))
-    gru_fwd = lambda D: 2 * (D + H) * 3 * H
-    gru_bwd = lambda D: 2 * D * 3 * H + 2 * 2 * H * 3 * H
+    gru_fwd = lambda D: 2 * (D + H) * G * H
+    gru_bwd = lambda D: 2 * D * G * H + 2 * 2 * H * G * H
     per_sample = 3 * (fwd(w.dims_actor) + fwd(w.dims_critic)) + gru_fwd(w.Da) + gru_fwd(w.Dc) + gru_bwd(w.Da) + gru_bwd(w.Dc)
     act_flops = fwd(w.dims_actor) + fwd(w.dims_critic) + gru_fwd(w.Da) + gru_fwd(w.Dc)
     return {
-        "metric": "recurrent PPO (GRU memories, BPTT) transitions/sec: act + GAE + update, 1 GPU",
+        "metric": "recurrent PPO (%s memories, BPTT) transitions/sec: act + GAE + update, 1 GPU" % ("LSTM" if lstm else "GRU"),
         "value": round(B / (ms_per_step * 1e-3), 1),
         "unit": "transitions/s (whole iteration: %d act + GAE + %dx%d PPO update)" % (T, w.epochs, w.minibatches),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: N=%d envs, T=%d, obs %d, act %d, GRU %d + MLP %s ELU per network, %d epochs x %d minibatches "
-                               "of %d environment columns" % (w.name, N, T, w.Da, A, H, list(w.hidden), w.epochs, w.minibatches,
-                                                             N // w.minibatches)},
+        "config": {"workload": "%s: N=%d envs, T=%d, obs %d, act %d, %s %d + MLP %s ELU per network, %d epochs x %d minibatches "
+                               "of %d environment columns" % (w.name, N, T, w.Da, A, "LSTM" if lstm else "GRU", H, list(w.hidden),
+                                                             w.epochs, w.minibatches, N // w.minibatches)},
         "phase_ms": {k: round(v, 4) for k, v in med.items()},
         "update_tflops": round(per_sample * B * w.epochs / (med["update"] * 1e-3) / 1e12, 2),
         "act_tflops": round(act_flops * (T + 1) * N / (med["act"] * 1e-3) / 1e12, 2),
