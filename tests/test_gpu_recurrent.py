@@ -316,3 +316,11 @@ def test_recurrent_empty_calls_are_no_ops(rx):
     assert step.value == 3
     for n, b in zip(nets, before):
         assert np.array_equal(host(n.params), b)
+
+
+@pytest.mark.parametrize("name", ["recurrent", "recurrent_lstm"])
+def test_recurrent_update_full_size(rx, name):
+    """The benchmark's configuration itself (4096 environments, minibatches of 1024 columns x 24 steps): the first and
+    the last optimiser step of an epoch replayed from the oracle's state, and the collection loop's first steps."""
+    case = RCase(WORKLOADS[name], 1)
+    check_forced_steps(rx, case, steps={0, 3})
