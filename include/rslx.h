@@ -332,6 +332,22 @@ int32_t rslx_ppo_update_recurrent(rslx_memory* mem_actor, rslx_mlp* actor, rslx_
                                   int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
                                   void* stream);
 
+/* Replayable variants (see rslx_dev_counters): the noise position / permutation stream / optimiser
+ * step count come from device memory and are advanced by the calls' own kernels, so a recurrent
+ * iteration can be recorded as a HIP graph like a feed-forward one. */
+int32_t rslx_act_recurrent_dc(const rslx_memory* mem_actor, const rslx_mlp* actor, const rslx_memory* mem_critic,
+                              const rslx_mlp* critic, const float* obs_actor, const float* obs_critic,
+                              int32_t N, float* h_actor, float* h_critic, const uint8_t* reset_or_null,
+                              float* h0_actor_out, float* h0_critic_out, uint64_t seed,
+                              rslx_dev_counters* counters, const float* eps_or_null, float* actions,
+                              float* logp, float* values, float* mu, float* sigma, uint32_t flags,
+                              void* ws, size_t ws_bytes, void* stream);
+int32_t rslx_ppo_update_recurrent_dc(rslx_memory* mem_actor, rslx_mlp* actor, rslx_memory* mem_critic,
+                                     rslx_mlp* critic, const rslx_rollout* ro, const uint8_t* dones,
+                                     const float* h0_actor, const float* h0_critic, const rslx_ppo_cfg* cfg,
+                                     rslx_dev_counters* counters, float* stats, void* ws, size_t ws_bytes,
+                                     void* stream);
+
 /* One step of a single memory (the recurrent student of the distillation loop, paper Sec. 2.1 with
  * Sec. 3): sin = reset[n] ? 0 : s[n];  s[n] <- cell(obs[n], sin), in place on the packed state
  * s [N, S]; s0_out (optional, [N, S]) receives sin; h_dense_out (optional, [N, H]) receives the

@@ -15,6 +15,7 @@ __all__ = [
     "rslx_bc_collect", "Memory", "Gru", "Lstm", "CELL_GRU", "CELL_LSTM", "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent",
     "rslx_ppo_update_recurrent_workspace_bytes", "rslx_ppo_update_recurrent", "rslx_memory_step_workspace_bytes",
     "rslx_memory_step", "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
+    "rslx_act_recurrent_dc", "rslx_ppo_update_recurrent_dc",
 ]
 
 MAX_LAYERS = 8
@@ -30,7 +31,8 @@ EXPORTS = [
     "rslx_act_dc", "rslx_ppo_update_dc", "rslx_bc_update_dc", "rslx_bc_collect_workspace_bytes", "rslx_bc_collect",
     "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent", "rslx_ppo_update_recurrent_workspace_bytes",
     "rslx_ppo_update_recurrent", "rslx_memory_step_workspace_bytes", "rslx_memory_step",
-    "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
+    "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent", "rslx_act_recurrent_dc",
+    "rslx_ppo_update_recurrent_dc",
 ]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librslx.so")
@@ -134,6 +136,11 @@ _sig("rslx_act_recurrent_workspace_bytes", C.c_size_t, [_P(_CMemory), _P(_CMlp),
 _sig("rslx_act_recurrent", C.c_int32, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp,
                                        _vp, C.c_uint64, C.c_uint64, _vp, _vp, _vp, _vp, _vp, _vp, C.c_uint32, _vp,
                                        C.c_size_t, _vp])
+_sig("rslx_act_recurrent_dc", C.c_int32, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _vp, _vp, C.c_int32, _vp, _vp, _vp,
+                                          _vp, _vp, C.c_uint64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_uint32, _vp,
+                                          C.c_size_t, _vp])
+_sig("rslx_ppo_update_recurrent_dc", C.c_int32, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _P(_CRollout), _vp, _vp, _vp,
+                                                 _P(_CPpoCfg), _vp, _vp, _vp, C.c_size_t, _vp])
 _sig("rslx_ppo_update_recurrent_workspace_bytes", C.c_size_t, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _P(_CRollout),
                                                                _P(_CPpoCfg)])
 _sig("rslx_ppo_update_recurrent", C.c_int32, [_P(_CMemory), _P(_CMlp), _P(_CMemory), _P(_CMlp), _P(_CRollout), _vp, _vp, _vp,
@@ -443,6 +450,23 @@ def rslx_act_recurrent(gru_actor, actor, gru_critic, critic, obs_actor, obs_crit
                                   _ptr(h_actor), _ptr(h_critic), _ptr(reset), _ptr(h0_actor_out), _ptr(h0_critic_out), seed,
                                   step, _ptr(eps), _ptr(actions), _ptr(logp), _ptr(values), _ptr(mu), _ptr(sigma), flags,
                                   _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "rslx_act_recurrent")
+
+
+def rslx_act_recurrent_dc(gru_actor, actor, gru_critic, critic, obs_actor, obs_critic, N, h_actor, h_critic, reset, h0_actor_out,
+                          h0_critic_out, seed, counters, eps, actions, logp, values, mu, sigma, flags, ws):
+    ga = gru_actor.c if gru_actor is not None else None
+    ca = actor.c if actor is not None else None
+    _check(lib.rslx_act_recurrent_dc(_ref(ga), _ref(ca), _ref(gru_critic.c), _ref(critic.c), _ptr(obs_actor), _ptr(obs_critic), N,
+                                     _ptr(h_actor), _ptr(h_critic), _ptr(reset), _ptr(h0_actor_out), _ptr(h0_critic_out), seed,
+                                     _ptr(counters), _ptr(eps), _ptr(actions), _ptr(logp), _ptr(values), _ptr(mu), _ptr(sigma),
+                                     flags, _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "rslx_act_recurrent_dc")
+
+
+def rslx_ppo_update_recurrent_dc(gru_actor, actor, gru_critic, critic, rollout, dones, h0_actor, h0_critic, cfg, counters, stats, ws):
+    _check(lib.rslx_ppo_update_recurrent_dc(_ref(gru_actor.c), _ref(actor.c), _ref(gru_critic.c), _ref(critic.c), _ref(rollout.c),
+                                            _ptr(dones), _ptr(h0_actor), _ptr(h0_critic), _ref(cfg.c), _ptr(counters),
+                                            _ptr(stats), _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
+           "rslx_ppo_update_recurrent_dc")
 
 
 def rslx_ppo_update_recurrent_workspace_bytes(gru_actor, actor, gru_critic, critic, rollout, cfg):

@@ -1268,17 +1268,27 @@ size_t rslx_act_recurrent_workspace_bytes(const rslx_memory* gru_actor, const rs
   return (c.off + 255) / 256 * 256 + rslx_act_workspace_bytes(actor, critic, N);
 }
 
-int32_t rslx_act_recurrent(const rslx_memory* gru_actor, const rslx_mlp* actor, const rslx_memory* gru_critic,
+}  // extern "C"
+
+namespace {
+// Shared body of rslx_act_recurrent and rslx_act_recurrent_dc (noise position from device memory).
+int32_t act_recurrent_impl(const rslx_memory* gru_actor, const rslx_mlp* actor, const rslx_memory* gru_critic,
                            const rslx_mlp* critic, const float* obs_actor, const float* obs_critic, int32_t N,
                            float* h_actor, float* h_critic, const uint8_t* reset_or_null, float* h0_actor_out,
-                           float* h0_critic_out, uint64_t seed, uint64_t step, const float* eps_or_null, float* actions,
-                           float* logp, float* values, float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes,
-                           void* stream) {
+                           float* h0_critic_out, uint64_t seed, uint64_t step, rslx_dev_counters* counters,
+                           const float* eps_or_null, float* actions, float* logp, float* values, float* mu, float* sigma,
+                           uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
   const bool values_only = (flags & RSLX_ACT_VALUES_ONLY) != 0;
   if (N < 0) return fail(RSLX_ERR_SHAPE, "rslx_act_recurrent: N = %d", N);
   RSLX_TRY(act_recurrent_validate(gru_actor, actor, gru_critic, critic, values_only));
   if (!obs_critic || !h_critic || !values) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: null critic input / state / output");
   if (!values_only && (!obs_actor || !h_actor)) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: null actor input / state");
+  // everything the MLP stage would reject is rejected here, before the memories advance the caller's states
+  if (!values_only && (!actions || !logp || !mu || !sigma)) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: null actor output");
+  if (!values_only && !actor->has_log_std) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: actor needs log_std");
+  if (critic->dims[critic->n_layers] != 1) return fail(RSLX_ERR_SHAPE, "rslx_act_recurrent: critic output width must be 1");
+  if (!values_only && actor->dims[actor->n_layers] > RSLX_MAX_ACTIONS)
+    return fail(RSLX_ERR_SHAPE, "rslx_act_recurrent: action width > %d", RSLX_MAX_ACTIONS);
   if (!aligned16(h_critic) || (!values_only && !aligned16(h_actor)) || (h0_actor_out && !aligned16(h0_actor_out)) ||
       (h0_critic_out && !aligned16(h0_critic_out)))
     return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent: state buffers not 16-byte aligned");
@@ -1315,9 +1325,35 @@ int32_t rslx_act_recurrent(const rslx_memory* gru_actor, const rslx_mlp* actor, 
     float* out[1] = {bc.hnew};
     RSLX_TRY(gru_step(g, obs, b, out, 1, N, s));
   }
-  return act_impl(a, critic, h_in_actor_mlp, h_in_critic_mlp, N, seed, step, nullptr, eps_or_null, actions, logp, values,
+  return act_impl(a, critic, h_in_actor_mlp, h_in_critic_mlp, N, seed, step, counters, eps_or_null, actions, logp, values,
                   mu, sigma, flags, static_cast<char*>(ws) + used, ws_bytes - used, stream, ga ? state_width(*ga) : 0,
                   state_width(*gru_critic));
+}
+}  // namespace
+
+extern "C" {
+
+int32_t rslx_act_recurrent(const rslx_memory* mem_actor, const rslx_mlp* actor, const rslx_memory* mem_critic,
+                           const rslx_mlp* critic, const float* obs_actor, const float* obs_critic, int32_t N,
+                           float* h_actor, float* h_critic, const uint8_t* reset_or_null, float* h0_actor_out,
+                           float* h0_critic_out, uint64_t seed, uint64_t step, const float* eps_or_null, float* actions,
+                           float* logp, float* values, float* mu, float* sigma, uint32_t flags, void* ws, size_t ws_bytes,
+                           void* stream) {
+  return act_recurrent_impl(mem_actor, actor, mem_critic, critic, obs_actor, obs_critic, N, h_actor, h_critic, reset_or_null,
+                            h0_actor_out, h0_critic_out, seed, step, nullptr, eps_or_null, actions, logp, values, mu, sigma,
+                            flags, ws, ws_bytes, stream);
+}
+
+int32_t rslx_act_recurrent_dc(const rslx_memory* mem_actor, const rslx_mlp* actor, const rslx_memory* mem_critic,
+                              const rslx_mlp* critic, const float* obs_actor, const float* obs_critic, int32_t N,
+                              float* h_actor, float* h_critic, const uint8_t* reset_or_null, float* h0_actor_out,
+                              float* h0_critic_out, uint64_t seed, rslx_dev_counters* counters, const float* eps_or_null,
+                              float* actions, float* logp, float* values, float* mu, float* sigma, uint32_t flags, void* ws,
+                              size_t ws_bytes, void* stream) {
+  if (!counters) return fail(RSLX_ERR_INVALID_ARG, "rslx_act_recurrent_dc: null counters");
+  return act_recurrent_impl(mem_actor, actor, mem_critic, critic, obs_actor, obs_critic, N, h_actor, h_critic, reset_or_null,
+                            h0_actor_out, h0_critic_out, seed, 0, counters, eps_or_null, actions, logp, values, mu, sigma,
+                            flags, ws, ws_bytes, stream);
 }
 
 }  // extern "C"
@@ -1525,11 +1561,17 @@ size_t rslx_ppo_update_recurrent_workspace_bytes(const rslx_memory* gru_actor, c
   return p.bytes;
 }
 
-int32_t rslx_ppo_update_recurrent(rslx_memory* gru_actor, rslx_mlp* actor, rslx_memory* gru_critic, rslx_mlp* critic,
+}  // extern "C"
+
+namespace {
+// Shared body of rslx_ppo_update_recurrent and its device-counter variant.
+int32_t ppo_update_recurrent_impl(rslx_memory* gru_actor, rslx_mlp* actor, rslx_memory* gru_critic, rslx_mlp* critic,
                                   const rslx_rollout* ro, const uint8_t* dones, const float* h0_actor, const float* h0_critic,
-                                  const rslx_ppo_cfg* cfg, int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
-                                  void* stream) {
+                                  const rslx_ppo_cfg* cfg, int64_t* adam_step, rslx_dev_counters* counters, float* stats,
+                                  void* ws, size_t ws_bytes, void* stream) {
   RSLX_TRY(rnn_validate(gru_actor, actor, gru_critic, critic, ro, cfg, true));
+  int64_t host_step = 0;
+  if (counters) adam_step = &host_step;
   if (!dones || !h0_actor || !h0_critic || !adam_step || !stats)
     return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: null dones, h0, adam_step or stats");
   if (!aligned16(h0_actor) || !aligned16(h0_critic)) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: h0 not 16-byte aligned");
@@ -1549,7 +1591,8 @@ int32_t rslx_ppo_update_recurrent(rslx_memory* gru_actor, rslx_mlp* actor, rslx_
     std::vector<uint64_t> bases(cfg->epochs);
     for (int e = 0; e < cfg->epochs; ++e)
       bases[e] = mix64_host(mix64_host(mix64_host(cfg->seed) ^ cfg->call_index) ^ (uint64_t)(e + cfg->epoch_offset));
-    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, p.N, p.perms, p.perm_ws, s));
+    RSLX_HIP(launch_permutations(bases.data(), cfg->epochs, p.N, p.perms, p.perm_ws, s, mix64_host(cfg->seed),
+                                 counters ? &counters->call_index : nullptr, cfg->epoch_offset));
     RSLX_HIP(launch_column_rows(p.perms, cfg->epochs, cfg->minibatches, T, p.N, p.rows_all, s));
   }
 
@@ -1623,12 +1666,35 @@ int32_t rslx_ppo_update_recurrent(rslx_memory* gru_actor, rslx_mlp* actor, rslx_
       aa.max_grad_norm = cfg->max_grad_norm;
       aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;
       aa.bc1 = bias_correction(cfg->beta1, t1); aa.bc2 = bias_correction(cfg->beta2, t1);
+      if (counters) { aa.step_dev = &counters->adam_step; aa.step_off = (int32_t)t1; }
       aa.grad_norm_out = stats_row + RSLX_STAT_GRAD_NORM;
       RSLX_HIP(launch_adam(aa, s));
       *adam_step = t1;
     }
   }
+  if (counters) RSLX_HIP(advance_counters(counters, 0, 1, host_step, 0, s));
   return RSLX_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t rslx_ppo_update_recurrent(rslx_memory* mem_actor, rslx_mlp* actor, rslx_memory* mem_critic, rslx_mlp* critic,
+                                  const rslx_rollout* ro, const uint8_t* dones, const float* h0_actor, const float* h0_critic,
+                                  const rslx_ppo_cfg* cfg, int64_t* adam_step, float* stats, void* ws, size_t ws_bytes,
+                                  void* stream) {
+  if (!adam_step) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent: null adam_step");
+  return ppo_update_recurrent_impl(mem_actor, actor, mem_critic, critic, ro, dones, h0_actor, h0_critic, cfg, adam_step, nullptr,
+                                   stats, ws, ws_bytes, stream);
+}
+
+int32_t rslx_ppo_update_recurrent_dc(rslx_memory* mem_actor, rslx_mlp* actor, rslx_memory* mem_critic, rslx_mlp* critic,
+                                     const rslx_rollout* ro, const uint8_t* dones, const float* h0_actor,
+                                     const float* h0_critic, const rslx_ppo_cfg* cfg, rslx_dev_counters* counters,
+                                     float* stats, void* ws, size_t ws_bytes, void* stream) {
+  if (!counters) return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update_recurrent_dc: null counters");
+  return ppo_update_recurrent_impl(mem_actor, actor, mem_critic, critic, ro, dones, h0_actor, h0_critic, cfg, nullptr, counters,
+                                   stats, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

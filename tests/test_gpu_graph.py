@@ -221,3 +221,112 @@ def test_iteration_graph_replays_match_eager(rx, name):
             assert torch.equal(tr, te), (k, i)
         assert host(rec.ctr).tolist() == [(k + 1) * w.T, k + 1, (k + 1) * n, (k + 1) * n if w.rnd else 0]
     assert torch.isfinite(rec.actor.params).all()
+
+
+class RecurrentLoop:
+    """The recurrent training iteration (memories carried across iterations, reset at episode ends) on device
+    counters, or on host counters for comparison."""
+
+    def __init__(self, rx, w, inp, device_counters):
+        self.rx, self.w, self.dc = rx, w, device_counters
+        T, N, A, H = w.T, w.N, w.A, w.memory_hidden
+        lstm = w.memory_cell == "lstm"
+        cid, S = (rx.CELL_LSTM, 2 * H) if lstm else (rx.CELL_GRU, H)
+        self.ga = rx.Memory(cid, w.Da, H, dev(inp["mem_actor"]), trainable=True)
+        self.gc = rx.Memory(cid, w.Dc, H, dev(inp["mem_critic"]), trainable=True)
+        self.ma = rx.Mlp(w.dims_actor, dev(inp["actor"]), trainable=True, has_log_std=True)
+        self.mc = rx.Mlp(w.dims_critic, dev(inp["critic"]), trainable=True)
+        self.obs, self.rewards, self.dones = dev(inp["obs"]), dev(inp["rewards"]), dev(inp["dones"])
+        self.h_a, self.h_c = dev(inp["h_actor"]), dev(inp["h_critic"])
+        self.h0_a, self.h0_c = torch.zeros(N, S, device="cuda"), torch.zeros(N, S, device="cuda")
+        self.actions, self.mu, self.sigma = (torch.zeros(T, N, A, device="cuda") for _ in range(3))
+        self.logp, self.values, self.adv, self.ret = (torch.zeros(T, N, device="cuda") for _ in range(4))
+        self.last = torch.zeros(N, device="cuda")
+        self.rollout = rx.Rollout(T, N, self.obs[:T], self.obs[:T], self.actions, self.logp, self.values, self.mu, self.sigma,
+                                  self.adv, self.ret)
+        self.cfg_kw = dict(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
+                           lr=w.lr, epochs=2, minibatches=w.minibatches, seed=SEED)
+        self.stats = torch.zeros(2 * w.minibatches, rx.NSTATS, device="cuda")
+        nets = (self.ga, self.ma, self.gc, self.mc)
+        self.aws = rx.workspace(rx.rslx_act_recurrent_workspace_bytes(*nets, N))
+        self.gws = rx.workspace(rx.rslx_gae_workspace_bytes(T, N))
+        self.uws = rx.workspace(rx.rslx_ppo_update_recurrent_workspace_bytes(*nets, self.rollout, rx.PpoCfg(**self.cfg_kw)))
+        self.act_step, self.call_index, self.adam_step = 0, 0, C.c_int64(0)
+        self.ctr = rx.dev_counters() if device_counters else None
+        self.state = [t.clone() for t in self.state_tensors()]
+
+    def state_tensors(self):
+        ts = [self.h_a, self.h_c]
+        for n in (self.ga, self.ma, self.gc, self.mc):
+            ts += [n.params, n.adam_m, n.adam_v]
+        if self.ctr is not None:
+            ts.append(self.ctr)
+        return ts
+
+    def reset(self):
+        for t, t0 in zip(self.state_tensors(), self.state):
+            t.copy_(t0)
+
+    def outputs(self):
+        return [self.actions, self.mu, self.sigma, self.logp, self.values, self.last, self.adv, self.ret, self.stats, self.h0_a,
+                self.h0_c, self.h_a, self.h_c, self.ga.params, self.ma.params, self.gc.params, self.mc.params, self.ga.adam_v]
+
+    def iterate(self):
+        rx, w = self.rx, self.w
+        T, N = w.T, w.N
+        nets = (self.ga, self.ma, self.gc, self.mc)
+        for t in range(T):
+            o = self.obs[t]
+            reset = self.dones[t - 1] if t > 0 else self.dones[T - 1]       # the previous roll-out ended with these flags
+            h0 = (self.h0_a, self.h0_c) if t == 0 else (None, None)
+            outs = (self.actions[t], self.logp[t], self.values[t], self.mu[t], self.sigma[t])
+            if self.dc:
+                rx.rslx_act_recurrent_dc(*nets, o, o, N, self.h_a, self.h_c, reset, *h0, SEED, self.ctr, None, *outs, 0, self.aws)
+            else:
+                rx.rslx_act_recurrent(*nets, o, o, N, self.h_a, self.h_c, reset, *h0, SEED, self.act_step, None, *outs, 0, self.aws)
+                self.act_step += 1
+        rx.rslx_act_recurrent(None, None, self.gc, self.mc, None, self.obs[T], N, None, self.h_c, self.dones[T - 1], None, None, 0, 0,
+                              None, None, None, self.last, None, None, rx.ACT_VALUES_ONLY, self.aws)
+        rx.rslx_gae(self.rewards, self.values, self.last, self.dones, None, T, N, w.gamma, w.lam, 1, self.adv, self.ret, self.gws)
+        if self.dc:
+            rx.rslx_ppo_update_recurrent_dc(*nets, self.rollout, self.dones, self.h0_a, self.h0_c, rx.PpoCfg(**self.cfg_kw), self.ctr,
+                                            self.stats, self.uws)
+        else:
+            rx.rslx_ppo_update_recurrent(*nets, self.rollout, self.dones, self.h0_a, self.h0_c,
+                                         rx.PpoCfg(call_index=self.call_index, **self.cfg_kw), self.adam_step, self.stats, self.uws)
+            self.call_index += 1
+
+
+@pytest.mark.parametrize("cell", ["gru", "lstm"])
+def test_recurrent_iteration_on_device_counters_and_as_a_graph(rx, cell):
+    w = replace(WORKLOADS["recurrent"].scaled(64), hidden=(64, 32), memory_hidden=32, done_p=0.05, memory_cell=cell)
+    inp = make_inputs(w)
+    n = 2 * w.minibatches
+    # device counters against host counters (Adam's bias corrections differ in the last bit at most)
+    h, d = RecurrentLoop(rx, w, inp, False), RecurrentLoop(rx, w, inp, True)
+    for it in range(2):
+        h.iterate(); d.iterate()
+        torch.cuda.synchronize()
+        if it == 0:
+            assert torch.equal(h.actions, d.actions) and torch.equal(h.h0_a, d.h0_a)
+        for th, td in zip(h.outputs(), d.outputs()):
+            assert rel_l2(host(td), host(th)) <= 1e-5
+        assert host(d.ctr).tolist() == [(it + 1) * w.T, it + 1, (it + 1) * n, 0]
+    # graph replays against the eager device-counter loop, bit for bit
+    eager, rec = RecurrentLoop(rx, w, inp, True), RecurrentLoop(rx, w, inp, True)
+    rec.iterate()
+    torch.cuda.synchronize()
+    rec.reset()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rec.iterate()
+    torch.cuda.synchronize()
+    assert host(rec.ctr).tolist() == [0, 0, 0, 0]
+    for k in range(3):
+        g.replay()
+        eager.iterate()
+        torch.cuda.synchronize()
+        for i, (tr, te) in enumerate(zip(rec.outputs(), eager.outputs())):
+            assert torch.equal(tr, te), (k, i)
+        assert host(rec.ctr).tolist() == [(k + 1) * w.T, k + 1, (k + 1) * n, 0]
