@@ -386,6 +386,33 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
         torch.cuda.synchronize()
         traced_ms = (time.perf_counter() - t2) * 1e3 / args.steps
         roofline, breakdown = summarize_trace(rx.rslx_trace_end(), w, args.steps)
+    graph_ms = None
+    if not args.no_graph:       # the same iteration on device-resident counters, recorded once and replayed
+        ctr = rx.dev_counters(act_step=(args.warmup + 2 * args.steps) * T, call_index=args.warmup + 2 * args.steps,
+                              adam_step=adam_step.value)
+
+        def step_dc():
+            for t in range(T):
+                reset = dones[t - 1] if t > 0 else dones[T - 1]
+                rx.rslx_act_recurrent_dc(ga, ma, gc, mc, obs[t], obs[t], N, h_a, h_c, reset, h0_a if t == 0 else None,
+                                         h0_c if t == 0 else None, 20250910, ctr, None, actions[t], logp[t], values[t], mu[t],
+                                         sigma[t], 0, aws)
+            rx.rslx_act_recurrent(None, None, gc, mc, None, obs[T], N, None, h_c, dones[T - 1], None, None, 0, 0, None, None, None,
+                                  last, None, None, rx.ACT_VALUES_ONLY, aws)
+            rx.rslx_gae(rewards, values, last, dones, None, T, N, w.gamma, w.lam, 1, adv, ret, gws)
+            rx.rslx_ppo_update_recurrent_dc(ga, ma, gc, mc, rollout, dones, h0_a, h0_c, rx.PpoCfg(**cfg_kw), ctr, stats, uws)
+
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step_dc()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t3) * 1e3 / args.steps
     assert torch.isfinite(ma.params).all() and torch.isfinite(ga.params).all() and torch.isfinite(stats).all()
     fwd = lambda dims: sum(2 * i * o for i, o in zip(dims[:-1], dims[1:]))
     gru_fwd = lambda D: 2 * (D + H) * G * H
@@ -406,6 +433,8 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
         "act_tflops": round(act_flops * (T + 1) * N / (med["act"] * 1e-3) / 1e12, 2),
         "act_env_steps_per_s": round((T + 1) * N / (med["act"] * 1e-3), 1),
         "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
+        "graph_replay": None if graph_ms is None else {"ms_per_step": round(graph_ms, 4),
+                                                       "value": round(B / (graph_ms * 1e-3), 1)},
         "roofline": roofline, "kernels": breakdown,
     }
 
