@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librslx.so")
-SOURCES = ["gemm.hip", "fused_forward.hip", "elementwise.hip", "recurrent.hip", "api.hip"]
+SOURCES = ["gemm.hip", "fused_forward.hip", "elementwise.hip", "recurrent.hip", "api.hip", "api_recurrent.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
