@@ -48,7 +48,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same iteration")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build is single-GPU; run with --gpus 1 (how the path would shard is described in DESIGN.md)")
+        print("bench.py: this library runs on one GPU; run with --gpus 1 (environments are independent columns, so the path "
+              "would shard by environment with one gradient all-reduce per optimiser step)")
         sys.exit(2)
 
     import numpy as np
