@@ -116,10 +116,19 @@ __device__ __forceinline__ void ff_contract(const FfWeights& wt, const FfTask& t
                                             float (&w0)[FF_CHUNK], f32x4 (&acc)[4][2]) {
   float w1[FF_CHUNK];
   const float* bp = actIn + (task.s_begin * 4 + wt.kq) * FF_ROWS + 2 * wt.m;
-  auto compute = [&](int c, const float (&src)[FF_CHUNK]) {
-    float2 b[FF_STEPS];
+  const int nch = (task.s_end - task.s_begin + FF_STEPS - 1) / FF_STEPS;
+  auto read_b = [&](int c, int s) { return *reinterpret_cast<const float2*>(bp + (c * FF_STEPS + s) * 4 * FF_ROWS); };
+  // One chunk: its matrix-core instructions with, dealt out between them, the loads of the following chunk into
+  // the other register buffer and the LDS reads of the activations two steps ahead; the first two steps' activations
+  // arrive in `bh`, read under the previous chunk (the last chunk reads its own again).
+  float2 bh[2] = {read_b(0, 0), read_b(0, 1)};
+  auto chunk = [&](int c, int s_next, const float (&src)[FF_CHUNK], float (&dst)[FF_CHUNK]) {
+    wt.load<VEC>(s_next, dst);
+    float2 b[FF_STEPS + 2];
+    b[0] = bh[0]; b[1] = bh[1];
+    const int cn = min(c + 1, ((nch + 1) & ~1) - 1);   // chunks come in pairs; an odd count's twin meets zero activations
 #pragma unroll
-    for (int s = 0; s < FF_STEPS; ++s) b[s] = *reinterpret_cast<const float2*>(bp + (c * FF_STEPS + s) * 4 * FF_ROWS);
+    for (int s = 2; s < FF_STEPS + 2; ++s) b[s] = s < FF_STEPS ? read_b(c, s) : read_b(cn, s - FF_STEPS);
 #pragma unroll
     for (int s = 0; s < FF_STEPS; ++s)
 #pragma unroll
@@ -127,21 +136,28 @@ __device__ __forceinline__ void ff_contract(const FfWeights& wt, const FfTask& t
         acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(src[4 * s + cb], b[s].x, acc[cb][0], 0, 0, 0);
         acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(src[4 * s + cb], b[s].y, acc[cb][1], 0, 0, 0);
       }
+    bh[0] = b[FF_STEPS]; bh[1] = b[FF_STEPS + 1];
+    // masks: 0x008 matrix core, 0x100 LDS read, 0x020 global load.  Per pair of steps (16 matrix-core instructions):
+    // the LDS read of the pair after next, then two groups of loads (one 16-byte load, or four 4-byte loads, per step)
+#pragma unroll
+    for (int pr = 0; pr < FF_STEPS / 2; ++pr) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, VEC ? 1 : 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, VEC ? 1 : 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
   // A task spans an even number of chunks (see the split plan), and the fetch of the following chunk is issued
   // without a test (rows are clamped: a chunk past the range reads valid memory and is not used).  The loop body
   // is therefore free of branches, and the compiler's count of the loads in flight is exact: the matrix-core
   // instructions of one buffer wait for that buffer's loads only, not for the ones just issued into the other.
-  const int nch = (task.s_end - task.s_begin + FF_STEPS - 1) / FF_STEPS;
   for (int c = 0; c < nch; c += 2) {
-    wt.load<VEC>(task.s_begin + (c + 1) * FF_STEPS, w1);
-    __builtin_amdgcn_sched_barrier(0);      // the fetches stay ahead of the other buffer's arithmetic
-    compute(c, w0);
-    __builtin_amdgcn_sched_barrier(0);
-    wt.load<VEC>(task.s_begin + (c + 2) * FF_STEPS, w0);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(c + 1, w1);
-    __builtin_amdgcn_sched_barrier(0);
+    chunk(c, task.s_begin + (c + 1) * FF_STEPS, w0, w1);
+    chunk(c + 1, task.s_begin + (c + 2) * FF_STEPS, w1, w0);
   }
 }
 
