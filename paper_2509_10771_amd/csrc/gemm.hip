@@ -41,20 +41,24 @@ struct KContig {
   static constexpr int NPTR = VEC ? R / RPV : R / RPS;
   static constexpr bool vec = VEC;
   const float* ptr[VEC ? 1 : NPTR];                 // scalar path: row pointers, gather applied
-  uint32_t off[VEC ? NPTR : 1];                     // vector path: element offsets of the rows from `base` (~0u = no row)
+  uint32_t off[VEC ? NPTR : 1];                     // vector path: element offsets of the rows from `base`; rows past the
+                                                    // end point at the last row, so every offset can be loaded from
   const float* base;
   uint32_t mapped;                                  // scalar path, bit p: row of pass p reads through col_map / col_sign
+  uint32_t valid;                                   // vector path, bit p: the row of pass p exists
 
   __device__ __forceinline__ void setup(const GemmProblem& P, const float* b, int ld, int row0, int row_end) {
     const int tid = threadIdx.x;
     mapped = 0;
+    valid = 0;
     base = b;
     if constexpr (VEC) {
 #pragma unroll
       for (int p = 0; p < R / RPV; ++p) {
         const int row = row0 + p * RPV + tid / LK;
-        off[p] = ~0u;
-        if (row < row_end) off[p] = (uint32_t)(IS_X ? src_row(P, row) : row) * (uint32_t)ld + 4u * (tid % LK);
+        if (row < row_end) valid |= 1u << p;
+        const int rc = min(row, row_end - 1);
+        off[p] = (uint32_t)(IS_X ? src_row(P, rc) : rc) * (uint32_t)ld + 4u * (tid % LK);
       }
     } else {
 #pragma unroll
@@ -69,17 +73,15 @@ struct KContig {
     }
   }
 
-  // FULL: the tile lies inside the matrix in both directions, so no lane needs a bounds check.
-  template <bool FULL>
   __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
     const int tid = threadIdx.x;
     if constexpr (VEC) {
       const float* bk = base + k0;                 // uniform; the per-lane part is the 32-bit offset
-      const bool kok = FULL || k0 + 4 * (tid % LK) < k_end;
+      const bool kok = k0 + 4 * (tid % LK) < k_end;
 #pragma unroll
       for (int p = 0; p < R / RPV; ++p) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (FULL || (kok && off[p] != ~0u)) v = *reinterpret_cast<const float4*>(bk + off[p]);
+        if (kok && ((valid >> p) & 1u)) v = *reinterpret_cast<const float4*>(bk + off[p]);
         reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
       }
     } else {
@@ -100,7 +102,8 @@ struct KContig {
     }
   }
 
-  // One 16-byte load / its LDS writes at a time, for tiles inside the matrix: the contraction loop places them
+  // One 16-byte load / its LDS writes at a time, without bounds checks (whole BK-tiles of the contraction only; rows
+  // past the end repeat the last row and feed output rows that are dropped): the contraction loop places them
   // between its matrix-core instructions.
   static constexpr int NPIECE = VEC ? R / RPV : 0;
   __device__ __forceinline__ void fetch_piece(int k0, float (&reg)[NREG], int p) const {
@@ -144,9 +147,11 @@ struct Direct {
   static constexpr int RPS = NT / Cw;               // scalar path: tile rows per pass
   const float* base;
   int ld, col, cm;
+  int colc;                                         // vector path: col, or the last whole 16-byte column group of the matrix
   float sg;
   bool col_ok, has_map;
   uint32_t off[VEC ? (BK / RPV > 0 ? BK / RPV : 1) : 1];   // vector path, rows not gathered: offsets from row k0
+  int next_row[(VEC && IS_X) ? (BK / RPV > 0 ? BK / RPV : 1) : 1];   // vector path, gathered rows: source rows of the next fetch
   static constexpr bool vec = VEC;
 
   __device__ __forceinline__ void setup(const GemmProblem& P, const float* b, int ld_, int col0, int col_end) {
@@ -155,9 +160,10 @@ struct Direct {
     col = vec ? col0 + 4 * (tid % V) : col0 + tid % Cw;
     col_ok = col < col_end;
     has_map = false; cm = col; sg = 1.0f;
+    colc = col_ok ? col : max(col_end - 4, 0);
     if constexpr (VEC) {
 #pragma unroll
-      for (int p = 0; p < BK / RPV; ++p) off[p] = (uint32_t)(p * RPV + tid / V) * (uint32_t)ld + (uint32_t)col;
+      for (int p = 0; p < BK / RPV; ++p) off[p] = (uint32_t)(p * RPV + tid / V) * (uint32_t)ld + (uint32_t)colc;
     }
     if (IS_X && !vec && col_ok && P.col_map != nullptr) {
       has_map = true;
@@ -166,8 +172,18 @@ struct Direct {
     }
   }
 
-  template <bool FULL>
-  __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) const {
+  // Gathered rows (vector path): the source rows of a tile are looked up while the previous tile is fetched, so
+  // that no fetch waits for its own index loads.  `prime` looks up the rows of the first tile; every fetch then
+  // looks up the rows of the tile BK further on (fetches walk the contraction range in steps of BK).
+  __device__ __forceinline__ void prime(const GemmProblem& P, int k0, int k_end) {
+    if constexpr (VEC && IS_X) {
+      const int tid = threadIdx.x;
+#pragma unroll
+      for (int p = 0; p < BK / RPV; ++p) next_row[p] = src_row(P, min(k0 + p * RPV + tid / V, k_end - 1));
+    }
+  }
+
+  __device__ __forceinline__ void fetch(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG]) {
     const int tid = threadIdx.x;
     if constexpr (VEC) {
       const float* bk = base + (long)k0 * ld;      // uniform
@@ -175,11 +191,15 @@ struct Direct {
       for (int p = 0; p < BK / RPV; ++p) {
         const int kk = k0 + p * RPV + tid / V;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (FULL || (col_ok && kk < k_end)) {
-          if constexpr (IS_X) v = *reinterpret_cast<const float4*>(base + (long)src_row(P, kk) * ld + col);
+        if (col_ok && kk < k_end) {
+          if constexpr (IS_X) v = *reinterpret_cast<const float4*>(base + (long)next_row[p] * ld + col);
           else v = *reinterpret_cast<const float4*>(bk + off[p]);
         }
         reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
+      }
+      if constexpr (IS_X) {
+#pragma unroll
+        for (int p = 0; p < BK / RPV; ++p) next_row[p] = src_row(P, min(k0 + BK + p * RPV + tid / V, k_end - 1));
       }
     } else {
 #pragma unroll
@@ -195,11 +215,19 @@ struct Direct {
     }
   }
 
-  // Piecewise variants for tiles inside the matrix whose contraction rows are not gathered (row kk is row kk).
+  // Piecewise variants without bounds checks (whole BK-tiles of the contraction; matrix widths that are multiples of
+  // four): columns past the end repeat the last column group and feed outputs that are dropped.  The first form is
+  // for contraction rows that are not gathered (row kk is row kk), the second walks the gathered rows like `fetch`.
   static constexpr int NPIECE = VEC ? BK / RPV : 0;
   __device__ __forceinline__ void fetch_piece(int k0, float (&reg)[NREG], int p) const {
     const float4 v = *reinterpret_cast<const float4*>(base + (long)k0 * ld + off[VEC ? p : 0]);
     reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
+  }
+  __device__ __forceinline__ void fetch_piece_gathered(const GemmProblem& P, int k0, int k_end, float (&reg)[NREG], int p) {
+    const int pi = (VEC && IS_X) ? p : 0;
+    const float4 v = *reinterpret_cast<const float4*>(base + (long)next_row[pi] * ld + colc);
+    reg[4 * p + 0] = v.x; reg[4 * p + 1] = v.y; reg[4 * p + 2] = v.z; reg[4 * p + 3] = v.w;
+    next_row[pi] = src_row(P, min(k0 + BK + p * RPV + (int)threadIdx.x / V, k_end - 1));
   }
   template <int S>
   __device__ __forceinline__ void stash_piece(float (*lds)[S], const float (&reg)[NREG], int p) const {
@@ -305,16 +333,16 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
     else a_k.template stash<SA>(As[buf], ra);
     b_d.template stash<SB>(Bs[buf], rb);
   };
-  // The loop exists twice: for tiles inside the matrix (no lane checks a bound, loads are base + fixed offset) and
-  // for edge tiles.
-  auto main_loop = [&](auto full_tag) {
-    constexpr bool FULL = decltype(full_tag)::value;
+  // The general loop: every lane checks its bounds (scalar operand paths, contraction ranges that are no multiple
+  // of BK).
+  auto main_loop = [&]() {
     auto fetch = [&](int k0) {
-      if (MODE == GEMM_DW) a_d.template fetch<FULL>(P, k0, k_end, ra);
-      else a_k.template fetch<FULL>(P, k0, k_end, ra);
-      b_d.template fetch<FULL>(P, k0, k_end, rb);
+      if (MODE == GEMM_DW) a_d.fetch(P, k0, k_end, ra);
+      else a_k.fetch(P, k0, k_end, ra);
+      b_d.fetch(P, k0, k_end, rb);
     };
     if (nk > 0) {
+      if (MODE == GEMM_DW) a_d.prime(P, k_begin, k_end);
       fetch(k_begin);
       stash(0);
     }
@@ -359,12 +387,15 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
       __syncthreads();
     }
   };
-  // Tiles inside the matrix whose contraction rows are not gathered run the same double buffer with the other
+  // 16-byte operand paths over whole BK-tiles run the same double buffer without bounds checks (operand rows and
+  // columns past the matrix repeat valid ones; the outputs they feed are dropped by the epilogue) and with the other
   // instructions dealt out between the matrix-core instructions, one per gap: the 16-byte loads of the next tile
   // in the first steps of a tile, their LDS writes in the last steps, the LDS operand reads of the next step after
   // the first matrix-core instruction of each step.  A wave then never issues a burst of memory instructions while
   // its matrix-core queue runs dry (measured: 6 % faster forward, 11 % faster input gradient at 128 x 128).
-  auto stream_loop = [&]() {
+  // GATHERED: the weight gradient's contraction rows go through row_idx / wrap (looked up one tile ahead).
+  auto stream_loop = [&](auto gathered_tag) {
+    constexpr bool GATHERED = decltype(gathered_tag)::value;
     constexpr int NA = MODE == GEMM_DW ? decltype(a_d)::NPIECE : decltype(a_k)::NPIECE;
     constexpr int NB = decltype(b_d)::NPIECE;
     constexpr int NP = NA + NB, STEPS = BK / 2;
@@ -373,7 +404,8 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
 #pragma unroll
       for (int p = 0; p < NA; ++p)
         if (q == p) {
-          if (MODE == GEMM_DW) a_d.fetch_piece(k0, ra, p);
+          if (MODE == GEMM_DW && GATHERED) a_d.fetch_piece_gathered(P, k0, k_end, ra, p);
+          else if (MODE == GEMM_DW) a_d.fetch_piece(k0, ra, p);
           else a_k.fetch_piece(k0, ra, p);
         }
 #pragma unroll
@@ -391,6 +423,7 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
       for (int p = 0; p < NB; ++p)
         if (q == NA + p) b_d.template stash_piece<SB>(Bs[buf], rb, p);
     };
+    if (GATHERED) a_d.prime(P, k_begin, k_end);
 #pragma unroll
     for (int q = 0; q < NP; ++q) load_piece(q, k_begin);
     stash(0);
@@ -449,14 +482,15 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
       __syncthreads();
     }
   };
-  const bool interior = AVEC && BVEC && m0 + BM <= P.M && n0 + BN <= P.N && (k_end - k_begin) % BK == 0;
+  const bool whole_tiles = nk > 0 && (k_end - k_begin) % BK == 0;
+  const bool widths_ok = P.N >= 4 && (P.N & 3) == 0 && (MODE != GEMM_DW || (P.M >= 4 && (P.M & 3) == 0));
   const bool plain_rows = MODE != GEMM_DW || (P.row_idx == nullptr && k_end <= P.idx_mod);
   if constexpr (AVEC && BVEC) {
-    if (interior && plain_rows && nk > 0) stream_loop();
-    else if (interior) main_loop(std::true_type{});
-    else main_loop(std::false_type{});
+    if (whole_tiles && widths_ok && plain_rows) stream_loop(std::false_type{});
+    else if (whole_tiles && widths_ok) stream_loop(std::true_type{});
+    else main_loop();
   } else {
-    main_loop(std::false_type{});
+    main_loop();
   }
 
   // ---- epilogue -------------------------------------------------------------------------------
