@@ -503,69 +503,93 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
   const int bias_off = P.bias_off;
   float* Cb = P.C;
   if (MODE == GEMM_DW) Cb += (long)split * P.split_stride;
+  // Tiles inside the matrix.  Loads issued after a block's stores would have to wait for those stores as well (one
+  // counter covers both), so everything a block reads is requested before the previous block's stores: the biases
+  // of all blocks up front, the activation values that gate the input gradient one block ahead.
+  if (full_mn) {
+    float bias[TN];
+#pragma unroll
+    for (int y = 0; y < TN; ++y) bias[y] = (MODE == GEMM_FWD && aux != nullptr) ? aux[n0 + wn * (TN * 32) + y * 32 + j] : 0.f;
+    constexpr bool GATE_PIPE = MODE == GEMM_DX && !AUX_AHEAD;
+    float hx[2][16];
+    auto block_offset = [&](int b) {
+      const int x = b / TN, y = b % TN;
+      // register r of a 32x32 block sits 8 * (r / 4) + r % 4 rows below its first row: a uniform offset
+      return (long)(m0 + wm * (TM * 32) + x * 32 + 4 * g) * ldc + (n0 + wn * (TN * 32) + y * 32 + j);
+    };
+    auto load_gate = [&](int b, float (&h)[16]) {
+      const float* hp = aux + block_offset(b);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) h[r] = hp[(8 * (r / 4) + (r % 4)) * ldc];
+    };
+    if (GATE_PIPE && aux != nullptr) load_gate(0, hx[0]);
+#pragma unroll
+    for (int b = 0; b < TM * TN; ++b) {
+      const int x = b / TN, y = b % TN;
+      float* cp = Cb + block_offset(b);
+      if (MODE == GEMM_DX && aux != nullptr) {
+        if constexpr (AUX_AHEAD) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) hx[b & 1][r] = hpre[b * 16 + r];
+        } else if (b + 1 < TM * TN) {
+          load_gate(b + 1, hx[(b + 1) & 1]);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[x][y][r];
+        if (MODE == GEMM_FWD) {
+          v += bias[y];
+          if (elu) {
+            const float e = alpha * (__expf(v) - 1.0f);
+            v = v > 0.f ? v : e;
+          }
+        } else if (MODE == GEMM_DX) {
+          if (aux != nullptr) v *= (hx[b & 1][r] > 0.f) ? 1.0f : (hx[b & 1][r] + alpha);
+        }
+        cp[(8 * (r / 4) + (r % 4)) * ldc] = v;
+      }
+    }
+    if (MODE == GEMM_DW && tm == 0 && bias_off >= 0 && tid < BN && n0 + tid < Nc) Cb[bias_off + n0 + tid] = bsum;
+    return;
+  }
 #pragma unroll
   for (int x = 0; x < TM; ++x) {
 #pragma unroll
     for (int y = 0; y < TN; ++y) {
       const int col = n0 + wn * (TN * 32) + y * 32 + j;
       const int row_base = m0 + wm * (TM * 32) + x * 32 + 4 * g;
-      if (full_mn) {
-        // register r of a 32x32 block sits 8 * (r / 4) + r % 4 rows below row_base: a uniform offset
-        const long o0 = (long)row_base * ldc + col;
-        float* cp = Cb + o0;
-        float hx[16];
-        float bias = 0.f;
-        if (MODE == GEMM_FWD && aux != nullptr) bias = aux[col];
-        if (MODE == GEMM_DX && aux != nullptr) {
-          if constexpr (AUX_AHEAD) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) hx[r] = hpre[(x * TN + y) * 16 + r];
-          } else {                                  // all 16 loads of the block are in flight together
-            const float* hp = aux + o0;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) hx[r] = hp[(8 * (r / 4) + (r % 4)) * ldc];
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = acc[x][y][r];
-          if (MODE == GEMM_FWD) {
-            v += bias;
-            if (elu) {
-              const float e = alpha * (__expf(v) - 1.0f);
-              v = v > 0.f ? v : e;
-            }
-          } else if (MODE == GEMM_DX) {
-            if (aux != nullptr) v *= (hx[r] > 0.f) ? 1.0f : (hx[r] + alpha);
-          }
-          cp[(8 * (r / 4) + (r % 4)) * ldc] = v;
-        }
-        continue;
-      }
-      if (col >= Nc) continue;
+      // Edge tiles: what a block reads is read through clamped indices and turned into the block's 16 results before
+      // the first conditional store, so that no store has to wait behind a load (or behind the store before it).
+      const int colc = min(col, Nc - 1);
       float bias = 0.f;
-      if (MODE == GEMM_FWD && aux != nullptr) bias = aux[col];
-      float hx[16];
-      if (MODE == GEMM_DX && aux != nullptr) {
+      if (MODE == GEMM_FWD && aux != nullptr) bias = aux[colc];
+      float out[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = min(row_base + 8 * (r / 4) + (r % 4), Mr - 1);
-          hx[r] = aux[(long)row * ldc + col];
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[x][y][r];
+        if (MODE == GEMM_FWD) {
+          v += bias;
+          if (elu) {
+            const float e = alpha * (__expf(v) - 1.0f);
+            v = v > 0.f ? v : e;
+          }
+        } else if (MODE == GEMM_DX) {
+          if (aux != nullptr) {
+            const int rowc = min(row_base + 8 * (r / 4) + (r % 4), Mr - 1);
+            const float h = aux[(long)rowc * ldc + colc];
+            v *= (h > 0.f) ? 1.0f : (h + alpha);
+          }
         }
+        out[r] = v;
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(out[r]));   // the results exist before the branches below
+      if (col >= Nc) continue;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + 8 * (r / 4) + (r % 4);
-        if (row >= Mr) continue;
-        float v = acc[x][y][r];
-        const long o = (long)row * ldc + col;
-        if (MODE == GEMM_FWD) {
-          v += bias;
-          if (elu) v = v > 0.f ? v : alpha * (__expf(v) - 1.0f);
-        } else if (MODE == GEMM_DX) {
-          if (aux != nullptr) v *= (hx[r] > 0.f) ? 1.0f : (hx[r] + alpha);
-        }
-        Cb[o] = v;
+        if (row < Mr) Cb[(long)row * ldc + col] = out[r];
       }
     }
   }
