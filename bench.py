@@ -22,9 +22,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the matrix-core kernels on the "flat" workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (2.0 * FETCH + 1.0 * WRITE after calibration against a kernel of known size; profiles/flat_iteration_hbm_traffic.txt).
 HBM_TRAFFIC_BYTES_PER_LAUNCH_FLAT = {
-    "gemm_dwdx_128x128_64x128": 437.8e6,   # algorithmic 437.3e6 (dW 512x256 incl. 33.6e6 of split partials + dX 256->512)
-    "gemm_fwd_128x128": 159.6e6,           # algorithmic 152.0e6
-    "gemm_dwdx_64x128_128x128": 237.4e6,   # algorithmic 235.0e6 (dW 256x128 + dX 128->256)
+    "gemm_dwdx_128x128_64x128": 451.8e6,   # algorithmic 437.3e6 (dW 512x256 incl. 33.6e6 of split partials + dX 256->512)
+    "gemm_fwd_128x128": 161.9e6,           # algorithmic 152.0e6
+    "gemm_dwdx_64x128_128x128": 236.1e6,   # algorithmic 235.0e6 (dW 256x128 + dX 128->256)
 }
 
 

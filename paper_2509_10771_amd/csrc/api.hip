@@ -283,6 +283,9 @@ struct PpoPlan {
   void* perm_ws = nullptr;
   TrainBufs actor, critic, pred;
   NetBufs targ;
+  float* stage_a = nullptr;          // staged (padded, mirrored) network inputs, when worth it (see staged_width)
+  float* stage_c = nullptr;
+  int dp_a = 0, dp_c = 0;            // their row widths, 0 = not staged
   double* sumsq_all = nullptr;       // actor blocks, critic blocks, log_std slot
   double* loss_partials = nullptr;
   double* mse_partials = nullptr;
@@ -296,6 +299,10 @@ void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rs
   p.rows = sym ? 2 * p.mb : p.mb;
   p.perms = c.take<int32_t>((size_t)cfg->epochs * p.B);
   p.perm_ws = c.take<char>(perm_workspace_bytes(p.B));
+  p.dp_a = staged_width(*actor, ro->Da, sym != nullptr);
+  p.dp_c = staged_width(*critic, ro->Dc, sym != nullptr);
+  if (p.dp_a) p.stage_a = c.take<float>((size_t)(sym ? 2 : 1) * p.B * p.dp_a);
+  if (p.dp_c) p.stage_c = c.take<float>((size_t)(sym ? 2 : 1) * p.B * p.dp_c);
   carve_train(c, *actor, p.rows, 2, p.actor);
   carve_train(c, *critic, p.rows, 2, p.critic);
   p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 2);
@@ -394,20 +401,39 @@ int32_t ppo_update_impl(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
                                  counters ? &counters->call_index : nullptr, cfg->epoch_offset));
   }
 
+  // The observations do not change during the call: where the 16-byte operand paths cannot read them in place,
+  // a padded copy (with the mirrored rows below the originals) is made once and serves every minibatch.
+  if (p.dp_a)
+    RSLX_HIP(launch_stage_input(ro->obs_actor, ro->Da, (int32_t)p.B, ro->Da, p.dp_a, sym ? sym->perm_obs_a : nullptr,
+                                sym ? sym->sign_obs_a : nullptr, p.stage_a, s));
+  if (p.dp_c)
+    RSLX_HIP(launch_stage_input(ro->obs_critic, ro->Dc, (int32_t)p.B, ro->Dc, p.dp_c, sym ? sym->perm_obs_c : nullptr,
+                                sym ? sym->sign_obs_c : nullptr, p.stage_c, s));
+  auto obs_view = [&](const float* obs, int D, const float* staged, int dp, const int32_t* col_map, const float* col_sign,
+                      const int32_t* idx) {
+    XView x;
+    x.row_idx = idx;
+    if (sym) x.idx_mod = p.mb;
+    if (dp) {
+      x.base = staged; x.ld = dp; x.cols = dp;
+      x.src_rows = (sym ? 2 : 1) * (int64_t)p.B;
+      if (sym) x.wrap_add = (int)p.B;
+    } else {
+      x.base = obs; x.ld = D; x.src_rows = p.B;
+      if (sym) { x.map_from = p.mb; x.col_map = col_map; x.col_sign = col_sign; }
+    }
+    return x;
+  };
+
   for (int e = 0; e < cfg->epochs; ++e) {
     for (int m = 0; m < cfg->minibatches; ++m) {
       const int32_t* idx = p.perms + (size_t)e * p.B + (size_t)m * p.mb;
       float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
 
-      XView xa, xc;
-      xa.base = ro->obs_actor; xa.ld = ro->Da; xa.row_idx = idx; xa.src_rows = p.B;
-      xc.base = ro->obs_critic; xc.ld = ro->Dc; xc.row_idx = idx; xc.src_rows = p.B;
-      if (sym) {
-        xa.idx_mod = xc.idx_mod = p.mb;
-        xa.map_from = xc.map_from = p.mb;
-        xa.col_map = sym->perm_obs_a; xa.col_sign = sym->sign_obs_a;
-        xc.col_map = sym->perm_obs_c; xc.col_sign = sym->sign_obs_c;
-      }
+      const XView xa = obs_view(ro->obs_actor, ro->Da, p.stage_a, p.dp_a, sym ? sym->perm_obs_a : nullptr,
+                                sym ? sym->sign_obs_a : nullptr, idx);
+      const XView xc = obs_view(ro->obs_critic, ro->Dc, p.stage_c, p.dp_c, sym ? sym->perm_obs_c : nullptr,
+                                sym ? sym->sign_obs_c : nullptr, idx);
       NetJob fj[2] = {NetJob{actor, xa, p.rows, &p.actor.act}, NetJob{critic, xc, p.rows, &p.critic.act}};
       RSLX_TRY(forward_nets(fj, 2, s, p.fused_head));
 

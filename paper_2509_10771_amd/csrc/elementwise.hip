@@ -1217,6 +1217,37 @@ hipError_t launch_sym_augment(const float* in, int32_t B, int32_t D, const int32
   return hipGetLastError();
 }
 
+// One lane per group of four output columns (Dp is a multiple of four, out is 16-byte aligned).
+__global__ __launch_bounds__(256) void stage_input_kernel(const float* __restrict__ in, int ld, long B, int D, int Dp,
+                                                          const int32_t* __restrict__ perm, const float* __restrict__ sign,
+                                                          float* __restrict__ out, long groups) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= groups) return;
+  const int q = Dp / 4;
+  const long r = i / q;
+  const int c0 = 4 * (int)(i - r * q);
+  const bool mirrored = r >= B;
+  const float* row = in + (mirrored ? r - B : r) * (long)ld;
+  float v[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int c = c0 + k;
+    v[k] = 0.f;
+    if (c < D) v[k] = mirrored ? sign[c] * row[perm[c]] : row[c];
+  }
+  *reinterpret_cast<float4*>(out + r * (long)Dp + c0) = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+hipError_t launch_stage_input(const float* in, int32_t ld, int32_t B, int32_t D, int32_t Dp, const int32_t* perm,
+                              const float* sign, float* out, hipStream_t stream) {
+  const long groups = (long)B * (perm ? 2 : 1) * (Dp / 4);
+  if (groups <= 0) return hipSuccess;
+  TraceScope ts(stream, "stage_input", 0.0, 4.0 * (double)B * (perm ? 2 : 1) * (D + Dp));
+  hipLaunchKernelGGL(stage_input_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream, in, ld, (long)B, D, Dp,
+                     perm, sign, out, groups);
+  return hipGetLastError();
+}
+
 // ---- RND reward ---------------------------------------------------------------------------------------
 int rnd_num_blocks(int32_t N) { return (N + 255) / 256; }
 

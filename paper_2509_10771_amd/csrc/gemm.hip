@@ -25,7 +25,8 @@ __device__ __forceinline__ int wrap_row(const GemmProblem& P, int r) { return r 
 
 __device__ __forceinline__ int src_row(const GemmProblem& P, int r) {
   int rr = wrap_row(P, r);
-  return P.row_idx ? P.row_idx[rr] : rr;
+  const int v = P.row_idx ? P.row_idx[rr] : rr;
+  return r >= P.idx_mod ? v + P.wrap_add : v;
 }
 
 // ---- operand with the contraction index contiguous in memory (tile rows = M or N index) ---------------------
@@ -303,7 +304,8 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
   KContig<BM, BK, MODE == GEMM_FWD, AVEC> a_k;
   Direct<BM, BK, true, AVEC> a_d;
   Direct<BN, BK, false, BVEC> b_d;
-  if (MODE == GEMM_DW) a_d.setup(P, P.A, P.lda, m0, P.M);
+  const int a_cols = (MODE == GEMM_DW && P.a_cols > P.M) ? P.a_cols : P.M;   // DW: readable (zero-padded) width of X
+  if (MODE == GEMM_DW) a_d.setup(P, P.A, P.lda, m0, a_cols);
   else a_k.setup(P, P.A, P.lda, m0, P.M);
   b_d.setup(P, P.B, P.ldb, n0, P.N);
 
@@ -483,7 +485,7 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, int lin, const i
     }
   };
   const bool whole_tiles = nk > 0 && (k_end - k_begin) % BK == 0;
-  const bool widths_ok = P.N >= 4 && (P.N & 3) == 0 && (MODE != GEMM_DW || (P.M >= 4 && (P.M & 3) == 0));
+  const bool widths_ok = P.N >= 4 && (P.N & 3) == 0 && (MODE != GEMM_DW || (a_cols >= 4 && (a_cols & 3) == 0));
   const bool plain_rows = MODE != GEMM_DW || (P.row_idx == nullptr && k_end <= P.idx_mod);
   if constexpr (AVEC && BVEC) {
     if (whole_tiles && widths_ok && plain_rows) stream_loop(std::false_type{});

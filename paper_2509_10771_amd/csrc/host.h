@@ -97,7 +97,21 @@ struct XView {
   int idx_mod = INT_MAX;
   int map_from = INT_MAX;
   int64_t src_rows = 0;     // rows of the matrix behind row_idx
+  int wrap_add = 0;         // rows past idx_mod read this many rows further down (staged mirrored copy)
+  int cols = 0;             // staged input: zero-padded width of the rows (a multiple of 16), 0 = the network's input width
 };
+
+// Staged network input (see launch_stage_input): worth it when the rows cannot be fetched 16 bytes at a time, when
+// their width is no whole number of contraction tiles, or when mirrored rows would go through a column map.  The
+// first layer then contracts over the padded width, which reads rows of W past its end: those meet zero columns,
+// but they must lie inside the parameter buffer.
+inline int staged_width(const rslx_mlp& n, int32_t ld, bool mirrored) {
+  const int D = n.dims[0];
+  if (!mirrored && D % 16 == 0 && ld % 4 == 0) return 0;
+  const int Dp = (D + 15) / 16 * 16;
+  if ((int64_t)Dp * n.dims[1] > weight_count(n)) return 0;
+  return Dp;
+}
 
 // Per-network activation storage for `rows` rows: out[l] = output of layer l, dz[l] = gradient w.r.t. the
 // pre-activation of hidden layer l.  The caller may point out[last] at its own buffer.
@@ -124,7 +138,7 @@ inline GemmProblem blank_problem() {
 
 inline void set_x(GemmProblem& p, const XView& x) {
   p.A = x.base; p.lda = x.ld; p.row_idx = x.row_idx; p.col_map = x.col_map; p.col_sign = x.col_sign;
-  p.idx_mod = x.idx_mod; p.map_from = x.map_from; p.a_src_rows = x.src_rows;
+  p.idx_mod = x.idx_mod; p.map_from = x.map_from; p.a_src_rows = x.src_rows; p.wrap_add = x.wrap_add;
 }
 
 struct NetJob {
@@ -158,7 +172,7 @@ inline int32_t forward_nets(const NetJob* jobs, int count, hipStream_t stream, b
       p.B = W; p.ldb = n.dims[l + 1];
       p.aux = W + (int64_t)n.dims[l] * n.dims[l + 1];
       p.C = jobs[i].bufs->out[l]; p.ldc = n.dims[l + 1];
-      p.M = jobs[i].rows; p.N = n.dims[l + 1]; p.K = n.dims[l];
+      p.M = jobs[i].rows; p.N = n.dims[l + 1]; p.K = (l == 0 && jobs[i].x.cols) ? jobs[i].x.cols : n.dims[l];
       p.elu = (l + 1 < L) ? 1 : 0;
       p.alpha = n.elu_alpha;
       p.a_vec = (p.K % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
@@ -266,12 +280,13 @@ inline int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, 
       const SplitPlan& sp = *jobs[i].plan;
       p.C = jobs[i].partials + sp.part_off[l]; p.ldc = n.dims[l + 1];
       p.M = n.dims[l]; p.N = n.dims[l + 1]; p.K = jobs[i].rows;
+      if (l == 0) p.a_cols = jobs[i].x.cols;
       p.n_split = sp.split[l];
       p.k_chunk = sp.chunk[l];
       p.split_stride = sp.pitch[l];
       p.bias_off = n.dims[l] * n.dims[l + 1];
       p.dw_big = sp.big[l];
-      p.a_vec = (p.M % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
+      p.a_vec = ((p.a_cols ? p.a_cols : p.M) % 4 == 0 && p.lda % 4 == 0 && aligned16(p.A) && p.col_map == nullptr) ? 1 : 0;
       p.b_vec = (p.N % 4 == 0 && aligned16(p.B)) ? 1 : 0;
       bw.p[i] = p;
       if ((l > 0 || dx_in) && !(skip_last_dx && l == L - 1)) {

@@ -43,6 +43,7 @@ struct GemmProblem {
   const int32_t* col_map;   // optional column map for X (device)
   const float* col_sign;    // optional column sign for X (device, with col_map)
   int32_t idx_mod;          // rows r >= idx_mod wrap to r - idx_mod (INT32_MAX = no wrap)
+  int32_t wrap_add;         // added to the source row of a wrapped row (a second copy of the matrix further down)
   int32_t map_from;         // rows >= map_from use col_map / col_sign
   int32_t M, N, K;          // GEMM extents (K is the contraction length)
   int32_t lda, ldb, ldc;
@@ -55,6 +56,7 @@ struct GemmProblem {
   int32_t dw_big;           // DW: 1 = 128x128 tiles were planned for this layer, 0 = 64x128
   int32_t a_vec, b_vec;     // 1 = operand may be fetched with 16-byte loads
   int64_t a_src_rows;       // rows of the matrix that row_idx gathers from (0 = unknown)
+  int32_t a_cols;           // DW: readable width of X's rows when it exceeds M (zero-padded storage), 0 = M
 };
 
 struct GemmBatch {
@@ -226,6 +228,10 @@ hipError_t launch_mse_finish(const double* partials, int32_t blocks, int64_t cou
 
 hipError_t launch_sym_augment(const float* in, int32_t B, int32_t D, const int32_t* perm, const float* sign,
                               float* out, hipStream_t stream);
+// Network input staged for the 16-byte operand paths: out [B (+ B), Dp] holds in [B, D] (row stride ld) with the
+// columns D..Dp-1 zero and, when perm is given, below it the mirrored rows sign[j] * in[r, perm[j]].
+hipError_t launch_stage_input(const float* in, int32_t ld, int32_t B, int32_t D, int32_t Dp, const int32_t* perm,
+                              const float* sign, float* out, hipStream_t stream);
 
 // RND reward: row sums of squared differences, batch moments, running-stat merge, normalisation.
 int rnd_num_blocks(int32_t N);
