@@ -53,3 +53,18 @@ def test_recurrent_update_irregular_shapes(rx, i, shape):
                 memory_cell="lstm" if i % 2 else "gru")
     case = R.RCase(w, 1, perturb=0.1)
     R.check_forced_steps(rx, case, floor=5e-2)
+
+
+# Observation widths around the staged-input decision of the update: a width that is a whole number of 16-column
+# tiles is read in place unless the minibatch is mirrored; any other width is copied into zero-padded rows once per
+# call, unless the first layer is too small for the padded contraction to stay inside the parameter buffer, in
+# which case the rows are read in place through the slow path.  All four must agree with the oracle.
+@pytest.mark.parametrize("D,hidden,sym", [(48, (64, 64), True), (37, (64, 64), False), (37, (64,), False), (235, (128, 64), True),
+                                          (16, (8,), True)])
+def test_ppo_update_staged_and_in_place_inputs(rx, D, hidden, sym):
+    base = WORKLOADS["rough" if sym else "tiny"]
+    w = replace(base, N=96, T=5, Da=D, Dc=D, A=4, hidden=hidden, minibatches=3, height_scan=0)
+    if sym:
+        w = replace(w, symmetry=True)
+    case = U.Case(w, 1, sym_on=sym, perturb=0.15)
+    U.check_forced_steps(rx, case)
