@@ -57,7 +57,8 @@ def act(actor_flat, critic_flat, dims_a, dims_c, obs_a, obs_c, eps, alpha=1.0):
     return dict(actions=a, logp=gaussian.log_prob(a, mu, sigma), values=V[:, 0], mu=mu, sigma=sigma)
 
 
-def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg, sym=None, input_grads=False):
+def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg, sym=None, input_grads=False,
+                             sides=None, per_row=False):
     """Loss terms and flat gradients for one minibatch.
 
     batch: dict of row-gathered arrays obs_a, obs_c, actions, logp, adv, returns,
@@ -67,6 +68,14 @@ def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg
     copied) and every mean runs over the 2*mb rows.
     With input_grads the derivatives of the loss w.r.t. obs_a and obs_c are returned as well (a recurrent
     memory in front of the networks needs them).
+
+    The clipped surrogate and the clipped value loss have a kink where the ratio (the value change) meets the
+    clip range; there both one-sided derivatives are sub-gradients, and which one an implementation takes for a
+    row that sits on the kink to within rounding is decided by its rounding.  `sides` lets a caller evaluate the
+    other one: dict(policy={row: bool}, value={row: bool}) replaces, for the listed rows of this minibatch
+    (mirrored copies count from mb), the predicate "inside the clip range" by the given truth value.  The loss
+    terms do not depend on it (they are continuous); the gradient and the clip fraction do.  With per_row the
+    returned terms also hold the per-row ratio, new value and the two predicates.
     """
     alpha = cfg.elu_alpha
     layers_a, log_std = mlp.unpack(actor_flat, dims_a, log_std=True)
@@ -95,16 +104,29 @@ def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg
     s1, s2 = -adv * ratio, -adv * ratio_c
     surrogate = np.mean(np.maximum(s1, s2))
     in_range = (ratio >= 1.0 - cfg.clip) & (ratio <= 1.0 + cfg.clip)
-    d_ratio = np.where(in_range | (s1 >= s2), -adv, 0.0) / n        # clipped branch is flat in ratio outside the range
+    active = in_range | (s1 >= s2)                                  # clipped branch is flat in ratio outside the range
+    for r, side in ((sides or {}).get("policy") or {}).items():
+        # outside the range the unclipped term is the larger one iff moving further out raises -A*ratio
+        upper = abs(ratio[r] - (1.0 + cfg.clip)) <= abs(ratio[r] - (1.0 - cfg.clip))
+        in_range[r] = side
+        active[r] = side or (adv[r] < 0.0 if upper else adv[r] > 0.0)
+    d_ratio = np.where(active, -adv, 0.0) / n
 
     if cfg.use_clipped_value_loss:
         v_clip = v_old + np.clip(V - v_old, -cfg.clip, cfg.clip)
         e1, e2 = (V - ret) ** 2, (v_clip - ret) ** 2
         value_loss = np.mean(np.maximum(e1, e2))
         # the clipped branch is flat in V only where the clamp is active; inside the clip range V_clip == V
-        dV = np.where((np.abs(V - v_old) <= cfg.clip) | (e1 >= e2), 2.0 * (V - ret), 0.0) / n
+        v_in_range = np.abs(V - v_old) <= cfg.clip
+        v_active = v_in_range | (e1 >= e2)
+        for r, side in ((sides or {}).get("value") or {}).items():
+            # outside the range the unclipped square is the larger one iff V moves away from the return
+            v_in_range[r] = side
+            v_active[r] = side or ((V[r] - ret[r]) * (V[r] - v_old[r]) > 0.0)
+        dV = np.where(v_active, 2.0 * (V - ret), 0.0) / n
     else:
         value_loss = np.mean((ret - V) ** 2)
+        v_in_range = np.ones(n, bool)
         dV = 2.0 * (V - ret) / n
 
     d_logp = d_ratio * ratio
@@ -126,7 +148,9 @@ def minibatch_loss_and_grads(actor_flat, critic_flat, dims_a, dims_c, batch, cfg
     mu_old, sigma_old = f64("mu"), f64("sigma")
     kl = np.mean(gaussian.kl_old_new(mu_old, sigma_old, mu[:mb], np.broadcast_to(sigma, mu_old.shape)))
     terms = dict(loss=float(loss), surrogate=float(surrogate), value_loss=float(value_loss), entropy=float(H),
-                 kl=float(kl), clip_frac=float(np.mean(np.abs(ratio - 1.0) > cfg.clip)), mirror_loss=float(mirror_l))
+                 kl=float(kl), clip_frac=float(np.mean(~in_range)), mirror_loss=float(mirror_l))
+    if per_row:
+        terms.update(ratio=ratio, V=V, in_range=in_range, v_in_range=v_in_range, adv=adv)
     if input_grads:
         return terms, g_actor, g_critic, dx_a, dx_c
     return terms, g_actor, g_critic
@@ -142,7 +166,38 @@ def rnd_predictor_loss_and_grad(pred_flat, targ_flat, dims, x, alpha=1.0):
     return float(np.mean(diff ** 2)), mlp.pack(grads)
 
 
-def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=None, record=False):
+def optimiser_step(actor, critic, dims_a, dims_c, batch, cfg, opt, sym=None, rnd=None, sides=None, per_row=False):
+    """One optimiser step on one minibatch: loss and gradients, global gradient-norm clip, Adam on actor and
+    critic with the shared step counter, then (with rnd) one Adam step of the RND predictor on the same rows.
+
+    opt and rnd are updated in place (their arrays are replaced, not written into).  Returns
+    (actor, critic, terms, g_actor, g_critic, grad_norm, rnd_loss).
+    """
+    terms, g_a, g_c = minibatch_loss_and_grads(actor, critic, dims_a, dims_c, batch, cfg, sym, sides=sides, per_row=per_row)
+    norm = adam.global_norm([g_a, g_c])
+    s = adam.clip_scale(norm, cfg.max_grad_norm)
+    t0 = opt["step"]
+    actor, opt["m_a"], opt["v_a"], _ = adam.adam_step(actor, s * g_a, opt["m_a"], opt["v_a"], t0, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
+    critic, opt["m_c"], opt["v_c"], opt["step"] = adam.adam_step(critic, s * g_c, opt["m_c"], opt["v_c"], t0, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
+    rnd_loss = 0.0
+    if rnd is not None:
+        x = np.asarray(batch["obs_a"], np.float64)
+        if rnd.get("subset") is not None:
+            x = x[:, np.asarray(rnd["subset"])]
+        rnd_loss, g_p = rnd_predictor_loss_and_grad(rnd["pred"], rnd["targ"], rnd["dims"], x, cfg.elu_alpha)
+        rnd["pred"], rnd["m"], rnd["v"], rnd["step"] = adam.adam_step(
+            rnd["pred"], g_p, rnd["m"], rnd["v"], rnd["step"], rnd.get("lr", cfg.lr), cfg.beta1, cfg.beta2, cfg.adam_eps)
+        rnd["g"] = g_p
+    return actor, critic, terms, g_a, g_c, norm, rnd_loss
+
+
+def copy_state(actor, critic, opt, rnd):
+    """Deep copy of everything an optimiser step changes."""
+    return dict(actor=actor.copy(), critic=critic.copy(), opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()},
+                rnd=None if rnd is None else {k: (np.copy(v) if k in ("pred", "m", "v") else v) for k, v in rnd.items()})
+
+
+def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=None, record=False, sides=None):
     """E epochs x M minibatches over the flattened [T*N] rollout.
 
     actor/critic: flat parameter vectors.  opt: dict with m_a, v_a, m_c, v_c (flat
@@ -150,7 +205,9 @@ def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=N
     leading rows (flat index b = t*N + n).  rnd: optional dict with
     pred, targ (flat), dims, subset (column indices or None), m, v, step, lr.
     Returns dict(actor, critic, opt, stats[E*M, 8], g_actor, g_critic, rnd, perms); with record=True also
-    `trace`: per optimiser step the state before it, its gradients and the state after it.
+    `trace`: per optimiser step the state before it, its gradients, the state after it and the per-row ratio,
+    new value, clip predicates and advantages of its minibatch.
+    sides: optional {optimiser step index within this call: sides dict of minibatch_loss_and_grads}.
     """
     actor = np.asarray(actor, np.float64).copy(); critic = np.asarray(critic, np.float64).copy()
     opt = {k: (np.asarray(v, np.float64).copy() if k != "step" else int(v)) for k, v in opt.items()}
@@ -171,26 +228,14 @@ def ppo_update(actor, critic, dims_a, dims_c, rollout, cfg, opt, sym=None, rnd=N
         for m in range(cfg.minibatches):
             I = perm[m * mb:(m + 1) * mb]
             batch = {k: v[I] for k, v in flat.items()}
-            before = dict(actor=actor.copy(), critic=critic.copy(), opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()},
-                          rnd=None if rnd is None else {k: (np.copy(v) if k in ("pred", "m", "v") else v) for k, v in rnd.items()}) if record else None
-            terms, g_a, g_c = minibatch_loss_and_grads(actor, critic, dims_a, dims_c, batch, cfg, sym)
-            norm = adam.global_norm([g_a, g_c])
-            s = adam.clip_scale(norm, cfg.max_grad_norm)
-            t0 = opt["step"]
-            actor, opt["m_a"], opt["v_a"], _ = adam.adam_step(actor, s * g_a, opt["m_a"], opt["v_a"], t0, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
-            critic, opt["m_c"], opt["v_c"], opt["step"] = adam.adam_step(critic, s * g_c, opt["m_c"], opt["v_c"], t0, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
-            rnd_loss = 0.0
-            if rnd is not None:
-                x = np.asarray(batch["obs_a"], np.float64)
-                if rnd.get("subset") is not None:
-                    x = x[:, np.asarray(rnd["subset"])]
-                rnd_loss, g_p = rnd_predictor_loss_and_grad(rnd["pred"], rnd["targ"], rnd["dims"], x, cfg.elu_alpha)
-                rnd["pred"], rnd["m"], rnd["v"], rnd["step"] = adam.adam_step(
-                    rnd["pred"], g_p, rnd["m"], rnd["v"], rnd["step"], rnd.get("lr", cfg.lr), cfg.beta1, cfg.beta2, cfg.adam_eps)
-                rnd["g"] = g_p
+            before = copy_state(actor, critic, opt, rnd) if record else None
+            actor, critic, terms, g_a, g_c, norm, rnd_loss = optimiser_step(
+                actor, critic, dims_a, dims_c, batch, cfg, opt, sym, rnd, (sides or {}).get(e * cfg.minibatches + m), per_row=record)
             if record:
                 trace.append(dict(rows=I, before=before, g_actor=g_a, g_critic=g_c, actor=actor.copy(), critic=critic.copy(),
-                                  g_pred=None if rnd is None else rnd["g"], pred=None if rnd is None else rnd["pred"].copy()))
+                                  g_pred=None if rnd is None else rnd["g"], pred=None if rnd is None else rnd["pred"].copy(),
+                                  opt={k: (v.copy() if k != "step" else v) for k, v in opt.items()},
+                                  per_row={k: terms[k] for k in ("ratio", "V", "in_range", "v_in_range", "adv")}))
             stats.append([terms["surrogate"], terms["value_loss"], terms["entropy"], terms["kl"], norm,
                           terms["clip_frac"], terms["mirror_loss"], rnd_loss])
     return dict(actor=actor, critic=critic, opt=opt, stats=np.array(stats), g_actor=g_a, g_critic=g_c,

@@ -250,3 +250,65 @@ def test_value_clip_inside_range_has_plain_mse_gradient():
     t1, _, gc1 = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, b, ppo.PPOConfig(use_clipped_value_loss=False))
     np.testing.assert_allclose(gc0, gc1, rtol=1e-12, atol=1e-15)
     assert abs(t0["value_loss"] - t1["value_loss"]) < 1e-7
+
+
+def _kink_batch(adv_sign, offset):
+    """One row of a 6-row batch put at ratio = (1 + clip) * exp(offset) with an advantage of the given sign."""
+    actor, critic, b = _setup(seed=3, n=6, perturb=0.05)
+    cfg = ppo.PPOConfig(entropy_coef=0.0, value_coef=0.0)
+    t = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, b, cfg, per_row=True)[0]
+    b["logp"] = b["logp"].copy(); b["adv"] = b["adv"].copy()
+    b["logp"][2] += np.log(t["ratio"][2]) - np.log(1.0 + cfg.clip) - offset
+    b["adv"][2] = adv_sign * 1.5
+    return actor, critic, b, cfg
+
+
+def test_sides_equal_to_the_natural_predicates_change_nothing():
+    actor, critic, b = _setup(seed=2, n=10, perturb=0.3)
+    cfg = ppo.PPOConfig()
+    t0, ga0, gc0 = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, b, cfg, per_row=True)
+    assert 0 < t0["in_range"].sum() < 10                            # both kinds of rows present
+    sides = dict(policy={r: bool(t0["in_range"][r]) for r in range(10)}, value={r: bool(t0["v_in_range"][r]) for r in range(10)})
+    t1, ga1, gc1 = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, b, cfg, sides=sides)
+    assert np.array_equal(ga0, ga1) and np.array_equal(gc0, gc1) and t1["clip_frac"] == t0["clip_frac"]
+
+
+def test_policy_side_override_is_the_other_one_sided_derivative():
+    """Just outside the range with A > 0 the row's policy gradient is zero, just inside it is -A d(ratio); the
+    override turns one into the other without touching the loss terms (continuous at the kink)."""
+    h = 1e-9
+    a_out = _kink_batch(+1, +h); a_in = _kink_batch(+1, -h)
+    t_out, g_out, _ = ppo.minibatch_loss_and_grads(*a_out[:2], DIMS_A, DIMS_C, a_out[2], a_out[3], per_row=True)
+    t_in, g_in, _ = ppo.minibatch_loss_and_grads(*a_in[:2], DIMS_A, DIMS_C, a_in[2], a_in[3], per_row=True)
+    assert not t_out["in_range"][2] and t_in["in_range"][2]
+    assert np.linalg.norm(g_out - g_in) > 1e-3 * np.linalg.norm(g_in)          # the kink is visible in the gradient
+    t_ovr, g_ovr, _ = ppo.minibatch_loss_and_grads(*a_out[:2], DIMS_A, DIMS_C, a_out[2], a_out[3], sides=dict(policy={2: True}))
+    np.testing.assert_allclose(g_ovr, g_in, rtol=1e-6, atol=1e-12)
+    assert abs(t_ovr["surrogate"] - t_out["surrogate"]) < 1e-15 and abs(t_ovr["clip_frac"] - (t_out["clip_frac"] - 1 / 6)) < 1e-15
+    t_ovr, g_ovr, _ = ppo.minibatch_loss_and_grads(*a_in[:2], DIMS_A, DIMS_C, a_in[2], a_in[3], sides=dict(policy={2: False}))
+    np.testing.assert_allclose(g_ovr, g_out, rtol=1e-6, atol=1e-12)
+    # with A < 0 the unclipped branch is the larger one outside the range: no kink in the gradient, the override is inert
+    n_out = _kink_batch(-1, +h)
+    _, g_nat, _ = ppo.minibatch_loss_and_grads(*n_out[:2], DIMS_A, DIMS_C, n_out[2], n_out[3])
+    t2, g_ovr, _ = ppo.minibatch_loss_and_grads(*n_out[:2], DIMS_A, DIMS_C, n_out[2], n_out[3], sides=dict(policy={2: True}))
+    assert np.array_equal(g_nat, g_ovr)
+
+
+def test_value_side_override_is_the_other_one_sided_derivative():
+    actor, critic, b = _setup(seed=4, n=6, perturb=0.05)
+    cfg = ppo.PPOConfig(entropy_coef=0.0, value_coef=1.0)
+    t = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, b, cfg, per_row=True)[0]
+    h = 1e-9
+    grads = {}
+    for name, off in (("out", +h), ("in", -h)):
+        bb = dict(b); bb["values"] = b["values"].copy(); bb["returns"] = b["returns"].copy()
+        bb["values"][1] = t["V"][1] - (cfg.clip + off)            # V - V_old = clip + off
+        bb["returns"][1] = t["V"][1] + 1.0                         # R above V: outside the range the clipped square is the larger
+        tt, _, gc = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, bb, cfg, per_row=True)
+        grads[name] = (bb, tt, gc)
+    assert not grads["out"][1]["v_in_range"][1] and grads["in"][1]["v_in_range"][1]
+    assert np.linalg.norm(grads["out"][2] - grads["in"][2]) > 1e-3 * np.linalg.norm(grads["in"][2])
+    _, _, g_ovr = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, grads["out"][0], cfg, sides=dict(value={1: True}))
+    np.testing.assert_allclose(g_ovr, grads["in"][2], rtol=1e-6, atol=1e-12)
+    _, _, g_ovr = ppo.minibatch_loss_and_grads(actor, critic, DIMS_A, DIMS_C, grads["in"][0], cfg, sides=dict(value={1: False}))
+    np.testing.assert_allclose(g_ovr, grads["out"][2], rtol=1e-6, atol=1e-12)
