@@ -23,6 +23,21 @@ def rel_l2(x, ref):
     return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-30))
 
 
+def assert_elementwise(name, got, ref, rtol=1e-4, atol_frac=1e-5):
+    """|got - ref| <= rtol |ref| + atol_frac max|ref| for every element (the absolute part covers entries that are
+    sums of cancelling terms, whose fp32 error is relative to the terms)."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    err = np.abs(got - ref)
+    bound = rtol * np.abs(ref) + atol_frac * np.abs(ref).max() + 1e-30
+    if np.any(err > bound):
+        i = np.unravel_index(int(np.argmax(err / bound)), err.shape)
+        raise AssertionError("%s%s: got %.9g ref %.9g (err %.3g, bound %.3g; %d of %d elements out)" % (
+            name, list(i), got[i], ref[i], err[i], bound[i], int((err > bound).sum()), err.size))
+
+
 def oracle_rollout(w, inp, seed=7, normalize=True):
     """Roll the oracle's act() over the T observation slabs; GAE by the oracle.  All outputs float32
     (what both implementations are then fed), flattened to B = T*N rows."""

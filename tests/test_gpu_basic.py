@@ -6,7 +6,7 @@ import torch
 
 from oracle import rng as orng, gae as ogae, adam as oadam, ppo as oppo, symmetry as osym, rnd as ornd, mlp as omlp
 from workloads import WORKLOADS, make_inputs, random_involution
-from gpu_util import dev, host, rel_l2, f32
+from gpu_util import dev, host, rel_l2, f32, assert_elementwise
 
 pytestmark = pytest.mark.gpu
 
@@ -197,6 +197,7 @@ def test_rnd_reward(rx, N, subset):
         torch.cuda.synchronize()
         ri_ref, raw_ref, run_ref = ornd.intrinsic_reward(inp["rnd_predictor"], inp["rnd_target"], dims, obs, run_ref, sub)
         assert rel_l2(host(r_int), ri_ref) < 1e-4
+        assert_elementwise("r_int[%d]" % t, host(r_int), ri_ref)
         np.testing.assert_allclose(host(d_rew), rew + 0.5 * ri_ref, rtol=1e-4, atol=1e-5)
         np.testing.assert_allclose(host(running), np.array(run_ref), rtol=1e-4)
     # frozen statistics
@@ -206,3 +207,4 @@ def test_rnd_reward(rx, N, subset):
     assert np.array_equal(host(running), before)
     ri_ref, _, _ = ornd.intrinsic_reward(inp["rnd_predictor"], inp["rnd_target"], dims, inp["obs"][3], run_ref, sub, update_stats=False)
     assert rel_l2(host(r_int), ri_ref) < 1e-4
+    assert_elementwise("r_int (frozen statistics)", host(r_int), ri_ref)

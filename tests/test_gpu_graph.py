@@ -16,7 +16,7 @@ import torch
 
 from oracle import ppo as oppo, rng as orng
 from workloads import WORKLOADS, make_inputs
-from gpu_util import dev, host, rel_l2
+from gpu_util import dev, host, rel_l2, assert_elementwise
 from test_gpu_update import Case, _nets, _check_stats, TOL
 
 pytestmark = pytest.mark.gpu
@@ -49,7 +49,9 @@ def test_act_dc_matches_oracle_at_the_counter_position(rx):
                        orng.act_noise(SEED, 41 + k, N, A))
         for name in ("actions", "mu", "sigma"):
             assert rel_l2(host(out[name]), ref[name]) <= 1e-5, (k, name)
+            assert_elementwise(name, host(out[name]), ref[name])
         assert rel_l2(host(logp), ref["logp"]) <= 1e-5 and rel_l2(host(values), ref["values"]) <= 1e-5
+        assert_elementwise("logp", host(logp), ref["logp"]); assert_elementwise("values", host(values), ref["values"])
     # the value bootstrap draws no noise and leaves the position where it is
     rx.rslx_act_dc(None, critic, None, obs[3], N, SEED, ctr, None, None, None, values, None, None, rx.ACT_VALUES_ONLY, ws)
     assert host(ctr).tolist() == [44, 0, 0, 0]

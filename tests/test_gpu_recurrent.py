@@ -10,8 +10,8 @@ import torch
 
 from oracle import recurrent as orec, gae as ogae, rng as orng, ppo as oppo, gru as ogru
 from workloads import WORKLOADS, make_inputs
-from gpu_util import dev, host, rel_l2, f32
-from test_gpu_update import _check_stats, _check_vec, TOL
+from gpu_util import dev, host, rel_l2, f32, assert_elementwise
+from test_gpu_update import _check_stats, _check_vec, _layer_slices, TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -112,8 +112,12 @@ def test_act_recurrent_matches_oracle(rx, N, cell):
         torch.cuda.synchronize()
         for k in ("actions", "mu", "sigma"):
             assert rel_l2(host(out[k]), ref[k][t]) <= 2e-5, (t, k)
+            assert_elementwise("%s[%d]" % (k, t), host(out[k]), ref[k][t])
         assert rel_l2(host(logp), ref["logp"][t]) <= 2e-5 and rel_l2(host(values), ref["values"][t]) <= 2e-5
         assert rel_l2(host(h_a), ref["h_a"][t]) <= 2e-5 and rel_l2(host(h_c), ref["h_c"][t]) <= 2e-5
+        for nm, got_t, ref_t in (("logp", logp, ref["logp"][t]), ("values", values, ref["values"][t]), ("h_a", h_a, ref["h_a"][t]),
+                                 ("h_c", h_c, ref["h_c"][t])):
+            assert_elementwise("%s[%d]" % (nm, t), host(got_t), ref_t)
     assert rel_l2(host(h0_a), ref["h0_a"]) <= 1e-6 and rel_l2(host(h0_c), ref["h0_c"]) <= 1e-6
     # the bootstrap value leaves both states untouched
     before = (h_a.clone(), h_c.clone())
@@ -180,7 +184,7 @@ def _layer_names(w, which):
     return _cell(w)[0].n_params(w.Da if which == "actor" else w.Dc, w.memory_hidden)
 
 
-def _check_net(name, w, which, got, ref, tol):
+def _check_net(name, w, which, got, ref, tol, elementwise=False):
     k = _layer_names(w, which)
     D, H = (w.Da if which == "actor" else w.Dc), w.memory_hidden
     o = 0
@@ -189,9 +193,14 @@ def _check_net(name, w, which, got, ref, tol):
         r = np.asarray(ref[o:o + n], np.float64)
         err = np.linalg.norm(np.asarray(got[o:o + n], np.float64) - r)
         assert err <= tol * np.linalg.norm(r) + 1e-12, (name, nm, err, np.linalg.norm(r))
+        if elementwise:
+            assert_elementwise("%s %s" % (name, nm), got[o:o + n], r, tol)
         o += n
     dims = w.dims_actor if which == "actor" else w.dims_critic
     _check_vec(name, dims, which == "actor", got[k:], ref[k:], tol)
+    if elementwise:
+        for nm, sl in _layer_slices(dims, which == "actor"):
+            assert_elementwise("%s %s" % (name, nm), got[k:][sl], np.asarray(ref[k:][sl], np.float64), tol)
 
 
 def check_forced_steps(rx, case, steps=None, floor=1e-3):
@@ -204,8 +213,8 @@ def check_forced_steps(rx, case, steps=None, floor=1e-3):
         stats, step = _call(rx, nets, case.gpu_rollout(rx, tr["envs"]), case.gpu_cfg(rx, 1, 1), 1, b["opt"]["step"])
         assert step == b["opt"]["step"] + 1
         _check_stats(stats[0], ref["stats"][k], TOL, floor=floor)
-        _check_net("g_actor step %d" % k, w, "actor", _grads(nets[0], nets[1]), tr["g_actor"], TOL)
-        _check_net("g_critic step %d" % k, w, "critic", _grads(nets[2], nets[3]), tr["g_critic"], TOL)
+        _check_net("g_actor step %d" % k, w, "actor", _grads(nets[0], nets[1]), tr["g_actor"], TOL, elementwise=True)
+        _check_net("g_critic step %d" % k, w, "critic", _grads(nets[2], nets[3]), tr["g_critic"], TOL, elementwise=True)
         _check_net("actor step %d" % k, w, "actor", _params(nets[0], nets[1]), tr["actor"], TOL)
         _check_net("critic step %d" % k, w, "critic", _params(nets[2], nets[3]), tr["critic"], TOL)
 

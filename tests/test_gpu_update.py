@@ -2,19 +2,27 @@
 
 Two kinds of comparison:
   * step-forced: every optimiser step of the oracle's trajectory is replayed on the GPU from the oracle's own
-    state before that step (parameters, Adam moments, step count) on exactly that minibatch's rows; loss terms,
-    gradients and post-step parameters must agree to relative 1e-4.
-  * free-running: one whole multi-step call; the first step and the final parameters must agree to 1e-4, later
-    loss terms to a looser bound, because Adam's early steps (update ~ lr * sign(g)) turn rounding-level
-    differences of near-zero gradient entries into full-size steps that no fp32 implementation can track.
+    state before that step (parameters, Adam moments, step count, rounded to fp32) on exactly that minibatch's rows,
+    and compared with the oracle's step from that same rounded state: loss terms to relative 1e-4; gradients and
+    Adam moments element by element (|x - ref| <= 1e-4 |ref| + 1e-5 max|ref| per tensor) and per tensor in relative
+    L2 (1e-4); the applied step of every network element by element (1e-3 of the step, widened only where Adam's
+    formula itself is ill-conditioned in the gradient) and post-step parameters to 1e-4.
+  * free-running: one whole multi-step call; the first step's loss terms, the final parameters (1e-4) and the last
+    gradient (1e-3) must agree, later loss terms to a looser bound.
+
+The clipped surrogate and the clipped value loss have kinks; a row that sits on one to within fp32 rounding may take
+either one-sided derivative.  Such rows are listed from the oracle's own per-row ratios, and the oracle is re-run
+with the side the GPU took (tests/test_oracle_kink.py shows on the CPU that one such row moves the parameters of
+the largest workload by more than the tolerance, so this cannot be absorbed by a bound).
 """
 import ctypes as C
+import itertools
 from dataclasses import replace
 import numpy as np
 import pytest
 import torch
 
-from oracle import ppo as oppo, bc as obc
+from oracle import ppo as oppo, bc as obc, adam as oadam
 from workloads import WORKLOADS, make_inputs, xavier_mlp
 from gpu_util import dev, host, rel_l2, oracle_rollout, flat_rollout, oracle_cfg, f32
 
@@ -84,8 +92,15 @@ class Case:
             npred = inp["rnd_predictor"].size
             ornd = dict(pred=inp["rnd_predictor"], targ=inp["rnd_target"], dims=self.rnd_dims, subset=self.rnd_sub,
                         m=np.zeros(npred), v=np.zeros(npred), step=0, lr=f32(w.lr))
+        self._start = (opt0, ornd)
         self.ref = oppo.ppo_update(self.actor0, self.critic0, w.dims_actor, w.dims_critic, self.flat, self.ocfg, opt0,
                                    self.osym, ornd, record=True)
+
+    def rerun(self, sides, record=False):
+        """The oracle's trajectory with the given {step: sides} overrides at kink rows."""
+        opt0, ornd = self._start
+        return oppo.ppo_update(self.actor0, self.critic0, self.w.dims_actor, self.w.dims_critic, self.flat, self.ocfg, opt0,
+                               self.osym, ornd, record=record, sides=sides)
 
     def gpu_sym(self, rx):
         i = self.inp
@@ -135,8 +150,159 @@ def _call(rx, case, a, c, rnd, rollout, cfg, n_rows, step0):
     return host(stats), step.value
 
 
+# Element-wise bound of a gradient or an Adam moment: |x - ref| <= RTOL |ref| + ATOL_FRAC max|ref| over the tensor
+# (layer weight, layer bias, log-std).  The absolute part covers entries that are sums of cancelling terms: fp32
+# accumulation over tens of thousands of rows leaves an error relative to the terms, not to their sum (measured:
+# at most 1.6e-6 of the tensor's maximum on the workloads of this file).
+RTOL, ATOL_FRAC = 1e-4, 1e-5
+# A row counts as sitting on a kink of the clipped losses when its ratio (value change) is within this relative
+# distance of the clip boundary: fp32 log-densities of magnitude ~20 carry an absolute error of a few 1e-6.
+KINK_MARGIN = 2e-5
+STEP_RTOL = 1e-3
+
+
+def f32_state(x):
+    """An oracle array as the fp32 values the GPU is handed, back in fp64."""
+    return np.asarray(np.asarray(x, np.float32), np.float64)
+
+
+def _elem_violations(name, dims, log_std, got, ref, rtol=RTOL, atol_frac=ATOL_FRAC):
+    out = []
+    for nm, sl in _layer_slices(dims, log_std):
+        g, r = np.asarray(got[sl], np.float64), np.asarray(ref[sl], np.float64)
+        err = np.abs(g - r)
+        bound = rtol * np.abs(r) + atol_frac * np.abs(r).max() + 1e-30
+        if np.any(err > bound):
+            i = int(np.argmax(err / bound))
+            out.append("%s.%s[%d]: got %.9g ref %.9g (err %.3g, bound %.3g, %d of %d entries out)" % (
+                name, nm, i, g[i], r[i], err[i], bound[i], int((err > bound).sum()), err.size))
+        l2 = np.linalg.norm(g - r)
+        if l2 > rtol * np.linalg.norm(r) + 1e-12:
+            out.append("%s.%s: relative L2 error %.3g" % (name, nm, l2 / max(np.linalg.norm(r), 1e-300)))
+    return out
+
+
+def _grad_tolerance(dims, log_std, ref):
+    tol = np.empty(ref.size)
+    for nm, sl in _layer_slices(dims, log_std):
+        tol[sl] = RTOL * np.abs(ref[sl]) + ATOL_FRAC * np.abs(ref[sl]).max()
+    return tol
+
+
+def _step_violations(name, dims, log_std, theta0, got_theta, ref_theta, g_ref, scale, m0, v0, t0, cfg):
+    """The applied step theta_after - theta_before, element by element.  Adam's step is lr m^/(sqrt(v^) + eps): for
+    an entry whose gradient is small against its tolerance this is ill-conditioned (on the first step it is
+    lr sign(g)), so the bound of an entry is STEP_RTOL of the reference step plus what the oracle's own Adam
+    formula makes of a gradient moved by the gradient tolerance, plus the fp32 rounding of the parameter."""
+    d_got = np.asarray(got_theta, np.float64) - theta0
+    d_ref = ref_theta - theta0
+    gtol = scale * _grad_tolerance(dims, log_std, g_ref)
+    zero = np.zeros_like(theta0)
+    upd = lambda g: oadam.adam_step(zero, g, m0, v0, t0, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)[0]
+    u0 = upd(scale * g_ref)
+    swing = np.maximum(np.abs(upd(scale * g_ref + gtol) - u0), np.abs(upd(scale * g_ref - gtol) - u0))
+    bound = STEP_RTOL * np.abs(d_ref) + 2.0 * swing + 4 * np.finfo(np.float32).eps * np.abs(theta0) + 1e-30
+    err = np.abs(d_got - d_ref)
+    out = []
+    if np.any(err > bound):
+        i = int(np.argmax(err / bound))
+        out.append("step(%s)[%d]: got %.6g ref %.6g (err %.3g, bound %.3g, %d entries out)" % (
+            name, i, d_got[i], d_ref[i], err[i], bound[i], int((err > bound).sum())))
+    well = swing <= STEP_RTOL * np.abs(d_ref)           # entries whose step is well conditioned
+    l2 = np.linalg.norm((d_got - d_ref)[well]) / max(np.linalg.norm(d_ref[well]), 1e-300)
+    if l2 > STEP_RTOL:
+        out.append("step(%s): relative L2 error %.3g over the %d well-conditioned entries" % (name, l2, int(well.sum())))
+    return out
+
+
+def kink_rows(case, tr):
+    """Rows of one recorded step whose gradient has a kink within KINK_MARGIN (policy: ratio at the clip boundary
+    on the side where the clipped term takes over; value: value change at the clip boundary with the return on the
+    far side), and the number of rows near any clip boundary (these move the clip-fraction count)."""
+    pr, clip = tr["per_row"], case.ocfg.clip
+    ratio, adv = pr["ratio"], pr["adv"]
+    up, lo = np.abs(ratio - (1 + clip)) <= KINK_MARGIN * (1 + clip), np.abs(ratio - (1 - clip)) <= KINK_MARGIN * (1 - clip)
+    pol = np.nonzero((up & (adv > 0)) | (lo & (adv < 0)))[0]
+    n = ratio.shape[0]
+    rows = tr["rows"]
+    f = case.flat
+    v_old, ret = f["values"][rows].astype(np.float64), f["returns"][rows].astype(np.float64)
+    if n == 2 * rows.shape[0]:
+        v_old, ret = np.concatenate([v_old, v_old]), np.concatenate([ret, ret])
+    dv = pr["V"] - v_old
+    val = np.nonzero((np.abs(np.abs(dv) - clip) <= KINK_MARGIN) & ((pr["V"] - ret) * dv < 0))[0]
+    return pol, val, int((up | lo).sum())
+
+
+def _side_candidates(tr, pol, val):
+    """No override first, then every single kink row taken on its other side, then pairs."""
+    flips = [("policy", int(r), not bool(tr["per_row"]["in_range"][r])) for r in pol] + \
+            [("value", int(r), not bool(tr["per_row"]["v_in_range"][r])) for r in val]
+    yield None
+    for n in (1, 2):
+        for combo in itertools.combinations(flips, n):
+            sides = dict(policy={}, value={})
+            for kind, r, side in combo:
+                sides[kind][r] = side
+            yield sides
+
+
+def oracle_step_from_fp32(case, tr, sides=None):
+    """The oracle's optimiser step of one recorded minibatch, started from the fp32-rounded state the GPU is given."""
+    w, b = case.w, tr["before"]
+    actor, critic = f32_state(b["actor"]), f32_state(b["critic"])
+    opt = {k: (f32_state(v) if k != "step" else v) for k, v in b["opt"].items()}
+    rnd = None
+    if case.rnd_on:
+        rnd = dict(b["rnd"])
+        for k in ("pred", "m", "v"):
+            rnd[k] = f32_state(rnd[k])
+    batch = {k: v[tr["rows"]] for k, v in case.flat.items()}
+    start = dict(actor=actor, critic=critic, opt=dict(opt), rnd=None if rnd is None else dict(rnd))
+    a1, c1, terms, g_a, g_c, norm, rnd_loss = oppo.optimiser_step(actor, critic, w.dims_actor, w.dims_critic, batch, case.ocfg,
+                                                                  opt, case.osym, rnd, sides)
+    stats = np.array([terms["surrogate"], terms["value_loss"], terms["entropy"], terms["kl"], norm, terms["clip_frac"],
+                      terms["mirror_loss"], rnd_loss])
+    return dict(start=start, actor=a1, critic=c1, opt=opt, rnd=rnd, g_actor=g_a, g_critic=g_c, norm=norm, stats=stats)
+
+
+def _forced_step_violations(case, gpu, one, n_near):
+    w, cfg, st = case.w, case.ocfg, one["start"]
+    out = []
+    n_rows = one["n_rows"]
+    for col in range(8):
+        tol = RTOL * max(abs(one["stats"][col]), 1e-3) + (n_near / n_rows if col == 5 else 0.0)
+        if abs(gpu["stats"][col] - one["stats"][col]) > tol:
+            out.append("stats[%d]: got %.9g ref %.9g" % (col, gpu["stats"][col], one["stats"][col]))
+    scale = oadam.clip_scale(one["norm"], cfg.max_grad_norm)
+    for nm, dims, ls, key in (("actor", w.dims_actor, True, "a"), ("critic", w.dims_critic, False, "c")):
+        g_ref = one["g_" + nm]
+        out += _elem_violations("g_" + nm, dims, ls, gpu["g_" + nm], g_ref)
+        out += _elem_violations("m_" + nm, dims, ls, gpu["m_" + nm], one["opt"]["m_" + key])
+        out += _elem_violations("v_" + nm, dims, ls, gpu["v_" + nm], one["opt"]["v_" + key])
+        out += _step_violations(nm, dims, ls, st[nm], gpu[nm], one[nm], g_ref, scale, st["opt"]["m_" + key], st["opt"]["v_" + key],
+                                st["opt"]["step"], cfg)
+        if rel_l2(gpu[nm], one[nm]) > RTOL:
+            out.append("params(%s): relative L2 error %.3g" % (nm, rel_l2(gpu[nm], one[nm])))
+    if case.rnd_on:
+        r0, r1 = st["rnd"], one["rnd"]
+        out += _elem_violations("g_pred", case.rnd_dims, False, gpu["g_pred"], r1["g"])
+        out += _elem_violations("m_pred", case.rnd_dims, False, gpu["m_pred"], r1["m"])
+        out += _elem_violations("v_pred", case.rnd_dims, False, gpu["v_pred"], r1["v"])
+        rcfg = replace(cfg, lr=r0.get("lr", cfg.lr))
+        out += _step_violations("pred", case.rnd_dims, False, r0["pred"], gpu["pred"], r1["pred"], r1["g"], 1.0, r0["m"], r0["v"],
+                                r0["step"], rcfg)
+    return out
+
+
 def check_forced_steps(rx, case, steps=None):
-    w, ref = case.w, case.ref
+    """Every recorded optimiser step replayed on the GPU from the oracle's (fp32-rounded) state before it and
+    compared element by element with the oracle's step from that same state: loss terms, gradients, Adam moments
+    and the applied step of every network.  Where rows of the minibatch sit on a kink of the clipped losses, the
+    GPU may take either one-sided derivative for them; the comparison then runs against the oracle with those
+    rows' side chosen accordingly (at most two rows differ).  Returns {step: sides} for the steps where that was
+    needed, so that a free-running comparison can follow the same branch."""
+    w, ref, found = case.w, case.ref, {}
     for k, tr in enumerate(ref["trace"]):
         if steps is not None and k not in steps:
             continue
@@ -144,54 +310,121 @@ def check_forced_steps(rx, case, steps=None):
         a, c, rnd = _nets(rx, case, b["actor"], b["critic"], b["opt"], b["rnd"])
         stats, step = _call(rx, case, a, c, rnd, case.gpu_rollout(rx, tr["rows"]), case.gpu_cfg(rx, 1, 1), 1, b["opt"]["step"])
         assert step == b["opt"]["step"] + 1
-        _check_stats(stats[0], ref["stats"][k], TOL)
-        _check_vec("g_actor", w.dims_actor, True, host(a.grads), tr["g_actor"], TOL)
-        _check_vec("g_critic", w.dims_critic, False, host(c.grads), tr["g_critic"], TOL)
-        assert rel_l2(host(a.params), tr["actor"]) <= TOL and rel_l2(host(c.params), tr["critic"]) <= TOL
-        # the applied step itself; float32 copies of the oracle's state bound this from below
-        d_got = host(a.params).astype(np.float64) - np.float32(b["actor"])
-        assert rel_l2(d_got, tr["actor"] - b["actor"]) <= 5e-2
+        gpu = dict(stats=stats[0], actor=host(a.params), critic=host(c.params), g_actor=host(a.grads), g_critic=host(c.grads),
+                   m_actor=host(a.adam_m), v_actor=host(a.adam_v), m_critic=host(c.adam_m), v_critic=host(c.adam_v))
         if case.rnd_on:
-            _check_vec("g_pred", case.rnd_dims, False, host(rnd.predictor.grads), tr["g_pred"], TOL)
-            assert rel_l2(host(rnd.predictor.params), tr["pred"]) <= TOL
             assert rnd.step.value == b["rnd"]["step"] + 1
+            gpu.update(pred=host(rnd.predictor.params), g_pred=host(rnd.predictor.grads), m_pred=host(rnd.predictor.adam_m),
+                       v_pred=host(rnd.predictor.adam_v))
+        pol, val, n_near = kink_rows(case, tr)
+        first = None
+        for tries, sides in enumerate(_side_candidates(tr, pol, val)):
+            one = oracle_step_from_fp32(case, tr, sides)
+            one["n_rows"] = tr["per_row"]["ratio"].shape[0]
+            bad = _forced_step_violations(case, gpu, one, n_near)
+            if not bad:
+                if sides is not None:
+                    found[k] = sides
+                break
+            first = first or bad
+            assert tries < 40, ("step %d" % k, first)
+        else:
+            raise AssertionError(("step %d: no choice of sides for the %d + %d kink rows matches" % (k, len(pol), len(val)), first))
+    return found
 
 
-def check_free_running(rx, case, later_tol=2e-2, param_tol=None, grad_tol=5e-2):
-    w, ref = case.w, case.ref
+def _free_running_violations(case, ref, a, c, rnd, stats, later_tol, param_tol, grad_tol):
+    bad = []
+    try:
+        _check_stats(stats[0], ref["stats"][0], TOL)
+        _check_stats(stats, ref["stats"], later_tol, floor=1e-2)
+    except AssertionError as e:
+        bad.append("stats %s" % (e,))
+    worst = 0.0
+    for nm, net in (("actor", a), ("critic", c)):
+        err = rel_l2(host(net.params), ref[nm])
+        worst = max(worst, err)
+        if err > param_tol:
+            bad.append("params(%s) %.3g" % (nm, err))
+        if rel_l2(host(net.grads), ref["g_" + nm]) > grad_tol:
+            bad.append("last grads(%s) %.3g" % (nm, rel_l2(host(net.grads), ref["g_" + nm])))
+    if case.rnd_on:
+        if rel_l2(host(rnd.predictor.params), ref["rnd"]["pred"]) > TOL or rnd.step.value != ref["rnd"]["step"]:
+            bad.append("predictor")
+    return bad, worst
+
+
+def _nearest_kinks(case, ref, limit):
+    """The gradient-relevant kink rows of a recorded trajectory, nearest first: (distance, step, kind, row, other side)."""
+    clip, out = case.ocfg.clip, []
+    for k, tr in enumerate(ref["trace"][:-1]):                # a flip in the last step only shows in the last gradient
+        pol, val, _ = kink_rows(case, tr)
+        pr = tr["per_row"]
+        for r in pol:
+            d = min(abs(pr["ratio"][r] - (1 + clip)), abs(pr["ratio"][r] - (1 - clip)))
+            out.append((float(d), k, "policy", int(r), not bool(pr["in_range"][r])))
+        for r in val:
+            out.append((KINK_MARGIN, k, "value", int(r), not bool(pr["v_in_range"][r])))
+    return sorted(out)[:limit]
+
+
+def check_free_running(rx, case, found=None, later_tol=2e-2, param_tol=None, grad_tol=1e-3):
+    """One whole multi-step call against the oracle's trajectory: first step's loss terms and the final parameters
+    to 1e-4, the last gradient to 1e-3.  If that fails and the oracle's trajectory has rows on a kink of the clipped
+    losses, the oracle is re-run with the nearest such rows (one at a time, at most two together) taken on their
+    other side, and the GPU must agree with one of these trajectories to the same bounds.  `found` (what the
+    step-forced comparison identified) is tried first."""
+    w = case.w
     a, c, rnd = _nets(rx, case, case.actor0, case.critic0)
     n = case.epochs * w.minibatches
     stats, step = _call(rx, case, a, c, rnd, case.gpu_rollout(rx), case.gpu_cfg(rx, case.epochs, w.minibatches), n, 0)
-    assert step == n == ref["opt"]["step"]
-    _check_stats(stats[0], ref["stats"][0], TOL)
-    _check_stats(stats, ref["stats"], later_tol, floor=1e-2)
+    assert step == n == case.ref["opt"]["step"]
     param_tol = TOL * max(1, case.epochs) if param_tol is None else param_tol
-    assert rel_l2(host(a.params), ref["actor"]) <= param_tol
-    assert rel_l2(host(c.params), ref["critic"]) <= param_tol
-    assert rel_l2(host(a.grads), ref["g_actor"]) <= grad_tol and rel_l2(host(c.grads), ref["g_critic"]) <= grad_tol
-    if case.rnd_on:
-        assert rel_l2(host(rnd.predictor.params), ref["rnd"]["pred"]) <= TOL and rnd.step.value == ref["rnd"]["step"]
-    return a, c, stats
+    args = (a, c, rnd, stats, later_tol, param_tol, grad_tol)
+    bad, worst = _free_running_violations(case, case.ref, *args)
+    if not bad:
+        return a, c, stats
+    log = [("oracle trajectory", bad)]
+    if found:
+        bad, _ = _free_running_violations(case, case.rerun(found), *args)
+        if not bad:
+            return a, c, stats
+        log.append((found, bad))
+    base, base_sides = case.ref, {}
+    for depth in range(2):
+        best = None
+        for d, k, kind, r, side in _nearest_kinks(case, base, 5):
+            sides = {kk: dict(policy=dict(v["policy"]), value=dict(v["value"])) for kk, v in base_sides.items()}
+            sides.setdefault(k, dict(policy={}, value={}))[kind][r] = side
+            ref = case.rerun(sides, record=True)
+            bad, err = _free_running_violations(case, ref, *args)
+            print("free-running: step %d %s row %d (distance %.2e) on its other side: parameter error %.2e" % (k, kind, r, d, err))
+            if not bad:
+                return a, c, stats
+            log.append((sides, bad))
+            if best is None or err < best[0]:
+                best = (err, ref, sides)
+        if best is None or best[0] > 0.5 * worst:
+            break
+        worst, base, base_sides = best
+    raise AssertionError(log)
 
 
 def test_ppo_tiny(rx):
     case = Case(WORKLOADS["tiny"], 1)
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def test_ppo_tiny_off_policy_start(rx):
     case = Case(WORKLOADS["tiny"], 1, perturb=0.3)
     assert case.ref["stats"][0, 5] > 0.02          # clip fraction: the clipped branches are exercised from step one
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def test_ppo_odd_hidden_width_takes_the_unfused_loss_path(rx):
     """A last hidden width outside {32, 64, 128, 256} uses the per-layer output GEMMs and the stand-alone loss kernel."""
     case = Case(replace(WORKLOADS["tiny"], N=50, hidden=(64, 96)), 1, perturb=0.2)
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 @pytest.mark.parametrize("base,N,A,hidden,sym_on", [
@@ -206,49 +439,82 @@ def test_ppo_fused_head_widths(rx, base, N, A, hidden, sym_on):
     mirrored rows, must agree with the oracle like the default one."""
     w = replace(WORKLOADS[base].scaled(N), A=A, hidden=hidden)
     case = Case(w, 1, sym_on=sym_on, perturb=0.2)
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def test_ppo_flat_ragged(rx):
     case = Case(WORKLOADS["flat"].scaled(250), 1)     # mb = 1500 rows: 11 full 128-row tiles and a 92-row tail
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def test_ppo_rough_symmetry(rx):
     case = Case(WORKLOADS["rough"].scaled(125), 1, sym_on=True)
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def test_ppo_curiosity_rnd(rx):
     case = Case(replace(WORKLOADS["curiosity"].scaled(336), minibatches=8), 1, rnd_on=True)
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def test_ppo_curiosity_rnd_state_subset(rx):
     """The RND networks read 20 of the 48 observation columns (strict subset): the column map rides in the first
     layer's operand loads of the forward and of the weight-gradient contraction."""
     case = Case(replace(WORKLOADS["curiosity"].scaled(168), minibatches=4), 1, rnd_on=True, rnd_subset=20)
-    check_forced_steps(rx, case)
-    check_free_running(rx, case, param_tol=1e-3, grad_tol=0.25)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
-def test_ppo_five_epoch_drift_is_bounded(rx):
+def _five_epoch_drift(rx, case):
+    """Five epochs free-running on the GPU, one call per epoch (epoch_offset carries the permutation stream, the
+    parameters, moments and step count stay on the device), against the oracle's recorded trajectory: per epoch the
+    relative parameter error of both networks and the differences of the last minibatch's loss terms."""
+    w, ref = case.w, case.ref
+    M = w.minibatches
+    a, c, rnd = _nets(rx, case, case.actor0, case.critic0)
+    ro, step, table = case.gpu_rollout(rx), 0, []
+    for e in range(case.epochs):
+        stats, step = _call(rx, case, a, c, rnd, ro, case.gpu_cfg(rx, 1, M, epoch_offset=e), M, step)
+        tr = ref["trace"][(e + 1) * M - 1]
+        rs = ref["stats"][(e + 1) * M - 1]
+        table.append((e + 1, rel_l2(host(a.params), tr["actor"]), rel_l2(host(c.params), tr["critic"]),
+                      abs(stats[M - 1, 0] - rs[0]), abs(stats[M - 1, 1] - rs[1]) / abs(rs[1])))
+    return table
+
+
+def _report_drift(name, table, record_property):
+    print("\nfive-epoch drift, %s: epoch | actor rel. err | critic rel. err | |d surrogate| | rel. d value loss" % name)
+    for row in table:
+        print("  %d | %.2e | %.2e | %.2e | %.2e" % row)
+        record_property("%s_epoch_%d" % (name, row[0]), "%.3e %.3e %.3e %.3e" % row[1:])
+
+
+def test_ppo_five_epoch_drift_is_bounded(rx, record_property):
+    """Bounded drift over five epochs (20 optimiser steps) on the small workload: Adam carries every rounding-level
+    difference of an early step forward, and rows on a kink of the clipped losses may take the other one-sided
+    derivative, so the free-running bound is looser than the step-forced one; it must stay bounded."""
     case = Case(WORKLOADS["tiny"], 5)
-    a, c, stats = check_free_running(rx, case, later_tol=5e-2)
-    ref = case.ref
-    drift = [abs(stats[4 * e + 3, 0] - ref["stats"][4 * e + 3, 0]) for e in range(5)]
-    print("surrogate drift per epoch:", drift, "param rel err:", rel_l2(host(a.params), ref["actor"]))
-    assert rel_l2(host(a.params), ref["actor"]) <= 1e-2 and rel_l2(host(c.params), ref["critic"]) <= 1e-2
+    table = _five_epoch_drift(rx, case)
+    _report_drift("tiny", table, record_property)
+    for e, da, dc, ds, dv in table:
+        assert da <= 1e-3 and dc <= 1e-3 and ds <= 1e-3 and dv <= 1e-3, table
+
+
+def test_ppo_five_epoch_drift_at_4096_envs(rx, record_property):
+    """The same at the size the throughput is quoted on (flat workload, N = 4096, 24 576 rows per minibatch).  Here
+    the oracle's trajectory is not re-run along the kink rows the GPU took (measured: 1e-6 for two epochs, then
+    single rows on a kink of the clipped surrogate move the later epochs to ~1e-3); the bound states what a user
+    of the free-running update can rely on."""
+    case = Case(WORKLOADS["flat"], 5)
+    table = _five_epoch_drift(rx, case)
+    _report_drift("flat", table, record_property)
+    for e, da, dc, ds, dv in table:
+        assert da <= 5e-3 and dc <= 5e-3 and ds <= 5e-3 and dv <= 5e-3, table
 
 
 def test_ppo_resume_with_epoch_offset(rx):
     case = Case(WORKLOADS["tiny"], 2)
     w = case.w
-    full_a, full_c, _ = check_free_running(rx, case, later_tol=5e-2)
+    full_a, full_c, _ = check_free_running(rx, case, later_tol=5e-2, grad_tol=5e-2)
     a, c, _ = _nets(rx, case, case.actor0, case.critic0)
     ro = case.gpu_rollout(rx)
     _, step = _call(rx, case, a, c, None, ro, case.gpu_cfg(rx, 1, w.minibatches), w.minibatches, 0)
@@ -259,15 +525,10 @@ def test_ppo_resume_with_epoch_offset(rx):
 
 @pytest.mark.parametrize("name,kw", [("flat", {}), ("rough", {"sym_on": True}), ("curiosity", {"rnd_on": True})])
 def test_ppo_full_size(rx, name, kw):
+    """The three PPO workloads at full size, one epoch: every optimiser step forced and compared element by
+    element, then the whole epoch free-running to 1e-4 on the parameters."""
     case = Case(WORKLOADS[name], 1, **kw)
-    check_forced_steps(rx, case, steps={0, case.w.minibatches - 1})
-    # With 49 152 rows per minibatch and 8 steps, one sample whose ratio lies within fp32 rounding of the clip
-    # boundary takes the other branch of the (discontinuous) surrogate gradient than in fp64; every later step
-    # inherits that difference, so the free-running bound of the largest workload is looser.
-    # (the policy gradient is a sum of nearly cancelling terms, so its relative error after 8 free-running steps is
-    # far larger than that of the parameters; the step-forced check above is the gradient's parity test)
-    big = name == "curiosity"
-    check_free_running(rx, case, param_tol=1e-3 if big else None, grad_tol=0.25 if big else 5e-2)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def run_bc(rx, w, epochs, clip=0.0):
@@ -309,6 +570,7 @@ def run_bc(rx, w, epochs, clip=0.0):
     torch.cuda.synchronize()
     loss, g = obc.bc_loss_and_grad(inp["student"], w.dims_student, obs_s, tgt)
     _check_vec("g_student", w.dims_student, False, host(student3.grads), g, TOL)
+    assert not _elem_violations("g_student", w.dims_student, False, host(student3.grads), g)
     assert abs(host(stats)[0, 0] - loss) <= TOL * loss
 
 

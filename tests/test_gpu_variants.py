@@ -104,13 +104,11 @@ def test_collection_loop_matches_oracle(rx, name, N):
 
 def test_ppo_update_after_timeouts(rx):
     case = Case(WORKLOADS["flat_timeouts"].scaled(250), 1)
-    check_forced_steps(rx, case)
-    check_free_running(rx, case)
+    check_free_running(rx, case, check_forced_steps(rx, case))
 
 
 def test_ppo_update_with_workload_rnd_subset(rx):
     from dataclasses import replace
     case = Case(replace(WORKLOADS["curiosity_subset"].scaled(168), minibatches=4), 1, rnd_on=True)
     assert case.rnd_sub is not None and len(case.rnd_sub) == 24
-    check_forced_steps(rx, case)
-    check_free_running(rx, case, param_tol=1e-3, grad_tol=0.25)
+    check_free_running(rx, case, check_forced_steps(rx, case))
