@@ -202,6 +202,22 @@ int32_t rslx_gae(const float* rewards, const float* values, const float* last_va
                  float gamma, float lam, int32_t normalize_adv, float* advantages, float* returns,
                  void* ws, size_t ws_bytes, void* stream);
 
+/* rslx_gae for callers that cannot allocate or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments, layouts,
+ * results (bit for bit) and error behaviour as rslx_gae, without ws / ws_bytes: the partial sums
+ * of the advantage normalisation live in a 65 600-byte array inside the library's device image,
+ * of which every GPU the library runs on holds its own copy until the process ends.  The call
+ * allocates and frees nothing (with rslx_trace_begin active the trace still creates events).
+ * Limit: N <= RSLX_GAE_NOALLOC_MAX_ENVS, else RSLX_ERR_SHAPE and nothing is launched (T is not
+ * limited).  All calls on one GPU share that GPU's array: calls that overlap on one GPU (two
+ * streams, two host threads) race on it and must be serialised by the caller; calls on one
+ * stream, and replays of a graph that holds one, are ordered and need no clearing in between. */
+#define RSLX_GAE_NOALLOC_MAX_ENVS (1 << 20)
+int32_t rslx_gae_noalloc(const float* rewards, const float* values, const float* last_values,
+                         const uint8_t* dones, const uint8_t* timeouts_or_null, int32_t T,
+                         int32_t N, float gamma, float lam, int32_t normalize_adv,
+                         float* advantages, float* returns, void* stream);
+
 /* ---- fused gradient-clip + Adam over one flat buffer (update steps U5/U6) ------------- */
 
 /* s = min(1, max_grad_norm / (||g||_2 + 1e-6)) (1 when max_grad_norm <= 0), then Adam

@@ -15,7 +15,7 @@ __all__ = [
     "rslx_bc_collect", "Memory", "Gru", "Lstm", "CELL_GRU", "CELL_LSTM", "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent",
     "rslx_ppo_update_recurrent_workspace_bytes", "rslx_ppo_update_recurrent", "rslx_memory_step_workspace_bytes",
     "rslx_memory_step", "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent",
-    "rslx_act_recurrent_dc", "rslx_ppo_update_recurrent_dc",
+    "rslx_act_recurrent_dc", "rslx_ppo_update_recurrent_dc", "rslx_gae_noalloc", "GAE_NOALLOC_MAX_ENVS",
 ]
 
 MAX_LAYERS = 8
@@ -32,8 +32,9 @@ EXPORTS = [
     "rslx_act_recurrent_workspace_bytes", "rslx_act_recurrent", "rslx_ppo_update_recurrent_workspace_bytes",
     "rslx_ppo_update_recurrent", "rslx_memory_step_workspace_bytes", "rslx_memory_step",
     "rslx_bc_update_recurrent_workspace_bytes", "rslx_bc_update_recurrent", "rslx_act_recurrent_dc",
-    "rslx_ppo_update_recurrent_dc",
+    "rslx_ppo_update_recurrent_dc", "rslx_gae_noalloc",
 ]
+GAE_NOALLOC_MAX_ENVS = 1 << 20
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librslx.so")
 
@@ -117,6 +118,7 @@ _sig("rslx_act_dc", C.c_int32, [_P(_CMlp), _P(_CMlp), _vp, _vp, C.c_int32, C.c_u
 _sig("rslx_gae_workspace_bytes", C.c_size_t, [C.c_int32, C.c_int32])
 _sig("rslx_gae", C.c_int32, [_vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_int32, _vp, _vp,
                              _vp, C.c_size_t, _vp])
+_sig("rslx_gae_noalloc", C.c_int32, [_vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_int32, _vp, _vp, _vp])
 _sig("rslx_adam_workspace_bytes", C.c_size_t, [C.c_int64])
 _sig("rslx_adam_step", C.c_int32, [_vp, _vp, _vp, _vp, C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float, C.c_float,
                                    _P(C.c_int64), _vp, _vp, C.c_size_t, _vp])
@@ -359,6 +361,11 @@ def rslx_gae(rewards, values, last_values, dones, timeouts, T, N, gamma, lam, no
     _check(lib.rslx_gae(_ptr(rewards), _ptr(values), _ptr(last_values), _ptr(dones), _ptr(timeouts), T, N, gamma, lam,
                         int(normalize_adv), _ptr(advantages), _ptr(returns), _ptr(ws), ws.numel() if ws is not None else 0,
                         _stream()), "rslx_gae")
+
+
+def rslx_gae_noalloc(rewards, values, last_values, dones, timeouts, T, N, gamma, lam, normalize_adv, advantages, returns):
+    _check(lib.rslx_gae_noalloc(_ptr(rewards), _ptr(values), _ptr(last_values), _ptr(dones), _ptr(timeouts), T, N, gamma, lam,
+                                int(normalize_adv), _ptr(advantages), _ptr(returns), _stream()), "rslx_gae_noalloc")
 
 
 def rslx_adam_workspace_bytes(n):

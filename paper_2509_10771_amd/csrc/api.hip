@@ -2,6 +2,8 @@
 // declared in include/rslx.h.  No entry point synchronises with the host or allocates device memory.
 #include "host.h"
 
+#include <mutex>
+
 namespace {
 
 using namespace rslx;
@@ -15,6 +17,33 @@ struct TraceRec {
 bool g_trace_on = false;
 size_t g_trace_cap = 0;
 std::vector<TraceRec> g_trace;
+
+// Scratch of rslx_gae_noalloc: the per-workgroup partial sums of the advantage normalisation, then the mean and
+// the inverse deviation, for up to RSLX_GAE_NOALLOC_MAX_ENVS environments.  Every device the library runs on
+// holds its own copy of the array at its own address; host code never uses the array's name as an address, only
+// the per-device pointer resolved below.
+constexpr int kGaeScratchDoubles = 2 * (RSLX_GAE_NOALLOC_MAX_ENVS / 256) + 2 + 6;     // 8200 doubles = 65 600 bytes
+static __device__ __align__(256) double scratch[kGaeScratchDoubles];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, resolved once per device.
+int32_t gae_scratch(double** out) {
+  int dev = 0;
+  RSLX_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(RSLX_ERR_UNSUPPORTED, "rslx_gae_noalloc: device index %d", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    double* p = nullptr;
+    RSLX_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(RSLX_ERR_HIP, "rslx_gae_noalloc: no device address for the scratch array on device %d", dev);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return RSLX_OK;
+}
 
 }  // namespace
 
@@ -234,6 +263,30 @@ int32_t rslx_gae(const float* rewards, const float* values, const float* last_va
     Carver c(ws);
     partials = c.take<double>((size_t)gae_num_blocks(N) * 2 + 2);
   }
+  RSLX_HIP(launch_gae(rewards, values, last_values, dones, timeouts_or_null, T, N, gamma, lam, normalize_adv ? 1 : 0,
+                      advantages, returns, partials, (hipStream_t)stream));
+  return RSLX_OK;
+}
+
+int32_t rslx_gae_noalloc(const float* rewards, const float* values, const float* last_values, const uint8_t* dones,
+                         const uint8_t* timeouts_or_null, int32_t T, int32_t N, float gamma, float lam,
+                         int32_t normalize_adv, float* advantages, float* returns, void* stream) {
+  if (T < 0 || N < 0) return fail(RSLX_ERR_SHAPE, "rslx_gae_noalloc: T = %d, N = %d", T, N);
+  if (N > RSLX_GAE_NOALLOC_MAX_ENVS)
+    return fail(RSLX_ERR_SHAPE, "rslx_gae_noalloc: N = %d exceeds the built-in scratch (at most %d environments); use rslx_gae",
+                N, RSLX_GAE_NOALLOC_MAX_ENVS);
+  if (T == 0 || N == 0) return RSLX_OK;
+  if (!rewards || !values || !last_values || !dones || !advantages || !returns)
+    return fail(RSLX_ERR_INVALID_ARG, "rslx_gae_noalloc: null pointer");
+  if (!aligned16(advantages)) return fail(RSLX_ERR_INVALID_ARG, "rslx_gae_noalloc: advantages not 16-byte aligned");
+  if ((int64_t)T * N > (int64_t)INT_MAX * 4) return fail(RSLX_ERR_SHAPE, "rslx_gae_noalloc: T*N too large");
+  double* partials = nullptr;
+  if (normalize_adv) {
+    if ((size_t)gae_num_blocks(N) * 2 + 2 > (size_t)kGaeScratchDoubles)
+      return fail(RSLX_ERR_SHAPE, "rslx_gae_noalloc: N = %d needs more partial sums than the built-in scratch holds", N);
+    RSLX_TRY(gae_scratch(&partials));
+  }
+  // every slot the kernels read is written by the same call first, so the previous call's contents need no clearing
   RSLX_HIP(launch_gae(rewards, values, last_values, dones, timeouts_or_null, T, N, gamma, lam, normalize_adv ? 1 : 0,
                       advantages, returns, partials, (hipStream_t)stream));
   return RSLX_OK;
