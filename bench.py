@@ -101,7 +101,7 @@ def main():
     phase = {"act": [], "gae": [], "update": []}
 
     def step(it, timed):
-        e = [ev() for _ in range(4)] if timed else None
+        e = [ev() for _ in range(5)] if timed else None
         if timed:
             e[0].record()
         rew = rewards
@@ -113,6 +113,8 @@ def main():
                         mu[t], sigma[t], 0, aws)
             if w.rnd:
                 rx.rslx_rnd(rnd_t, rnd_p, obs[t], N, w.Da, rnd_sub, w.dims_rnd[0], running, w.rnd_weight, 1, r_int, rew[t], rws)
+        if timed:
+            e[4].record()      # end of the T acting calls (env-steps are counted over these, not over the bootstrap)
         rx.rslx_act(None, critic, None, obs[T], N, 0, 0, None, None, None, last, None, None, rx.ACT_VALUES_ONLY, aws)
         if timed:
             e[1].record()
@@ -133,9 +135,10 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    phase["act_calls"] = []
     for e in evs:
         phase["act"].append(e[0].elapsed_time(e[1])); phase["gae"].append(e[1].elapsed_time(e[2]))
-        phase["update"].append(e[2].elapsed_time(e[3]))
+        phase["update"].append(e[2].elapsed_time(e[3])); phase["act_calls"].append(e[0].elapsed_time(e[4]))
     # the same K iterations again with the library's HIP-event trace on: per-kernel launch durations for the
     # roofline entry (two event records per launch cost ~10 % of throughput, so `value` comes from the run above)
     trace, traced_ms = [("untraced", 0.0, 0.0, 1.0)], None
@@ -196,7 +199,7 @@ def main():
         "update_transitions_per_s": round(B / (med["update"] * 1e-3), 1),
         "update_sample_passes_per_s": round(sample_passes / (med["update"] * 1e-3), 1),
         "update_tflops": round(upd_flops / (med["update"] * 1e-3) / 1e12, 2),
-        "act_env_steps_per_s": round((T + 1) * N / (med["act"] * 1e-3), 1),
+        "act_env_steps_per_s": round(T * N / (med["act_calls"] * 1e-3), 1),
         "phase_ms": {k: round(v, 4) for k, v in med.items()},
         "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
         "graph_replay": None if graph_ms is None else {"ms_per_step": round(graph_ms, 4),
@@ -349,7 +352,7 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def step(it, timed):
-        e = [ev() for _ in range(4)] if timed else None
+        e = [ev() for _ in range(5)] if timed else None
         if timed:
             e[0].record()
         for t in range(T):
@@ -357,6 +360,8 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
             rx.rslx_act_recurrent(ga, ma, gc, mc, obs[t], obs[t], N, h_a, h_c, reset, h0_a if t == 0 else None,
                                   h0_c if t == 0 else None, 20250910, it * T + t, None, actions[t], logp[t], values[t], mu[t],
                                   sigma[t], 0, aws)
+        if timed:
+            e[4].record()      # end of the T acting calls
         rx.rslx_act_recurrent(None, None, gc, mc, None, obs[T], N, None, h_c, dones[T - 1], None, None, 0, 0, None, None, None,
                               last, None, None, rx.ACT_VALUES_ONLY, aws)
         if timed:
@@ -378,6 +383,7 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     med = {k: float(np.median([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, k in enumerate(("act", "gae", "update"))}
+    med["act_calls"] = float(np.median([e[0].elapsed_time(e[4]) for e in evs]))
     roofline, breakdown, traced_ms = None, None, None
     if not args.no_trace:
         rx.rslx_trace_begin(1 << 17)
@@ -432,7 +438,7 @@ def recurrent_iteration(args, rx, torch, np, w, inp):
         "phase_ms": {k: round(v, 4) for k, v in med.items()},
         "update_tflops": round(per_sample * B * w.epochs / (med["update"] * 1e-3) / 1e12, 2),
         "act_tflops": round(act_flops * (T + 1) * N / (med["act"] * 1e-3) / 1e12, 2),
-        "act_env_steps_per_s": round((T + 1) * N / (med["act"] * 1e-3), 1),
+        "act_env_steps_per_s": round(T * N / (med["act_calls"] * 1e-3), 1),
         "traced_ms_per_step": None if traced_ms is None else round(traced_ms, 4),
         "graph_replay": None if graph_ms is None else {"ms_per_step": round(graph_ms, 4),
                                                        "value": round(B / (graph_ms * 1e-3), 1)},
@@ -499,43 +505,64 @@ def streaming_kernels(rx, torch, T, N, n_params):
 
 
 def cpu_baseline(w, inp):
-    """The fp64 oracle on the host cores: the full act loop and GAE, and ONE of the update epochs (scaled up)."""
+    """The fp64 numpy oracle on the host cores, as it stands.  All cores: the whole iteration (act loop, GAE and
+    every update epoch) on the headline workload; on the larger workloads one update epoch is timed and scaled to
+    the epoch count (said in `sample`).  One thread: two act steps and one optimiser step, scaled to the
+    iteration (a bounded sample: the whole iteration takes minutes on one core)."""
     import numpy as np
     from oracle import ppo as oppo, gae as ogae, rng as orng
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
-    except Exception:
-        cores = os.cpu_count()
+    from threadpoolctl import threadpool_info, threadpool_limits
+    pools = [p for p in threadpool_info() if p.get("user_api") == "blas"] or threadpool_info()
+    cores = max([p.get("num_threads", 1) for p in pools] or [os.cpu_count()])
+    blas = ", ".join(sorted({"%s %s" % (p.get("internal_api", "?"), p.get("version", "")) for p in pools})) or "unknown BLAS"
     T, N, A, B = w.T, w.N, w.A, w.B
+    act_step = lambda t: oppo.act(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, inp["obs"][t], inp["obs"][t],
+                                  orng.act_noise(1, t, N, A))
     t0 = time.perf_counter()
-    acts, logp, vals, mu, sg = [], [], [], [], []
-    for t in range(T):
-        o = oppo.act(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, inp["obs"][t], inp["obs"][t], orng.act_noise(1, t, N, A))
-        acts.append(o["actions"]); logp.append(o["logp"]); vals.append(o["values"]); mu.append(o["mu"]); sg.append(o["sigma"])
+    outs = [act_step(t) for t in range(T)]
     lastv = oppo.act(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, inp["obs"][T], inp["obs"][T], np.zeros((N, A)))["values"]
     t_act = time.perf_counter() - t0
+    vals = np.stack([o["values"] for o in outs])
     t0 = time.perf_counter()
-    adv, ret = ogae.gae(inp["rewards"], np.stack(vals), lastv, inp["dones"], w.gamma, w.lam, timeouts=inp.get("timeouts"))
+    adv, ret = ogae.gae(inp["rewards"], vals, lastv, inp["dones"], w.gamma, w.lam, timeouts=inp.get("timeouts"))
     advn = ogae.normalize_advantages(adv)
     t_gae = time.perf_counter() - t0
-    flat = dict(obs_a=inp["obs"][:T].reshape(B, -1), obs_c=inp["obs"][:T].reshape(B, -1), actions=np.stack(acts).reshape(B, A),
-                logp=np.stack(logp).reshape(B), values=np.stack(vals).reshape(B), mu=np.stack(mu).reshape(B, A),
-                sigma=np.stack(sg).reshape(B, A), adv=advn.reshape(B), returns=ret.reshape(B))
+    stack = lambda k: np.stack([o[k] for o in outs])
+    flat = dict(obs_a=inp["obs"][:T].reshape(B, -1), obs_c=inp["obs"][:T].reshape(B, -1), actions=stack("actions").reshape(B, A),
+                logp=stack("logp").reshape(B), values=vals.reshape(B), mu=stack("mu").reshape(B, A),
+                sigma=stack("sigma").reshape(B, A), adv=advn.reshape(B), returns=ret.reshape(B))
+    whole = w.name == "flat" or B * w.epochs <= 500000          # the whole update fits the time budget
+    epochs_timed = w.epochs if whole else 1
     cfg = oppo.PPOConfig(clip=w.clip, value_coef=w.value_coef, entropy_coef=w.entropy_coef, max_grad_norm=w.max_grad_norm,
-                         lr=w.lr, epochs=1, minibatches=w.minibatches, seed=1)
+                         lr=w.lr, epochs=epochs_timed, minibatches=w.minibatches, seed=1)
     na, nc = inp["actor"].size, inp["critic"].size
+    opt0 = lambda: dict(m_a=np.zeros(na), v_a=np.zeros(na), m_c=np.zeros(nc), v_c=np.zeros(nc), step=0)
     sym = None
     if w.symmetry:
         sym = oppo.SymSpec(inp["perm_obs"], inp["sign_obs"], inp["perm_obs"], inp["sign_obs"], inp["perm_act"], inp["sign_act"], w.mirror_loss_coef)
     t0 = time.perf_counter()
-    oppo.ppo_update(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, flat, cfg,
-                    dict(m_a=np.zeros(na), v_a=np.zeros(na), m_c=np.zeros(nc), v_c=np.zeros(nc), step=0), sym)
-    t_epoch = time.perf_counter() - t0
-    total = t_act + t_gae + w.epochs * t_epoch
+    oppo.ppo_update(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, flat, cfg, opt0(), sym)
+    t_upd = (time.perf_counter() - t0) * (w.epochs / epochs_timed)
+    total = t_act + t_gae + t_upd
+    # one thread, bounded sample
+    mb = B // w.minibatches
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        for t in range(2):
+            act_step(t)
+        t1_act = (time.perf_counter() - t0) / 2 * (T + 1)
+        t0 = time.perf_counter()
+        oppo.ppo_update(inp["actor"], inp["critic"], w.dims_actor, w.dims_critic, {k: v[:mb] for k, v in flat.items()},
+                        oppo.PPOConfig(clip=cfg.clip, value_coef=cfg.value_coef, entropy_coef=cfg.entropy_coef,
+                                       max_grad_norm=cfg.max_grad_norm, lr=cfg.lr, epochs=1, minibatches=1, seed=1), opt0(), sym)
+        t1_upd = (time.perf_counter() - t0) * w.epochs * w.minibatches
     return {"value": round(B / total, 1), "unit": "transitions/s (whole iteration)", "cores": int(cores), "kind": "oracle",
-            "sample": "fp64 numpy oracle: full act loop (%.2f s) and GAE (%.3f s) timed; 1 of %d update epochs timed (%.2f s) and multiplied by %d"
-                      % (t_act, t_gae, w.epochs, t_epoch, w.epochs)}
+            "sample": "fp64 numpy oracle (%s, %d threads): whole act loop (%.2f s), GAE (%.3f s) and %s (%.2f s) timed"
+                      % (blas, cores, t_act, t_gae, "all %d update epochs" % w.epochs if whole
+                         else "1 of %d update epochs, multiplied by %d" % (w.epochs, w.epochs), t_upd),
+            "one_thread": {"value": round(B / (t1_act + t_gae + t1_upd), 1), "cores": 1,
+                           "sample": "2 of %d act steps and 1 of %d optimiser steps timed on one thread and scaled to the iteration "
+                                     "(%.1f s + %.1f s)" % (T + 1, w.epochs * w.minibatches, t1_act, t1_upd)}}
 
 
 if __name__ == "__main__":

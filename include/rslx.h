@@ -149,7 +149,8 @@ int32_t rslx_device_check(void);
  * keeps at most max_records launches.  rslx_trace_end stops recording, WAITS on the host for the
  * recorded events, and copies up to `cap` records (launch order) to `out` (host); *n_out receives the
  * number recorded.  Calling it with out == NULL only reports the count and keeps the records for a
- * second call.  `kernel` names a launch site: "gemm_<fwd|dx|dw>_<BM>x<BN>" are the matrix-core
+ * second call.  Launches beyond max_records are counted, not recorded: rslx_trace_end then still
+ * delivers the records it has and returns RSLX_ERR_WORKSPACE.  `kernel` names a launch site: "gemm_<fwd|dx|dw>_<BM>x<BN>" are the matrix-core
  * kernels (flops = 2 M N K summed over the grouped problems), the others are streaming kernels
  * (bytes = algorithmic HBM bytes).  Not thread-safe; tracing costs two event records per launch. */
 typedef struct rslx_trace_record {

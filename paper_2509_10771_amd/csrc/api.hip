@@ -16,6 +16,7 @@ struct TraceRec {
 };
 bool g_trace_on = false;
 size_t g_trace_cap = 0;
+long g_trace_dropped = 0;      // launches seen while the trace was on that got no record
 std::vector<TraceRec> g_trace;
 
 // Scratch of rslx_gae_noalloc: the per-workgroup partial sums of the advantage normalisation, then the mean and
@@ -48,19 +49,21 @@ int32_t gae_scratch(double** out) {
 }  // namespace
 
 namespace rslx {
-void trace_open(hipStream_t stream, const char* kernel, double flops, double bytes) {
-  if (!g_trace_on || g_trace.size() >= g_trace_cap) return;
+int trace_open(hipStream_t stream, const char* kernel, double flops, double bytes) {
+  if (!g_trace_on) return -1;
+  if (g_trace.size() >= g_trace_cap) { ++g_trace_dropped; return -1; }
   TraceRec r;
-  if (hipEventCreate(&r.a) != hipSuccess) return;
-  if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+  if (hipEventCreate(&r.a) != hipSuccess) { ++g_trace_dropped; return -1; }
+  if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); ++g_trace_dropped; return -1; }
   snprintf(r.kernel, sizeof r.kernel, "%s", kernel);
   r.flops = flops; r.bytes = bytes;
   (void)hipEventRecord(r.a, stream);
   g_trace.push_back(r);
+  return (int)g_trace.size() - 1;
 }
-void trace_close(hipStream_t stream) {
-  if (!g_trace_on || g_trace.empty()) return;
-  (void)hipEventRecord(g_trace.back().b, stream);
+void trace_close(hipStream_t stream, int record) {
+  if (record < 0 || (size_t)record >= g_trace.size()) return;
+  (void)hipEventRecord(g_trace[record].b, stream);
 }
 }  // namespace rslx
 
@@ -73,6 +76,7 @@ int32_t rslx_trace_begin(int32_t max_records) {
   g_trace.clear();
   g_trace.reserve(max_records);
   g_trace_cap = (size_t)max_records;
+  g_trace_dropped = 0;
   g_trace_on = true;
   return RSLX_OK;
 }
@@ -96,9 +100,10 @@ int32_t rslx_trace_end(rslx_trace_record* out, int32_t cap, int32_t* n_out) {
   if (out) {
     for (TraceRec& r : g_trace) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     g_trace.clear();
-  } else {
-    g_trace_on = false;
   }
+  if (g_trace_dropped > 0)
+    return fail(RSLX_ERR_WORKSPACE, "rslx_trace_end: %ld launches were not recorded (max_records = %zu too small, or no event could be created)",
+                g_trace_dropped, g_trace_cap);
   return RSLX_OK;
 }
 
@@ -478,6 +483,12 @@ int32_t ppo_update_impl(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
     return x;
   };
 
+  {   // transposed weights once per call; every Adam launch below keeps them current
+    const XView none;
+    BwdJob tj[2] = {BwdJob{actor, none, p.rows, &p.actor.act, p.actor.d_out, p.actor.wt, p.actor.partials, &p.actor.plan},
+                    BwdJob{critic, none, p.rows, &p.critic.act, p.critic.d_out, p.critic.wt, p.critic.partials, &p.critic.plan}};
+    if (cfg->epochs > 0) RSLX_TRY(transpose_weights(tj, 2, s, false));
+  }
   for (int e = 0; e < cfg->epochs; ++e) {
     for (int m = 0; m < cfg->minibatches; ++m) {
       const int32_t* idx = p.perms + (size_t)e * p.B + (size_t)m * p.mb;
@@ -520,7 +531,7 @@ int32_t ppo_update_impl(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
       }
       BwdJob bj[2] = {BwdJob{actor, xa, p.rows, &p.actor.act, p.actor.d_out, p.actor.wt, p.actor.partials, &p.actor.plan},
                       BwdJob{critic, xc, p.rows, &p.critic.act, p.critic.d_out, p.critic.wt, p.critic.partials, &p.critic.plan}};
-      RSLX_TRY(backward_nets(bj, 2, s, p.fused_head));
+      RSLX_TRY(backward_nets(bj, 2, s, p.fused_head, true));
       {   // one launch: both networks' split sums and the loss head's sums
         ReduceArgs ra;
         memset(&ra, 0, sizeof ra);
@@ -542,6 +553,8 @@ int32_t ppo_update_impl(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
       aa.seg[0] = AdamSegment{actor->params, actor->grads, actor->adam_m, actor->adam_v, param_count(*actor)};
       aa.seg[1] = AdamSegment{critic->params, critic->grads, critic->adam_m, critic->adam_v, param_count(*critic)};
       aa.n_seg = 2;
+      adam_keeps_transposed(aa.seg[0], *actor, p.actor.wt);
+      adam_keeps_transposed(aa.seg[1], *critic, p.critic.wt);
       aa.sumsq_blocks = p.sumsq_all; aa.n_sumsq = p.actor.n_sumsq + p.critic.n_sumsq + 1;
       aa.max_grad_norm = cfg->max_grad_norm;
       aa.lr = cfg->lr; aa.beta1 = cfg->beta1; aa.beta2 = cfg->beta2; aa.eps = cfg->adam_eps;

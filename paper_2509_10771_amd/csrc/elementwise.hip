@@ -419,6 +419,26 @@ hipError_t launch_sumsq(const float* g, int64_t n, double* sumsq_blocks, hipStre
 // ---- fused clip + Adam ------------------------------------------------------------------------------
 // Every workgroup re-reduces the (short) list of per-block squared norms in the same order, so the clip
 // scale is identical everywhere and no extra launch or atomic is needed.
+// Writes the updated weight with flat parameter index i to its transposed position (biases and the layers below
+// wt_from have none).
+__device__ __forceinline__ void adam_store_transposed(const AdamSegment& sg, long i, float value) {
+  long o = 0;
+  for (int l = 0; l < sg.n_layers; ++l) {
+    const int rows = sg.dims[l], cols = sg.dims[l + 1];
+    const long w = (long)rows * cols;
+    if (i < o + w) {
+      if (l >= sg.wt_from) {
+        const int e = (int)(i - o);
+        const int r = e / cols, c = e - r * cols;
+        sg.wt[o + (long)c * rows + r] = value;
+      }
+      return;
+    }
+    o += w + cols;
+    if (i < o) return;
+  }
+}
+
 __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
   __shared__ double smem[4];
   __shared__ float s_scale, s_bc1, s_bc2;
@@ -462,6 +482,10 @@ __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
     *reinterpret_cast<float4*>(sg.params + i0) = p;
     *reinterpret_cast<float4*>(sg.m + i0) = m;
     *reinterpret_cast<float4*>(sg.v + i0) = v;
+    if (sg.wt != nullptr) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) adam_store_transposed(sg, i0 + c, pp[c]);
+    }
   } else {
     for (long i = i0; i < sg.n; ++i) {
       const float gg = sg.grads[i] * scale;
@@ -469,7 +493,9 @@ __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
       const float v = a.beta2 * sg.v[i] + ob2 * gg * gg;
       sg.m[i] = m;
       sg.v[i] = v;
-      sg.params[i] -= a.lr * (m * inv_bc1) / (sqrtf(v * inv_bc2) + a.eps);
+      const float pn = sg.params[i] - a.lr * (m * inv_bc1) / (sqrtf(v * inv_bc2) + a.eps);
+      sg.params[i] = pn;
+      if (sg.wt != nullptr) adam_store_transposed(sg, i, pn);
     }
   }
 }

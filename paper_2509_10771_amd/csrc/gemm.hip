@@ -10,6 +10,7 @@
 //   A operand: A[row = j][k = g]      B operand: B[k = g][col = j]
 //   D/C, 16 accumulators r = 0..15:   D[row = 8 * (r / 4) + 4 * g + r % 4][col = j]
 #include <cstdio>
+#include <cstring>
 #include <type_traits>
 
 #include "kernels.h"
@@ -608,24 +609,33 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void ge
 // Weight gradient and input gradient of one layer in one launch (both read the same dZ and neither reads the
 // other's result): the workgroups of the second fill the CUs as those of the first drain, so one launch tail and
 // one output phase disappear.  Workgroups [0, nw) belong to the weight gradient (gw tiles x sw splits per
-// problem), the rest to the input gradient (gx tiles per problem).  16-byte operand paths only.
+// problem), the next ne to an optional second weight gradient of narrow output (the network's output layer, whose
+// operands are ready at the same time: 128 x 32 tiles, ge tiles x se splits per problem), the rest to the input
+// gradient (gx tiles per problem).  16-byte operand paths only (the narrow one reads dZ with scalar loads).
 template <int WBM, int WBN, int WWM, int WWN, int XBM, int XBN, int XWM, int XWN, int BK>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void gemm_pair_kernel(
-    const GemmBatch bw, const GemmBatch bx, const int gw, const int sw, const int gx) {
+    const GemmBatch bw, const GemmBatch bx, const GemmBatch be, const int gw, const int sw, const int gx, const int ge,
+    const int se) {
   constexpr int LW = gemm_lds_floats<WBM, WBN, BK>(), LX = gemm_lds_floats<XBM, XBN, BK>();
-  __shared__ __align__(16) float smem[LW > LX ? LW : LX];
-  const int per_w = gw * sw;
-  const int nw = bw.count * per_w;
+  constexpr int LE = gemm_lds_floats<128, 32, BK>();
+  constexpr int LWX = LW > LX ? LW : LX;
+  __shared__ __align__(16) float smem[LWX > LE ? LWX : LE];
+  const int per_w = gw * sw, per_e = ge * se;
+  const int nw = bw.count * per_w, ne = be.count * per_e;
   const int b = blockIdx.x;
   // When the weight-gradient workgroups alone fill the chip (4 resident workgroups on each of 256 CUs), the input
   // gradient is the tail of the launch: its waves then issue ahead of the weight gradient's that are still running
   // (measured: 4 % off such a launch; 5 % on, when the two kinds share the chip from the start).
-  if (b >= nw && nw >= 1024) __builtin_amdgcn_s_setprio(3);
+  if (b >= nw + ne && nw >= 1024) __builtin_amdgcn_s_setprio(3);
   if (b < nw) {
     const int z = b / per_w;
     gemm_tile<GEMM_DW, WBM, WBN, WWM, WWN, BK, true, true>(bw.p[z], b - z * per_w, per_w, gw, smem);
-  } else {
+  } else if (b < nw + ne) {
     const int c = b - nw;
+    const int z = c / per_e;
+    gemm_tile<GEMM_DW, 128, 32, 4, 1, BK, true, false>(be.p[z], c - z * per_e, per_e, ge, smem);
+  } else {
+    const int c = b - nw - ne;
     const int z = c / gx;
     gemm_tile<GEMM_DX, XBM, XBN, XWM, XWN, BK, true, true>(bx.p[z], c - z * gx, gx, gx, smem);
   }
@@ -761,29 +771,56 @@ static BatchGeom batch_geom(GemmMode mode, const GemmBatch& batch, int BM, int B
 }
 
 template <int WBM, int WBN, int WWM, int WWN, int XBM, int XBN, int XWM, int XWN>
-static hipError_t launch_pair_cfg(const GemmBatch& bw, const GemmBatch& bx, const BatchGeom& gw, const BatchGeom& gx,
-                                  hipStream_t stream) {
+static hipError_t launch_pair_cfg(const GemmBatch& bw, const GemmBatch& bx, const GemmBatch& be, const BatchGeom& gw,
+                                  const BatchGeom& gx, const BatchGeom& ge, hipStream_t stream) {
   char name[48];
   snprintf(name, sizeof name, "gemm_dwdx_%dx%d_%dx%d", WBM, WBN, XBM, XBN);
-  TraceScope ts(stream, name, gw.flops + gx.flops, 0.0);
-  const int blocks = bw.count * gw.tiles * gw.splits + bx.count * gx.tiles;
+  TraceScope ts(stream, name, gw.flops + gx.flops + ge.flops, 0.0);
+  const int blocks = bw.count * gw.tiles * gw.splits + bx.count * gx.tiles + be.count * ge.tiles * ge.splits;
   hipLaunchKernelGGL((gemm_pair_kernel<WBM, WBN, WWM, WWN, XBM, XBN, XWM, XWN, 16>), dim3(blocks), dim3(NT), 0, stream,
-                     bw, bx, gw.tiles, gw.splits, gx.tiles);
+                     bw, bx, be, gw.tiles, gw.splits, gx.tiles, ge.tiles, ge.splits);
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_dw_dx(const GemmBatch& bw, const GemmBatch& bx, hipStream_t stream) {
+// The narrow weight gradient can ride in the paired launch when it takes 128 x 32 tiles and its X operand allows
+// 16-byte loads (what gemm_kernel<GEMM_DW, 128, 32, 4, 1, 16, true, false> needs).
+static bool narrow_dw_fits(const GemmBatch& be) {
+  if (be.count <= 0 || pick_tile(GEMM_DW, be) != TILE_128x32) return false;
+  for (int i = 0; i < be.count; ++i) {
+    const GemmProblem& P = be.p[i];
+    const int64_t a_rows = P.row_idx != nullptr ? P.a_src_rows : P.K;
+    if (!P.a_vec || a_rows <= 0 || a_rows * (int64_t)P.lda >= ((int64_t)1 << 32)) return false;
+  }
+  return true;
+}
+
+hipError_t launch_gemm_dw_dx(const GemmBatch& bw, const GemmBatch& bx, hipStream_t stream, const GemmBatch* narrow_dw) {
   const TileCfg tw = pick_tile(GEMM_DW, bw), tx = pick_tile(GEMM_DX, bx);
   const bool w_ok = tw == TILE_128x128 || tw == TILE_64x128, x_ok = tx == TILE_128x128 || tx == TILE_64x128;
   if (w_ok && x_ok && bw.count > 0 && bx.count > 0) {
     const BatchGeom gw = batch_geom(GEMM_DW, bw, tw == TILE_128x128 ? 128 : 64, 128);
     const BatchGeom gx = batch_geom(GEMM_DX, bx, tx == TILE_128x128 ? 128 : 64, 128);
     if (gw.vec && gx.vec && gw.tiles > 0 && gx.tiles > 0) {
-      if (tw == TILE_128x128 && tx == TILE_128x128) return launch_pair_cfg<128, 128, 2, 2, 128, 128, 2, 2>(bw, bx, gw, gx, stream);
-      if (tw == TILE_128x128) return launch_pair_cfg<128, 128, 2, 2, 64, 128, 1, 4>(bw, bx, gw, gx, stream);
-      if (tx == TILE_128x128) return launch_pair_cfg<64, 128, 1, 4, 128, 128, 2, 2>(bw, bx, gw, gx, stream);
-      return launch_pair_cfg<64, 128, 1, 4, 64, 128, 1, 4>(bw, bx, gw, gx, stream);
+      GemmBatch be;
+      memset(&be, 0, sizeof be);
+      BatchGeom ge;
+      ge.tiles = 0; ge.splits = 0;
+      if (narrow_dw != nullptr && narrow_dw_fits(*narrow_dw)) {
+        be = *narrow_dw;
+        ge = batch_geom(GEMM_DW, be, 128, 32);
+      } else if (narrow_dw != nullptr) {
+        hipError_t e = launch_gemm(GEMM_DW, *narrow_dw, stream);
+        if (e != hipSuccess) return e;
+      }
+      if (tw == TILE_128x128 && tx == TILE_128x128) return launch_pair_cfg<128, 128, 2, 2, 128, 128, 2, 2>(bw, bx, be, gw, gx, ge, stream);
+      if (tw == TILE_128x128) return launch_pair_cfg<128, 128, 2, 2, 64, 128, 1, 4>(bw, bx, be, gw, gx, ge, stream);
+      if (tx == TILE_128x128) return launch_pair_cfg<64, 128, 1, 4, 128, 128, 2, 2>(bw, bx, be, gw, gx, ge, stream);
+      return launch_pair_cfg<64, 128, 1, 4, 64, 128, 1, 4>(bw, bx, be, gw, gx, ge, stream);
     }
+  }
+  if (narrow_dw != nullptr) {
+    hipError_t e = launch_gemm(GEMM_DW, *narrow_dw, stream);
+    if (e != hipSuccess) return e;
   }
   hipError_t e = launch_gemm(GEMM_DW, bw, stream);
   if (e != hipSuccess) return e;

@@ -248,21 +248,40 @@ struct BwdJob {
 // Backward of up to two networks of equal depth: per layer one grouped weight-gradient launch (split over
 // rows, partial sums) and one grouped input-gradient launch.
 // With skip_last_dx the input gradient of the output layer (dz of the last hidden layer) already exists.
-inline int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, bool skip_last_dx = false) {
-  if (count == 2 && jobs[0].net->n_layers != jobs[1].net->n_layers) {
-    RSLX_TRY(backward_nets(jobs, 1, stream, skip_last_dx));
-    return backward_nets(jobs + 1, 1, stream, skip_last_dx);
-  }
-  const int L = jobs[0].net->n_layers;
+// Transposed copies of the weight matrices that the input-gradient contractions of backward_nets read.
+inline int32_t transpose_weights(const BwdJob* jobs, int count, hipStream_t stream, bool skip_last_dx) {
   TransposeBatch tb;
   tb.count = 0;
-  const bool dx_in = jobs[0].dx0 != nullptr;     // all jobs of a call agree on this
-  for (int i = 0; i < count; ++i)
-    for (int l = dx_in ? 0 : 1; l < (skip_last_dx ? L - 1 : L); ++l) {
-      const rslx_mlp& n = *jobs[i].net;
+  for (int i = 0; i < count; ++i) {
+    const rslx_mlp& n = *jobs[i].net;
+    for (int l = jobs[i].dx0 != nullptr ? 0 : 1; l < (skip_last_dx ? n.n_layers - 1 : n.n_layers); ++l)
       tb.job[tb.count++] = TransposeJob{n.params + layer_offset(n, l), jobs[i].wt + layer_offset(n, l), n.dims[l], n.dims[l + 1]};
-    }
+  }
   RSLX_HIP(launch_transpose(tb, stream));
+  return RSLX_OK;
+}
+
+// Lets the Adam launch keep a job's transposed weights current (see AdamSegment::wt).
+inline void adam_keeps_transposed(AdamSegment& sg, const rslx_mlp& n, float* wt, bool first_has_dx = false) {
+  sg.wt = wt;
+  sg.n_layers = n.n_layers;
+  sg.wt_from = first_has_dx ? 0 : 1;
+  for (int i = 0; i <= n.n_layers; ++i) sg.dims[i] = n.dims[i];
+}
+
+// wt_ready: the transposed weights in jobs[i].wt are current (transpose_weights at the start of the call, kept up
+// to date by the Adam launches since), so no transposition is launched here.
+inline int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, bool skip_last_dx = false,
+                             bool wt_ready = false) {
+  if (count == 2 && jobs[0].net->n_layers != jobs[1].net->n_layers) {
+    RSLX_TRY(backward_nets(jobs, 1, stream, skip_last_dx, wt_ready));
+    return backward_nets(jobs + 1, 1, stream, skip_last_dx, wt_ready);
+  }
+  const int L = jobs[0].net->n_layers;
+  const bool dx_in = jobs[0].dx0 != nullptr;     // all jobs of a call agree on this
+  if (!wt_ready) RSLX_TRY(transpose_weights(jobs, count, stream, skip_last_dx));
+  GemmBatch pending;
+  bool has_pending = false;
   for (int l = L - 1; l >= 0; --l) {
     GemmBatch bw, bx;
     bw.count = bx.count = count;
@@ -302,9 +321,20 @@ inline int32_t backward_nets(const BwdJob* jobs, int count, hipStream_t stream, 
         bx.p[i] = q;
       }
     }
-    if ((l > 0 || dx_in) && !(skip_last_dx && l == L - 1)) RSLX_HIP(launch_gemm_dw_dx(bw, bx, stream));
-    else RSLX_HIP(launch_gemm(GEMM_DW, bw, stream));
+    if ((l > 0 || dx_in) && !(skip_last_dx && l == L - 1)) {
+      RSLX_HIP(launch_gemm_dw_dx(bw, bx, stream, has_pending ? &pending : nullptr));
+      has_pending = false;
+    } else if (skip_last_dx && l == L - 1 && l > 0) {
+      // the output layer's weight gradient (its input gradient exists already): it joins the next layer's launch
+      pending = bw;
+      has_pending = true;
+    } else {
+      if (has_pending) RSLX_HIP(launch_gemm(GEMM_DW, pending, stream));
+      has_pending = false;
+      RSLX_HIP(launch_gemm(GEMM_DW, bw, stream));
+    }
   }
+  if (has_pending) RSLX_HIP(launch_gemm(GEMM_DW, pending, stream));
   return RSLX_OK;
 }
 

@@ -12,12 +12,16 @@ namespace rslx {
 // events on the launch stream and tags it with its algorithmic flops / bytes.  Disabled by default
 // (then these calls do nothing).
 // ---------------------------------------------------------------------------------------------
-void trace_open(hipStream_t stream, const char* kernel, double flops, double bytes);
-void trace_close(hipStream_t stream);
+// trace_open returns the index of the record it opened, or -1 when none was opened (trace off, record limit
+// reached, event creation failed); trace_close records the end event of exactly that record.
+int trace_open(hipStream_t stream, const char* kernel, double flops, double bytes);
+void trace_close(hipStream_t stream, int record);
 struct TraceScope {
   hipStream_t s;
-  TraceScope(hipStream_t stream, const char* kernel, double flops, double bytes) : s(stream) { trace_open(s, kernel, flops, bytes); }
-  ~TraceScope() { trace_close(s); }
+  int record;
+  TraceScope(hipStream_t stream, const char* kernel, double flops, double bytes)
+      : s(stream), record(trace_open(stream, kernel, flops, bytes)) {}
+  ~TraceScope() { trace_close(s, record); }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -66,7 +70,9 @@ struct GemmBatch {
 
 hipError_t launch_gemm(GemmMode mode, const GemmBatch& batch, hipStream_t stream);
 // Weight gradient (bw) and input gradient (bx) of one layer; one launch when both fit the paired kernel.
-hipError_t launch_gemm_dw_dx(const GemmBatch& bw, const GemmBatch& bx, hipStream_t stream);
+// narrow_dw: optional further weight gradient whose operands are ready as well (the output layer's, a few columns
+// wide); it rides in the same launch when it can, else it is launched on its own first.
+hipError_t launch_gemm_dw_dx(const GemmBatch& bw, const GemmBatch& bx, hipStream_t stream, const GemmBatch* narrow_dw = nullptr);
 // Out-of-place transposes of up to 16 row-major matrices in one launch: dst[c, r] = src[r, c].
 struct TransposeJob { const float* src; float* dst; int32_t rows, cols; };
 struct TransposeBatch { TransposeJob job[16]; int32_t count; };
@@ -159,6 +165,12 @@ hipError_t launch_sumsq(const float* g, int64_t n, double* sumsq_blocks, hipStre
 struct AdamSegment {
   float* params; const float* grads; float* m; float* v;
   int64_t n;
+  // Optional: every updated weight of layers >= wt_from is also written to its place in `wt`, the flat buffer of
+  // transposed weight matrices the input-gradient contraction reads (W_l^T at the layer's parameter offset), so
+  // that no transposition launch is needed before the next optimiser step.  dims: the MLP's layer widths.
+  float* wt;
+  int32_t n_layers, wt_from;
+  int32_t dims[9];
 };
 struct AdamArgs {
   AdamSegment seg[4];
