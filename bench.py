@@ -19,13 +19,45 @@ if ROOT not in sys.path:
 
 FP32_MFMA_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the matrix-core kernels on the "flat" workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# (2.0 * FETCH + 1.0 * WRITE after calibration against a kernel of known size; profiles/flat_iteration_hbm_traffic.txt).
-HBM_TRAFFIC_BYTES_PER_LAUNCH_FLAT = {
-    "gemm_dwdx_128x128_64x128": 451.8e6,   # algorithmic 437.3e6 (dW 512x256 incl. 33.6e6 of split partials + dX 256->512)
-    "gemm_fwd_128x128": 161.9e6,           # algorithmic 152.0e6
-    "gemm_dwdx_64x128_128x128": 236.1e6,   # algorithmic 235.0e6 (dW 256x128 + dX 128->256)
-}
+
+
+def kernel_sources_hash():
+    """sha256/16 of the HIP sources, the stamp the counter summaries under profiles/ carry."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2509_10771_amd", "csrc", "*.hip")) +
+                    glob.glob(os.path.join(ROOT, "paper_2509_10771_amd", "csrc", "*.h"))):
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def hbm_traffic_per_launch(workload, site):
+    """HBM bytes per launch of a matrix-core launch site, from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary of
+    this workload under profiles/ (calibrated there against a kernel of known size).  None when there is no
+    summary, when it was taken on other kernel sources than the ones in the tree, or when the site is not listed."""
+    import re
+    path = os.path.join(ROOT, "profiles", "%s_iteration_hbm_traffic.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    m = re.search(r"kernel sources sha256/16: ([0-9a-f]{16})", text)
+    if not m or m.group(1) != kernel_sources_hash():
+        return None
+    m = re.match(r"gemm_dwdx_(\d+)x(\d+)_(\d+)x(\d+)$", site)
+    if m:
+        pat = r"gemm_pair_kernel<%s, %s, \d+, \d+, %s, %s, " % m.groups()
+    else:
+        m = re.match(r"gemm_(fwd|dx|dw)_(\d+)x(\d+)$", site)
+        if not m:
+            return None
+        pat = r"gemm_kernel<%d, %s, %s, " % ({"fwd": 0, "dx": 1, "dw": 2}[m.group(1)], m.group(2), m.group(3))
+    calls = total = 0.0
+    for line in text.splitlines():
+        if re.match(pat, line):
+            f = line.split()
+            calls += float(f[-4]); total += float(f[-4]) * float(f[-1]) * 1e6
+    return total / calls if calls else None
 
 
 def flops_per_sample_pass(dims_a, dims_c):
@@ -457,7 +489,8 @@ def summarize_trace(trace, w, steps):
     achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
     roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=round(achieved / FP32_MFMA_PEAK_TFLOPS, 4),
-                    traffic=HBM_TRAFFIC_BYTES_PER_LAUNCH_FLAT.get(dom) if w.name == "flat" else None,
+                    traffic=hbm_traffic_per_launch(w.name, dom),
+                    traffic_source="profiles/%s_iteration_hbm_traffic.txt (rocprofv3 FETCH_SIZE / WRITE_SIZE of these kernel sources)" % w.name,
                     launches=d["n"], avg_launch_us=round(d["ms"] * 1e3 / d["n"], 2),
                     flops_per_launch=d["flops"] / d["n"])
     breakdown = {k: dict(launches=v["n"], total_ms_per_step=round(v["ms"] / steps, 4),
