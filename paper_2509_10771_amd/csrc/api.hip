@@ -138,6 +138,10 @@ int32_t rslx_permutation(uint64_t seed, uint64_t call_index, int32_t epoch, int3
 }
 
 // ---- act ---------------------------------------------------------------------------------------------------
+// A workspace query reads the layer table before any other check has run: a depth outside the table must not be
+// walked (the entry point proper rejects it with a message; the query answers 0).
+static bool depth_ok(const rslx_mlp* n) { return n == nullptr || (n->n_layers >= 1 && n->n_layers <= RSLX_MAX_LAYERS); }
+
 static size_t act_carve(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, int32_t N, NetBufs* ba, NetBufs* bc) {
   NetBufs ta, tc;
   if (actor) carve_net(c, *actor, N, false, ta);
@@ -148,6 +152,7 @@ static size_t act_carve(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic
 }
 
 size_t rslx_act_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* critic, int32_t N) {
+  if (!depth_ok(actor) || !depth_ok(critic)) return 0;
   if (N <= 0) return 256;
   Carver c(nullptr);
   return act_carve(c, actor, critic, N, nullptr, nullptr);
@@ -365,7 +370,7 @@ void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rs
   carve_train(c, *critic, p.rows, 2, p.critic);
   p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 2);
   p.actor.sumsq = p.sumsq_all;
-  p.critic.sumsq = p.sumsq_all + p.actor.n_sumsq;
+  p.critic.sumsq = p.sumsq_all ? p.sumsq_all + p.actor.n_sumsq : nullptr;      // null while only sizing the workspace
   p.fused_head = actor->n_layers >= 2 && critic->n_layers >= 2 &&
                  ppo_head_supported(actor->dims[actor->n_layers - 1], critic->dims[critic->n_layers - 1], ro->A);
   p.loss_blocks = p.fused_head ? ppo_head_num_blocks(p.mb, sym != nullptr) : ppo_loss_num_blocks(p.mb);
@@ -759,6 +764,7 @@ int32_t rslx_bc_update_dc(rslx_mlp* student, const rslx_mlp* teacher, const floa
 
 // ---- one collection step of the distillation loop ---------------------------------------------------------------------
 size_t rslx_bc_collect_workspace_bytes(const rslx_mlp* student, const rslx_mlp* teacher, int32_t N) {
+  if (!depth_ok(student) || !depth_ok(teacher)) return 0;
   if (N <= 0 || !student || !teacher) return 256;
   Carver c(nullptr);
   return act_carve(c, student, teacher, N, nullptr, nullptr);
