@@ -101,9 +101,13 @@ typedef struct rslx_ppo_cfg {
   int32_t epoch_offset; /* permutation of epoch e uses e + epoch_offset (resume mid-update) */
 } rslx_ppo_cfg;
 
-/* Mirror maps (paper Sec. 2.2): mirror(x)[j] = sign[j] * x[perm[j]].  Each map is given twice:
- * a host copy (validated: must be a signed permutation with mirror o mirror = id) and a device
- * copy used by the kernels.  Both copies must hold the same values. */
+/* Mirror maps (paper Sec. 2.2): mirror(x)[j] = sign[j] * x[perm[j]].  The host copies are
+ * validated (each must be a signed permutation with mirror o mirror = id).  The device copies are
+ * what the kernels read.  rslx_ppo_update accepts all six device pointers NULL: it then uploads
+ * the validated host copies into its workspace itself (hipMemcpyAsync from the caller's host arrays
+ * on the call's stream: not under stream capture, where device copies must be passed).  Where
+ * device copies are passed they must hold the same values as the host copies; the library cannot
+ * check that.  rslx_sym_augment has no workspace and needs the device copies. */
 typedef struct rslx_sym {
   const int32_t* perm_obs_a_host; const float* sign_obs_a_host; /* [Da] */
   const int32_t* perm_obs_c_host; const float* sign_obs_c_host; /* [Dc] */

@@ -275,7 +275,8 @@ class BcCfg:
 
 
 class Sym:
-    """Mirror maps: host copies (int32 / float32 CPU tensors) plus device copies."""
+    """Mirror maps: host copies (int32 / float32 CPU tensors) plus device copies (device=None: none; rslx_ppo_update
+    then uploads the host copies itself)."""
 
     def __init__(self, perm_obs_a, sign_obs_a, perm_obs_c, sign_obs_c, perm_act, sign_act, mirror_loss_coef=1.0, device="cuda"):
         host = [torch.as_tensor(perm_obs_a, dtype=torch.int32).contiguous(), torch.as_tensor(sign_obs_a, dtype=torch.float32).contiguous(),

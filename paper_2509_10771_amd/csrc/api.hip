@@ -349,6 +349,8 @@ struct PpoPlan {
   float* stage_a = nullptr;          // staged (padded, mirrored) network inputs, when worth it (see staged_width)
   float* stage_c = nullptr;
   int dp_a = 0, dp_c = 0;            // their row widths, 0 = not staged
+  int32_t* sym_perm = nullptr;       // device copies of the mirror maps made by the call when the caller passes none:
+  float* sym_sign = nullptr;         // [Da + Dc + A] each
   double* sumsq_all = nullptr;       // actor blocks, critic blocks, log_std slot
   double* loss_partials = nullptr;
   double* mse_partials = nullptr;
@@ -368,6 +370,10 @@ void ppo_plan(Carver& c, const rslx_mlp* actor, const rslx_mlp* critic, const rs
   if (p.dp_c) p.stage_c = c.take<float>((size_t)(sym ? 2 : 1) * p.B * p.dp_c);
   carve_train(c, *actor, p.rows, 2, p.actor);
   carve_train(c, *critic, p.rows, 2, p.critic);
+  if (sym) {
+    p.sym_perm = c.take<int32_t>((size_t)ro->Da + ro->Dc + ro->A);
+    p.sym_sign = c.take<float>((size_t)ro->Da + ro->Dc + ro->A);
+  }
   p.sumsq_all = c.take<double>((size_t)p.actor.n_sumsq + p.critic.n_sumsq + 2);
   p.actor.sumsq = p.sumsq_all;
   p.critic.sumsq = p.sumsq_all ? p.sumsq_all + p.actor.n_sumsq : nullptr;      // null while only sizing the workspace
@@ -409,8 +415,10 @@ int32_t ppo_validate(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_r
         !involution_ok(sym->perm_obs_c_host, sym->sign_obs_c_host, ro->Dc) ||
         !involution_ok(sym->perm_act_host, sym->sign_act_host, ro->A))
       return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: mirror map is not an involutive signed permutation");
-    if (need_buffers && (!sym->perm_obs_a || !sym->sign_obs_a || !sym->perm_obs_c || !sym->sign_obs_c || !sym->perm_act || !sym->sign_act))
-      return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: null device mirror map");
+    const int n_dev = (sym->perm_obs_a != nullptr) + (sym->sign_obs_a != nullptr) + (sym->perm_obs_c != nullptr) +
+                      (sym->sign_obs_c != nullptr) + (sym->perm_act != nullptr) + (sym->sign_act != nullptr);
+    if (need_buffers && n_dev != 0 && n_dev != 6)
+      return fail(RSLX_ERR_INVALID_ARG, "rslx_ppo_update: device mirror maps must be given all or not at all");
   }
   if (rnd) {
     RSLX_TRY(check_mlp(rnd->target, "rslx_ppo_update rnd target", false));
@@ -455,6 +463,23 @@ int32_t ppo_update_impl(rslx_mlp* actor, rslx_mlp* critic, const rslx_rollout* r
   ppo_plan(c, actor, critic, ro, cfg, sym, rnd, p);
   if (!ws || ws_bytes < p.bytes) return fail(RSLX_ERR_WORKSPACE, "rslx_ppo_update: workspace %zu < %zu bytes", ws_bytes, p.bytes);
   const int A = ro->A, L_a = actor->n_layers, L_c = critic->n_layers;
+
+  // Mirror maps without device copies: the validated host copies are uploaded into the workspace, so the kernels
+  // cannot see other values than the ones that were checked.
+  rslx_sym sym_dev;
+  if (sym && sym->perm_obs_a == nullptr) {
+    sym_dev = *sym;
+    const int Da = ro->Da, Dc = ro->Dc;
+    RSLX_HIP(hipMemcpyAsync(p.sym_perm, sym->perm_obs_a_host, sizeof(int32_t) * Da, hipMemcpyHostToDevice, s));
+    RSLX_HIP(hipMemcpyAsync(p.sym_perm + Da, sym->perm_obs_c_host, sizeof(int32_t) * Dc, hipMemcpyHostToDevice, s));
+    RSLX_HIP(hipMemcpyAsync(p.sym_perm + Da + Dc, sym->perm_act_host, sizeof(int32_t) * A, hipMemcpyHostToDevice, s));
+    RSLX_HIP(hipMemcpyAsync(p.sym_sign, sym->sign_obs_a_host, sizeof(float) * Da, hipMemcpyHostToDevice, s));
+    RSLX_HIP(hipMemcpyAsync(p.sym_sign + Da, sym->sign_obs_c_host, sizeof(float) * Dc, hipMemcpyHostToDevice, s));
+    RSLX_HIP(hipMemcpyAsync(p.sym_sign + Da + Dc, sym->sign_act_host, sizeof(float) * A, hipMemcpyHostToDevice, s));
+    sym_dev.perm_obs_a = p.sym_perm; sym_dev.perm_obs_c = p.sym_perm + Da; sym_dev.perm_act = p.sym_perm + Da + Dc;
+    sym_dev.sign_obs_a = p.sym_sign; sym_dev.sign_obs_c = p.sym_sign + Da; sym_dev.sign_act = p.sym_sign + Da + Dc;
+    sym = &sym_dev;
+  }
 
   {
     std::vector<uint64_t> bases(cfg->epochs);

@@ -104,9 +104,35 @@ __global__ __launch_bounds__(256) void adv_stats_kernel(const double* __restrict
   }
 }
 
+// mean_inv != null: mean and 1 / (std + 1e-8) were formed by adv_stats_kernel.  mean_inv == null: every workgroup
+// forms them itself from the scan's block partials, in the same order and arithmetic as adv_stats_kernel (short
+// lists only: saves a launch where the whole problem is a few MB).
 __global__ __launch_bounds__(256) void adv_normalize_kernel(float* __restrict__ adv, long count,
-                                                            const float* __restrict__ mean_inv) {
-  const float mean = mean_inv[0], inv = mean_inv[1];
+                                                            const float* __restrict__ mean_inv,
+                                                            const double* __restrict__ partials, int nblocks) {
+  __shared__ double smem[4];
+  __shared__ float s_mi[2];
+  float mean, inv;
+  if (mean_inv != nullptr) {
+    mean = mean_inv[0]; inv = mean_inv[1];
+  } else {
+    double s = 0.0, q = 0.0;
+    for (int i = threadIdx.x; i < nblocks; i += 256) {
+      s += partials[2 * i];
+      q += partials[2 * i + 1];
+    }
+    const double ts = block_sum(s, smem);
+    const double tq = block_sum(q, smem);
+    if (threadIdx.x == 0) {
+      const double m = ts / (double)count;
+      double var = count > 1 ? (tq - ts * m) / (double)(count - 1) : 0.0;
+      if (var < 0.0) var = 0.0;
+      s_mi[0] = (float)m;
+      s_mi[1] = (float)(1.0 / (sqrt(var) + 1e-8));
+    }
+    __syncthreads();
+    mean = s_mi[0]; inv = s_mi[1];
+  }
   long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i + 3 < count) {
     float4 v = *reinterpret_cast<float4*>(adv + i);
@@ -136,10 +162,14 @@ hipError_t launch_gae(const float* rewards, const float* values, const float* la
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !normalize) return e;
   const long count = (long)T * N;
+  const unsigned blocks = (unsigned)((count + 1023) / 1024);
+  if (nb <= 512) {      // short partial list: the normalisation launch sums it itself
+    hipLaunchKernelGGL(adv_normalize_kernel, dim3(blocks), dim3(256), 0, stream, adv, count, (const float*)nullptr, partials, nb);
+    return hipGetLastError();
+  }
   float* mean_inv = reinterpret_cast<float*>(partials + 2 * (size_t)nb);
   hipLaunchKernelGGL(adv_stats_kernel, dim3(1), dim3(256), 0, stream, partials, nb, count, mean_inv);
-  const unsigned blocks = (unsigned)((count + 1023) / 1024);
-  hipLaunchKernelGGL(adv_normalize_kernel, dim3(blocks), dim3(256), 0, stream, adv, count, mean_inv);
+  hipLaunchKernelGGL(adv_normalize_kernel, dim3(blocks), dim3(256), 0, stream, adv, count, mean_inv, (const double*)nullptr, 0);
   return hipGetLastError();
 }
 

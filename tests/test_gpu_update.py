@@ -452,6 +452,28 @@ def test_ppo_rough_symmetry(rx):
     check_free_running(rx, case, check_forced_steps(rx, case))
 
 
+def test_ppo_symmetry_without_device_copies_of_the_maps(rx):
+    """The update uploads the validated host copies of the mirror maps itself when no device copies are passed: same
+    bits as with device copies."""
+    case = Case(WORKLOADS["rough"].scaled(64), 1, sym_on=True)
+    w = case.w
+    out = []
+    for device in ("cuda", None):
+        a, c, _ = _nets(rx, case, case.actor0, case.critic0)
+        i = case.inp
+        sym = rx.Sym(i["perm_obs"], i["sign_obs"], i["perm_obs"], i["sign_obs"], i["perm_act"], i["sign_act"], w.mirror_loss_coef,
+                     device=device)
+        ro, cfg = case.gpu_rollout(rx), case.gpu_cfg(rx, 1, w.minibatches)
+        stats = torch.zeros(w.minibatches, rx.NSTATS, device="cuda")
+        ws = rx.workspace(rx.rslx_ppo_update_workspace_bytes(a, c, ro, cfg, sym, None))
+        step = C.c_int64(0)
+        rx.rslx_ppo_update(a, c, ro, cfg, sym, None, step, stats, ws)
+        torch.cuda.synchronize()
+        out.append((a.params.clone(), c.params.clone(), stats.clone()))
+    assert all(torch.equal(x, y) for x, y in zip(*out))
+    assert rel_l2(host(out[0][0]), case.ref["actor"]) <= TOL
+
+
 def test_ppo_curiosity_rnd(rx):
     case = Case(replace(WORKLOADS["curiosity"].scaled(336), minibatches=8), 1, rnd_on=True)
     check_free_running(rx, case, check_forced_steps(rx, case))
