@@ -250,7 +250,9 @@ int32_t rslx_adam_step(float* params, const float* grads, float* m, float* v, in
  * With `rnd`: the predictor is trained on the same rows with its own Adam on
  * mean((pred(x) - target(x))^2), outside the PPO gradient norm.
  * In-out: actor/critic params, adam_m, adam_v (device), *adam_step (host, shared by both nets).
- * Out: grads hold the last minibatch's unclipped gradient; stats: device [E*M, RSLX_NSTATS]. */
+ * Out: grads hold the last minibatch's unclipped gradient; stats: device [E*M, RSLX_NSTATS].
+ * Action widths up to RSLX_MAX_ACTIONS; the fused output-layer + loss launch covers A <= 32 with
+ * a last hidden width of 32, 64, 128 or 256, everything else runs the same arithmetic unfused. */
 size_t rslx_ppo_update_workspace_bytes(const rslx_mlp* actor, const rslx_mlp* critic,
                                        const rslx_rollout* ro, const rslx_ppo_cfg* cfg,
                                        const rslx_sym* sym_or_null, const rslx_rnd_train* rnd_or_null);

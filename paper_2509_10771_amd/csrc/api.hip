@@ -401,7 +401,7 @@ int32_t ppo_validate(const rslx_mlp* actor, const rslx_mlp* critic, const rslx_r
   if (ro->Da != actor->dims[0] || ro->Dc != critic->dims[0] || ro->A != actor->dims[actor->n_layers] ||
       critic->dims[critic->n_layers] != 1)
     return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: rollout widths do not match the networks");
-  if (ro->A > 32) return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update: action width %d > 32", ro->A);
+  if (ro->A > RSLX_MAX_ACTIONS) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: action width %d > %d", ro->A, RSLX_MAX_ACTIONS);
   if (cfg->epochs < 0 || cfg->minibatches < 1) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: epochs / minibatches");
   if ((ro->T * ro->N) % cfg->minibatches != 0)
     return fail(RSLX_ERR_SHAPE, "rslx_ppo_update: T*N = %d is not a multiple of minibatches = %d", ro->T * ro->N, cfg->minibatches);

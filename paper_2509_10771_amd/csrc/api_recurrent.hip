@@ -286,7 +286,7 @@ int32_t rnn_validate(const rslx_memory* ga, const rslx_mlp* actor, const rslx_me
       ro->A != actor->dims[actor->n_layers] || critic->dims[critic->n_layers] != 1)
     return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: rollout, memory and network widths do not match");
   if (ga->cell != gc->cell) return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: the two memories use different cells");
-  if (ro->A > 32) return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: action width %d > 32", ro->A);
+  if (ro->A > RSLX_MAX_ACTIONS) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: action width %d > %d", ro->A, RSLX_MAX_ACTIONS);
   if (actor->n_layers + critic->n_layers + 4 > 16)
     return fail(RSLX_ERR_UNSUPPORTED, "rslx_ppo_update_recurrent: more than 12 MLP layers in total");
   if (cfg->epochs < 0 || cfg->minibatches < 1) return fail(RSLX_ERR_SHAPE, "rslx_ppo_update_recurrent: epochs / minibatches");

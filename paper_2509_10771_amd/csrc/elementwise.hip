@@ -338,29 +338,41 @@ int reduce_num_blocks(int64_t n) { return (int)((n + RED_PER_BLOCK - 1) / RED_PE
 // Sums the per-block partial sums of the PPO loss head in a fixed order (lane c of every wavefront takes
 // component c over every 4th block), then wavefront 0 writes the statistics row and the log_std gradient.
 __device__ void loss_finish_block(const LossFinishArgs& f) {
-  __shared__ double wpart[4][64];
-  const int c = threadIdx.x & 63, w = threadIdx.x >> 6;
+  constexpr int NC = PPO_NPART_FIXED + 64;          // components at the widest action vector
+  __shared__ double wpart[4][2 * 64];
+  static_assert(NC <= 2 * 64, "two components per lane cover every action width");
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int A = f.A, ncomp = PPO_NPART_FIXED + A;
-  double acc = 0.0;
-  if (c < ncomp) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int c = lane + 64 * h;
+    double acc = 0.0;
+    if (c < ncomp) {
 #pragma unroll 8
-    for (int b = w; b < f.blocks; b += 4) acc += f.partials[(long)b * ncomp + c];
+      for (int b = w; b < f.blocks; b += 4) acc += f.partials[(long)b * ncomp + c];
+    }
+    wpart[w][c] = acc;
   }
-  wpart[w][c] = acc;
   __syncthreads();
   if (w != 0) return;
-  const double s = wpart[0][c] + wpart[1][c] + wpart[2][c] + wpart[3][c];
-  double g2 = 0.0;
-  if (c >= PPO_NPART_FIXED && c < ncomp) {
-    const float g = (float)s - f.entropy_coef;
-    f.d_log_std[c - PPO_NPART_FIXED] = g;
-    g2 = (double)g * (double)g;
+  double s0 = 0.0, g2 = 0.0, ent = 0.0;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int c = lane + 64 * h;
+    const double s = wpart[0][c] + wpart[1][c] + wpart[2][c] + wpart[3][c];
+    if (h == 0) s0 = s;
+    if (c >= PPO_NPART_FIXED && c < ncomp) {
+      const float g = (float)s - f.entropy_coef;
+      f.d_log_std[c - PPO_NPART_FIXED] = g;
+      g2 += (double)g * (double)g;
+    }
   }
   g2 = wave_sum(g2);
-  double ent = 0.0;
-  if (c < A) ent = 0.5 + 0.5 * (double)LOG_2PI + (double)f.log_std[c];
+  if (lane < A) ent = 0.5 + 0.5 * (double)LOG_2PI + (double)f.log_std[lane];
   ent = wave_sum(ent);
   const int rows = f.rows, mb = f.mb;
+  const int c = lane;
+  const double s = s0;
   if (c == 0) {
     *f.sumsq_slot = g2;
     f.stats_row[0] = (float)(s / rows);
@@ -1197,8 +1209,11 @@ hipError_t launch_ppo_head(const PpoHeadArgs& h, hipStream_t stream) {
 
 hipError_t launch_ppo_loss(const PpoLossArgs& a, hipStream_t stream) {
   TraceScope ts(stream, "ppo_loss", 0.0, 0.0);
+  // the widest variant keeps a row's per-component values in per-lane scratch memory: correct, and only reached by
+  // action vectors wider than any locomotion or manipulation task of the paper uses
   if (a.A <= 16) hipLaunchKernelGGL(ppo_loss_kernel<16>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
-  else hipLaunchKernelGGL(ppo_loss_kernel<AMAX>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
+  else if (a.A <= AMAX) hipLaunchKernelGGL(ppo_loss_kernel<AMAX>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(ppo_loss_kernel<64>, dim3(ppo_loss_num_blocks(a.mb)), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -253,6 +253,14 @@ def test_recurrent_update_off_policy_start_odd_shapes(rx, cell):
     check_free_running(rx, case)
 
 
+def test_recurrent_update_action_vector_wider_than_the_fused_head(rx):
+    """40 action components: past the widths of the fused loss head, inside the ABI's maximum of 64."""
+    w = replace(WORKLOADS["recurrent"].scaled(48), T=6, A=40, hidden=(64, 64), memory_hidden=32, done_p=0.1)
+    case = RCase(w, 1, perturb=0.2)
+    check_forced_steps(rx, case)
+    check_free_running(rx, case)
+
+
 @pytest.mark.parametrize("cell", ["gru", "lstm"])
 def test_recurrent_update_two_epochs(rx, cell):
     w = replace(WORKLOADS["recurrent"].scaled(128), hidden=(256, 128), memory_hidden=128, done_p=0.03, memory_cell=cell)

@@ -442,6 +442,15 @@ def test_ppo_fused_head_widths(rx, base, N, A, hidden, sym_on):
     check_free_running(rx, case, check_forced_steps(rx, case))
 
 
+@pytest.mark.parametrize("base,N,A,sym_on", [("tiny", 40, 33, False), ("tiny", 30, 48, False), ("rough", 24, 64, True)])
+def test_ppo_action_vectors_wider_than_the_fused_head(rx, base, N, A, sym_on):
+    """Action widths 33..64 (the ABI's maximum) take the per-layer output GEMMs and the widest stand-alone loss
+    kernel; the log-std gradient then spans more than one wavefront's worth of components."""
+    w = replace(WORKLOADS[base].scaled(N), A=A)
+    case = Case(w, 1, sym_on=sym_on, perturb=0.2)
+    check_free_running(rx, case, check_forced_steps(rx, case))
+
+
 def test_ppo_flat_ragged(rx):
     case = Case(WORKLOADS["flat"].scaled(250), 1)     # mb = 1500 rows: 11 full 128-row tiles and a 92-row tail
     check_free_running(rx, case, check_forced_steps(rx, case))
