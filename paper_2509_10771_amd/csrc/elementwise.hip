@@ -335,34 +335,40 @@ hipError_t launch_permutations(const uint64_t* base_keys, int32_t n_perm, int32_
 constexpr int RED_PER_BLOCK = 1024;  // floats per workgroup of the plain squared-norm kernel
 int reduce_num_blocks(int64_t n) { return (int)((n + RED_PER_BLOCK - 1) / RED_PER_BLOCK); }
 
-// Sums the per-block partial sums of the PPO loss head in a fixed order (lane c of every wavefront takes
-// component c over every 4th block), then wavefront 0 writes the statistics row and the log_std gradient.
+// Sums the per-block partial sums of the PPO loss head in a fixed order: the 256 lanes form 256 / ncomp groups of
+// ncomp lanes (one lane per component, so a group reads one block's partials as consecutive words), group g takes
+// blocks g, g + G, ..; the groups' sums are then added in index order.  Wavefront 0 writes the statistics row and the
+// log_std gradient (two components per lane cover the widest action vector).
 __device__ void loss_finish_block(const LossFinishArgs& f) {
   constexpr int NC = PPO_NPART_FIXED + 64;          // components at the widest action vector
-  __shared__ double wpart[4][2 * 64];
   static_assert(NC <= 2 * 64, "two components per lane cover every action width");
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __shared__ double gpart[256];
+  __shared__ double total[2 * 64];
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int A = f.A, ncomp = PPO_NPART_FIXED + A;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int c = lane + 64 * h;
-    double acc = 0.0;
-    if (c < ncomp) {
+  const int G = 256 / ncomp;
+  const int grp = t / ncomp, c_own = t - grp * ncomp;
+  double acc = 0.0;
+  if (grp < G) {
 #pragma unroll 8
-      for (int b = w; b < f.blocks; b += 4) acc += f.partials[(long)b * ncomp + c];
-    }
-    wpart[w][c] = acc;
+    for (int b = grp; b < f.blocks; b += G) acc += f.partials[(long)b * ncomp + c_own];
+  }
+  gpart[t] = acc;
+  __syncthreads();
+  if (t < 2 * 64) {
+    double s = 0.0;
+    if (t < ncomp)
+      for (int g = 0; g < G; ++g) s += gpart[g * ncomp + t];
+    total[t] = s;
   }
   __syncthreads();
   if (w != 0) return;
-  double s0 = 0.0, g2 = 0.0, ent = 0.0;
+  double g2 = 0.0, ent = 0.0;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int c = lane + 64 * h;
-    const double s = wpart[0][c] + wpart[1][c] + wpart[2][c] + wpart[3][c];
-    if (h == 0) s0 = s;
     if (c >= PPO_NPART_FIXED && c < ncomp) {
-      const float g = (float)s - f.entropy_coef;
+      const float g = (float)total[c] - f.entropy_coef;
       f.d_log_std[c - PPO_NPART_FIXED] = g;
       g2 += (double)g * (double)g;
     }
@@ -372,7 +378,7 @@ __device__ void loss_finish_block(const LossFinishArgs& f) {
   ent = wave_sum(ent);
   const int rows = f.rows, mb = f.mb;
   const int c = lane;
-  const double s = s0;
+  const double s = total[lane];
   if (c == 0) {
     *f.sumsq_slot = g2;
     f.stats_row[0] = (float)(s / rows);
@@ -388,22 +394,25 @@ __device__ void loss_finish_block(const LossFinishArgs& f) {
 // One workgroup sums 256 consecutive gradient entries of one layer over all of that layer's splits: 64 lanes
 // cover the 256 floats with one 16-byte load each, the 4 wavefronts take every 4th split, LDS combines them
 // in a fixed order (deterministic result).  The layers of all networks trained in a step share one launch; its
-// last workgroup finishes the loss sums instead.
+// first workgroup finishes the loss sums instead.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceArgs a) {
-  if ((int)blockIdx.x == a.blocks) {
+  // the loss sums are a chain of dependent loads in one workgroup: it goes first so that it runs beside the others
+  const int has_finish = a.finish.blocks > 0 ? 1 : 0;
+  if (has_finish && blockIdx.x == 0) {
     loss_finish_block(a.finish);
     return;
   }
+  const int bid = (int)blockIdx.x - has_finish;
   __shared__ float4 part[4][64];
   __shared__ double smem[4];
   int si = 0;
-  while (si + 1 < a.n_seg && (int)blockIdx.x >= a.seg[si + 1].block_start) ++si;
+  while (si + 1 < a.n_seg && bid >= a.seg[si + 1].block_start) ++si;
   const ReduceSeg& sg = a.seg[si];
   const long size = sg.size;
   const int n_split = sg.split;
   const float* src = sg.partials;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const long j0 = ((long)(blockIdx.x - sg.block_start) * 64 + lane) * 4;
+  const long j0 = ((long)(bid - sg.block_start) * 64 + lane) * 4;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (j0 < size) {      // pitch is a multiple of 4, so the 16-byte load stays inside the split buffer's padding
     const long pitch = sg.pitch;
@@ -428,7 +437,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceArgs a
       }
   }
   double tot = block_sum(q, smem);
-  if (threadIdx.x == 0) a.sumsq_blocks[blockIdx.x] = tot;
+  if (threadIdx.x == 0) a.sumsq_blocks[bid] = tot;
 }
 
 hipError_t launch_reduce_partials(const ReduceArgs& a, hipStream_t stream) {
@@ -484,6 +493,18 @@ __device__ __forceinline__ void adam_store_transposed(const AdamSegment& sg, lon
 __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
   __shared__ double smem[4];
   __shared__ float s_scale, s_bc1, s_bc2;
+  // the lane's parameter, gradient and moment loads are requested before the squared-norm list is summed, so the
+  // two memory latencies overlap
+  const AdamSegment& sg = a.seg[blockIdx.y];
+  const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  const bool whole = i0 + 3 < sg.n;
+  float4 p = make_float4(0.f, 0.f, 0.f, 0.f), g = p, m = p, v = p;
+  if (whole) {
+    p = *reinterpret_cast<const float4*>(sg.params + i0);
+    g = *reinterpret_cast<const float4*>(sg.grads + i0);
+    m = *reinterpret_cast<const float4*>(sg.m + i0);
+    v = *reinterpret_cast<const float4*>(sg.v + i0);
+  }
   double q = 0.0;
   for (int i = threadIdx.x; i < a.n_sumsq; i += 256) q += a.sumsq_blocks[i];
   double tot = block_sum(q, smem);
@@ -503,16 +524,10 @@ __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a) {
   }
   __syncthreads();
   const float scale = s_scale;
-  const AdamSegment& sg = a.seg[blockIdx.y];
   const float ob1 = 1.0f - a.beta1, ob2 = 1.0f - a.beta2;
   const float inv_bc1 = 1.0f / s_bc1, inv_bc2 = 1.0f / s_bc2;
-  const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i0 >= sg.n) return;
-  if (i0 + 3 < sg.n) {
-    float4 p = *reinterpret_cast<float4*>(sg.params + i0);
-    float4 g = *reinterpret_cast<const float4*>(sg.grads + i0);
-    float4 m = *reinterpret_cast<float4*>(sg.m + i0);
-    float4 v = *reinterpret_cast<float4*>(sg.v + i0);
+  if (whole) {
     float* pp = &p.x; float* gp = &g.x; float* mp = &m.x; float* vp = &v.x;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -825,7 +840,7 @@ constexpr int HEAD_PAD = 4;         // LDS row padding of the activations: rows 
 // LDS plan (floats), shared by the kernel and the host-side size check.
 struct HeadLds {
   int A4, gp;
-  int ha, hc, wa, wc, mu, dmu, vv, dv, gat, bidx, pact, cst, dlp, scr, dls, total;
+  int ha, hc, wa, wc, mu, dmu, vv, dv, gat, pact, cst, dlp, scr, dls, total;
   // A4: padded number of action components = the kernel's template width (rows of W, mu, d_mu in LDS)
   __host__ __device__ HeadLds(int Ha, int Hc, int A, int AP) {
     A4 = AP;
@@ -841,7 +856,6 @@ struct HeadLds {
     vv = take(HEAD_ROWS);
     dv = take(HEAD_ROWS);
     gat = take(HEAD_ROWS * gp);
-    bidx = take(HEAD_ROWS);
     pact = take(A4);                    // mirror map of the action components
     cst = take(4 * A4);                 // per component: log_std, 1 / sigma, 1 / (2 sigma^2), mirror sign
     dlp = take(2 * HEAD_ROWS);          // d loss / d log-prob of the rows (and of their twins)
@@ -872,7 +886,6 @@ __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
   float* vv = lds + L.vv;
   float* dv = lds + L.dv;
   float* gat = lds + L.gat;       // [row][adv, ret, v_old, logp_old, actions[A], mu_old[A], sigma_old[A]]
-  int* bidx = reinterpret_cast<int*>(lds + L.bidx);
   int* pact = reinterpret_cast<int*>(lds + L.pact);
   float* cst = lds + L.cst;
   float* dlp = lds + L.dlp;
@@ -886,9 +899,27 @@ __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
     return lr < r_orig ? (long)(i0 + o) : (long)a.mb + i0 + o;
   };
 
-  // ---- phase 1: every global read of the block, issued before any of them is consumed ----
-  int my_b = -1;
-  if (tid < r_orig && i0 + tid < a.mb) my_b = a.idx[i0 + tid];
+  // ---- phase 1: every global read of the block.  Order of issue = order of arrival as far as the wave's load
+  //      counter can tell, so: the permutation entries of the rows this wave gathers (needed first, for the
+  //      addresses of the gather), the output-layer weights (cached, short), the activations (the long HBM reads),
+  //      then, once the permutation entries are there, the gathered rollout rows.  Each group is written to LDS in
+  //      the same order, so no wait covers more than it has to. ----
+  constexpr int GROWS = HEAD_ROWS / 4;                    // rows gathered per wave: r = wave + 4 i
+  int gb[GROWS];
+#pragma unroll
+  for (int i = 0; i < GROWS; ++i) {
+    const int r = wave + 4 * i;
+    gb[i] = (r < r_orig && i0 + r < a.mb) ? a.idx[i0 + r] : -1;
+  }
+  constexpr int WROUND = 8;                               // weight loads in flight per lane
+  const int w_elems = (Ha + 1) * AM;
+  float wv[WROUND];
+#pragma unroll
+  for (int i = 0; i < WROUND; ++i) {                      // first round (all of W for A <= 12 at 128 hidden units)
+    const int e = tid + 256 * i;
+    const int k = e / AM, jj = e - k * AM;
+    wv[i] = (e < w_elems && jj < A) ? h.w_a[k * A + jj] : 0.f;
+  }
   constexpr int HP = 8;                                   // 16-byte pieces per lane and network (H <= 256)
   float4 ra[HP], rc[HP];
   const int pa = Ha >> 2, pc = Hc >> 2;                   // pieces per row (powers of two)
@@ -907,18 +938,42 @@ __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
       if (gr >= 0) rc[i] = *reinterpret_cast<const float4*>(h.h_c + gr * Hc + 4 * (e & (pc - 1)));
     }
   }
-  for (int e0 = 0; e0 < (Ha + 1) * AM; e0 += 256 * 8) {   // 8 loads in flight per lane; rows padded with zeros
-    float wv[8];
+  // rollout rows, gathered through the permutation: wavefront w takes rows w, w + 4, ..; lanes run over the row
+  // [adv, ret, v_old, logp_old, actions[A], mu_old[A], sigma_old[A]]; the loads of all 8 rows are in flight together
+  const int gw = 4 + 3 * A;
+  auto gather_src = [&](int c, const float*& src, int& stride, int& off) {
+    stride = 1; off = 0;
+    if (c < 4) {
+      src = c == 0 ? a.adv : c == 1 ? a.returns : c == 2 ? a.v_old : a.logp_old;
+    } else {
+      const int q = (c - 4) / A;
+      src = q == 0 ? a.actions : q == 1 ? a.mu_old : a.sigma_old;
+      stride = A; off = (c - 4) - q * A;
+    }
+  };
+  float gv[GROWS];
+  {
+    const float* src = a.adv; int stride = 1, off = 0;
+    if (lane < gw) gather_src(lane, src, stride, off);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < GROWS; ++i) gv[i] = (lane < gw && gb[i] >= 0) ? src[(long)gb[i] * stride + off] : 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < WROUND; ++i) {
+    const int e = tid + 256 * i;
+    if (e < w_elems) wa[e] = wv[i];
+  }
+  for (int e0 = 256 * WROUND; e0 < w_elems; e0 += 256 * WROUND) {   // wider heads: the rest of W, rows padded with zeros
+#pragma unroll
+    for (int i = 0; i < WROUND; ++i) {
       const int e = e0 + tid + 256 * i;
       const int k = e / AM, jj = e - k * AM;
-      wv[i] = (e < (Ha + 1) * AM && jj < A) ? h.w_a[k * A + jj] : 0.f;
+      wv[i] = (e < w_elems && jj < A) ? h.w_a[k * A + jj] : 0.f;
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < WROUND; ++i) {
       const int e = e0 + tid + 256 * i;
-      if (e < (Ha + 1) * AM) wa[e] = wv[i];
+      if (e < w_elems) wa[e] = wv[i];
     }
   }
   for (int e = tid; e < Hc + 1; e += 256) wc[e] = h.w_c[e];
@@ -930,35 +985,6 @@ __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
     pact[tid] = sym ? a.perm_act[tid] : tid;
   }
   for (int e = tid; e < HEAD_ROWS * A4; e += 256) dmu[e] = 0.f;    // also the padding the 16-byte reads touch
-  if (tid < HEAD_ROWS) bidx[tid] = my_b;
-  __syncthreads();
-  // rollout rows, gathered through the permutation: wavefront w takes rows w, w + 4, ..; lanes run over the row;
-  // the loads of all 8 rows are in flight together
-  {
-    const int gw = 4 + 3 * A;
-    for (int c = lane; c < gw; c += 64) {
-      const float* src; int stride = 1, off = 0;
-      if (c < 4) {
-        src = c == 0 ? a.adv : c == 1 ? a.returns : c == 2 ? a.v_old : a.logp_old;
-      } else {
-        const int q = (c - 4) / A;
-        src = q == 0 ? a.actions : q == 1 ? a.mu_old : a.sigma_old;
-        stride = A; off = (c - 4) - q * A;
-      }
-      float gv[HEAD_ROWS / 4];
-#pragma unroll
-      for (int i = 0; i < HEAD_ROWS / 4; ++i) {
-        const int r = wave + 4 * i;
-        const long b = r < r_orig ? bidx[r] : -1;
-        gv[i] = b >= 0 ? src[b * stride + off] : 0.f;
-      }
-#pragma unroll
-      for (int i = 0; i < HEAD_ROWS / 4; ++i) {
-        const int r = wave + 4 * i;
-        if (r < r_orig) gat[r * gp + c] = gv[i];
-      }
-    }
-  }
 #pragma unroll
   for (int i = 0; i < HP; ++i) {
     const int e = tid + 256 * i;
@@ -967,6 +993,24 @@ __global__ __launch_bounds__(256) void ppo_head_kernel(const PpoHeadArgs h) {
     }
     if (e < HEAD_ROWS * pc) {
       *reinterpret_cast<float4*>(hc + (e >> shc) * sc + 4 * (e & (pc - 1))) = rc[i];
+    }
+  }
+  if (lane < gw) {
+#pragma unroll
+    for (int i = 0; i < GROWS; ++i) {
+      const int r = wave + 4 * i;
+      if (r < r_orig) gat[r * gp + lane] = gv[i];
+    }
+  }
+  for (int c = lane + 64; c < gw; c += 64) {              // more than 20 action components: the columns past the 64th
+    const float* src; int stride, off;
+    gather_src(c, src, stride, off);
+#pragma unroll
+    for (int i = 0; i < GROWS; ++i) gv[i] = gb[i] >= 0 ? src[(long)gb[i] * stride + off] : 0.f;
+#pragma unroll
+    for (int i = 0; i < GROWS; ++i) {
+      const int r = wave + 4 * i;
+      if (r < r_orig) gat[r * gp + c] = gv[i];
     }
   }
   __syncthreads();
