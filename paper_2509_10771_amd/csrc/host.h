@@ -198,10 +198,13 @@ struct SplitPlan {
 };
 
 // Enough workgroups to fill the 256 CUs once, but at least 128 rows per split: four 64-row-tile workgroups per CU,
-// three of the 128x128 ones (measured: 768 of those beat 1024).  A 128x128 weight gradient that shares its launch
-// with the layer's input gradient (every layer but the first) only needs two per CU - the input gradient's
-// workgroups take the other slots - which also halves its partial sums.
+// three of the 128x128 ones (measured: 768 of those beat 1024).  A weight gradient that shares its launch with the
+// layer's input gradient (every layer but the first) needs fewer - the input gradient's workgroups take the other
+// slots - which also shrinks its partial sums: two per CU for 128x128 tiles, one per CU for 64-row tiles (measured
+// on the 256x128 layer at 24 576 rows: 256 weight-gradient + 768 input-gradient workgroups are one resident round
+// of 1024; 192 and 320..1024 are all slower, 128 makes the weight gradient the launch's long pole).
 constexpr int DW_TARGET_WGS = 1024;
+constexpr int DW_TARGET_WGS_PAIRED = 256;
 constexpr int DW_TARGET_WGS_BIG = 768;
 constexpr int DW_TARGET_WGS_BIG_PAIRED = 512;
 
@@ -210,7 +213,11 @@ inline void plan_layer(SplitPlan& p, int l, int M, int N, int32_t rows, int grou
   const int tiles_big = ((M + 127) / 128) * ((N + 127) / 128);
   p.big[l] = (tiles_big * group >= 16) ? 1 : 0;
   const int tiles = gemm_dw_tiles(M, N, p.big[l] != 0);
-  const int target = p.big[l] ? (paired ? DW_TARGET_WGS_BIG_PAIRED : DW_TARGET_WGS_BIG) : DW_TARGET_WGS;
+  // 64-row tiles share a launch only where the paired kernel exists for both tile shapes (both widths above 64) or
+  // as the narrow output layer that rides in the next layer's paired launch
+  const bool small_shares = paired && ((M > 64 && N > 64) || N <= 32);
+  const int target = p.big[l] ? (paired ? DW_TARGET_WGS_BIG_PAIRED : DW_TARGET_WGS_BIG)
+                              : (small_shares ? DW_TARGET_WGS_PAIRED : DW_TARGET_WGS);
   int s = (target + tiles * group - 1) / (tiles * group);
   const int smax = rows / 128 > 1 ? rows / 128 : 1;
   if (s > smax) s = smax;
