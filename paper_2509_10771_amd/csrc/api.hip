@@ -736,23 +736,31 @@ int32_t bc_update_impl(rslx_mlp* student, const rslx_mlp* teacher, const float* 
                                  counters ? &counters->call_index : nullptr, cfg->epoch_offset));
   }
   const int nbm = mse_num_blocks((int64_t)p.mb * A);
+  if (cfg->epochs > 0) {
+    // once per call: the statistics rows start at zero (each step then writes its loss and gradient norm), and the
+    // transposed weights are formed; every Adam launch below keeps them current
+    RSLX_HIP(launch_fill(stats, (int64_t)cfg->epochs * cfg->minibatches * RSLX_NSTATS, 0.f, s));
+    const XView none;
+    BwdJob tj{student, none, p.mb, &p.student.act, p.student.d_out, p.student.wt, p.student.partials, &p.student.plan};
+    RSLX_TRY(transpose_weights(&tj, 1, s, false));
+  }
   for (int e = 0; e < cfg->epochs; ++e) {
     for (int m = 0; m < cfg->minibatches; ++m) {
       const int32_t* idx = p.perms + (size_t)e * B + (size_t)m * p.mb;
       float* stats_row = stats + ((size_t)e * cfg->minibatches + m) * RSLX_NSTATS;
-      RSLX_HIP(launch_fill(stats_row, RSLX_NSTATS, 0.f, s));
       XView xs; xs.base = obs_student; xs.ld = student->dims[0]; xs.row_idx = idx; xs.src_rows = B;
       NetJob fj{student, xs, p.mb, &p.student.act};
       RSLX_TRY(forward_nets(&fj, 1, s));
       RSLX_HIP(launch_mse(p.student.act.out[Ls - 1], targets, idx, p.mb, A, p.student.d_out, p.mse_partials, s));
       RSLX_HIP(launch_mse_finish(p.mse_partials, nbm, (int64_t)p.mb * A, stats_row, s));
       BwdJob bj{student, xs, p.mb, &p.student.act, p.student.d_out, p.student.wt, p.student.partials, &p.student.plan};
-      RSLX_TRY(backward_nets(&bj, 1, s));
+      RSLX_TRY(backward_nets(&bj, 1, s, false, true));
       RSLX_TRY(reduce_net(*student, p.student, s));
       const int64_t t = *adam_step + 1;
       AdamArgs aa;
       memset(&aa, 0, sizeof aa);
       aa.seg[0] = AdamSegment{student->params, student->grads, student->adam_m, student->adam_v, weight_count(*student)};
+      adam_keeps_transposed(aa.seg[0], *student, p.student.wt);
       aa.n_seg = 1;
       aa.sumsq_blocks = p.student.sumsq; aa.n_sumsq = p.student.n_sumsq;
       aa.max_grad_norm = cfg->max_grad_norm;
