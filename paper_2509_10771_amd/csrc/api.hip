@@ -200,7 +200,7 @@ int32_t act_impl(const rslx_mlp* actor, const rslx_mlp* critic, const float* obs
     fa.noise_base = mix64_host(noise_pre ^ step);
     fa.step_dev = step_dev; fa.noise_pre = noise_pre;
     fa.actions = actions; fa.logp = logp; fa.sigma = sigma;
-    if (fused_forward_supported(fa)) {
+    if (fused_forward_pays(fa)) {
       RSLX_HIP(launch_fused_forward(fa, s));
       if (counters && !values_only) RSLX_HIP(advance_counters(counters, 1, 0, 0, 0, s));
       return RSLX_OK;
@@ -823,7 +823,7 @@ int32_t rslx_bc_collect(const rslx_mlp* student, const rslx_mlp* teacher, const 
     fa.max_dim = max_dim_of(*student) > max_dim_of(*teacher) ? max_dim_of(*student) : max_dim_of(*teacher);
     fa.net[0] = fused_net(*student, obs_student, student->dims[0], nullptr, actions, false);
     fa.net[1] = fused_net(*teacher, obs_teacher, teacher->dims[0], nullptr, targets, false);
-    if (fused_forward_supported(fa)) {
+    if (fused_forward_pays(fa)) {
       RSLX_HIP(launch_fused_forward(fa, s));
       return RSLX_OK;
     }
@@ -907,7 +907,7 @@ int32_t rslx_rnd(const rslx_mlp* target, const rslx_mlp* predictor, const float*
   fa.n_rows = N; fa.n_nets = 2; fa.max_dim = max_dim_of(*target);
   fa.net[0] = fused_net(*predictor, obs, D, subset_idx_or_null, bp.out[L - 1], false);
   fa.net[1] = fused_net(*target, obs, D, subset_idx_or_null, bt.out[L - 1], false);
-  if (fused_forward_supported(fa)) {
+  if (fused_forward_pays(fa)) {
     RSLX_HIP(launch_fused_forward(fa, s));
   } else {
     NetJob jobs[2] = {NetJob{predictor, x, N, &bp}, NetJob{target, x, N, &bt}};

@@ -356,6 +356,16 @@ inline FusedNet fused_net(const rslx_mlp& n, const float* x, int ldx, const int3
   return f;
 }
 
+// The layer-fused launch holds one workgroup per CU and walks 32 rows through all layers as one dependent chain:
+// unbeatable while a network's row blocks fit the chip once (two networks: two rounds), but each further round costs the whole
+// chain again, and the tiled per-layer launches then do the same work faster (measured at 16 384 rows, two
+// networks [48, 512, 256, 128, 12]: 4 rounds, 176 us fused against 127 us layered).
+// The choice depends on the row count alone, so that a values-only call and a full call on the same batch take the
+// same path and return bit-identical values.
+inline bool fused_forward_pays(const FusedForwardArgs& fa) {
+  return fused_forward_supported(fa) && (fa.n_rows + 31) / 32 <= 256;
+}
+
 inline int max_dim_of(const rslx_mlp& n) {
   int m = 0;
   for (int i = 0; i <= n.n_layers; ++i) m = n.dims[i] > m ? n.dims[i] : m;

@@ -122,6 +122,16 @@ def test_act_matches_oracle(rx, name, N):
     _act_case(rx, w, inp, N, use_eps=False)
 
 
+@pytest.mark.parametrize("name,N", [("flat", 8192), ("flat", 8193), ("curiosity", 16384)])
+def test_act_large_batches_switch_to_the_per_layer_launches(rx, name, N):
+    """Up to 8192 rows (256 row blocks per network) the layer-fused launch is used, beyond that the tiled per-layer
+    launches: the same outputs either side of the switch and at the curiosity workload's size."""
+    w = WORKLOADS[name].scaled(N)
+    inp = make_inputs(w)
+    inp["actor"][-w.A:] = np.random.default_rng(2).normal(scale=0.3, size=w.A).astype(np.float32)
+    _act_case(rx, w, inp, N, use_eps=False)
+
+
 def test_act_wide_layers_take_the_layered_path(rx):
     """Hidden layers wider than 512 do not fit the layer-fused kernel's LDS budget; the per-layer path must agree too."""
     from dataclasses import replace
