@@ -166,7 +166,7 @@ typedef struct rslx_trace_record {
 int32_t rslx_trace_begin(int32_t max_records);
 int32_t rslx_trace_end(rslx_trace_record* out, int32_t cap, int32_t* n_out);
 
-/* ---- permutation of one epoch (update step U0) --------------------------------------- */
+/* ---- permutation of one epoch (first step of the update: minibatch order) -------------- */
 
 /* Shuffled minibatch order (paper Sec. 2.1: multi-epoch minibatch updates; the generator is this
  * library's own):  mix64 = SplitMix64 output function,
@@ -223,7 +223,7 @@ int32_t rslx_gae_noalloc(const float* rewards, const float* values, const float*
                          int32_t N, float gamma, float lam, int32_t normalize_adv,
                          float* advantages, float* returns, void* stream);
 
-/* ---- fused gradient-clip + Adam over one flat buffer (update steps U5/U6) ------------- */
+/* ---- fused gradient-clip + Adam over one flat buffer (last steps of the update) -------- */
 
 /* s = min(1, max_grad_norm / (||g||_2 + 1e-6)) (1 when max_grad_norm <= 0), then Adam
  * (Kingma & Ba 2015) with g*s:  m,v moments in place, bias correction with step t = *adam_step+1,
